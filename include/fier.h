@@ -1,0 +1,170 @@
+/*
+ * libfier -- the decode hot path of Fier (arxiv 2508.08256, "token-level KV retrieval
+ * via 1-bit quantization") for one AMD MI355X (gfx950).
+ *
+ * One decode step of one attention layer, per (batch element, kv head) "unit":
+ *   1. keep a 1-bit copy of the key cache, group size g = 32 tokens per channel, with
+ *      one (s, z) pair per group and channel                     (Alg. 1 step 1, Eq. 5)
+ *   2. score every cached token: q . dequant(1-bit key)           (Alg. 1 step 2)
+ *   3. pick the top-B tokens per kv head                          (Alg. 1 step 3)
+ *   4. exact softmax attention over the selected K/V rows only    (Alg. 1 step 4)
+ *
+ * General rules of this ABI
+ *   - Plain C.  Every pointer in fier_cache and every pointer argument documented as
+ *     "device" is device memory owned by the caller; the library allocates nothing,
+ *     keeps no state between calls and never frees.  "host" pointers are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and never synchronise; results are valid once the stream has been
+ *     synchronised by the caller.  Calls that touch the same buffers must be ordered by
+ *     the caller (same stream, or events).
+ *   - Every device pointer must be 16-byte aligned (FIER_EALIGN otherwise).
+ *   - Arguments are validated on the host before anything is launched; on any error
+ *     nothing has been enqueued.  FIER_EHIP reports a failed launch.
+ *   - Units are ordered batch-major: u = b * n_kv_heads + h.  The query heads that
+ *     share kv head h are h * n_rep .. h * n_rep + n_rep - 1, n_rep = n_q_heads / n_kv_heads.
+ *
+ * Data layout in device memory (D = head_dim = 128, g = group_size = 32)
+ *   k, v     [batch][n_kv_heads][max_ctx][D]     16-bit floats (binary16 or bfloat16)
+ *   kbits    [units][max_ctx / 64][D][2] uint32  "pair block" = 64 tokens = 1 KiB:
+ *              word (P, c, h) holds channel c of tokens 64 P + 32 h + i in bit i, i.e. the
+ *              two words of a channel form a 64-bit mask over the 64 tokens of the block
+ *              (lane = token in a 64-wide wavefront).  Bits of tokens not present are 0.
+ *   kmeta    [units][max_ctx / 32][D] uint32      low half = s, high half = z of group
+ *              (u, G, c), both in the K dtype: dequant(k) = z + bit * s.
+ *   Together 32 bytes per cached token and unit: 1/8 of a 16-bit key cache, the ratio
+ *   (1 + 32/g)/16 of Eq. 8.
+ *   seq_lens [batch] int32, device: tokens currently valid in each sequence.
+ */
+#ifndef FIER_H
+#define FIER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FIER_OK = 0,
+  FIER_EINVAL = -1,       /* null pointer, negative size, bad enum            */
+  FIER_ESHAPE = -2,       /* head counts / context capacity not supported      */
+  FIER_EALIGN = -3,       /* a device pointer is not 16-byte aligned            */
+  FIER_EWORKSPACE = -4,   /* workspace missing                                  */
+  FIER_EUNSUPPORTED = -5, /* head_dim != 128, group_size != 32, n_rep > 8       */
+  FIER_EHIP = -6          /* a kernel launch failed                             */
+} fier_status;
+
+typedef enum { FIER_F16 = 0, FIER_BF16 = 1 } fier_dtype;
+
+typedef struct fier_config {
+  int32_t n_q_heads;  /* multiple of n_kv_heads, n_rep = n_q_heads / n_kv_heads <= 8 */
+  int32_t n_kv_heads;
+  int32_t head_dim;   /* 128 */
+  int32_t group_size; /* 32 (tokens per quantization group, along each channel)      */
+  int32_t max_ctx;    /* row capacity of every unit's cache; multiple of 64, <= 2^20 */
+  int32_t batch;
+  int32_t kv_dtype;   /* fier_dtype of k, v, q, k_new, v_new and of (s, z)           */
+  float sm_scale;     /* softmax scale of step 4, e.g. 1/sqrt(head_dim)              */
+} fier_config;
+
+typedef struct fier_cache { /* one layer; all pointers device, caller-owned */
+  void *k;
+  void *v;
+  uint32_t *kbits;         /* fier_packed_bits_bytes(cfg) bytes */
+  uint32_t *kmeta;         /* fier_packed_meta_bytes(cfg) bytes */
+  const int32_t *seq_lens; /* [batch] */
+} fier_cache;
+
+/* Sizes (host only, no GPU needed).  0 if cfg is invalid. */
+size_t fier_packed_bits_bytes(const fier_config *cfg);
+size_t fier_packed_meta_bytes(const fier_config *cfg);
+/* Scratch needed by fier_sparse_attn / fier_dense_attn / fier_decode_step for selections of at
+ * most max_budget tokens per unit (fier_dense_attn: pass max_budget = max_ctx). */
+size_t fier_workspace_bytes(const fier_config *cfg, int32_t max_budget);
+const char *fier_status_string(int status);
+/* Check cfg alone: FIER_OK or the error the other calls would return for it. */
+int fier_check_config(const fier_config *cfg);
+
+/*
+ * Alg. 1 step 1 (Eq. 5 as 1-bit round-to-nearest, Sec. 3.3).  For every unit, quantize tokens
+ * [0, seq_len): per group of 32 consecutive tokens of a channel, z = the smallest element
+ * (-0 stored as +0), s = (largest - z) rounded once to the K dtype (held at the largest finite
+ * value on overflow), bit = 1 iff 2 * (k - z) >= s, all three evaluated in binary32.  A partial
+ * last group uses the tokens present.  Writes every pair block that holds a valid token, and
+ * the (s, z) of both of its groups (zeros for a group with no token); the rest is untouched.
+ */
+int fier_quantize_keys(const fier_config *cfg, const fier_cache *cache, void *stream);
+
+/*
+ * Sec. 3.1 decode-stage append.  For every unit write k_new / v_new ([batch][n_kv_heads][D],
+ * device) into row seq_len of k / v, then re-derive the (s, z) and the bits of the group that
+ * row falls in from the keys present (rows 32*floor(seq_len/32) .. seq_len).  After the call the
+ * packed state equals fier_quantize_keys over seq_len + 1 tokens, bit for bit.  seq_lens is not
+ * modified (the caller increments it); a unit with seq_len >= max_ctx is left unchanged.
+ */
+int fier_append_key(const fier_config *cfg, const fier_cache *cache, const void *k_new,
+                    const void *v_new, void *stream);
+
+/*
+ * Alg. 1 step 2.  scores[u][j] = sum over the unit's n_rep query heads of q_r . (z + bit * s)
+ * for j < seq_len + extra_tokens, binary32, unscaled.  q is [batch][n_q_heads][D] device;
+ * scores is [units][max_ctx] device; entries at and past the scored length are not written.
+ * extra_tokens is 0, or 1 to include a row appended in this step.
+ */
+int fier_score(const fier_config *cfg, const fier_cache *cache, const void *q, int32_t extra_tokens,
+               float *scores, void *stream);
+
+/*
+ * Alg. 1 step 3.  Per unit: the min(budget, len) tokens of largest score among the first
+ * len = seq_lens[b] + extra_tokens; equal scores go to the lower token index (-0 == +0);
+ * indices are written in ascending order to idx[u][0 .. count[u]).  budgets is [batch] device
+ * (values < 1 select nothing), max_budget is the row pitch of idx (host value >= every budget;
+ * larger budgets are clamped to it).  Scores must be finite.  No workspace is used.
+ */
+int fier_topk(const fier_config *cfg, const float *scores, const int32_t *seq_lens,
+              int32_t extra_tokens, const int32_t *budgets, int32_t max_budget, int32_t *idx,
+              int32_t *count, void *stream);
+
+/*
+ * Alg. 1 step 4.  For every query head: p = softmax(sm_scale * q . K[S]^T), out = p V[S], with
+ * S = idx[u][0 .. count[u]) (rows of this unit's cache, any order, each < max_ctx).  Inputs are
+ * read in the K dtype, logits, softmax and the output are binary32.  out is
+ * [batch][n_q_heads][D] float, device.  count[u] == 0 gives zeros.
+ */
+int fier_sparse_attn(const fier_config *cfg, const fier_cache *cache, const void *q,
+                     const int32_t *idx, const int32_t *count, int32_t max_budget, float *out,
+                     void *workspace, void *stream);
+
+/* Sec. 3.1 full-cache decode attention softmax(sm_scale * q K^T) V over rows [0, seq_len +
+ * extra_tokens): the "Full KV" comparison of Sec. 4.5, same kernels as step 4 without the gather.
+ * workspace: fier_workspace_bytes(cfg, max_ctx). */
+int fier_dense_attn(const fier_config *cfg, const fier_cache *cache, const void *q,
+                    int32_t extra_tokens, float *out, void *workspace, void *stream);
+
+/*
+ * One whole decode step (Alg. 1 with the append of Sec. 3.1) for n_layers layers, one enqueue:
+ * for each layer l: append k_new[l] / v_new[l] (skipped if k_new is NULL), score all
+ * seq_len (+1 if appended) tokens, select the top budgets[b], attend over the selection.
+ *   layers   [n_layers] host array of fier_cache (device pointers inside)
+ *   q        [n_layers][batch][n_q_heads][D] device;   k_new, v_new [n_layers][batch][n_kv_heads][D]
+ *   out      [n_layers][batch][n_q_heads][D] float device
+ *   idx_out / count_out   optional (NULL): [n_layers][units][max_budget] / [n_layers][units], the
+ *            selection of every layer, for inspection
+ *   workspace  fier_workspace_bytes(cfg, max_budget) bytes, reused by every layer
+ * seq_lens are not modified.
+ */
+int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
+                     const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
+                     float *out, int32_t *idx_out, int32_t *count_out, void *workspace, void *stream);
+
+/* Host helpers for inspection: physical packed layout -> logical arrays, all host memory.
+ * bits [units][max_ctx][D] one byte (0/1) per element; s, z [units][max_ctx/32][D] raw 16-bit words. */
+void fier_unpack_bits(const fier_config *cfg, const uint32_t *kbits_host, uint8_t *bits_host);
+void fier_unpack_meta(const fier_config *cfg, const uint32_t *kmeta_host, uint16_t *s_host,
+                      uint16_t *z_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIER_H */

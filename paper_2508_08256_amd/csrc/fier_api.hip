@@ -1,0 +1,268 @@
+// C-ABI entry points of libfier (declared in include/fier.h): argument validation on the host,
+// workspace carving, and kernel enqueue.  No allocation, no synchronisation, no global state.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "fier.h"
+#include "fier_kernels.h"
+
+namespace {
+
+constexpr int kD = 128;
+constexpr int kG = 32;
+constexpr int kPair = 64;
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_cfg(const fier_config* c) {
+  if (!c) return FIER_EINVAL;
+  if (c->batch <= 0 || c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->max_ctx <= 0) return FIER_EINVAL;
+  if (c->kv_dtype != FIER_F16 && c->kv_dtype != FIER_BF16) return FIER_EINVAL;
+  if (!(c->sm_scale == c->sm_scale)) return FIER_EINVAL;
+  if (c->head_dim != kD || c->group_size != kG) return FIER_EUNSUPPORTED;
+  if (c->n_q_heads % c->n_kv_heads != 0) return FIER_ESHAPE;
+  if (c->n_q_heads / c->n_kv_heads > 8) return FIER_EUNSUPPORTED;
+  if (c->max_ctx % kPair != 0 || c->max_ctx > (1 << 20)) return FIER_ESHAPE;
+  if ((int64_t)c->batch * c->n_kv_heads > 65535) return FIER_ESHAPE;
+  return FIER_OK;
+}
+
+int check_cache(const fier_cache* k) {
+  if (!k || !k->k || !k->v || !k->kbits || !k->kmeta || !k->seq_lens) return FIER_EINVAL;
+  if (misaligned(k->k) || misaligned(k->v) || misaligned(k->kbits) || misaligned(k->kmeta)) return FIER_EALIGN;
+  return FIER_OK;
+}
+
+inline int units_of(const fier_config* c) { return c->batch * c->n_kv_heads; }
+inline int n_rep_of(const fier_config* c) { return c->n_q_heads / c->n_kv_heads; }
+inline int splits_for(int max_budget) { return (max_budget + fier::kAttnRowsSparse - 1) / fier::kAttnRowsSparse; }
+
+struct Workspace {
+  float* po;
+  float* pm;
+  float* pl;
+  float* scores;
+  int32_t* idx;
+  int32_t* count;
+  size_t bytes;
+};
+
+// Carve the workspace for selections of up to max_budget rows per unit.  base may be null (sizing only).
+Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
+  const size_t units = (size_t)units_of(c), heads = units * (size_t)n_rep_of(c);
+  const size_t splits = (size_t)splits_for(max_budget);
+  char* p = static_cast<char*>(base);
+  size_t off = 0;
+  Workspace w;
+  w.po = reinterpret_cast<float*>(p + off);
+  off += align_up(heads * splits * kD * sizeof(float));
+  w.pm = reinterpret_cast<float*>(p + off);
+  off += align_up(heads * splits * sizeof(float));
+  w.pl = reinterpret_cast<float*>(p + off);
+  off += align_up(heads * splits * sizeof(float));
+  w.scores = reinterpret_cast<float*>(p + off);
+  off += align_up(units * (size_t)c->max_ctx * sizeof(float));
+  w.idx = reinterpret_cast<int32_t*>(p + off);
+  off += align_up(units * (size_t)max_budget * sizeof(int32_t));
+  w.count = reinterpret_cast<int32_t*>(p + off);
+  off += align_up(units * sizeof(int32_t));
+  w.bytes = off;
+  return w;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? FIER_OK : FIER_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* fier_status_string(int status) {
+  switch (status) {
+    case FIER_OK: return "ok";
+    case FIER_EINVAL: return "invalid argument";
+    case FIER_ESHAPE: return "unsupported shape";
+    case FIER_EALIGN: return "device pointer not 16-byte aligned";
+    case FIER_EWORKSPACE: return "workspace missing";
+    case FIER_EUNSUPPORTED: return "unsupported configuration";
+    case FIER_EHIP: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int fier_check_config(const fier_config* cfg) { return check_cfg(cfg); }
+
+size_t fier_packed_bits_bytes(const fier_config* cfg) {
+  if (check_cfg(cfg) != FIER_OK) return 0;
+  return (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / kPair) * kD * 2 * sizeof(uint32_t);
+}
+
+size_t fier_packed_meta_bytes(const fier_config* cfg) {
+  if (check_cfg(cfg) != FIER_OK) return 0;
+  return (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / kG) * kD * sizeof(uint32_t);
+}
+
+size_t fier_workspace_bytes(const fier_config* cfg, int32_t max_budget) {
+  if (check_cfg(cfg) != FIER_OK || max_budget < 1) return 0;
+  if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
+  return carve(cfg, max_budget, nullptr).bytes;
+}
+
+int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  st = check_cache(cache);
+  if (st != FIER_OK) return st;
+  return hip_status(fier::launch_quantize(cfg->kv_dtype, cache->k, cache->kbits, cache->kmeta, cache->seq_lens,
+                                          units_of(cfg), cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
+}
+
+int fier_append_key(const fier_config* cfg, const fier_cache* cache, const void* k_new, const void* v_new,
+                    void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  st = check_cache(cache);
+  if (st != FIER_OK) return st;
+  if (!k_new || !v_new) return FIER_EINVAL;
+  if (misaligned(k_new) || misaligned(v_new)) return FIER_EALIGN;
+  return hip_status(fier::launch_append(cfg->kv_dtype, cache->k, cache->v, cache->kbits, cache->kmeta,
+                                        cache->seq_lens, k_new, v_new, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
+                                        (hipStream_t)stream));
+}
+
+int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, int32_t extra_tokens, float* scores,
+               void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  st = check_cache(cache);
+  if (st != FIER_OK) return st;
+  if (!q || !scores || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
+  if (misaligned(q) || misaligned(scores)) return FIER_EALIGN;
+  return hip_status(fier::launch_score(cfg->kv_dtype, n_rep_of(cfg), cache->kbits, cache->kmeta, q, cache->seq_lens,
+                                       extra_tokens, scores, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
+                                       (hipStream_t)stream));
+}
+
+int fier_topk(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
+              const int32_t* budgets, int32_t max_budget, int32_t* idx, int32_t* count, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  if (!scores || !seq_lens || !budgets || !idx || !count) return FIER_EINVAL;
+  if (extra_tokens < 0 || extra_tokens > 1 || max_budget < 1) return FIER_EINVAL;
+  if (misaligned(scores) || misaligned(idx)) return FIER_EALIGN;
+  return hip_status(fier::launch_topk(scores, seq_lens, extra_tokens, budgets, max_budget, idx, count, units_of(cfg),
+                                      cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
+}
+
+int fier_sparse_attn(const fier_config* cfg, const fier_cache* cache, const void* q, const int32_t* idx,
+                     const int32_t* count, int32_t max_budget, float* out, void* workspace, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  st = check_cache(cache);
+  if (st != FIER_OK) return st;
+  if (!q || !idx || !count || !out || max_budget < 1) return FIER_EINVAL;
+  if (!workspace) return FIER_EWORKSPACE;
+  if (misaligned(q) || misaligned(idx) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
+  if (max_budget > cfg->max_ctx) return FIER_EINVAL;
+  Workspace w = carve(cfg, max_budget, workspace);
+  return hip_status(fier::launch_attn(cfg->kv_dtype, n_rep_of(cfg), cache->k, cache->v, q, idx, count,
+                                      cache->seq_lens, 0, max_budget, fier::kAttnRowsSparse, splits_for(max_budget),
+                                      cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
+                                      cfg->max_ctx, (hipStream_t)stream));
+}
+
+int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void* q, int32_t extra_tokens, float* out,
+                    void* workspace, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  st = check_cache(cache);
+  if (st != FIER_OK) return st;
+  if (!q || !out || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
+  if (!workspace) return FIER_EWORKSPACE;
+  if (misaligned(q) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
+  Workspace w = carve(cfg, cfg->max_ctx, workspace);
+  const int n_splits = (cfg->max_ctx + fier::kAttnRowsDense - 1) / fier::kAttnRowsDense;
+  return hip_status(fier::launch_attn(cfg->kv_dtype, n_rep_of(cfg), cache->k, cache->v, q, nullptr, nullptr,
+                                      cache->seq_lens, extra_tokens, cfg->max_ctx, fier::kAttnRowsDense, n_splits,
+                                      cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
+                                      cfg->max_ctx, (hipStream_t)stream));
+}
+
+int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
+                     const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget, float* out,
+                     int32_t* idx_out, int32_t* count_out, void* workspace, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
+  if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
+  if (max_budget > cfg->max_ctx) return FIER_EINVAL;
+  if (!workspace) return FIER_EWORKSPACE;
+  if (misaligned(q) || misaligned(out) || misaligned(workspace) || misaligned(k_new) || misaligned(v_new) ||
+      misaligned(idx_out))
+    return FIER_EALIGN;
+  for (int l = 0; l < n_layers; ++l) {
+    st = check_cache(&layers[l]);
+    if (st != FIER_OK) return st;
+  }
+  const int units = units_of(cfg), n_rep = n_rep_of(cfg);
+  const int extra = k_new ? 1 : 0;
+  const size_t esz = 2;
+  hipStream_t s = (hipStream_t)stream;
+  Workspace w = carve(cfg, max_budget, workspace);
+  for (int l = 0; l < n_layers; ++l) {
+    const fier_cache* c = &layers[l];
+    const char* ql = static_cast<const char*>(q) + (size_t)l * cfg->batch * cfg->n_q_heads * kD * esz;
+    float* outl = out + (size_t)l * cfg->batch * cfg->n_q_heads * kD;
+    int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : w.idx;
+    int32_t* cntl = count_out ? count_out + (size_t)l * units : w.count;
+    hipError_t e;
+    if (extra) {
+      const char* kn = static_cast<const char*>(k_new) + (size_t)l * units * kD * esz;
+      const char* vn = static_cast<const char*>(v_new) + (size_t)l * units * kD * esz;
+      e = fier::launch_append(cfg->kv_dtype, c->k, c->v, c->kbits, c->kmeta, c->seq_lens, kn, vn, units,
+                              cfg->n_kv_heads, cfg->max_ctx, s);
+      if (e != hipSuccess) return FIER_EHIP;
+    }
+    e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, ql, c->seq_lens, extra, w.scores, units,
+                           cfg->n_kv_heads, cfg->max_ctx, s);
+    if (e != hipSuccess) return FIER_EHIP;
+    e = fier::launch_topk(w.scores, c->seq_lens, extra, budgets, max_budget, idxl, cntl, units, cfg->n_kv_heads,
+                          cfg->max_ctx, s);
+    if (e != hipSuccess) return FIER_EHIP;
+    e = fier::launch_attn(cfg->kv_dtype, n_rep, c->k, c->v, ql, idxl, cntl, c->seq_lens, extra, max_budget,
+                          fier::kAttnRowsSparse, splits_for(max_budget), cfg->sm_scale, w.po, w.pm, w.pl, outl, units,
+                          cfg->n_kv_heads, cfg->max_ctx, s);
+    if (e != hipSuccess) return FIER_EHIP;
+  }
+  return FIER_OK;
+}
+
+void fier_unpack_bits(const fier_config* cfg, const uint32_t* kbits_host, uint8_t* bits_host) {
+  if (check_cfg(cfg) != FIER_OK || !kbits_host || !bits_host) return;
+  const size_t units = (size_t)units_of(cfg);
+  const size_t n_pairs = (size_t)cfg->max_ctx / kPair;
+  for (size_t u = 0; u < units; ++u)
+    for (size_t p = 0; p < n_pairs; ++p)
+      for (int c = 0; c < kD; ++c)
+        for (int h = 0; h < 2; ++h) {
+          const uint32_t w = kbits_host[((u * n_pairs + p) * kD + c) * 2 + h];
+          for (int i = 0; i < 32; ++i) {
+            const size_t t = p * kPair + (size_t)h * 32 + i;
+            bits_host[(u * cfg->max_ctx + t) * kD + c] = (uint8_t)((w >> i) & 1u);
+          }
+        }
+}
+
+void fier_unpack_meta(const fier_config* cfg, const uint32_t* kmeta_host, uint16_t* s_host, uint16_t* z_host) {
+  if (check_cfg(cfg) != FIER_OK || !kmeta_host || !s_host || !z_host) return;
+  const size_t n = (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / kG) * kD;
+  for (size_t i = 0; i < n; ++i) {
+    s_host[i] = (uint16_t)(kmeta_host[i] & 0xffffu);
+    z_host[i] = (uint16_t)(kmeta_host[i] >> 16);
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,266 @@
+// Top-B token selection per unit (Alg. 1 step 3): the B largest scores, ties to the lower index,
+// indices emitted in ascending order.
+//
+// One 1024-thread workgroup per unit; everything except the scores themselves lives in LDS.
+//   1. min / max of the scores.
+//   2. value-space histogram: 2048 equal-width bins between min and max.  (A radix pass over the raw
+//      float bits would put most scores of one magnitude into a handful of bins and serialise the
+//      LDS atomics; equal-width bins spread a bell-shaped score distribution.)
+//   3. the bin holding the B-th largest score is found with a suffix scan; its members are the only
+//      candidates for the threshold, their order-preserving integer keys are gathered into LDS.
+//   4. exact radix select (4 x 8 bits) among the candidates gives the threshold key T and the number
+//      r of tokens equal to T that still fit.
+//   5. one ordered pass writes every index with key > T, and the first r with key == T.
+// All decisions are integer comparisons of keys, so the result is exact and deterministic.
+#include "fier_dev.h"
+#include "fier_kernels.h"
+
+namespace fier {
+
+constexpr int kTkThreads = 1024;
+constexpr int kTkWaves = kTkThreads / 64;
+constexpr int kTkBins = 2048;
+constexpr int kTkCandMax = 8192;
+
+// order-preserving map binary32 -> uint32 (larger score <=> larger key); -0 and +0 share a key
+__device__ __forceinline__ uint32_t score_key(float v) {
+  v += 0.0f;
+  uint32_t u = __float_as_uint(v);
+  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// Exclusive scan of one value per thread over the workgroup (thread order); also returns the total.
+// `tmp` is kTkWaves + 1 words of LDS; contains two barriers.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* tmp, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = wave_incl_scan(v, lane);
+  __syncthreads();  // tmp may still be read by a previous call
+  if (lane == 63) tmp[wave] = incl;
+  __syncthreads();
+  uint32_t wsum = lane < kTkWaves ? tmp[lane] : 0;
+  uint32_t wincl = wave_incl_scan(wsum, lane);
+  uint32_t wave_off = __shfl(wincl, wave, 64) - __shfl(wsum, wave, 64);
+  total = __shfl(wincl, kTkWaves - 1, 64);
+  return wave_off + incl - v;
+}
+
+template <bool IsMax>
+__device__ __forceinline__ float block_minmax(float v, float* tmp) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    float o = __shfl_xor(v, d, 64);
+    v = IsMax ? fmaxf(v, o) : fminf(v, o);
+  }
+  __syncthreads();
+  if (lane == 0) tmp[wave] = v;
+  __syncthreads();
+  float r = tmp[0];
+#pragma unroll
+  for (int w = 1; w < kTkWaves; ++w) r = IsMax ? fmaxf(r, tmp[w]) : fminf(r, tmp[w]);
+  return r;
+}
+
+// Find in hist[0..nb) (counts per bin, ascending value order) the bin b such that
+// (count in bins > b) < want <= (count in bins >= b).  Returns b and the count above it.
+// nb <= 2 * kTkThreads.  Contains barriers; result valid in every thread.
+__device__ __forceinline__ void find_bin_from_top(const uint32_t* hist, int nb, uint32_t want, uint32_t* tmp,
+                                                  int* res, int& bin, uint32_t& above) {
+  const int t = threadIdx.x;
+  // thread t owns the two bins nb-1-2t and nb-2-2t (descending order)
+  const int b0 = nb - 1 - 2 * t, b1 = nb - 2 - 2 * t;
+  const uint32_t c0 = b0 >= 0 ? hist[b0] : 0, c1 = b1 >= 0 ? hist[b1] : 0;
+  uint32_t total;
+  const uint32_t before = block_excl_scan(c0 + c1, tmp, total);
+  if (before < want && want <= before + c0) {
+    res[0] = b0;
+    res[1] = (int)before;
+  } else if (before + c0 < want && want <= before + c0 + c1) {
+    res[0] = b1;
+    res[1] = (int)(before + c0);
+  }
+  __syncthreads();
+  bin = res[0];
+  above = (uint32_t)res[1];
+}
+
+__global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restrict__ scores,
+                                                          const int32_t* __restrict__ seq_lens, int extra,
+                                                          const int32_t* __restrict__ budgets, int max_budget,
+                                                          int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                          int n_kv_heads, int max_ctx) {
+  __shared__ uint32_t hist[kTkBins];
+  __shared__ uint32_t cand[kTkCandMax];
+  __shared__ uint32_t scan_tmp[kTkWaves + 1];
+  __shared__ float red_tmp[kTkWaves];
+  __shared__ int res[2];
+  __shared__ uint32_t n_cand_sh;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int unit = blockIdx.x;
+  const int b = unit / n_kv_heads;
+  int n = seq_lens[b] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  int B = budgets[b];
+  B = B > max_budget ? max_budget : B;
+  B = B > n ? n : B;
+  const float* __restrict__ s = scores + (size_t)unit * max_ctx;
+  int32_t* __restrict__ out = idx + (size_t)unit * max_budget;
+  if (B <= 0) {
+    if (tid == 0) count[unit] = 0;
+    return;
+  }
+  if (tid == 0) count[unit] = B;
+  if (B >= n) {  // the whole context is selected
+    for (int i = tid; i < n; i += kTkThreads) out[i] = i;
+    return;
+  }
+
+  // ---- 1. range of the scores ----------------------------------------------------------------
+  float lo = INFINITY, hi = -INFINITY;
+  for (int i = tid; i < n; i += kTkThreads) {
+    const float v = s[i];
+    lo = fminf(lo, v);
+    hi = fmaxf(hi, v);
+  }
+  lo = block_minmax<false>(lo, red_tmp);
+  hi = block_minmax<true>(hi, red_tmp);
+
+  uint32_t T;      // threshold key
+  uint32_t r_eq;   // how many tokens with key == T are selected (the lowest indices)
+  if (!(hi > lo)) {
+    T = score_key(lo);
+    r_eq = (uint32_t)B;
+  } else {
+    // ---- 2. equal-width histogram ------------------------------------------------------------
+    const float scale = (float)kTkBins / (hi - lo);
+    for (int i = tid; i < kTkBins; i += kTkThreads) hist[i] = 0;
+    if (tid == 0) n_cand_sh = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += kTkThreads) {
+      int bin = (int)((s[i] - lo) * scale);
+      bin = bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
+      atomicAdd(&hist[bin], 1u);
+    }
+    __syncthreads();
+    // ---- 3. threshold bin and its candidates -------------------------------------------------
+    int tbin;
+    uint32_t above;
+    find_bin_from_top(hist, kTkBins, (uint32_t)B, scan_tmp, res, tbin, above);
+    uint32_t r = (uint32_t)B - above;      // rank of the threshold inside the bin, 1-based from the top
+    const uint32_t n_cand = hist[tbin];
+    const bool in_lds = n_cand <= (uint32_t)kTkCandMax;
+    __syncthreads();
+    if (in_lds) {
+      for (int i0 = 0; i0 < n; i0 += kTkThreads) {
+        const int i = i0 + tid;
+        bool is_c = false;
+        uint32_t key = 0;
+        if (i < n) {
+          const float v = s[i];
+          int bin = (int)((v - lo) * scale);
+          bin = bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
+          is_c = bin == tbin;
+          key = score_key(v);
+        }
+        const uint64_t m = __ballot(is_c);
+        if (m) {
+          uint32_t base = 0;
+          if (lane == 0) base = atomicAdd(&n_cand_sh, (uint32_t)__popcll(m));
+          base = __shfl(base, 0, 64);
+          if (is_c) cand[base + __popcll(m & ((1ull << lane) - 1))] = key;
+        }
+      }
+      __syncthreads();
+    }
+    // ---- 4. exact radix select of the r-th largest candidate key -----------------------------
+    uint32_t prefix = 0, mask = 0;
+#pragma unroll 1
+    for (int pass = 3; pass >= 0; --pass) {
+      const int shift = 8 * pass;
+      for (int i = tid; i < 256; i += kTkThreads) hist[i] = 0;
+      __syncthreads();
+      if (in_lds) {
+        for (uint32_t i = tid; i < n_cand; i += kTkThreads) {
+          const uint32_t key = cand[i];
+          if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+      } else {  // more candidates than LDS holds (heavily clustered scores): stream them from memory
+        for (int i = tid; i < n; i += kTkThreads) {
+          const float v = s[i];
+          int bin = (int)((v - lo) * scale);
+          bin = bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
+          const uint32_t key = score_key(v);
+          if (bin == tbin && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+      }
+      __syncthreads();
+      int dbin;
+      uint32_t dabove;
+      find_bin_from_top(hist, 256, r, scan_tmp, res, dbin, dabove);
+      r -= dabove;
+      prefix |= (uint32_t)dbin << shift;
+      mask |= 0xffu << shift;
+      __syncthreads();
+    }
+    T = prefix;
+    r_eq = r;
+  }
+
+  // ---- 5. ordered emission ---------------------------------------------------------------------
+  uint32_t run_gt = 0, run_eq = 0;  // counts over all earlier tokens (uniform across the workgroup)
+  for (int i0 = 0; i0 < n; i0 += 4 * kTkThreads) {
+    const int i = i0 + 4 * tid;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i + 3 < n) {
+      v = *reinterpret_cast<const float4*>(s + i);
+    } else {
+      if (i < n) v.x = s[i];
+      if (i + 1 < n) v.y = s[i + 1];
+      if (i + 2 < n) v.z = s[i + 2];
+    }
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    uint32_t gt[4], eq[4], cg = 0, ce = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t key = score_key(vv[j]);
+      const bool ok = i + j < n;
+      gt[j] = ok && key > T;
+      eq[j] = ok && key == T;
+      cg += gt[j];
+      ce += eq[j];
+    }
+    uint32_t total;
+    const uint32_t ex = block_excl_scan(cg | (ce << 16), scan_tmp, total);
+    uint32_t g_before = run_gt + (ex & 0xffffu);
+    uint32_t e_before = run_eq + (ex >> 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (gt[j] || (eq[j] && e_before < r_eq)) out[g_before + (e_before < r_eq ? e_before : r_eq)] = i + j;
+      g_before += gt[j];
+      e_before += eq[j];
+    }
+    run_gt += total & 0xffffu;
+    run_eq += total >> 16;
+  }
+}
+
+hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
+                       int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,
+                       hipStream_t st) {
+  topk_kernel<<<units, kTkThreads, 0, st>>>(scores, seq_lens, extra, budgets, max_budget, idx, count, n_kv_heads,
+                                            max_ctx);
+  return hipGetLastError();
+}
+
+}  // namespace fier

@@ -1,0 +1,110 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, validates arguments on the
+host before launching anything, and its packed layout has the size Eq. 8 says (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2508_08256_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "fier.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(fier_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
+    lib = B.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    assert B.status_string(0) == "ok"
+    for st in (-1, -2, -3, -4, -5, -6):
+        assert B.status_string(st) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_config_validation():
+    ok = B.make_config(2, 32, 8, 4096, B.BF16)
+    assert B.check_config(ok) == B.OK
+    assert B.check_config(B.make_config(2, 32, 8, 4096, head_dim=64)) == B.EUNSUPPORTED
+    assert B.check_config(B.make_config(2, 32, 8, 4096, group_size=128)) == B.EUNSUPPORTED
+    assert B.check_config(B.make_config(2, 30, 8, 4096)) == B.ESHAPE
+    assert B.check_config(B.make_config(2, 72, 8, 4096)) == B.EUNSUPPORTED      # n_rep = 9
+    assert B.check_config(B.make_config(2, 32, 8, 4100)) == B.ESHAPE            # not a multiple of 64
+    assert B.check_config(B.make_config(0, 32, 8, 4096)) == B.EINVAL
+    assert B.check_config(B.make_config(2, 32, 8, 4096, kv_dtype=7)) == B.EINVAL
+    assert B.packed_bits_bytes(B.make_config(2, 30, 8, 4096)) == 0
+    assert B.workspace_bytes(ok, 0) == 0 and B.workspace_bytes(ok, 512) > 0
+
+
+def test_packed_size_is_one_eighth_of_the_key_cache():
+    """Eq. 8 at g = 32: (1 + 32/g)/16 = 0.125 of a 16-bit key cache; Tab. 4 prints 0.125 for Fier-g32."""
+    cfg = B.make_config(4, 32, 8, 131072, B.BF16)
+    key_bytes = cfg.units * cfg.max_ctx * cfg.head_dim * 2
+    packed = B.packed_bits_bytes(cfg) + B.packed_meta_bytes(cfg)
+    assert packed / key_bytes == 0.125
+    assert B.packed_bits_bytes(cfg) == key_bytes // 16 and B.packed_meta_bytes(cfg) == key_bytes // 16
+    assert packed == 32 * cfg.units * cfg.max_ctx
+
+
+def test_calls_reject_bad_arguments_before_any_launch():
+    lib = B.lib()
+    cfg = B.make_config(1, 8, 8, 256)
+    cache = B.Cache(0, 0, 0, 0, 0)
+    assert lib.fier_quantize_keys(C.byref(cfg), C.byref(cache), None) == B.EINVAL
+    assert lib.fier_quantize_keys(None, C.byref(cache), None) == B.EINVAL
+    cache = B.Cache(0x1000, 0x2008, 0x3000, 0x4000, 0x5000)
+    assert lib.fier_quantize_keys(C.byref(cfg), C.byref(cache), None) == B.EALIGN
+    good = B.Cache(0x1000, 0x2000, 0x3000, 0x4000, 0x5000)
+    assert lib.fier_append_key(C.byref(cfg), C.byref(good), None, None, None) == B.EINVAL
+    assert lib.fier_score(C.byref(cfg), C.byref(good), 0x6000, 2, 0x7000, None) == B.EINVAL
+    assert lib.fier_score(C.byref(cfg), C.byref(good), 0x6004, 0, 0x7000, None) == B.EALIGN
+    assert lib.fier_topk(C.byref(cfg), 0x6000, 0x5000, 0, 0x5100, 0, 0x7000, 0x8000, None) == B.EINVAL
+    assert lib.fier_sparse_attn(C.byref(cfg), C.byref(good), 0x6000, 0x7000, 0x8000, 16, 0x9000, None,
+                                None) == B.EWORKSPACE
+    assert lib.fier_sparse_attn(C.byref(cfg), C.byref(good), 0x6000, 0x7000, 0x8000, 512, 0x9000, 0xA000,
+                                None) == B.EINVAL                                 # budget above capacity
+    assert lib.fier_dense_attn(C.byref(cfg), C.byref(good), 0x6000, 0, 0x9000, None, None) == B.EWORKSPACE
+    arr = (B.Cache * 1)(good)
+    assert lib.fier_decode_step(C.byref(cfg), arr, 1, 0x6000, 0x7000, None, 0x5100, 16, 0x9000, None, None,
+                                0xA000, None) == B.EINVAL                         # k_new without v_new
+    assert lib.fier_decode_step(C.byref(cfg), arr, 0, 0x6000, None, None, 0x5100, 16, 0x9000, None, None,
+                                0xA000, None) == B.EINVAL
+    bad = B.make_config(1, 8, 8, 256, head_dim=96)
+    assert lib.fier_quantize_keys(C.byref(bad), C.byref(good), None) == B.EUNSUPPORTED
+
+
+def test_unpack_helpers_follow_the_documented_layout():
+    """word (P, c, h) bit i <-> token 64 P + 32 h + i, channel c;  meta word = s | z << 16."""
+    cfg = B.make_config(1, 2, 2, 128)
+    lib = B.lib()
+    rng = np.random.default_rng(0)
+    bits = rng.integers(0, 2, (cfg.units, cfg.max_ctx, 128)).astype(np.uint8)
+    packed = np.zeros((cfg.units, cfg.max_ctx // 64, 128, 2), np.uint32)
+    for u in range(cfg.units):
+        for t in range(cfg.max_ctx):
+            P, h, i = t // 64, (t % 64) // 32, t % 32
+            packed[u, P, :, h] |= bits[u, t].astype(np.uint32) << np.uint32(i)
+    got = np.zeros_like(bits)
+    lib.fier_unpack_bits(C.byref(cfg), packed.ctypes.data_as(C.c_void_p), got.ctypes.data_as(C.c_void_p))
+    assert np.array_equal(got, bits)
+    s = rng.integers(0, 65536, (cfg.units, cfg.max_ctx // 32, 128)).astype(np.uint16)
+    z = rng.integers(0, 65536, s.shape).astype(np.uint16)
+    meta = s.astype(np.uint32) | (z.astype(np.uint32) << np.uint32(16))
+    s2, z2 = np.zeros_like(s), np.zeros_like(z)
+    lib.fier_unpack_meta(C.byref(cfg), meta.ctypes.data_as(C.c_void_p), s2.ctypes.data_as(C.c_void_p),
+                         z2.ctypes.data_as(C.c_void_p))
+    assert np.array_equal(s2, s) and np.array_equal(z2, z)
+
+
+def test_no_cpu_fallback_when_library_missing(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libfier.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()

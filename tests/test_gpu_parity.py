@@ -1,0 +1,307 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element, on the same seeded inputs.
+
+Bars: packed bits, (s, z), counts and (given identical scores) index sets are bit-exact; approximate scores
+within 1e-3 relative (or 1e-5 of the sum of absolute terms where the sum cancels); index sets from the GPU's
+own binary32 scores equal the oracle's except near-ties within 1e-3 relative of the threshold score; attention
+within 2e-3 max-abs of the fp64 oracle."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from helpers import check_index_sets, oracle_step, score_tolerance_ok  # noqa: E402
+from paper_2508_08256_amd import binding as B  # noqa: E402
+from paper_2508_08256_amd import synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+F16, BF16 = 0, 1
+G = 32
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def _workloads():
+    return [
+        ("ragged_f16", lambda: synth.small_ragged(7, F16, 1)),
+        ("ragged_bf16_gqa", lambda: synth.small_ragged(8, BF16, 4)),
+        ("config1", lambda: synth.config1()),
+        ("edge_lens", lambda: synth.make_workload("edge", 11, 8, 16, 8, [0, 1, 31, 32, 33, 64, 65, 191],
+                                                  [1, 1, 5, 32, 40, 7, 65, 20], F16, max_ctx=192, n_planted=1,
+                                                  plant=False)),
+    ]
+
+
+@pytest.fixture(scope="module", params=_workloads(), ids=lambda p: p[0])
+def case(request, gu, oracle):
+    name, make = request.param
+    wl = make()
+    print(f"[case] {name} units={wl.units} max_ctx={wl.max_ctx}", flush=True)
+    return wl, gu.DeviceWorkload(wl)
+
+
+def _compare_packed(dw, L, bits_o, s_o, z_o):
+    bits, s, z = dw.cache.unpack()
+    for u in range(dw.wl.units):
+        n = int(L[u])
+        ng = -(-n // G)
+        npair_tok = -(-n // 64) * 64
+        assert np.array_equal(bits[u, :n], bits_o[u, :n]), f"bits differ in unit {u}"
+        assert np.all(bits[u, n:npair_tok] == 0), f"bits of absent tokens set in unit {u}"
+        assert np.array_equal(s[u, :ng], s_o[u, :ng]), f"s differs in unit {u}"
+        assert np.array_equal(z[u, :ng], z_o[u, :ng]), f"z differs in unit {u}"
+
+
+def test_quantize_keys_bit_exact(case, oracle):
+    wl, dw = case
+    B.quantize_keys(dw.cfg, dw.cache)
+    torch.cuda.synchronize()
+    L = wl.unit_lens
+    bits_o, s_o, z_o = oracle.quantize(wl.K, L, G, wl.dtype, 4)
+    _compare_packed(dw, L, bits_o, s_o, z_o)
+
+
+def test_quantize_special_values(gu, oracle):
+    """Signed zeros, constant groups, exact midpoints, large magnitudes: still bit-exact."""
+    rng = np.random.default_rng(5)
+    U, L, D = 2, 128, 128
+    for dtype in (F16, BF16):
+        x = rng.standard_normal((U, L, D)).astype(np.float32)
+        x[0, :32, 0:8] = -0.0
+        x[0, :32, 8:16] = 3.25
+        x[0, 32:64, :] = np.where(rng.integers(0, 2, (32, D)) == 1, -0.0, 0.0)
+        x[0, 64:96, 0:32] = rng.integers(-4, 5, (32, 32))           # many exact midpoints
+        x[1, :64, :] *= 20000.0 if dtype == F16 else 1e30          # ranges near the top of the format
+        x[1, 64:, :] *= 1e-6                                        # subnormal binary16 inputs
+        wl = synth.make_workload("special", 1, 1, 2, 2, [L], [8], dtype, max_ctx=L, plant=False)
+        wl.K[:] = synth.f32_to_words(x, dtype)
+        dw = gu.DeviceWorkload(wl)
+        B.quantize_keys(dw.cfg, dw.cache)
+        torch.cuda.synchronize()
+        bits_o, s_o, z_o = oracle.quantize(wl.K, wl.unit_lens, G, dtype)
+        _compare_packed(dw, wl.unit_lens, bits_o, s_o, z_o)
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_append_equals_bulk_quantize(gu, oracle, dtype):
+    """After every append the packed state equals the oracle's (and so a bulk quantize of the prefix)."""
+    wl = synth.make_workload("app", 21 + dtype, 2, 4, 2, [29, 64], [8, 8], dtype, max_ctx=192, plant=False)
+    full = synth.make_workload("app_src", 22 + dtype, 2, 4, 2, [192, 192], [8, 8], dtype, max_ctx=192, plant=False)
+    dw = gu.DeviceWorkload(wl)
+    B.quantize_keys(dw.cfg, dw.cache)
+    K, V = wl.K.copy(), wl.V.copy()
+    L = wl.unit_lens.copy()
+    bits_o, s_o, z_o = oracle.quantize(K, L, G, dtype)
+    lens = wl.seq_lens.copy()
+    for step in range(70):
+        k_new = np.stack([full.K[u, L[u]] for u in range(wl.units)])
+        v_new = np.stack([full.V[u, L[u]] for u in range(wl.units)])
+        B.append_key(dw.cfg, dw.cache, gu.to_dev(k_new, dtype), gu.to_dev(v_new, dtype))
+        oracle.append(K, V, L, k_new, v_new, bits_o, s_o, z_o, G, dtype)
+        L = (L + 1).astype(np.int32)
+        lens = (lens + 1).astype(np.int32)
+        dw.seq_lens.copy_(gu.i32(lens))
+        if step % 7 == 0 or step > 60:
+            torch.cuda.synchronize()
+            _compare_packed(dw, L, bits_o, s_o, z_o)
+            assert np.array_equal(gu.words_of(dw.K), K) and np.array_equal(gu.words_of(dw.V), V)
+    # a full cache is left unchanged
+    dw.seq_lens.copy_(gu.i32(np.full(2, 192)))
+    before = dw.cache.kbits.clone()
+    B.append_key(dw.cfg, dw.cache, gu.to_dev(k_new, dtype), gu.to_dev(v_new, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(before, dw.cache.kbits) and np.array_equal(gu.words_of(dw.K), K)
+
+
+def _abs_terms(oracle, wl, bits, s, z, L):
+    Kt = np.abs(oracle.dequantize(bits, s, z, L, G, wl.dtype))
+    qa = np.abs(synth.words_to_f32(wl.q, wl.dtype).astype(np.float64)).sum(axis=1)     # [U][D]
+    return np.einsum("utd,ud->ut", Kt, qa)
+
+
+def test_score_within_tolerance(case, oracle, gu):
+    wl, dw = case
+    B.quantize_keys(dw.cfg, dw.cache)
+    scores = torch.full((wl.units, wl.max_ctx), float("nan"), dtype=torch.float32, device="cuda")
+    B.score(dw.cfg, dw.cache, dw.q, 0, scores)
+    torch.cuda.synchronize()
+    L = wl.unit_lens
+    bits, s, z = oracle.quantize(wl.K, L, G, wl.dtype, 4)
+    want = oracle.score(bits, s, z, wl.q, L, G, wl.dtype, 4)
+    absterm = _abs_terms(oracle, wl, bits, s, z, L)
+    got = scores.cpu().numpy()
+    for u in range(wl.units):
+        n = int(L[u])
+        ok = score_tolerance_ok(got[u, :n], want[u, :n], absterm[u, :n])
+        assert np.all(ok), (u, np.flatnonzero(~ok)[:5], got[u, :n][~ok][:5], want[u, :n][~ok][:5])
+        assert np.all(np.isnan(got[u, n:])), "entries past the scored length must not be written"
+
+
+def _run_topk(gu, cfg, scores_np, lens, budgets, max_budget, extra=0):
+    sc = torch.from_numpy(scores_np.astype(np.float32)).cuda()
+    idx = torch.full((cfg.units, max_budget), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((cfg.units,), -7, dtype=torch.int32, device="cuda")
+    B.topk(cfg, sc, gu.i32(lens), extra, gu.i32(budgets), max_budget, idx, cnt)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), cnt.cpu().numpy()
+
+
+@pytest.mark.parametrize("kind", ["gauss", "equal", "ties", "two_values", "clustered", "signed_zero", "tiny_range"])
+def test_topk_exact_on_identical_scores(gu, oracle, kind):
+    """Same binary32 scores on both sides: the selected sets must be identical, ties to the lower index."""
+    rng = np.random.default_rng(hash(kind) % 1000)
+    batch, H, Lcap = 3, 2, 40960
+    lens = np.array([40960, 12345, 70], np.int32)
+    budgets = np.array([4505, 1, 69], np.int32)
+    cfg = B.make_config(batch, H, H, Lcap)
+    sc = rng.standard_normal((cfg.units, Lcap)).astype(np.float32) * 50
+    if kind == "equal":
+        sc[:] = 1.5
+    elif kind == "ties":
+        sc = np.round(sc / 8).astype(np.float32)          # ~40 distinct values: massive ties at the threshold
+    elif kind == "two_values":
+        sc = np.where(sc > 40, 2.0, -1.0).astype(np.float32)
+    elif kind == "clustered":                              # > 8192 candidates fall into the threshold bin
+        sc = (100.0 + rng.standard_normal((cfg.units, Lcap)) * 1e-4).astype(np.float32)
+        sc[:, ::97] = -1e6
+        sc[:, 5::1013] = 1e6
+    elif kind == "signed_zero":
+        sc = np.where(rng.integers(0, 2, sc.shape) == 1, -0.0, 0.0).astype(np.float32)
+        sc[:, ::11] = -3.0
+    elif kind == "tiny_range":
+        sc = (1.0 + rng.integers(0, 3, sc.shape) * 2.0 ** -23).astype(np.float32)
+    max_budget = 4608
+    idx, cnt = _run_topk(gu, cfg, sc, lens, budgets, max_budget)
+    ul = np.repeat(lens, H)
+    ub = np.repeat(budgets, H)
+    idx_o, cnt_o = oracle.topk(sc.astype(np.float64), ul, ub, max_budget)
+    assert np.array_equal(cnt, cnt_o)
+    for u in range(cfg.units):
+        assert np.array_equal(idx[u, :cnt[u]], idx_o[u, :cnt[u]]), (kind, u)
+        assert np.all(idx[u, cnt[u]:] == -7), "entries past count must not be written"
+
+
+def test_topk_budget_edges(gu, oracle):
+    rng = np.random.default_rng(3)
+    cfg = B.make_config(6, 1, 1, 1024)
+    lens = np.array([1000, 1000, 1000, 0, 1, 1024], np.int32)
+    budgets = np.array([1, 999, 5000, 10, 1, 0], np.int32)
+    sc = rng.standard_normal((6, 1024)).astype(np.float32)
+    idx, cnt = _run_topk(gu, cfg, sc, lens, budgets, 1024)
+    idx_o, cnt_o = oracle.topk(sc.astype(np.float64), lens, budgets, 1024)
+    assert np.array_equal(cnt, cnt_o) and list(cnt) == [1, 999, 1000, 0, 1, 0]
+    for u in range(6):
+        assert np.array_equal(idx[u, :cnt[u]], idx_o[u, :cnt[u]])
+    # an appended row competes like any other (extra_tokens = 1), and max_budget clamps the budget
+    idx, cnt = _run_topk(gu, cfg, sc, np.array([999, 5, 0, 0, 0, 1023], np.int32), np.full(6, 64, np.int32), 32, 1)
+    idx_o, cnt_o = oracle.topk(sc.astype(np.float64), np.array([1000, 6, 1, 1, 1, 1024], np.int32),
+                               np.full(6, 32, np.int32), 32)
+    assert np.array_equal(cnt, cnt_o)
+    for u in range(6):
+        assert np.array_equal(idx[u, :cnt[u]], idx_o[u, :cnt[u]])
+
+
+def test_sparse_attn_on_oracle_selection(case, oracle, gu):
+    wl, dw = case
+    r = oracle_step(oracle, wl, append=False)
+    mb = r["max_budget"]
+    idx = gu.i32(np.where(r["idx"] < 0, 0, r["idx"]))
+    cnt = gu.i32(r["count"])
+    out = torch.full((wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
+    B.sparse_attn(dw.cfg, dw.cache, dw.q, idx, cnt, mb, out, dw.workspace(mb))
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy() - r["out"]).max()
+    assert err <= 2e-3, err
+
+
+def test_full_budget_equals_dense(case, oracle, gu):
+    """Selection = every token: step 4 equals the dense decode attention, on the GPU and in the oracle."""
+    wl, dw = case
+    L = wl.unit_lens
+    mb = wl.max_ctx
+    idx_np = np.tile(np.arange(mb, dtype=np.int32), (wl.units, 1))
+    out_s = torch.zeros((wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+    out_d = torch.full_like(out_s, float("nan"))
+    ws = dw.workspace(mb)
+    B.sparse_attn(dw.cfg, dw.cache, dw.q, gu.i32(idx_np), gu.i32(L), mb, out_s, ws)
+    B.dense_attn(dw.cfg, dw.cache, dw.q, 0, out_d, ws)
+    torch.cuda.synchronize()
+    want = oracle.attention(wl.K, wl.V, wl.q, L, 1 / np.sqrt(128), wl.dtype, None, None, 4)
+    assert np.abs(out_s.cpu().numpy() - want).max() <= 2e-3
+    assert np.abs(out_d.cpu().numpy() - want).max() <= 2e-3
+
+
+def test_sparse_attn_degenerate_selections(gu, oracle):
+    wl = synth.make_workload("deg", 31, 1, 8, 2, [500], [16], BF16, max_ctx=512, n_planted=2)
+    dw = gu.DeviceWorkload(wl)
+    idx = np.zeros((2, 16), np.int32)
+    idx[0, 0] = 499                      # a single row: the output is that value row
+    idx[1, :3] = [7, 7, 300]             # repeated and unordered entries are weighted as listed
+    cnt = np.array([1, 3], np.int32)
+    out = torch.zeros((2, 4, 128), dtype=torch.float32, device="cuda")
+    B.sparse_attn(dw.cfg, dw.cache, dw.q, gu.i32(idx), gu.i32(cnt), 16, out, dw.workspace(16))
+    torch.cuda.synchronize()
+    want = oracle.attention(wl.K, wl.V, wl.q, wl.unit_lens, 1 / np.sqrt(128), BF16, idx, cnt)
+    got = out.cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-3
+    assert np.array_equal(got[0, 0], synth.words_to_f32(wl.V[0, 499], BF16))
+    cnt0 = np.zeros(2, np.int32)         # nothing selected: zeros
+    out.fill_(5.0)
+    B.sparse_attn(dw.cfg, dw.cache, dw.q, gu.i32(idx), gu.i32(cnt0), 16, out, dw.workspace(16))
+    torch.cuda.synchronize()
+    assert torch.all(out == 0)
+
+
+@pytest.mark.parametrize("append", [False, True])
+def test_fused_decode_step(case, oracle, gu, append):
+    wl, dw = case
+    import gpu_util
+
+    dw = gpu_util.DeviceWorkload(wl)      # fresh buffers: the step appends in place
+    B.quantize_keys(dw.cfg, dw.cache)
+    r = oracle_step(oracle, wl, append=append)
+    mb = r["max_budget"]
+    out = torch.full((1, wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1, wl.units), -1, dtype=torch.int32, device="cuda")
+    kn = dw.k_new[None].contiguous() if append else None
+    vn = dw.v_new[None].contiguous() if append else None
+    B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt,
+                  dw.workspace(mb))
+    torch.cuda.synchronize()
+    idx_g, cnt_g = idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
+    swapped = check_index_sets(idx_g, cnt_g, r["idx"], r["count"], r["scores"], r["L"])
+    # the attention is compared on the GPU's own selection, now that it has passed the index rule
+    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                            np.ascontiguousarray(np.where(idx_g < 0, 0, idx_g)), cnt_g, 4)
+    err = np.abs(out.cpu().numpy()[0] - want).max()
+    assert err <= 2e-3, err
+    if append:
+        _compare_packed(dw, r["L"], r["bits"], r["s"], r["z"])
+    print(f"[fused] swapped near-ties: {swapped}, attention max err {err:.2e}", flush=True)
+    for u in range(wl.units):
+        sel = set(idx_g[u, :cnt_g[u]].tolist())
+        if cnt_g[u] >= 4 * len(wl.planted[u]) and len(wl.planted[u]):
+            assert set(wl.planted[u].tolist()) <= sel
+
+
+def test_results_are_deterministic(gu):
+    wl = synth.config1()
+    dw = gu.DeviceWorkload(wl)
+    B.quantize_keys(dw.cfg, dw.cache)
+    outs = []
+    for _ in range(3):
+        out = torch.zeros((1, wl.units, 1, 128), dtype=torch.float32, device="cuda")
+        idx = torch.zeros((1, wl.units, 512), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+        B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), None, None, dw.budgets, 512, out, idx, cnt,
+                      dw.workspace(512))
+        torch.cuda.synchronize()
+        outs.append((out.clone(), idx.clone(), dw.cache.kbits.clone()))
+    for o, i, kb in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(i, outs[0][1]) and torch.equal(kb, outs[0][2])
