@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the Fier decode hot path on one MI355X.
+
+A "step" is one whole per-layer decode step of Alg. 1 with the append of Sec. 3.1 -- append one key/value
+row, score every cached token from the 1-bit keys, select the top-B tokens per kv head, attend over the
+selected rows -- issued as ONE call of ``fier_decode_step`` on one layer's cache.  Successive steps rotate
+over R distinct layer caches (R x touched bytes >= 1 GB) so that the 256 MB Infinity Cache cannot hold the
+working set; all inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line (see the design doc for the byte model).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+WORKLOADS = {
+    # LLaMA-7B-shaped decode layer (the configuration the headline metric is quoted on)
+    "config2": dict(batch=1, n_q_heads=32, n_kv_heads=32, L=32768, budget=3604, dtype=0, chan="ones",
+                    n_planted=64, rotate=12, label="llama7b_mha32_ctx32768_budget3604_fp16_append1"),
+    # Llama-3-8B-shaped GQA layer, batch 4, 128k context
+    "config3": dict(batch=4, n_q_heads=32, n_kv_heads=8, L=131072, budget=4096, dtype=1, chan="lognormal",
+                    n_planted=64, rotate=5, label="llama3_8b_gqa32x8_b4_ctx131072_budget4096_bf16_append1"),
+    "config1": dict(batch=1, n_q_heads=8, n_kv_heads=8, L=4096, budget=512, dtype=0, chan="ones",
+                    n_planted=16, rotate=4, label="small_mha8_ctx4096_budget512_fp16_append1"),
+}
+
+
+def algorithmic_bytes(w):
+    """Bytes the method has to move per layer step: packed keys + (s, z) metadata (32 B per cached token and
+    unit), the selected K and V rows (512 B per selected token and unit), query in and fp32 output out."""
+    units = w["batch"] * w["n_kv_heads"]
+    heads = w["batch"] * w["n_q_heads"]
+    n_tok = w["L"] + 1
+    packed = units * n_tok * 32
+    kv = units * min(w["budget"], n_tok) * 512
+    qo = heads * (256 + 512)
+    return dict(packed=packed, selected_kv=kv, q_out=qo, total=packed + kv + qo)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=600)
+    ap.add_argument("--warmup", type=int, default=60)
+    ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage-steps", type=int, default=240, help="launches per stage for the per-stage timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2508_08256_amd import binding as B
+    from paper_2508_08256_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    B.lib()  # fail loudly if the HIP library is missing
+    w = WORKLOADS[args.workload]
+    R = w["rotate"]
+    batch, Hq, Hkv, L, budget, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["L"], w["budget"], w["dtype"]
+    max_ctx = -(-(L + 1) // 64) * 64
+    cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype)
+    units, n_rep = cfg.units, cfg.n_rep
+    tdt = torch.float16 if dtype == 0 else torch.bfloat16
+
+    # ---- resident inputs: R layer caches, quantized once (prefill), fresh q / k_new / v_new per cache ------
+    t0 = time.time()
+    caches, qs, kns, vns, hosts = [], [], [], [], None
+    seq_lens = torch.full((batch,), L, dtype=torch.int32, device="cuda")
+    budgets = torch.full((batch,), budget, dtype=torch.int32, device="cuda")
+    for r in range(R):
+        d = synth.make_workload_device(f"{args.workload}_cache{r}", 1000 * 2 + r, batch, Hq, Hkv, [L] * batch,
+                                       [budget] * batch, dtype, max_ctx=max_ctx, chan=w["chan"],
+                                       n_planted=w["n_planted"])
+        c = B.DeviceCache(cfg, d["K"], d["V"], seq_lens)
+        B.quantize_keys(cfg, c)
+        caches.append(c)
+        qs.append(d["q"].reshape(1, batch, Hq, 128).contiguous())
+        kns.append(d["k_new"].reshape(1, units, 128).contiguous())
+        vns.append(d["v_new"].reshape(1, units, 128).contiguous())
+        if r == 0:
+            hosts = d
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    ws = torch.empty(max(B.workspace_bytes(cfg, budget), B.workspace_bytes(cfg, max_ctx)), dtype=torch.uint8,
+                     device="cuda")
+    out = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((1, units, budget), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1, units), dtype=torch.int32, device="cuda")
+    scores = torch.zeros((units, max_ctx), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        r = i % R
+        B.decode_step(cfg, [caches[r]], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, ws)
+
+    def timed(fn, n, warm):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_wall = time.perf_counter()
+        e0.record()
+        for i in range(n):
+            fn(warm + i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3, (time.perf_counter() - t_wall) / n * 1e6   # us (events), us (wall)
+
+    # ---- the timed region: K whole steps ----------------------------------------------------------------
+    us_step, us_wall = timed(step, args.steps, args.warmup)
+
+    # ---- per-stage timing, each entry point launched alone (events on the launch stream) ----------------
+    ns = args.stage_steps
+    step(0)
+    torch.cuda.synchronize()
+
+    def st_append(i):
+        r = i % R
+        B.append_key(cfg, caches[r], kns[r], vns[r])
+
+    def st_score(i):
+        r = i % R
+        B.score(cfg, caches[r], qs[r], 1, scores)
+
+    def st_topk(i):
+        B.topk(cfg, scores, seq_lens, 1, budgets, budget, idx, cnt)
+
+    def st_attn(i):
+        r = i % R
+        B.sparse_attn(cfg, caches[r], qs[r], idx, cnt, budget, out, ws)
+
+    def st_dense(i):
+        r = i % R
+        B.dense_attn(cfg, caches[r], qs[r], 1, out, ws)
+
+    us_append, _ = timed(st_append, ns, 10)
+    us_score, _ = timed(st_score, ns, 10)
+    us_topk, _ = timed(st_topk, ns, 10)
+    us_attn, _ = timed(st_attn, ns, 10)
+    us_dense, _ = timed(st_dense, max(24, ns // 10), 4)
+
+    ab = algorithmic_bytes(w)
+    achieved = ab["total"] / (us_step * 1e-6) / 1e9
+    # dominant kernel by algorithmic bytes: the gather attention (selected K/V rows + q + out)
+    attn_bytes = ab["selected_kv"] + ab["q_out"]
+    attn_gbps = attn_bytes / (us_attn * 1e-6) / 1e9
+    score_gbps = ab["packed"] / (us_score * 1e-6) / 1e9
+    dense_bytes = units * (L + 1) * 512 + ab["q_out"]
+
+    res = {
+        "metric": "per-layer decode-step latency (us) + achieved HBM GB/s vs peak",
+        "value": round(us_step, 3),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(us_step / 1e3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16" if dtype == 0 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w["label"], "batch": batch, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128,
+                   "context": L, "budget": budget, "group_size": 32, "rotating_caches": R,
+                   "algorithmic_bytes_per_step": ab["total"]},
+        "achieved_GBps": round(achieved, 1),
+        "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "us_per_step_wall": round(us_wall, 3),
+        "stages_us": {"append": round(us_append, 3), "score": round(us_score, 3), "topk": round(us_topk, 3),
+                      "sparse_attn": round(us_attn, 3), "sum": round(us_append + us_score + us_topk + us_attn, 3)},
+        "stage_GBps": {"score": round(score_gbps, 1), "sparse_attn": round(attn_gbps, 1)},
+        "dense_attn_us": round(us_dense, 3),
+        "dense_attn_GBps": round(dense_bytes / (us_dense * 1e-6) / 1e9, 1),
+        "speedup_vs_dense_attn": round(us_dense / us_step, 3),
+        "roofline": {"bound": "hbm", "kernel": "fier_sparse_attn (attn_split_kernel + attn_merge_kernel)",
+                     "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": attn_bytes, "us_per_launch": round(us_attn, 3)},
+        "setup_s": round(t_setup, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(hosts, w, max_ctx)
+    print(json.dumps(res), flush=True)
+
+
+def cpu_baseline(d, w, max_ctx):
+    """The CPU oracle, as it stands, timed on this machine's host cores on the same kind of layer step."""
+    import oracle
+    from paper_2508_08256_amd import synth
+
+    oracle.build()
+    threads = oracle.max_threads()
+    units = w["batch"] * w["n_kv_heads"]
+    n_rep = w["n_q_heads"] // w["n_kv_heads"]
+    # bounded sample: at most 32 units of cache 0 (all of config 2; the first 32 units of larger ones)
+    su = min(units, 32)
+    K = synth.words_of(d["K"][:su])
+    V = synth.words_of(d["V"][:su])
+    q = synth.words_of(d["q"][:su]).reshape(su, n_rep, 128)
+    kn = synth.words_of(d["k_new"][:su])
+    vn = synth.words_of(d["v_new"][:su])
+    L = np.full(su, w["L"], np.int32)
+    bud = np.full(su, w["budget"], np.int32)
+    bits, s, z = oracle.quantize(K, L, 32, w["dtype"], threads)        # prefill, not timed
+    reps, t_total = 0, 0.0
+    while reps < 3 or (t_total < 10.0 and reps < 20):
+        t0 = time.perf_counter()
+        oracle.append(K, V, L, kn, vn, bits, s, z, 32, w["dtype"])
+        L1 = (L + 1).astype(np.int32)
+        sc = oracle.score(bits, s, z, q, L1, 32, w["dtype"], threads)
+        idx, cnt = oracle.topk(sc, L1, bud, w["budget"])
+        oracle.attention(K, V, q, L1, 1.0 / np.sqrt(128.0), w["dtype"], idx, cnt, threads)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    us = t_total / reps * 1e6 * (units / su)
+    return {"value": round(us, 1), "unit": "us per layer step", "cores": threads, "kind": "oracle",
+            "sample": f"{reps} repetitions of the layer step on {su} of {units} units of cache 0"
+                      f"{' (scaled to all units)' if su != units else ''}, OpenMP over units"}
+
+
+if __name__ == "__main__":
+    main()
