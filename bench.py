@@ -96,8 +96,8 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
-    ws = torch.empty(max(B.workspace_bytes(cfg, budget), B.workspace_bytes(cfg, max_ctx)), dtype=torch.uint8,
-                     device="cuda")
+    ws = B.make_workspace(cfg, budget)
+    ws_dense = B.make_workspace(cfg, max_ctx)
     out = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
     idx = torch.zeros((1, units, budget), dtype=torch.int32, device="cuda")
     cnt = torch.zeros((1, units), dtype=torch.int32, device="cuda")
@@ -145,7 +145,7 @@ def main():
 
     def st_dense(i):
         r = i % R
-        B.dense_attn(cfg, caches[r], qs[r], 1, out, ws)
+        B.dense_attn(cfg, caches[r], qs[r], 1, out, ws_dense)
 
     us_append, _ = timed(st_append, ns, 10)
     us_score, _ = timed(st_score, ns, 10)

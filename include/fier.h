@@ -25,15 +25,23 @@
  *
  * Data layout in device memory (D = head_dim = 128, g = group_size = 32)
  *   k, v     [batch][n_kv_heads][max_ctx][D]     16-bit floats (binary16 or bfloat16)
- *   kbits    [units][max_ctx / 64][D][2] uint32  "pair block" = 64 tokens = 1 KiB:
- *              word (P, c, h) holds channel c of tokens 64 P + 32 h + i in bit i, i.e. the
- *              two words of a channel form a 64-bit mask over the 64 tokens of the block
- *              (lane = token in a 64-wide wavefront).  Bits of tokens not present are 0.
+ *   kbits    [units][max_ctx][4] uint32            one 128-bit code word (16 bytes) per token:
+ *              bit i of word d holds channel c = 64 (d & 1) + 2 i + (d >> 1), i.e. words 0 / 1 carry
+ *              the even channels 0..62 / 64..126 and words 2 / 3 the odd channels 1..63 / 65..127.
+ *              Bits of tokens not present are 0.  A wavefront reads the 64 tokens of a "pair block"
+ *              (two quantization groups) as one coalesced 1 KiB request, lane = token.
  *   kmeta    [units][max_ctx / 32][D] uint32      low half = s, high half = z of group
  *              (u, G, c), both in the K dtype: dequant(k) = z + bit * s.
  *   Together 32 bytes per cached token and unit: 1/8 of a 16-bit key cache, the ratio
  *   (1 + 32/g)/16 of Eq. 8.
+ *   kabsmax  [units][D] float: max over the quantized tokens of max(|z|, |z + s|) per channel.  With
+ *              it |score| <= R = sum_c |q_c| kabsmax_c is known before any score is computed, which
+ *              lets the scoring kernel histogram its scores in the same pass (512 bytes per unit).
  *   seq_lens [batch] int32, device: tokens currently valid in each sequence.
+ *
+ * Workspace: fier_workspace_bytes(cfg, max_budget) bytes of device memory, 256-byte aligned.  The
+ * caller zero-fills it ONCE after allocating it; every call leaves the counters inside it zero again,
+ * so it can be reused by any later call with the same cfg and max_budget (one call at a time).
  */
 #ifndef FIER_H
 #define FIER_H
@@ -73,6 +81,8 @@ typedef struct fier_cache { /* one layer; all pointers device, caller-owned */
   void *v;
   uint32_t *kbits;         /* fier_packed_bits_bytes(cfg) bytes */
   uint32_t *kmeta;         /* fier_packed_meta_bytes(cfg) bytes */
+  float *kabsmax;          /* [units][D]: per channel, an upper bound of |dequantized key| over the
+                              tokens quantized so far; written by fier_quantize_keys, raised by appends */
   const int32_t *seq_lens; /* [batch] */
 } fier_cache;
 

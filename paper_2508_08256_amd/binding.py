@@ -44,7 +44,7 @@ class Config(C.Structure):
 
 class Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("kbits", C.c_void_p), ("kmeta", C.c_void_p),
-                ("seq_lens", C.c_void_p)]
+                ("kabsmax", C.c_void_p), ("seq_lens", C.c_void_p)]
 
 
 def make_config(batch, n_q_heads, n_kv_heads, max_ctx, kv_dtype=F16, head_dim=128, group_size=32, sm_scale=None):
@@ -129,6 +129,15 @@ def workspace_bytes(cfg: Config, max_budget: int) -> int:
     return int(lib().fier_workspace_bytes(C.byref(cfg), int(max_budget)))
 
 
+def make_workspace(cfg: Config, max_budget: int):
+    """A zero-filled workspace on the GPU (the library keeps its counters zero from then on)."""
+    import torch
+
+    n = workspace_bytes(cfg, max_budget)
+    assert n > 0
+    return torch.zeros(n, dtype=torch.uint8, device="cuda")
+
+
 def check_config(cfg: Config) -> int:
     return int(lib().fier_check_config(C.byref(cfg)))
 
@@ -146,8 +155,9 @@ class DeviceCache:
         assert seq_lens.dtype == torch.int32 and seq_lens.numel() == cfg.batch
         self.kbits = torch.zeros(packed_bits_bytes(cfg) // 4, dtype=torch.int32, device=k.device)
         self.kmeta = torch.zeros(packed_meta_bytes(cfg) // 4, dtype=torch.int32, device=k.device)
+        self.kabsmax = torch.zeros(cfg.units * cfg.head_dim, dtype=torch.float32, device=k.device)
         self.c = Cache(k.data_ptr(), v.data_ptr(), self.kbits.data_ptr(), self.kmeta.data_ptr(),
-                       seq_lens.data_ptr())
+                       self.kabsmax.data_ptr(), seq_lens.data_ptr())
 
     def unpack(self):
         """Logical view of the packed state on the host: bits [units][max_ctx][D] u8, s, z [units][groups][D] u16."""

@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libfier.so")
-SOURCES = ["fier_api.hip", "fier_quantize.hip", "fier_score.hip", "fier_topk.hip", "fier_attn.hip"]
+SOURCES = ["fier_api.hip", "fier_quantize.hip", "fier_score.hip", "fier_select.hip", "fier_topk.hip",
+           "fier_attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]

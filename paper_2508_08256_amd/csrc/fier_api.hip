@@ -31,8 +31,10 @@ int check_cfg(const fier_config* c) {
 }
 
 int check_cache(const fier_cache* k) {
-  if (!k || !k->k || !k->v || !k->kbits || !k->kmeta || !k->seq_lens) return FIER_EINVAL;
-  if (misaligned(k->k) || misaligned(k->v) || misaligned(k->kbits) || misaligned(k->kmeta)) return FIER_EALIGN;
+  if (!k || !k->k || !k->v || !k->kbits || !k->kmeta || !k->kabsmax || !k->seq_lens) return FIER_EINVAL;
+  if (misaligned(k->k) || misaligned(k->v) || misaligned(k->kbits) || misaligned(k->kmeta) ||
+      misaligned(k->kabsmax))
+    return FIER_EALIGN;
   return FIER_OK;
 }
 
@@ -40,35 +42,46 @@ inline int units_of(const fier_config* c) { return c->batch * c->n_kv_heads; }
 inline int n_rep_of(const fier_config* c) { return c->n_q_heads / c->n_kv_heads; }
 inline int splits_for(int max_budget) { return (max_budget + fier::kAttnRowsSparse - 1) / fier::kAttnRowsSparse; }
 
+inline int ranges_of(const fier_config* c) { return (c->max_ctx + fier::kRangeTokens - 1) / fier::kRangeTokens; }
+
 struct Workspace {
-  float* po;
+  fier::StepBuffers sb;  // fused step: control blocks, histograms, candidates, scores, partials
+  float* po;             // stand-alone attention partials (split kernel + merge kernel)
   float* pm;
   float* pl;
-  float* scores;
   int32_t* idx;
   int32_t* count;
   size_t bytes;
 };
 
 // Carve the workspace for selections of up to max_budget rows per unit.  base may be null (sizing only).
+// The control blocks and histograms come first: they are the part that must be zero before the first call.
 Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
   const size_t units = (size_t)units_of(c), heads = units * (size_t)n_rep_of(c);
-  const size_t splits = (size_t)splits_for(max_budget);
+  const size_t splits = (size_t)splits_for(max_budget), ranges = (size_t)ranges_of(c);
   char* p = static_cast<char*>(base);
   size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* r = p + off;
+    off += align_up(bytes);
+    return r;
+  };
   Workspace w;
-  w.po = reinterpret_cast<float*>(p + off);
-  off += align_up(heads * splits * kD * sizeof(float));
-  w.pm = reinterpret_cast<float*>(p + off);
-  off += align_up(heads * splits * sizeof(float));
-  w.pl = reinterpret_cast<float*>(p + off);
-  off += align_up(heads * splits * sizeof(float));
-  w.scores = reinterpret_cast<float*>(p + off);
-  off += align_up(units * (size_t)c->max_ctx * sizeof(float));
-  w.idx = reinterpret_cast<int32_t*>(p + off);
-  off += align_up(units * (size_t)max_budget * sizeof(int32_t));
-  w.count = reinterpret_cast<int32_t*>(p + off);
-  off += align_up(units * sizeof(int32_t));
+  w.sb.ctl = reinterpret_cast<fier::UnitCtl*>(take(units * sizeof(fier::UnitCtl)));
+  w.sb.hist = reinterpret_cast<uint32_t*>(take(units * fier::kSelBins * sizeof(uint32_t)));
+  w.sb.range_cnt = reinterpret_cast<uint32_t*>(take(units * ranges * sizeof(uint32_t)));
+  const size_t chunks = ((size_t)c->max_ctx + fier::kClassifyTokens - 1) / fier::kClassifyTokens;
+  w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * chunks * fier::kSegCand * sizeof(unsigned long long)));
+  w.sb.seg_cnt = reinterpret_cast<uint32_t*>(take(units * chunks * sizeof(uint32_t)));
+  w.sb.scores = reinterpret_cast<float*>(take(units * (size_t)c->max_ctx * sizeof(float)));
+  w.sb.po = reinterpret_cast<float*>(take(heads * ranges * kD * sizeof(float)));
+  w.sb.pm = reinterpret_cast<float*>(take(heads * ranges * sizeof(float)));
+  w.sb.pl = reinterpret_cast<float*>(take(heads * ranges * sizeof(float)));
+  w.po = reinterpret_cast<float*>(take(heads * splits * kD * sizeof(float)));
+  w.pm = reinterpret_cast<float*>(take(heads * splits * sizeof(float)));
+  w.pl = reinterpret_cast<float*>(take(heads * splits * sizeof(float)));
+  w.idx = reinterpret_cast<int32_t*>(take(units * (size_t)max_budget * sizeof(int32_t)));
+  w.count = reinterpret_cast<int32_t*>(take(units * sizeof(int32_t)));
   w.bytes = off;
   return w;
 }
@@ -96,7 +109,7 @@ int fier_check_config(const fier_config* cfg) { return check_cfg(cfg); }
 
 size_t fier_packed_bits_bytes(const fier_config* cfg) {
   if (check_cfg(cfg) != FIER_OK) return 0;
-  return (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / kPair) * kD * 2 * sizeof(uint32_t);
+  return (size_t)units_of(cfg) * (size_t)cfg->max_ctx * 4 * sizeof(uint32_t);
 }
 
 size_t fier_packed_meta_bytes(const fier_config* cfg) {
@@ -115,8 +128,9 @@ int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* st
   if (st != FIER_OK) return st;
   st = check_cache(cache);
   if (st != FIER_OK) return st;
-  return hip_status(fier::launch_quantize(cfg->kv_dtype, cache->k, cache->kbits, cache->kmeta, cache->seq_lens,
-                                          units_of(cfg), cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
+  return hip_status(fier::launch_quantize(cfg->kv_dtype, cache->k, cache->kbits, cache->kmeta, cache->kabsmax,
+                                          cache->seq_lens, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
+                                          (hipStream_t)stream));
 }
 
 int fier_append_key(const fier_config* cfg, const fier_cache* cache, const void* k_new, const void* v_new,
@@ -128,8 +142,8 @@ int fier_append_key(const fier_config* cfg, const fier_cache* cache, const void*
   if (!k_new || !v_new) return FIER_EINVAL;
   if (misaligned(k_new) || misaligned(v_new)) return FIER_EALIGN;
   return hip_status(fier::launch_append(cfg->kv_dtype, cache->k, cache->v, cache->kbits, cache->kmeta,
-                                        cache->seq_lens, k_new, v_new, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
-                                        (hipStream_t)stream));
+                                        cache->kabsmax, cache->seq_lens, k_new, v_new, units_of(cfg),
+                                        cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
 }
 
 int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, int32_t extra_tokens, float* scores,
@@ -140,9 +154,9 @@ int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, i
   if (st != FIER_OK) return st;
   if (!q || !scores || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
   if (misaligned(q) || misaligned(scores)) return FIER_EALIGN;
-  return hip_status(fier::launch_score(cfg->kv_dtype, n_rep_of(cfg), cache->kbits, cache->kmeta, q, cache->seq_lens,
-                                       extra_tokens, scores, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
-                                       (hipStream_t)stream));
+  return hip_status(fier::launch_score(cfg->kv_dtype, n_rep_of(cfg), cache->kbits, cache->kmeta, cache->kabsmax, q,
+                                       cache->seq_lens, extra_tokens, scores, nullptr, nullptr, 0, units_of(cfg),
+                                       cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
 }
 
 int fier_topk(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
@@ -217,24 +231,23 @@ int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n
     const char* ql = static_cast<const char*>(q) + (size_t)l * cfg->batch * cfg->n_q_heads * kD * esz;
     float* outl = out + (size_t)l * cfg->batch * cfg->n_q_heads * kD;
     int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : w.idx;
-    int32_t* cntl = count_out ? count_out + (size_t)l * units : w.count;
+    int32_t* cntl = count_out ? count_out + (size_t)l * units : nullptr;
     hipError_t e;
     if (extra) {
       const char* kn = static_cast<const char*>(k_new) + (size_t)l * units * kD * esz;
       const char* vn = static_cast<const char*>(v_new) + (size_t)l * units * kD * esz;
-      e = fier::launch_append(cfg->kv_dtype, c->k, c->v, c->kbits, c->kmeta, c->seq_lens, kn, vn, units,
+      e = fier::launch_append(cfg->kv_dtype, c->k, c->v, c->kbits, c->kmeta, c->kabsmax, c->seq_lens, kn, vn, units,
                               cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
-    e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, ql, c->seq_lens, extra, w.scores, units,
-                           cfg->n_kv_heads, cfg->max_ctx, s);
+    e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra, w.sb.scores,
+                           &w.sb, budgets, max_budget, units, cfg->n_kv_heads, cfg->max_ctx, s);
     if (e != hipSuccess) return FIER_EHIP;
-    e = fier::launch_topk(w.scores, c->seq_lens, extra, budgets, max_budget, idxl, cntl, units, cfg->n_kv_heads,
-                          cfg->max_ctx, s);
+    e = fier::launch_threshold(w.sb, c->seq_lens, extra, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
     if (e != hipSuccess) return FIER_EHIP;
-    e = fier::launch_attn(cfg->kv_dtype, n_rep, c->k, c->v, ql, idxl, cntl, c->seq_lens, extra, max_budget,
-                          fier::kAttnRowsSparse, splits_for(max_budget), cfg->sm_scale, w.po, w.pm, w.pl, outl, units,
-                          cfg->n_kv_heads, cfg->max_ctx, s);
+    e = fier::launch_select_attend(cfg->kv_dtype, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
+                                   cfg->sm_scale, idx_out ? idxl : nullptr, outl, units, cfg->n_kv_heads,
+                                   cfg->max_ctx, s);
     if (e != hipSuccess) return FIER_EHIP;
   }
   return FIER_OK;
@@ -242,18 +255,15 @@ int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n
 
 void fier_unpack_bits(const fier_config* cfg, const uint32_t* kbits_host, uint8_t* bits_host) {
   if (check_cfg(cfg) != FIER_OK || !kbits_host || !bits_host) return;
-  const size_t units = (size_t)units_of(cfg);
-  const size_t n_pairs = (size_t)cfg->max_ctx / kPair;
-  for (size_t u = 0; u < units; ++u)
-    for (size_t p = 0; p < n_pairs; ++p)
-      for (int c = 0; c < kD; ++c)
-        for (int h = 0; h < 2; ++h) {
-          const uint32_t w = kbits_host[((u * n_pairs + p) * kD + c) * 2 + h];
-          for (int i = 0; i < 32; ++i) {
-            const size_t t = p * kPair + (size_t)h * 32 + i;
-            bits_host[(u * cfg->max_ctx + t) * kD + c] = (uint8_t)((w >> i) & 1u);
-          }
-        }
+  const size_t n_tok = (size_t)units_of(cfg) * (size_t)cfg->max_ctx;
+  for (size_t t = 0; t < n_tok; ++t)
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t w = kbits_host[t * 4 + d];
+      for (int i = 0; i < 32; ++i) {
+        const int c = 64 * (d & 1) + 2 * i + (d >> 1);
+        bits_host[t * kD + c] = (uint8_t)((w >> i) & 1u);
+      }
+    }
 }
 
 void fier_unpack_meta(const fier_config* cfg, const uint32_t* kmeta_host, uint16_t* s_host, uint16_t* z_host) {

@@ -16,6 +16,129 @@ namespace fier {
 constexpr int kAttnUnroll = 4;                  // rows per 16-lane row per iteration
 constexpr int kRowsPerIter = 4 * 4 * kAttnUnroll;  // 4 waves x 4 lane rows x unroll
 
+// Running softmax state of one 16-lane row of a wavefront, per query head: lane cn holds channels 8cn..8cn+7.
+template <int NREP>
+struct AttnState {
+  float m[NREP], l[NREP], o[NREP][8];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int r = 0; r < NREP; ++r) {
+      m[r] = -INFINITY;
+      l[r] = 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[r][c] = 0.f;
+    }
+  }
+};
+
+// Attend over entries [start, end) of a row list; row_of(j) gives the cache row of entry j.  The workgroup's
+// 16 lane rows (4 waves x 4) take entries round-robin in batches of kAttnUnroll.
+template <int DT, int NREP, class RowOf>
+__device__ __forceinline__ void attend_rows(const uint4* __restrict__ Ku, const uint4* __restrict__ Vu,
+                                            const uint4 (&qr)[NREP], RowOf row_of, int start, int end, int max_ctx,
+                                            float scale_log2e, AttnState<NREP>& st) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rs = lane >> 4, cn = lane & 15;
+  for (int i0 = start + wave * (4 * kAttnUnroll); i0 < end; i0 += kRowsPerIter) {
+    uint4 kk[kAttnUnroll], vv[kAttnUnroll];
+    bool valid[kAttnUnroll];
+#pragma unroll
+    for (int u = 0; u < kAttnUnroll; ++u) {
+      const int j = i0 + u * 4 + rs;
+      valid[u] = j < end;
+      int t = valid[u] ? row_of(j) : 0;
+      t = (t < 0 || t >= max_ctx) ? 0 : t;
+      kk[u] = Ku[(size_t)t * (kD / 8) + cn];
+      vv[u] = Vu[(size_t)t * (kD / 8) + cn];
+    }
+#pragma unroll
+    for (int r = 0; r < NREP; ++r) {
+      float logit[kAttnUnroll];
+      float mx = st.m[r];
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) {
+        float d = dot2<DT>(kk[u].x, qr[r].x, 0.f);
+        d = dot2<DT>(kk[u].y, qr[r].y, d);
+        d = dot2<DT>(kk[u].z, qr[r].z, d);
+        d = dot2<DT>(kk[u].w, qr[r].w, d);
+        d = row_allsum(d);
+        logit[u] = valid[u] ? d * scale_log2e : -INFINITY;
+        mx = fmaxf(mx, logit[u]);
+      }
+      const float mref = mx == -INFINITY ? 0.f : mx;
+      const float alpha = __builtin_amdgcn_exp2f(st.m[r] - mref);
+      float p[kAttnUnroll], psum = 0.f;
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) {
+        p[u] = __builtin_amdgcn_exp2f(logit[u] - mref);
+        psum += p[u];
+      }
+      st.m[r] = mx;
+      st.l[r] = st.l[r] * alpha + psum;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) st.o[r][c] *= alpha;
+#pragma unroll
+      for (int u = 0; u < kAttnUnroll; ++u) {
+        const uint32_t vw[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          st.o[r][2 * c] += p[u] * lo16f<DT>(vw[c]);
+          st.o[r][2 * c + 1] += p[u] * hi16f<DT>(vw[c]);
+        }
+      }
+    }
+  }
+}
+
+// Combine the 16 lane-row states of the workgroup per query head and write one partial (m, l, o[128]) per head
+// into slot `slot` of the unit's partial arrays.  Contains barriers: every thread of the workgroup calls it.
+template <int NREP, bool COHERENT>
+__device__ __forceinline__ void store_partials(const AttnState<NREP>& st, float (*sh_o)[16][8 + 2], int unit,
+                                               int n_slots, int slot, float* __restrict__ po, float* __restrict__ pm,
+                                               float* __restrict__ pl) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int rs = lane >> 4, cn = lane & 15;
+#pragma unroll
+  for (int r = 0; r < NREP; ++r) {
+    __syncthreads();
+    float* dst = sh_o[wave * 4 + rs][cn];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) dst[c] = st.o[r][c];
+    dst[8] = st.m[r];
+    dst[9] = st.l[r];
+    __syncthreads();
+    if (tid < kD) {
+      const int chunk = tid >> 3, e = tid & 7;
+      float M = -INFINITY;
+#pragma unroll
+      for (int s = 0; s < 16; ++s) M = fmaxf(M, sh_o[s][chunk][8]);
+      float acc = 0.f, lsum = 0.f;
+#pragma unroll
+      for (int s = 0; s < 16; ++s) {
+        const float ms = sh_o[s][chunk][8];
+        const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+        acc += w * sh_o[s][chunk][e];
+        lsum += w * sh_o[s][chunk][9];
+      }
+      const size_t ps = ((size_t)unit * NREP + r) * n_slots + slot;
+      if (COHERENT) {  // read back by another workgroup of this kernel
+        store_coherent(&po[ps * kD + tid], acc);
+        if (tid == 0) {
+          store_coherent(&pm[ps], M);
+          store_coherent(&pl[ps], lsum);
+        }
+      } else {
+        po[ps * kD + tid] = acc;
+        if (tid == 0) {
+          pm[ps] = M;
+          pl[ps] = lsum;
+        }
+      }
+    }
+  }
+}
+
 template <int DT, int NREP>
 __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                          const uint4* __restrict__ q, const int32_t* __restrict__ idx,
@@ -27,9 +150,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
                                                          int n_kv_heads, int max_ctx) {
   __shared__ float sh_o[16][16][8 + 2];  // [wave*4 + lane row][channel chunk][o[8], m, l]
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int rs = lane >> 4, cn = lane & 15;
+  const int cn = threadIdx.x & 15;
   const int unit = blockIdx.y, split = blockIdx.x;
   const int b = unit / n_kv_heads;
   int n;
@@ -51,96 +172,144 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
 #pragma unroll
   for (int r = 0; r < NREP; ++r) qr[r] = q[((size_t)unit * NREP + r) * (kD / 8) + cn];
 
-  float m_run[NREP], l_run[NREP], o[NREP][8];
-#pragma unroll
-  for (int r = 0; r < NREP; ++r) {
-    m_run[r] = -INFINITY;
-    l_run[r] = 0.f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) o[r][c] = 0.f;
-  }
+  AttnState<NREP> st;
+  st.init();
+  if (sel)
+    attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st);
+  else
+    attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st);
+  store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
+}
 
-  for (int i0 = start + wave * (4 * kAttnUnroll); i0 < end; i0 += kRowsPerIter) {
-    uint4 kk[kAttnUnroll], vv[kAttnUnroll];
-    bool valid[kAttnUnroll];
+// Merge n_used partial slots of one (unit, query head) into out[128]; 256 threads: thread (c, half) folds the
+// slots of its parity for channel c with a running maximum, eight independent coherent loads at a time so
+// that the round trips to memory overlap; the two halves meet in LDS.  sh: 2 * 130 floats.  Has barriers.
+__device__ __forceinline__ void merge_head(const float* __restrict__ po, const float* __restrict__ pm,
+                                           const float* __restrict__ pl, size_t base, int n_used, float* sh,
+                                           float* __restrict__ out_head) {
+  constexpr int BATCH = 8;
+  const int tid = threadIdx.x;
+  const int c = tid & 127, half = tid >> 7;
+  float M = -INFINITY, acc = 0.f, lsum = 0.f;
+  for (int s0 = half; s0 < n_used; s0 += 2 * BATCH) {
+    float ms[BATCH], ls[BATCH], os[BATCH];
 #pragma unroll
-    for (int u = 0; u < kAttnUnroll; ++u) {
-      const int j = i0 + u * 4 + rs;
-      valid[u] = j < end;
-      int t = valid[u] ? (sel ? sel[j] : j) : 0;
-      t = (t < 0 || t >= max_ctx) ? 0 : t;
-      kk[u] = Ku[(size_t)t * (kD / 8) + cn];
-      vv[u] = Vu[(size_t)t * (kD / 8) + cn];
+    for (int k = 0; k < BATCH; ++k) {
+      const int s = s0 + 2 * k;
+      const bool ok = s < n_used;
+      const size_t slot = base + (ok ? s : s0);
+      ms[k] = load_coherent(&pm[slot]);
+      ls[k] = load_coherent(&pl[slot]);
+      os[k] = load_coherent(&po[slot * kD + c]);
+      if (!ok) ms[k] = -INFINITY;
     }
+    float mx = M;
 #pragma unroll
-    for (int r = 0; r < NREP; ++r) {
-      float logit[kAttnUnroll];
-      float mx = m_run[r];
+    for (int k = 0; k < BATCH; ++k) mx = fmaxf(mx, ms[k]);
+    const float mref = mx == -INFINITY ? 0.f : mx;
+    const float alpha = __builtin_amdgcn_exp2f(M - mref);
+    acc *= alpha;
+    lsum *= alpha;
 #pragma unroll
-      for (int u = 0; u < kAttnUnroll; ++u) {
-        float d = dot2<DT>(kk[u].x, qr[r].x, 0.f);
-        d = dot2<DT>(kk[u].y, qr[r].y, d);
-        d = dot2<DT>(kk[u].z, qr[r].z, d);
-        d = dot2<DT>(kk[u].w, qr[r].w, d);
-        d = row_allsum(d);
-        logit[u] = valid[u] ? d * scale_log2e : -INFINITY;
-        mx = fmaxf(mx, logit[u]);
-      }
-      const float mref = mx == -INFINITY ? 0.f : mx;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[r] - mref);
-      float p[kAttnUnroll], psum = 0.f;
-#pragma unroll
-      for (int u = 0; u < kAttnUnroll; ++u) {
-        p[u] = __builtin_amdgcn_exp2f(logit[u] - mref);
-        psum += p[u];
-      }
-      m_run[r] = mx;
-      l_run[r] = l_run[r] * alpha + psum;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) o[r][c] *= alpha;
-#pragma unroll
-      for (int u = 0; u < kAttnUnroll; ++u) {
-        const uint32_t vw[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          o[r][2 * c] += p[u] * lo16f<DT>(vw[c]);
-          o[r][2 * c + 1] += p[u] * hi16f<DT>(vw[c]);
-        }
-      }
+    for (int k = 0; k < BATCH; ++k) {
+      const float w = __builtin_amdgcn_exp2f(ms[k] - mref);  // 0 for an empty slot
+      acc += w * os[k];
+      lsum += w * ls[k];
     }
+    M = mx;
   }
+  __syncthreads();
+  sh[half * 130 + c] = acc;
+  if (c == 0) {
+    sh[half * 130 + 128] = lsum;
+    sh[half * 130 + 129] = M;
+  }
+  __syncthreads();
+  if (half == 0) {
+    const float m0 = sh[129], m1 = sh[130 + 129];
+    const float mx = fmaxf(m0, m1);
+    const float mref = mx == -INFINITY ? 0.f : mx;
+    const float w0 = __builtin_amdgcn_exp2f(m0 - mref), w1 = __builtin_amdgcn_exp2f(m1 - mref);
+    const float l = w0 * sh[128] + w1 * sh[130 + 128];
+    const float a = w0 * sh[c] + w1 * sh[130 + c];
+    out_head[c] = l > 0.f ? a / l : 0.f;
+  }
+}
 
-  // combine the 16 (wave, lane row) states of the workgroup per query head and channel
+// Third kernel of the fused decode step.  grid (n_ranges, units), block 256: the workgroup owns tokens
+// [1024 r, 1024 r + 1024) of its unit.  It re-reads their scores, applies the exact selection rule fixed by the
+// threshold kernel, writes its part of the ascending index list, and attends over its selected rows straight
+// from an LDS list -- the index list never has to be read back.  The unit's last workgroup merges the partials.
+template <int DT, int NREP>
+__global__ __launch_bounds__(256) void select_attend_kernel(
+    const float* __restrict__ scores, UnitCtl* __restrict__ ctl, const uint32_t* __restrict__ range_off,
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ q,
+    const int32_t* __restrict__ seq_lens, int extra, int max_budget, float scale_log2e, float* __restrict__ po,
+    float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
+    int n_ranges, int n_kv_heads, int max_ctx) {
+  __shared__ float sh_o[16][16][8 + 2];
+  __shared__ int32_t rows[kRangeTokens];
+  __shared__ uint32_t scan_tmp[4];
+  __shared__ uint32_t flag;
+
+  const int tid = threadIdx.x;
+  const int cn = tid & 15;
+  const int unit = blockIdx.y, r = blockIdx.x;
+  const int b = unit / n_kv_heads;
+  int n = seq_lens[b] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  if (r * kRangeTokens >= n && r != 0) return;
+  UnitCtl* __restrict__ c = &ctl[unit];
+  const int tbin = c->tbin;
+  const float R = c->R, hscale = c->scale;
+  const uint32_t T = c->T;
+  const int32_t idxT = c->idxT;
+
+  // ---- exact selection inside this range, in token order -------------------------------------------------
+  const int i = r * kRangeTokens + 4 * tid;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n) v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
+  const float vv[4] = {v.x, v.y, v.z, v.w};
+  bool sel[4];
+  uint32_t cnt = 0;
 #pragma unroll
-  for (int r = 0; r < NREP; ++r) {
-    if (r > 0) __syncthreads();
-    float* dst = sh_o[wave * 4 + rs][cn];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) dst[c] = o[r][c];
-    dst[8] = m_run[r];
-    dst[9] = l_run[r];
-    __syncthreads();
-    if (tid < kD) {
-      const int chunk = tid >> 3, e = tid & 7;
-      float M = -INFINITY;
-#pragma unroll
-      for (int s = 0; s < 16; ++s) M = fmaxf(M, sh_o[s][chunk][8]);
-      float acc = 0.f, lsum = 0.f;
-#pragma unroll
-      for (int s = 0; s < 16; ++s) {
-        const float ms = sh_o[s][chunk][8];
-        const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-        acc += w * sh_o[s][chunk][e];
-        lsum += w * sh_o[s][chunk][9];
-      }
-      const size_t slot = ((size_t)unit * NREP + r) * n_splits + split;
-      po[slot * kD + tid] = acc;
-      if (tid == 0) {
-        pm[slot] = M;
-        pl[slot] = lsum;
-      }
-    }
+  for (int j = 0; j < 4; ++j) {
+    const int bin = sel_bin(vv[j], R, hscale, kSelBins);
+    const uint32_t key = score_key(vv[j]);
+    sel[j] = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
+    cnt += sel[j];
   }
+  uint32_t n_sel;
+  uint32_t pos = block_excl_scan_u32<4>(cnt, scan_tmp, n_sel);
+  const uint32_t off = r < n_ranges ? range_off[(size_t)unit * n_ranges + r] : 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (sel[j]) {
+      rows[pos] = i + j;
+      if (idx_out && off + pos < (uint32_t)max_budget) idx_out[(size_t)unit * max_budget + off + pos] = i + j;
+      ++pos;
+    }
+  __syncthreads();
+
+  // ---- attention over the selected rows of this range ----------------------------------------------------
+  const uint4* __restrict__ Ku = K + (size_t)unit * max_ctx * (kD / 8);
+  const uint4* __restrict__ Vu = V + (size_t)unit * max_ctx * (kD / 8);
+  uint4 qr[NREP];
+#pragma unroll
+  for (int h = 0; h < NREP; ++h) qr[h] = q[((size_t)unit * NREP + h) * (kD / 8) + cn];
+  AttnState<NREP> st;
+  st.init();
+  attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return rows[j]; }, 0, (int)n_sel, max_ctx, scale_log2e, st);
+  store_partials<NREP, true>(st, sh_o, unit, n_ranges, r, po, pm, pl);
+
+  const int nr = (n + kRangeTokens - 1) / kRangeTokens;
+  if (!last_arriver(&c->arrive[2], nr > 0 ? (uint32_t)nr : 1u, &flag)) return;
+  // ---- the unit's last workgroup merges the partials of all ranges ------------------------------------------
+  float* sh = &sh_o[0][0][0];
+#pragma unroll 1
+  for (int h = 0; h < NREP; ++h)
+    merge_head(po, pm, pl, ((size_t)unit * NREP + h) * n_ranges, nr, sh, out + ((size_t)unit * NREP + h) * kD);
+  if (tid == 0) c->arrive[2] = 0;
 }
 
 // grid (units * n_rep), block 128: thread c merges channel c of one query head over the splits in use.
@@ -206,6 +375,47 @@ static hipError_t launch_attn_dt(int n_rep, const void* K, const void* V, const 
   }
 #undef FIER_ATTN_CASE
   return hipGetLastError();
+}
+
+template <int DT>
+static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, const void* K, const void* V,
+                                          const void* q, const int32_t* seq_lens, int extra, int max_budget,
+                                          float sm_scale, int32_t* idx_out, float* out, int units, int n_kv_heads,
+                                          int max_ctx, hipStream_t st) {
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  dim3 grid(n_ranges, units);
+  const float sl2 = sm_scale * 1.4426950408889634f;
+#define FIER_SA_CASE(R)                                                                                             \
+  case R:                                                                                                           \
+    select_attend_kernel<DT, R><<<grid, 256, 0, st>>>(sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K,             \
+                                                      (const uint4*)V, (const uint4*)q, seq_lens, extra, max_budget, \
+                                                      sl2, sb.po, sb.pm, sb.pl, idx_out, out, n_ranges, n_kv_heads, \
+                                                      max_ctx);                                                     \
+    break;
+  switch (n_rep) {
+    FIER_SA_CASE(1)
+    FIER_SA_CASE(2)
+    FIER_SA_CASE(3)
+    FIER_SA_CASE(4)
+    FIER_SA_CASE(5)
+    FIER_SA_CASE(6)
+    FIER_SA_CASE(7)
+    FIER_SA_CASE(8)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef FIER_SA_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+                                const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
+                                int32_t* idx_out, float* out, int units, int n_kv_heads, int max_ctx, hipStream_t st) {
+  if (dtype == DT_F16)
+    return launch_select_attend_dt<DT_F16>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out,
+                                           units, n_kv_heads, max_ctx, st);
+  return launch_select_attend_dt<DT_BF16>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out,
+                                          units, n_kv_heads, max_ctx, st);
 }
 
 hipError_t launch_attn(int dtype, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,

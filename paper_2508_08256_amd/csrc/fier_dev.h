@@ -76,3 +76,81 @@ __device__ __forceinline__ float row_allsum(float x) {
 __device__ __forceinline__ int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
 
 }  // namespace fier
+
+namespace fier {
+
+// order-preserving map binary32 -> uint32 (larger score <=> larger key); -0 and +0 share a key
+__device__ __forceinline__ uint32_t score_key(float v) {
+  v += 0.0f;
+  uint32_t u = __float_as_uint(v);
+  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
+}
+
+// bin of the equal-width histogram over [-R, R]; monotone non-decreasing in v, the same in every kernel
+__device__ __forceinline__ int sel_bin(float v, float R, float scale, int n_bins) {
+  int bin = (int)((v + R) * scale);
+  return bin > n_bins - 1 ? n_bins - 1 : (bin < 0 ? 0 : bin);
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// Exclusive scan over the threads of a workgroup of NW wavefronts (thread order) and the total.
+// tmp: NW words of LDS.  Contains two barriers.
+template <int NW>
+__device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t* tmp, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v, lane);
+  __syncthreads();
+  if (lane == 63) tmp[wave] = incl;
+  __syncthreads();
+  const uint32_t wsum = lane < NW ? tmp[lane] : 0;
+  const uint32_t wincl = wave_incl_scan_u32(wsum, lane);
+  const uint32_t wave_off = __shfl(wincl, wave, 64) - __shfl(wsum, wave, 64);
+  total = __shfl(wincl, NW - 1, 64);
+  return wave_off + incl - v;
+}
+
+// ---- publishing results to another workgroup of the same kernel -------------------------------------------
+// The L2 caches of the eight XCDs are not coherent with each other.  A device-scope fence (__threadfence)
+// writes back / invalidates a whole L2 and costs tens of microseconds when a thousand workgroups do it, so
+// the few words one workgroup hands to another are instead written with device-scope atomic stores (write
+// through to memory) and read with device-scope atomic loads; the arrival counter is a device-scope atomic.
+// The workgroup-scope fences inside __syncthreads make every wave wait for the completion of its own stores
+// before the barrier, hence before the arrival is counted.
+__device__ __forceinline__ void store_coherent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_coherent(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t load_coherent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_coherent(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// "Last arriver": returns true in every thread of exactly one workgroup per counter: the one whose increment
+// brings it to `expected`.  Everything the other workgroups published with store_coherent / atomics before
+// arriving can then be read with load_coherent.  Nobody waits for anybody.  flag: one word of LDS.
+__device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expected, uint32_t* flag) {
+  __syncthreads();  // all of this workgroup's stores and atomics have completed
+  if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  return *flag == expected - 1;
+}
+
+}  // namespace fier

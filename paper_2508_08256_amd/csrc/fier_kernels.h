@@ -9,16 +9,66 @@ namespace fier {
 constexpr int kAttnRowsSparse = 128;  // selected rows per workgroup of the split attention kernel
 constexpr int kAttnRowsDense = 512;   // rows per workgroup when attending over the whole cache
 
-hipError_t launch_quantize(int dtype, const void* K, uint32_t* kbits, uint32_t* kmeta, const int32_t* seq_lens,
-                           int units, int n_kv_heads, int max_ctx, hipStream_t st);
+// ---- fused decode step -------------------------------------------------------------------------------
+// Three kernels per layer.  Each unit's tokens are spread over many workgroups; the few serial steps
+// (threshold bin from the merged histogram, exact threshold among the candidates, merge of the attention
+// partials) are done by whichever workgroup of the unit finishes last ("last arriver": a device-scope
+// counter after a release fence; nobody ever waits).
+constexpr int kSelBins = 512;          // equal-width score histogram bins over [-R, R] (few enough that the
+                                       // per-workgroup histograms merge with ~100 device atomics each)
+constexpr int kRangeTokens = 1024;     // tokens per workgroup in the score and the select+attend kernels
+constexpr int kClassifyTokens = 4096;  // tokens per workgroup in the threshold kernel
+constexpr int kSegCand = 1024;         // candidate slots per threshold-kernel workgroup
+constexpr int kSelCandMax = 8192;      // candidates per unit the exact selection handles in LDS
+constexpr int kSubBins = 1024;         // second-level bins inside the threshold bin
+constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 
-hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, const int32_t* seq_lens,
-                         const void* k_new, const void* v_new, int units, int n_kv_heads, int max_ctx,
-                         hipStream_t st);
+struct UnitCtl {        // one per unit at the head of the workspace
+  uint32_t arrive[3];   // arrival counters of the three kernels; zero between calls
+  uint32_t unused0;
+  int32_t tbin;         // bins above are selected, bins below are not (-1: everything, kSelBins: nothing)
+  uint32_t above;       // tokens in bins above tbin
+  int32_t budget;       // tokens to select = min(budget, length, max_budget), >= 0
+  float R;              // scores lie in [-R, R]
+  float scale;          // kSelBins / (2 R)
+  uint32_t T;           // threshold key inside tbin
+  int32_t idxT;         // among keys == T inside tbin, indices <= idxT are selected
+  uint32_t pad[5];
+};
+static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte line");
 
-hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const void* q,
-                        const int32_t* seq_lens, int extra, float* scores, int units, int n_kv_heads, int max_ctx,
+struct StepBuffers {    // carved from the caller's workspace
+  UnitCtl* ctl;         // [units]
+  uint32_t* hist;       // [units][kSelBins]; zero between calls
+  uint32_t* range_cnt;  // [units][n_ranges]: selected tokens per 1024-token range, then their exclusive scan
+  unsigned long long* cand;  // [units][n_chunks][kSegCand] (key << 32 | token index), one segment per workgroup
+  uint32_t* seg_cnt;    // [units][n_chunks] candidates found by each threshold-kernel workgroup
+  float* scores;        // [units][max_ctx]
+  float* po;            // attention partials, n_slots per (unit, query head)
+  float* pm;
+  float* pl;
+};
+
+hipError_t launch_quantize(int dtype, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+                           const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, hipStream_t st);
+
+hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+                         const int32_t* seq_lens, const void* k_new, const void* v_new, int units, int n_kv_heads,
+                         int max_ctx, hipStream_t st);
+
+// With sb != nullptr the kernel also builds the per-unit score histogram and its last workgroup per unit
+// finds the threshold bin for budgets[b] (first kernel of the fused step).
+hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
+                        const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
+                        const int32_t* budgets, int max_budget, int units, int n_kv_heads, int max_ctx,
                         hipStream_t st);
+
+hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, int32_t* count_out, int units,
+                            int n_kv_heads, int max_ctx, hipStream_t st);
+
+hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+                                const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
+                                int32_t* idx_out, float* out, int units, int n_kv_heads, int max_ctx, hipStream_t st);
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
                        int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,

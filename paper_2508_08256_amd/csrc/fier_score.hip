@@ -1,149 +1,257 @@
 // Approximate scores from the 1-bit key cache (Alg. 1 step 2):
 //   score[j] = sum_c q_c * (z[G(j)][c] + bit[j][c] * s[G(j)][c]),  q = sum of the unit's query heads.
 //
-// Lane = token.  One wavefront owns one pair block (64 tokens = groups 2P and 2P+1):
-//   * the 64-bit word pair of channel c is exactly the wavefront's lane mask "bit c of my token is 1";
-//     it is fetched with scalar loads (the address is uniform) and used as a select mask;
-//   * the per-group weights w[c] = q_c * s[G][c] differ between the two halves of the wavefront.  They are
-//     kept distributed: each row of 16 lanes holds all 128 weights of its own group in 8 registers
-//     (lane n of the row holds 8 channels), and a DPP row broadcast inside the select instruction hands
-//     weight (m, n) to the 16 lanes of the row.  No LDS, no replication through memory;
+// Lane = token.  One wavefront owns one pair block (64 tokens = groups 2P and 2P+1) at a time:
+//   * each lane loads the 16-byte code word of its own token (one coalesced 1 KiB request per block);
+//   * the per-group weights w[c] = q_c * s[G][c] differ between the two halves of the wavefront.  They
+//     stay distributed: each row of 16 lanes holds all 128 weights of its own group in 8 registers
+//     (lane n of the row holds 8 channels), and a DPP row broadcast inside the multiply-add hands weight
+//     (m, n) to the 16 lanes of the row.  No LDS and no replication through memory;
+//   * "bit ? w : 0" costs no select: a code word ANDed with a single-bit mask in the exponent field of a
+//     binary32 IS the number 2^k or 0 (bit 30 -> 2, 29 -> 2^-63, 28 -> 2^-95, 27 -> 2^-111).  The weight
+//     register carries the inverse power of two (folded into q once per kernel), so one v_and and one
+//     v_fmac with a DPP source accumulate bit * w exactly.  Eight rotations of each code word bring every
+//     bit to one of the four usable positions: 2 + 7/32 vector ops per (token, channel);
+//   * q is pre-scaled by 2^-16 so that w * 2^111 stays finite for |q_c s_c| < 2^32 (any binary16 data);
+//     the final score is scaled back by 2^16.  All scalings are powers of two: no rounding is added;
 //   * base[G] = sum_c q_c * z[G][c] is reduced inside each row with DPP rotates.
-// Per (token, channel) this is one select (v_cndmask with DPP source) and one add.
 //
-// Channel <-> (register m, lane n) map: lane n of a row loads (s,z) of channels 4n..4n+3 and 64+4n..64+4n+3
-// as two 16-byte requests: register m = 4*(c / 64) + (c % 4), lane n = (c % 64) / 4.
-#include <utility>
-
+// Channel bookkeeping.  Meta: lane n of a row loads (s,z) of channels 4n..4n+3 and 64+4n..64+4n+3 as two
+// 16-byte requests: register m = 4h + e holds channel c = 64h + 4n + e.  Bits: channel c sits in word
+// d = h + 2(e & 1) at bit i = 2n + (e >> 1).  Bit i is tested in rotation a = ((i - 27) mod 32) / 4 at
+// position 27 + ((i - 27) mod 4).
 #include "fier_dev.h"
 #include "fier_kernels.h"
 
 namespace fier {
 
-constexpr int kScorePairsPerWave = 4;  // pair blocks per wavefront -> 1024 tokens per 256-thread workgroup
+constexpr int kScorePairsPerWave = kRangeTokens / 256;  // pair blocks per wavefront (4 wavefronts per workgroup)
 
-typedef uint64_t mask8_t __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ uint32_t rotr32(uint32_t x, int r) { return __builtin_amdgcn_alignbit(x, x, r); }
 
-// Four consecutive channels (same broadcast lane BC, registers x0..x3 of one half):
-//   acc_j += bit_j(lane) ? x_j[row lane BC] : 0.
-// Each mask is the wave-uniform 64-bit lane mask of one channel.  The select takes the row-broadcast
-// weight as its DPP source where the (inverted) mask in VCC is clear, a zero register where it is set.
-template <int BC>
-__device__ __forceinline__ void select_add4(uint64_t m0, uint64_t m1, uint64_t m2, uint64_t m3, float x0, float x1,
-                                            float x2, float x3, float zero, float (&acc)[4]) {
-  float t0, t1;
-  asm("s_not_b64 vcc, %[m0]\n\t"
-      "v_cndmask_b32_dpp %[t0], %[x0], %[z], vcc row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "s_not_b64 vcc, %[m1]\n\t"
-      "v_cndmask_b32_dpp %[t1], %[x1], %[z], vcc row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "v_add_f32 %[a0], %[a0], %[t0]\n\t"
-      "s_not_b64 vcc, %[m2]\n\t"
-      "v_cndmask_b32_dpp %[t0], %[x2], %[z], vcc row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "v_add_f32 %[a1], %[a1], %[t1]\n\t"
-      "s_not_b64 vcc, %[m3]\n\t"
-      "v_cndmask_b32_dpp %[t1], %[x3], %[z], vcc row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "v_add_f32 %[a2], %[a2], %[t0]\n\t"
-      "v_add_f32 %[a3], %[a3], %[t1]"
+// 2^-16 / (value of a binary32 whose only set bit is bit 27 + j)
+__device__ __forceinline__ float position_scale(int j) {
+  // j = 0: 2^111, 1: 2^95, 2: 2^63, 3: 2^-1, each times 2^-16
+  const uint32_t e = j == 0 ? (127u + 95u) : j == 1 ? (127u + 79u) : j == 2 ? (127u + 47u) : (127u - 17u);
+  return __uint_as_float(e << 23);
+}
+
+// Four channels (h, n, e = 0..3):  acc_e += bit ? X[4h+e] broadcast from row lane n : 0
+template <int H, int N>
+__device__ __forceinline__ void accumulate_4(const uint32_t (&V)[4][8], const float (&X)[8], float (&acc)[4]) {
+  constexpr int I0 = 2 * N, I1 = 2 * N + 1;
+  constexpr int R0 = (I0 + 32 - 27) % 32, R1 = (I1 + 32 - 27) % 32;
+  constexpr int A0 = R0 / 4, A1 = R1 / 4;
+  constexpr uint32_t M0 = 1u << (27 + R0 % 4), M1 = 1u << (27 + R1 % 4);
+  uint32_t t0, t1;
+  asm("v_and_b32 %[t0], %[m0], %[va]\n\t"
+      "v_and_b32 %[t1], %[m0], %[vb]\n\t"
+      "v_fmac_f32_dpp %[a0], %[x0], %[t0] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
+      "v_and_b32 %[t0], %[m1], %[vc]\n\t"
+      "v_fmac_f32_dpp %[a1], %[x1], %[t1] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
+      "v_and_b32 %[t1], %[m1], %[vd]\n\t"
+      "v_fmac_f32_dpp %[a2], %[x2], %[t0] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %[a3], %[x3], %[t1] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf"
       : [t0] "=&v"(t0), [t1] "=&v"(t1), [a0] "+&v"(acc[0]), [a1] "+&v"(acc[1]), [a2] "+&v"(acc[2]),
         [a3] "+&v"(acc[3])
-      : [m0] "s"(m0), [m1] "s"(m1), [m2] "s"(m2), [m3] "s"(m3), [x0] "v"(x0), [x1] "v"(x1), [x2] "v"(x2),
-        [x3] "v"(x3), [z] "v"(zero), [bc] "n"(BC)
-      : "vcc");
+      : [va] "v"(V[H][A0]), [vb] "v"(V[H + 2][A0]), [vc] "v"(V[H][A1]), [vd] "v"(V[H + 2][A1]), [x0] "v"(X[4 * H]),
+        [x1] "v"(X[4 * H + 1]), [x2] "v"(X[4 * H + 2]), [x3] "v"(X[4 * H + 3]), [m0] "s"(M0), [m1] "s"(M1),
+        [bc] "n"(N));
 }
 
-// channels C0 .. C0+7, whose eight 64-bit masks arrive as one 64-byte scalar load
-template <int C0>
-__device__ __forceinline__ void accumulate_8(const mask8_t mk, const float (&X)[8], float zero, float (&acc)[4]) {
-  constexpr int H = 4 * (C0 / 64);
-  constexpr int N = (C0 % 64) / 4;
-  select_add4<N>(mk[0], mk[1], mk[2], mk[3], X[H], X[H + 1], X[H + 2], X[H + 3], zero, acc);
-  select_add4<N + 1>(mk[4], mk[5], mk[6], mk[7], X[H], X[H + 1], X[H + 2], X[H + 3], zero, acc);
-}
-
-template <int B>
-__device__ __forceinline__ void accumulate_all(const mask8_t* __restrict__ masks, mask8_t cur, const float (&X)[8],
-                                               float zero, float (&acc)[4]) {
-  if constexpr (B < 16) {
-    mask8_t nxt = cur;
-    if constexpr (B + 1 < 16) nxt = masks[B + 1];
-    accumulate_8<8 * B>(cur, X, zero, acc);
-    accumulate_all<B + 1>(masks, nxt, X, zero, acc);
+template <int H, int N>
+__device__ __forceinline__ void accumulate_from(const uint32_t (&V)[4][8], const float (&X)[8], float (&acc)[4]) {
+  if constexpr (H < 2) {
+    accumulate_4<H, N>(V, X, acc);
+    if constexpr (N + 1 < 16)
+      accumulate_from<H, N + 1>(V, X, acc);
+    else
+      accumulate_from<H + 1, 0>(V, X, acc);
   }
 }
 
-// grid (ceil(n_pairs / (4 * kScorePairsPerWave)), units), block 256.
-template <int DT, int NREP>
-__global__ __launch_bounds__(256) void score_kernel(const uint64_t* __restrict__ kbits,
-                                                    const uint4* __restrict__ kmeta, const uint16_t* __restrict__ q,
+// grid (ceil(max_ctx / 1024), units), block 256: workgroup x owns tokens [1024 x, 1024 x + 1024) of its unit,
+// wave w the pair blocks 16 x + w, + 4, + 8, + 12.
+//
+// HIST (first kernel of the fused step): every score is also counted in an equal-width histogram of kSelBins
+// bins over [-R, R], R = sum_c |q_c| * absmax_c >= |score| -- a bound known before any score exists, so that
+// scoring and histogramming are one pass.  The workgroup's LDS histogram is added to the unit's histogram in
+// memory; the unit's last workgroup reads the total, finds the bin that holds the budget-th largest score,
+// publishes it and clears the histogram for the next call.
+template <int DT, int NREP, bool HIST>
+__global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kbits, const uint4* __restrict__ kmeta,
+                                                    const float* __restrict__ kabsmax, const uint16_t* __restrict__ q,
                                                     const int32_t* __restrict__ seq_lens, int extra,
-                                                    float* __restrict__ scores, int n_kv_heads, int max_ctx) {
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+                                                    float* __restrict__ scores, UnitCtl* __restrict__ ctl,
+                                                    uint32_t* __restrict__ ghist, const int32_t* __restrict__ budgets,
+                                                    int max_budget, int n_kv_heads, int max_ctx) {
+  __shared__ uint32_t lhist[HIST ? kSelBins : 1];
+  __shared__ uint32_t scan_tmp[4];
+  __shared__ uint32_t flag;
+  __shared__ int found[2];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
   const int unit = blockIdx.y;
   const int b = unit / n_kv_heads;
   int L = seq_lens[b] + extra;
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
-  const int n_pairs = max_ctx / kPair;
+  // workgroup 0 of a unit always runs so that an empty unit still gets its control block written
+  if ((int)blockIdx.x * kRangeTokens >= L && !(HIST && blockIdx.x == 0)) return;
   const int n_groups = max_ctx / kG;
   const int row = lane >> 4, n = lane & 15;
 
-  // the lane's 8 query channels, summed over the query heads that share this kv head (binary32)
-  float qv[8];
+  // The lane's 8 query channels, summed over the query heads that share this kv head (binary32), times
+  // 2^-16: qz for the offsets, qx additionally times the inverse of the power of two its bit is tested at.
+  float qx[8], qz[8];
+  float R = 0.f, hscale = 0.f;
   {
-    const int h = unit - b * n_kv_heads;
-    const uint16_t* qb = q + ((size_t)(b * n_kv_heads + h) * NREP) * kD;
+    const uint16_t* qb = q + (size_t)unit * NREP * kD;
+    float rpart = 0.f;
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
-      const int c = 64 * (m >> 2) + 4 * n + (m & 3);
+      const int e = m & 3;
+      const int c = 64 * (m >> 2) + 4 * n + e;
       float s = 0.f;
 #pragma unroll
       for (int r = 0; r < NREP; ++r) s += w2f<DT>(qb[r * kD + c]);
-      qv[m] = s;
+      const int i = 2 * n + (e >> 1);
+      qz[m] = s * 1.52587890625e-05f;
+      qx[m] = s * position_scale((i + 32 - 27) & 3);
+      if (HIST) rpart += fabsf(s) * kabsmax[(size_t)unit * kD + c];
+    }
+    if (HIST) {
+      // every row holds all 128 channels; lane 0's sum is taken so that R is bit-identical in every lane, wave
+      // and workgroup (the binning must be the same function everywhere)
+      R = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(row_allsum(rpart))));
+      hscale = (float)kSelBins / (R + R);
+      for (int i = tid; i < kSelBins; i += 256) lhist[i] = 0;
+      __syncthreads();
     }
   }
-  const float zero = 0.f;
+
+  const int P0 = blockIdx.x * (4 * kScorePairsPerWave) + wave;  // this wave's blocks: P0, P0 + 4, ...
+  if (P0 * kPair < L) {
+    const uint4* __restrict__ bits_u = kbits + (size_t)unit * max_ctx;
+    const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
+    const int gsel = row >> 1;
+
+    uint4 w_cur = bits_u[P0 * kPair + lane];
+    uint4 ma_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + n];
+    uint4 mb_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + 16 + n];
 
 #pragma unroll 1
-  for (int i = 0; i < kScorePairsPerWave; ++i) {
-    const int P = (blockIdx.x * kScorePairsPerWave + i) * 4 + wave;
-    if (P * kPair >= L) break;
-    const int Gl = 2 * P + (row >> 1);
-    const uint4* mp = kmeta + ((size_t)unit * n_groups + Gl) * (kD / 4);
-    const uint4 ma = mp[n];
-    const uint4 mb = mp[16 + n];
-    const uint32_t mw[8] = {ma.x, ma.y, ma.z, ma.w, mb.x, mb.y, mb.z, mb.w};
-    float X[8];
-    float basep = 0.f;
+    for (int it = 0; it < kScorePairsPerWave; ++it) {
+      const int P = P0 + 4 * it;
+      if (P * kPair >= L) break;
+      // prefetch the next block of this wave (clamped to stay inside the unit's buffers)
+      int Pn = P + 4;
+      Pn = (it + 1 < kScorePairsPerWave && Pn * kPair < L) ? Pn : P;
+      const uint4 w_nxt = bits_u[Pn * kPair + lane];
+      const uint4 ma_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + n];
+      const uint4 mb_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + 16 + n];
+
+      const uint32_t mw[8] = {ma_cur.x, ma_cur.y, ma_cur.z, ma_cur.w, mb_cur.x, mb_cur.y, mb_cur.z, mb_cur.w};
+      float X[8];
+      float basep = 0.f;
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      X[m] = qv[m] * lo16f<DT>(mw[m]);
-      basep += qv[m] * hi16f<DT>(mw[m]);
+      for (int m = 0; m < 8; ++m) {
+        X[m] = qx[m] * lo16f<DT>(mw[m]);
+        basep += qz[m] * hi16f<DT>(mw[m]);
+      }
+      const uint32_t ww[4] = {w_cur.x, w_cur.y, w_cur.z, w_cur.w};
+      uint32_t V[4][8];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        V[d][0] = ww[d];
+#pragma unroll
+        for (int a = 1; a < 8; ++a) V[d][a] = rotr32(ww[d], 4 * a);
+      }
+      const float base = row_allsum(basep);
+      // A DPP source must not be read within two issue slots of the VALU write that produced it.  The weights
+      // pass through this fence so that every later DPP read of them is at least that far from their writes.
+      asm volatile("s_nop 1"
+                   : "+v"(X[0]), "+v"(X[1]), "+v"(X[2]), "+v"(X[3]), "+v"(X[4]), "+v"(X[5]), "+v"(X[6]), "+v"(X[7]));
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      accumulate_from<0, 0>(V, X, acc);
+      const float sc = (((acc[0] + acc[1]) + (acc[2] + acc[3])) + base) * 65536.0f;
+      const int tok = P * kPair + lane;
+      if (tok < L) {
+        scores[(size_t)unit * max_ctx + tok] = sc;
+        if (HIST) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
+      }
+      w_cur = w_nxt;
+      ma_cur = ma_nxt;
+      mb_cur = mb_nxt;
     }
-    const float base = row_allsum(basep);
-    // A DPP source must not be read within two issue slots of the VALU write that produced it.  The weights
-    // pass through this fence so that every later DPP read of them is at least that far from their writes.
-    asm volatile("s_nop 1"
-                 : "+v"(X[0]), "+v"(X[1]), "+v"(X[2]), "+v"(X[3]), "+v"(X[4]), "+v"(X[5]), "+v"(X[6]), "+v"(X[7]));
-    const uint64_t* masks = kbits + ((size_t)unit * n_pairs + P) * kD;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    const mask8_t* m8 = reinterpret_cast<const mask8_t*>(masks);
-    accumulate_all<0>(m8, m8[0], X, zero, acc);
-    const float sc = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + base;
-    const int tok = P * kPair + lane;
-    if (tok < L) scores[(size_t)unit * max_ctx + tok] = sc;
+  }
+
+  if constexpr (HIST) {
+    __syncthreads();
+    uint32_t* __restrict__ gh = ghist + (size_t)unit * kSelBins;
+    for (int i = tid; i < kSelBins; i += 256) {
+      const uint32_t c = lhist[i];
+      if (c) atomicAdd(&gh[i], c);
+    }
+    const uint32_t expected = L > 0 ? (uint32_t)((L + kRangeTokens - 1) / kRangeTokens) : 1u;
+    if (!last_arriver(&ctl[unit].arrive[0], expected, &flag)) return;
+    // ---- the unit's last workgroup: threshold bin for the budget ---------------------------------------
+    int B = budgets[b];
+    B = B > max_budget ? max_budget : B;
+    B = B > L ? L : B;
+    B = B < 0 ? 0 : B;
+    constexpr int PER = kSelBins / 256;
+    // thread t owns bins kSelBins-1-PER*t down to kSelBins-PER*(t+1), i.e. descending score order
+    uint32_t cnt[PER], sum = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      cnt[k] = load_coherent(&gh[kSelBins - 1 - (PER * tid + k)]);
+      sum += cnt[k];
+    }
+    uint32_t total;
+    uint32_t before = block_excl_scan_u32<4>(sum, scan_tmp, total);
+    if (tid == 0) {
+      found[0] = B >= L ? -1 : kSelBins;  // everything / nothing selected by bin alone
+      found[1] = 0;
+    }
+    __syncthreads();
+    if (B > 0 && B < L) {
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        if (before < (uint32_t)B && (uint32_t)B <= before + cnt[k]) {
+          found[0] = kSelBins - 1 - (PER * tid + k);
+          found[1] = (int)before;
+        }
+        before += cnt[k];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < PER; ++k) gh[kSelBins - 1 - (PER * tid + k)] = 0;
+    if (tid == 0) {
+      UnitCtl* c = &ctl[unit];
+      c->tbin = found[0];
+      c->above = (uint32_t)found[1];
+      c->budget = B;
+      c->R = R;
+      c->scale = hscale;
+      c->arrive[0] = 0;
+    }
   }
 }
 
-template <int DT>
-static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const void* q,
-                                  const int32_t* seq_lens, int extra, float* scores, int units, int n_kv_heads,
+template <int DT, bool HIST>
+static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
+                                  const void* q, const int32_t* seq_lens, int extra, float* scores, UnitCtl* ctl,
+                                  uint32_t* ghist, const int32_t* budgets, int max_budget, int units, int n_kv_heads,
                                   int max_ctx, hipStream_t st) {
-  const int n_pairs = max_ctx / kPair;
-  dim3 grid((n_pairs + 4 * kScorePairsPerWave - 1) / (4 * kScorePairsPerWave), units);
-#define FIER_SCORE_CASE(R)                                                                                     \
-  case R:                                                                                                      \
-    score_kernel<DT, R><<<grid, 256, 0, st>>>((const uint64_t*)kbits, (const uint4*)kmeta, (const uint16_t*)q, \
-                                              seq_lens, extra, scores, n_kv_heads, max_ctx);                   \
+  dim3 grid((max_ctx + kRangeTokens - 1) / kRangeTokens, units);
+#define FIER_SCORE_CASE(R)                                                                                        \
+  case R:                                                                                                         \
+    score_kernel<DT, R, HIST><<<grid, 256, 0, st>>>((const uint4*)kbits, (const uint4*)kmeta, kabsmax,            \
+                                                    (const uint16_t*)q, seq_lens, extra, scores, ctl, ghist,      \
+                                                    budgets, max_budget, n_kv_heads, max_ctx);                    \
     break;
   switch (n_rep) {
     FIER_SCORE_CASE(1)
@@ -161,12 +269,22 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
   return hipGetLastError();
 }
 
-hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const void* q,
-                        const int32_t* seq_lens, int extra, float* scores, int units, int n_kv_heads, int max_ctx,
+hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
+                        const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
+                        const int32_t* budgets, int max_budget, int units, int n_kv_heads, int max_ctx,
                         hipStream_t st) {
+  if (sb) {
+    if (dtype == DT_F16)
+      return launch_score_dt<DT_F16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb->ctl, sb->hist,
+                                           budgets, max_budget, units, n_kv_heads, max_ctx, st);
+    return launch_score_dt<DT_BF16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb->ctl, sb->hist,
+                                          budgets, max_budget, units, n_kv_heads, max_ctx, st);
+  }
   if (dtype == DT_F16)
-    return launch_score_dt<DT_F16>(n_rep, kbits, kmeta, q, seq_lens, extra, scores, units, n_kv_heads, max_ctx, st);
-  return launch_score_dt<DT_BF16>(n_rep, kbits, kmeta, q, seq_lens, extra, scores, units, n_kv_heads, max_ctx, st);
+    return launch_score_dt<DT_F16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
+                                          nullptr, 0, units, n_kv_heads, max_ctx, st);
+  return launch_score_dt<DT_BF16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
+                                         nullptr, 0, units, n_kv_heads, max_ctx, st);
 }
 
 }  // namespace fier

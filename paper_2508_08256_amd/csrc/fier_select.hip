@@ -1,0 +1,283 @@
+// Second kernel of the fused decode step: exact top-B threshold per unit (Alg. 1 step 3).
+//
+// The score kernel has left, per unit, the histogram bin `tbin` that contains the B-th largest score and
+// the number of scores in bins above it.  Here every workgroup re-reads 4096 scores of its unit and
+//   * counts, per 1024-token range, the tokens in bins above tbin (they are selected for certain);
+//   * writes the tokens that fall into tbin itself -- the only candidates for the threshold, about 1 % of
+//     the tokens for bell-shaped scores -- as (key, index) pairs into its own candidate segment.
+// The unit's last workgroup gathers the segments into LDS, histograms the candidates once more inside the
+// threshold bin (1024 sub-bins), ranks the handful of members of the decisive sub-bin pairwise (larger key
+// first, equal keys by lower index), which fixes the threshold key T and the last selected index idxT among
+// equal keys, and turns the per-range counts into the exclusive offsets at which the next kernel writes the
+// ascending index list.  If the candidates do not fit (scores clustered far more tightly than the a-priori
+// range resolves), the last workgroup falls back to a radix selection streamed over the unit's scores.
+#include "fier_dev.h"
+#include "fier_kernels.h"
+
+namespace fier {
+
+constexpr int kThrThreads = 1024;
+constexpr int kThrWaves = kThrThreads / 64;
+constexpr int kMaxRanges = (1 << 20) / kRangeTokens;  // max_ctx <= 2^20
+constexpr int kSpecCand = 64;                          // candidates per segment fetched before its count is known
+
+__device__ __forceinline__ float key_score(uint32_t key) {
+  const uint32_t u = key ^ ((key >> 31) ? 0x80000000u : 0xffffffffu);
+  return __uint_as_float(u);
+}
+
+// grid (ceil(max_ctx / 4096), units), block 1024
+__global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __restrict__ scores,
+                                                                const int32_t* __restrict__ seq_lens, int extra,
+                                                                UnitCtl* __restrict__ ctl,
+                                                                uint32_t* __restrict__ range_cnt,
+                                                                unsigned long long* __restrict__ cand,
+                                                                uint32_t* __restrict__ seg_cnt,
+                                                                int32_t* __restrict__ count_out, int n_ranges,
+                                                                int n_chunks, int n_kv_heads, int max_ctx) {
+  __shared__ uint32_t wsum[kThrWaves];
+  __shared__ uint32_t flag;
+  __shared__ uint32_t scan_tmp[kThrWaves];
+  __shared__ uint32_t hist[kSubBins];
+  __shared__ uint32_t res[2];
+  __shared__ uint32_t n_local;
+  __shared__ uint32_t n_sub;
+  __shared__ unsigned long long lcand[kSelCandMax];
+  __shared__ unsigned long long sub_list[kSubCandMax];
+  __shared__ uint32_t rsel[kMaxRanges];
+  __shared__ uint32_t seg_base[kThrThreads];  // one workgroup per 4096 tokens: at most 256 segments
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int b = unit / n_kv_heads;
+  int n = seq_lens[b] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  if (chunk * kClassifyTokens >= n && chunk != 0) return;
+  UnitCtl* __restrict__ c = &ctl[unit];
+  const int tbin = c->tbin;
+  const float R = c->R, scale = c->scale;
+  const float* __restrict__ s = scores + (size_t)unit * max_ctx;
+  unsigned long long* __restrict__ ucand = cand + (size_t)unit * n_chunks * kSegCand;
+  uint32_t* __restrict__ useg = seg_cnt + (size_t)unit * n_chunks;
+  uint32_t* __restrict__ urange = range_cnt + (size_t)unit * n_ranges;
+
+  // ---- classify this workgroup's 4096 scores -------------------------------------------------------
+  const int i = chunk * kClassifyTokens + 4 * tid;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n) v = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx; entries >= n are masked below
+  if (tid == 0) n_local = 0;
+  __syncthreads();
+  const float vv[4] = {v.x, v.y, v.z, v.w};
+  uint32_t n_gt = 0, n_c = 0;
+  bool is_c[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const bool ok = i + j < n;
+    const int bin = sel_bin(vv[j], R, scale, kSelBins);
+    n_gt += ok && bin > tbin;
+    is_c[j] = ok && bin == tbin;
+    n_c += is_c[j];
+  }
+  // selected-for-certain count of each 1024-token range (4 wavefronts per range)
+  uint32_t g = n_gt;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) g += __shfl_xor(g, d, 64);
+  if (lane == 0) wsum[wave] = g;
+  // candidates go to this workgroup's own segment; the slot comes from an LDS counter
+  if (n_c) {
+    uint32_t pos = atomicAdd(&n_local, n_c);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (is_c[j]) {
+        if (pos < (uint32_t)kSegCand)
+          store_coherent(&ucand[(size_t)chunk * kSegCand + pos],
+                         ((unsigned long long)score_key(vv[j]) << 32) | (uint32_t)(i + j));
+        ++pos;
+      }
+  }
+  __syncthreads();
+  if (tid < 4) {
+    const int r = chunk * 4 + tid;
+    if (r < n_ranges)
+      store_coherent(&urange[r], wsum[4 * tid] + wsum[4 * tid + 1] + wsum[4 * tid + 2] + wsum[4 * tid + 3]);
+  }
+  if (tid == 4) store_coherent(&useg[chunk], n_local);
+  const int nc = n > 0 ? (n + kClassifyTokens - 1) / kClassifyTokens : 1;  // workgroups of this unit
+  if (!last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) return;
+
+  // ---- the unit's last workgroup: exact threshold ------------------------------------------------------
+  const int nr = (n + kRangeTokens - 1) / kRangeTokens;  // ranges in use (<= n_ranges)
+  const int B = c->budget;
+  const bool need_threshold = tbin >= 0 && tbin < kSelBins && B > 0;
+  // segment sizes, and the first candidates of every segment in the same round trip
+  uint32_t my_cnt = 0;
+  if (tid < nc) my_cnt = load_coherent(&useg[tid]);
+  unsigned long long spec = 0;
+  const int sseg = tid / kSpecCand, sk = tid % kSpecCand;
+  if (need_threshold && sseg < nc) spec = load_coherent(&ucand[(size_t)sseg * kSegCand + sk]);
+  for (int r = tid; r < nr; r += kThrThreads) rsel[r] = 0;
+  // exclusive scan of the segment sizes (nc <= 256 for max_ctx <= 2^20; thread t < nc holds segment t)
+  bool overflow = false;
+  uint32_t total_cand;
+  {
+    const uint32_t capped = my_cnt > (uint32_t)kSegCand ? (uint32_t)kSegCand : my_cnt;
+    const uint32_t before = block_excl_scan_u32<kThrWaves>(capped, scan_tmp, total_cand);
+    if (tid < nc) seg_base[tid] = before;
+    overflow = __syncthreads_or(my_cnt > (uint32_t)kSegCand) || total_cand > (uint32_t)kSelCandMax;
+  }
+  uint32_t T = 0;
+  int32_t idxT = -1;
+  if (need_threshold) {
+    const uint32_t r_want = (uint32_t)B - c->above;  // candidates to take, >= 1
+    bool done = false;
+    if (!overflow) {
+      // gather the segments into LDS
+      if (sseg < nc) {
+        const uint32_t cnt_s = load_coherent(&useg[sseg]);  // hits the line fetched above
+        if ((uint32_t)sk < cnt_s) lcand[seg_base[sseg] + sk] = spec;
+      }
+      for (int sg = 0; sg < nc; ++sg) {
+        const uint32_t cnt_s = load_coherent(&useg[sg]);
+        const bool prefetched = sg < kThrThreads / kSpecCand;  // its first kSpecCand entries are already in LDS
+        for (uint32_t k = (prefetched ? kSpecCand : 0) + tid; k < cnt_s; k += kThrThreads)
+          lcand[seg_base[sg] + k] = load_coherent(&ucand[(size_t)sg * kSegCand + k]);
+      }
+      for (int k = tid; k < kSubBins; k += kThrThreads) hist[k] = 0;
+      if (tid == 0) n_sub = 0;
+      __syncthreads();
+      // second-level histogram inside the threshold bin
+      const float lo_b = (float)tbin / scale - R;
+      const float scale2 = scale * (float)kSubBins;
+      for (uint32_t k = tid; k < total_cand; k += kThrThreads) {
+        const float x = key_score((uint32_t)(lcand[k] >> 32));
+        atomicAdd(&hist[sel_bin(x, -lo_b, scale2, kSubBins)], 1u);
+      }
+      __syncthreads();
+      // sub-bin t with (count in sub-bins > t) < r_want <= (count in sub-bins >= t); thread t owns sub-bin 1023 - t
+      {
+        const uint32_t cnt = hist[kSubBins - 1 - tid];
+        uint32_t total;
+        const uint32_t before = block_excl_scan_u32<kThrWaves>(cnt, scan_tmp, total);
+        if (before < r_want && r_want <= before + cnt) {
+          res[0] = (uint32_t)(kSubBins - 1 - tid);
+          res[1] = before;
+        }
+        __syncthreads();
+      }
+      const int tsub = (int)res[0];
+      const uint32_t r2 = r_want - res[1];  // rank wanted inside the sub-bin, 1-based
+      const uint32_t n_in_sub = hist[tsub];
+      if (n_in_sub <= (uint32_t)kSubCandMax) {
+        for (uint32_t k = tid; k < total_cand; k += kThrThreads) {
+          const unsigned long long e = lcand[k];
+          const int sb = sel_bin(key_score((uint32_t)(e >> 32)), -lo_b, scale2, kSubBins);
+          if (sb > tsub) atomicAdd(&rsel[(uint32_t)e / kRangeTokens], 1u);
+          if (sb == tsub) sub_list[atomicAdd(&n_sub, 1u)] = e;
+        }
+        __syncthreads();
+        // rank the members of the decisive sub-bin: larger key first, equal keys by lower index
+        if ((uint32_t)tid < n_in_sub) {
+          const unsigned long long me = sub_list[tid];
+          const uint32_t mk = (uint32_t)(me >> 32), mi = (uint32_t)me;
+          uint32_t rank = 0;
+          for (uint32_t j = 0; j < n_in_sub; ++j) {
+            const unsigned long long o = sub_list[j];
+            const uint32_t ok = (uint32_t)(o >> 32), oi = (uint32_t)o;
+            rank += (ok > mk) || (ok == mk && oi < mi);
+          }
+          if (rank < r2) atomicAdd(&rsel[mi / kRangeTokens], 1u);
+          if (rank == r2 - 1) {
+            res[0] = mk;
+            res[1] = mi;
+          }
+        }
+        __syncthreads();
+        T = res[0];
+        idxT = (int32_t)res[1];
+        done = true;
+      }
+    }
+    if (!done) {
+      // ---- fallback: radix select over the unit's scores restricted to the threshold bin ------------
+      for (int r = tid; r < nr; r += kThrThreads) rsel[r] = 0;
+      uint32_t prefix = 0, mask = 0, r = r_want;
+#pragma unroll 1
+      for (int pass = 3; pass >= 0; --pass) {
+        const int shift = 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int k = tid; k < n; k += kThrThreads) {
+          const float x = s[k];
+          const uint32_t key = score_key(x);
+          if (sel_bin(x, R, scale, kSelBins) == tbin && (key & mask) == prefix)
+            atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        // digit d with (count of digits > d) < r <= (count of digits >= d): thread t owns digit 255 - t
+        const uint32_t cnt = tid < 256 ? hist[255 - tid] : 0;
+        uint32_t total;
+        const uint32_t before = block_excl_scan_u32<kThrWaves>(cnt, scan_tmp, total);
+        if (tid < 256 && before < r && r <= before + cnt) {
+          res[0] = 255u - (uint32_t)tid;
+          res[1] = before;
+        }
+        __syncthreads();
+        prefix |= res[0] << shift;
+        mask |= 0xffu << shift;
+        r -= res[1];
+        __syncthreads();
+      }
+      T = prefix;  // r = how many tokens with key == T (inside tbin) are selected: the lowest indices
+      // ordered pass: idxT = index of the r-th token with key == T; count selected candidates per range
+      uint32_t run_eq = 0;
+      for (int k0 = 0; k0 < n; k0 += kThrThreads) {
+        const int k = k0 + tid;
+        bool eq = false, gt = false;
+        if (k < n) {
+          const float x = s[k];
+          const uint32_t key = score_key(x);
+          const bool in_bin = sel_bin(x, R, scale, kSelBins) == tbin;
+          eq = in_bin && key == T;
+          gt = in_bin && key > T;
+        }
+        uint32_t total;
+        const uint32_t before = run_eq + block_excl_scan_u32<kThrWaves>(eq ? 1u : 0u, scan_tmp, total);
+        if (gt || (eq && before < r)) atomicAdd(&rsel[k / kRangeTokens], 1u);
+        if (eq && before == r - 1) res[1] = (uint32_t)k;
+        run_eq += total;
+      }
+      __syncthreads();
+      idxT = (int32_t)res[1];
+    }
+  }
+  __syncthreads();
+  // ---- offsets of the ranges in the ascending index list ------------------------------------------------
+  uint32_t run = 0;
+  for (int r0 = 0; r0 < nr; r0 += kThrThreads) {
+    const int r = r0 + tid;
+    const uint32_t cnt = r < nr ? load_coherent(&urange[r]) + rsel[r] : 0;
+    uint32_t total;
+    const uint32_t before = run + block_excl_scan_u32<kThrWaves>(cnt, scan_tmp, total);
+    if (r < nr) urange[r] = before;
+    run += total;
+  }
+  if (tid == 0) {
+    c->T = T;
+    c->idxT = idxT;
+    c->arrive[1] = 0;
+    if (count_out) count_out[unit] = B;
+  }
+}
+
+hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, int32_t* count_out, int units,
+                            int n_kv_heads, int max_ctx, hipStream_t st) {
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  const int n_chunks = (max_ctx + kClassifyTokens - 1) / kClassifyTokens;
+  dim3 grid(n_chunks, units);
+  threshold_kernel<<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.range_cnt, sb.cand, sb.seg_cnt,
+                                                 count_out, n_ranges, n_chunks, n_kv_heads, max_ctx);
+  return hipGetLastError();
+}
+
+}  // namespace fier

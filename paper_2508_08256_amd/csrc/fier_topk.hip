@@ -15,19 +15,17 @@
 #include "fier_dev.h"
 #include "fier_kernels.h"
 
+// Optional phase time stamps for kernel tuning; compiled out of the library.
+#ifndef FIER_PROF
+#define FIER_PROF(k)
+#endif
+
 namespace fier {
 
 constexpr int kTkThreads = 1024;
 constexpr int kTkWaves = kTkThreads / 64;
 constexpr int kTkBins = 2048;
 constexpr int kTkCandMax = 8192;
-
-// order-preserving map binary32 -> uint32 (larger score <=> larger key); -0 and +0 share a key
-__device__ __forceinline__ uint32_t score_key(float v) {
-  v += 0.0f;
-  uint32_t u = __float_as_uint(v);
-  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
-}
 
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
 #pragma unroll
@@ -93,20 +91,55 @@ __device__ __forceinline__ void find_bin_from_top(const uint32_t* hist, int nb, 
   above = (uint32_t)res[1];
 }
 
+// bin of the equal-width histogram; monotone non-decreasing in v
+__device__ __forceinline__ int value_bin(float v, float lo, float scale) {
+  int bin = (int)((v - lo) * scale);
+  return bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
+}
+
+// Visit the unit's scores as 16-byte chunks: chunk c of thread tid covers tokens (c * 1024 + tid) * 4 .. + 3.
+// NV > 0: the chunks were loaded into registers once; NV == 0: they are streamed from memory on every visit.
+// Entries at or past n hold unspecified data: the visitor masks them with the token index.
+template <int NV, class F>
+__device__ __forceinline__ void for_chunks(const float4 (&regs)[NV > 0 ? NV : 1], const float* __restrict__ s, int n,
+                                           int max_ctx, F&& f) {
+  const int tid = threadIdx.x;
+  if constexpr (NV > 0) {
+#pragma unroll
+    for (int c = 0; c < NV; ++c)
+      if (c * 4 * kTkThreads < n) f(c, regs[c], (c * kTkThreads + tid) * 4);
+  } else {
+    const int nch = (n + 4 * kTkThreads - 1) / (4 * kTkThreads);
+#pragma unroll 4
+    for (int c = 0; c < nch; ++c) {
+      const int i = (c * kTkThreads + tid) * 4;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < max_ctx) v = *reinterpret_cast<const float4*>(s + i);
+      f(c, v, i);
+    }
+  }
+}
+
+// NV > 0: register-resident variant for max_ctx <= NV * 4096; NV == 0: streaming variant for any length.
+template <int NV>
 __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restrict__ scores,
                                                           const int32_t* __restrict__ seq_lens, int extra,
                                                           const int32_t* __restrict__ budgets, int max_budget,
                                                           int32_t* __restrict__ idx, int32_t* __restrict__ count,
                                                           int n_kv_heads, int max_ctx) {
+  constexpr int NVR = NV > 0 ? NV : 1;
   __shared__ uint32_t hist[kTkBins];
   __shared__ uint32_t cand[kTkCandMax];
   __shared__ uint32_t scan_tmp[kTkWaves + 1];
   __shared__ float red_tmp[kTkWaves];
   __shared__ int res[2];
   __shared__ uint32_t n_cand_sh;
+  __shared__ uint32_t thr_sh[2];
+  __shared__ uint32_t wtot[NVR * kTkWaves];
+  __shared__ uint32_t offg[NVR * kTkWaves], offe[NVR * kTkWaves];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
+  const int lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.x;
   const int b = unit / n_kv_heads;
   int n = seq_lens[b] + extra;
@@ -126,16 +159,33 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     return;
   }
 
+  FIER_PROF(0)
+  float4 regs[NVR];
+  if constexpr (NV > 0) {
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+      const int i = (c * kTkThreads + tid) * 4;
+      regs[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c * 4 * kTkThreads < n && i < max_ctx) regs[c] = *reinterpret_cast<const float4*>(s + i);
+    }
+  }
+
+  FIER_PROF(1)
   // ---- 1. range of the scores ----------------------------------------------------------------
   float lo = INFINITY, hi = -INFINITY;
-  for (int i = tid; i < n; i += kTkThreads) {
-    const float v = s[i];
-    lo = fminf(lo, v);
-    hi = fmaxf(hi, v);
-  }
+  for_chunks<NV>(regs, s, n, max_ctx, [&](int, const float4 v, int i) {
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (i + j < n) {
+        lo = fminf(lo, vv[j]);
+        hi = fmaxf(hi, vv[j]);
+      }
+  });
   lo = block_minmax<false>(lo, red_tmp);
   hi = block_minmax<true>(hi, red_tmp);
 
+  FIER_PROF(2)
   uint32_t T;      // threshold key
   uint32_t r_eq;   // how many tokens with key == T are selected (the lowest indices)
   if (!(hi > lo)) {
@@ -147,12 +197,14 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     for (int i = tid; i < kTkBins; i += kTkThreads) hist[i] = 0;
     if (tid == 0) n_cand_sh = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += kTkThreads) {
-      int bin = (int)((s[i] - lo) * scale);
-      bin = bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
-      atomicAdd(&hist[bin], 1u);
-    }
+    for_chunks<NV>(regs, s, n, max_ctx, [&](int, const float4 v, int i) {
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (i + j < n) atomicAdd(&hist[value_bin(vv[j], lo, scale)], 1u);
+    });
     __syncthreads();
+    FIER_PROF(3)
     // ---- 3. threshold bin and its candidates -------------------------------------------------
     int tbin;
     uint32_t above;
@@ -161,105 +213,201 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     const uint32_t n_cand = hist[tbin];
     const bool in_lds = n_cand <= (uint32_t)kTkCandMax;
     __syncthreads();
+    FIER_PROF(4)
     if (in_lds) {
-      for (int i0 = 0; i0 < n; i0 += kTkThreads) {
-        const int i = i0 + tid;
-        bool is_c = false;
-        uint32_t key = 0;
-        if (i < n) {
-          const float v = s[i];
-          int bin = (int)((v - lo) * scale);
-          bin = bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
-          is_c = bin == tbin;
-          key = score_key(v);
+      for_chunks<NV>(regs, s, n, max_ctx, [&](int, const float4 v, int i) {
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+        bool is_c[4];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          is_c[j] = i + j < n && value_bin(vv[j], lo, scale) == tbin;
+          cnt += is_c[j];
         }
-        const uint64_t m = __ballot(is_c);
-        if (m) {
-          uint32_t base = 0;
-          if (lane == 0) base = atomicAdd(&n_cand_sh, (uint32_t)__popcll(m));
-          base = __shfl(base, 0, 64);
-          if (is_c) cand[base + __popcll(m & ((1ull << lane) - 1))] = key;
+        if (cnt) {
+          uint32_t pos = atomicAdd(&n_cand_sh, cnt);
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (is_c[j]) cand[pos++] = score_key(vv[j]);
+        }
+      });
+      __syncthreads();
+    }
+    FIER_PROF(5)
+    if (n_cand <= 512u) {
+      // ---- 4a. few candidates: rank each one against all others ------------------------------
+      if ((uint32_t)tid < n_cand) {
+        const uint32_t key = cand[tid];
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t j = 0; j < n_cand; ++j) {
+          const uint32_t o = cand[j];
+          gt += o > key;
+          ge += o >= key;
+        }
+        if (gt < r && r <= ge) {  // every thread holding the threshold value writes the same pair
+          thr_sh[0] = key;
+          thr_sh[1] = r - gt;
         }
       }
       __syncthreads();
-    }
-    // ---- 4. exact radix select of the r-th largest candidate key -----------------------------
-    uint32_t prefix = 0, mask = 0;
+      T = thr_sh[0];
+      r_eq = thr_sh[1];
+    } else {
+      // ---- 4b. exact radix select of the r-th largest candidate key --------------------------
+      uint32_t prefix = 0, mask = 0;
 #pragma unroll 1
-    for (int pass = 3; pass >= 0; --pass) {
-      const int shift = 8 * pass;
-      for (int i = tid; i < 256; i += kTkThreads) hist[i] = 0;
-      __syncthreads();
-      if (in_lds) {
-        for (uint32_t i = tid; i < n_cand; i += kTkThreads) {
-          const uint32_t key = cand[i];
-          if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      for (int pass = 3; pass >= 0; --pass) {
+        const int shift = 8 * pass;
+        for (int i = tid; i < 256; i += kTkThreads) hist[i] = 0;
+        __syncthreads();
+        if (in_lds) {
+          for (uint32_t i = tid; i < n_cand; i += kTkThreads) {
+            const uint32_t key = cand[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+          }
+        } else {  // more candidates than LDS holds (heavily clustered scores): stream them from memory
+          for (int i = tid; i < n; i += kTkThreads) {
+            const float v = s[i];
+            const uint32_t key = score_key(v);
+            if (value_bin(v, lo, scale) == tbin && (key & mask) == prefix)
+              atomicAdd(&hist[(key >> shift) & 255u], 1u);
+          }
         }
-      } else {  // more candidates than LDS holds (heavily clustered scores): stream them from memory
-        for (int i = tid; i < n; i += kTkThreads) {
-          const float v = s[i];
-          int bin = (int)((v - lo) * scale);
-          bin = bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
-          const uint32_t key = score_key(v);
-          if (bin == tbin && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
-        }
+        __syncthreads();
+        int dbin;
+        uint32_t dabove;
+        find_bin_from_top(hist, 256, r, scan_tmp, res, dbin, dabove);
+        r -= dabove;
+        prefix |= (uint32_t)dbin << shift;
+        mask |= 0xffu << shift;
+        __syncthreads();
       }
-      __syncthreads();
-      int dbin;
-      uint32_t dabove;
-      find_bin_from_top(hist, 256, r, scan_tmp, res, dbin, dabove);
-      r -= dabove;
-      prefix |= (uint32_t)dbin << shift;
-      mask |= 0xffu << shift;
-      __syncthreads();
+      T = prefix;
+      r_eq = r;
     }
-    T = prefix;
-    r_eq = r;
   }
 
+  FIER_PROF(6)
   // ---- 5. ordered emission ---------------------------------------------------------------------
-  uint32_t run_gt = 0, run_eq = 0;  // counts over all earlier tokens (uniform across the workgroup)
-  for (int i0 = 0; i0 < n; i0 += 4 * kTkThreads) {
-    const int i = i0 + 4 * tid;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i + 3 < n) {
-      v = *reinterpret_cast<const float4*>(s + i);
-    } else {
-      if (i < n) v.x = s[i];
-      if (i + 1 < n) v.y = s[i + 1];
-      if (i + 2 < n) v.z = s[i + 2];
-    }
-    const float vv[4] = {v.x, v.y, v.z, v.w};
-    uint32_t gt[4], eq[4], cg = 0, ce = 0;
+  // token order = (chunk, thread, element).  A token is selected iff key > T, or key == T and fewer than
+  // r_eq equal keys precede it; its output slot is the number of selected tokens before it.
+  if constexpr (NV > 0) {
+    // all chunks at once: per-wave scans of every chunk's counts, one scan over the (chunk, wave) totals
+    uint32_t cnt[NV], incl[NV];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t key = score_key(vv[j]);
-      const bool ok = i + j < n;
-      gt[j] = ok && key > T;
-      eq[j] = ok && key == T;
-      cg += gt[j];
-      ce += eq[j];
-    }
-    uint32_t total;
-    const uint32_t ex = block_excl_scan(cg | (ce << 16), scan_tmp, total);
-    uint32_t g_before = run_gt + (ex & 0xffffu);
-    uint32_t e_before = run_eq + (ex >> 16);
+    for (int c = 0; c < NV; ++c) {
+      const int i = (c * kTkThreads + tid) * 4;
+      const float vv[4] = {regs[c].x, regs[c].y, regs[c].z, regs[c].w};
+      uint32_t cg = 0, ce = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (gt[j] || (eq[j] && e_before < r_eq)) out[g_before + (e_before < r_eq ? e_before : r_eq)] = i + j;
-      g_before += gt[j];
-      e_before += eq[j];
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t key = score_key(vv[j]);
+        const bool ok = i + j < n;
+        cg += ok && key > T;
+        ce += ok && key == T;
+      }
+      cnt[c] = cg | (ce << 16);
+      incl[c] = wave_incl_scan(cnt[c], lane);
     }
-    run_gt += total & 0xffffu;
-    run_eq += total >> 16;
+    if (lane == 63) {
+#pragma unroll
+      for (int c = 0; c < NV; ++c) wtot[c * kTkWaves + wave] = incl[c];
+    }
+    __syncthreads();
+    if (wave == 0) {
+      constexpr int ENT = NV * kTkWaves;
+      constexpr int PER = (ENT + 63) / 64;
+      uint32_t g[PER], e[PER], sg = 0, se = 0;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int ent = lane * PER + k;
+        const uint32_t w = ent < ENT ? wtot[ent] : 0;
+        g[k] = w & 0xffffu;
+        e[k] = w >> 16;
+        sg += g[k];
+        se += e[k];
+      }
+      uint32_t pg = wave_incl_scan(sg, lane) - sg, pe = wave_incl_scan(se, lane) - se;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int ent = lane * PER + k;
+        if (ent < ENT) {
+          offg[ent] = pg;
+          offe[ent] = pe;
+        }
+        pg += g[k];
+        pe += e[k];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+      if (c * 4 * kTkThreads >= n) continue;
+      const int i = (c * kTkThreads + tid) * 4;
+      const float vv[4] = {regs[c].x, regs[c].y, regs[c].z, regs[c].w};
+      const uint32_t ex = incl[c] - cnt[c];
+      uint32_t g_before = offg[c * kTkWaves + wave] + (ex & 0xffffu);
+      uint32_t e_before = offe[c * kTkWaves + wave] + (ex >> 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t key = score_key(vv[j]);
+        const bool ok = i + j < n;
+        const bool gt = ok && key > T, eq = ok && key == T;
+        if (gt || (eq && e_before < r_eq)) out[g_before + (e_before < r_eq ? e_before : r_eq)] = i + j;
+        g_before += gt;
+        e_before += eq;
+      }
+    }
+  } else {
+    uint32_t run_gt = 0, run_eq = 0;  // counts over all earlier tokens (uniform across the workgroup)
+    for (int i0 = 0; i0 < n; i0 += 4 * kTkThreads) {
+      const int i = i0 + 4 * tid;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < max_ctx) v = *reinterpret_cast<const float4*>(s + i);
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+      uint32_t gt[4], eq[4], cg = 0, ce = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t key = score_key(vv[j]);
+        const bool ok = i + j < n;
+        gt[j] = ok && key > T;
+        eq[j] = ok && key == T;
+        cg += gt[j];
+        ce += eq[j];
+      }
+      uint32_t total;
+      const uint32_t ex = block_excl_scan(cg | (ce << 16), scan_tmp, total);
+      uint32_t g_before = run_gt + (ex & 0xffffu);
+      uint32_t e_before = run_eq + (ex >> 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (gt[j] || (eq[j] && e_before < r_eq)) out[g_before + (e_before < r_eq ? e_before : r_eq)] = i + j;
+        g_before += gt[j];
+        e_before += eq[j];
+      }
+      run_gt += total & 0xffffu;
+      run_eq += total >> 16;
+    }
   }
+  FIER_PROF(7)
 }
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
                        int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,
                        hipStream_t st) {
-  topk_kernel<<<units, kTkThreads, 0, st>>>(scores, seq_lens, extra, budgets, max_budget, idx, count, n_kv_heads,
-                                            max_ctx);
+#define FIER_TOPK(NV)                                                                                           \
+  topk_kernel<NV><<<units, kTkThreads, 0, st>>>(scores, seq_lens, extra, budgets, max_budget, idx, count, \
+                                                n_kv_heads, max_ctx)
+  const int chunks = (max_ctx + 4 * kTkThreads - 1) / (4 * kTkThreads);
+  if (chunks <= 2)
+    FIER_TOPK(2);
+  else if (chunks <= 4)
+    FIER_TOPK(4);
+  else if (chunks <= 9)
+    FIER_TOPK(9);
+  else
+    FIER_TOPK(0);
+#undef FIER_TOPK
   return hipGetLastError();
 }
 

@@ -36,6 +36,4 @@ class DeviceWorkload:
         self.cache = B.DeviceCache(self.cfg, self.K, self.V, self.seq_lens)
 
     def workspace(self, max_budget):
-        n = B.workspace_bytes(self.cfg, max_budget)
-        assert n > 0
-        return torch.empty(n, dtype=torch.uint8, device="cuda")
+        return B.make_workspace(self.cfg, max_budget)

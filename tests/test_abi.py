@@ -56,12 +56,12 @@ def test_packed_size_is_one_eighth_of_the_key_cache():
 def test_calls_reject_bad_arguments_before_any_launch():
     lib = B.lib()
     cfg = B.make_config(1, 8, 8, 256)
-    cache = B.Cache(0, 0, 0, 0, 0)
+    cache = B.Cache(0, 0, 0, 0, 0, 0)
     assert lib.fier_quantize_keys(C.byref(cfg), C.byref(cache), None) == B.EINVAL
     assert lib.fier_quantize_keys(None, C.byref(cache), None) == B.EINVAL
-    cache = B.Cache(0x1000, 0x2008, 0x3000, 0x4000, 0x5000)
+    cache = B.Cache(0x1000, 0x2008, 0x3000, 0x4000, 0x4800, 0x5000)
     assert lib.fier_quantize_keys(C.byref(cfg), C.byref(cache), None) == B.EALIGN
-    good = B.Cache(0x1000, 0x2000, 0x3000, 0x4000, 0x5000)
+    good = B.Cache(0x1000, 0x2000, 0x3000, 0x4000, 0x4800, 0x5000)
     assert lib.fier_append_key(C.byref(cfg), C.byref(good), None, None, None) == B.EINVAL
     assert lib.fier_score(C.byref(cfg), C.byref(good), 0x6000, 2, 0x7000, None) == B.EINVAL
     assert lib.fier_score(C.byref(cfg), C.byref(good), 0x6004, 0, 0x7000, None) == B.EALIGN
@@ -81,16 +81,16 @@ def test_calls_reject_bad_arguments_before_any_launch():
 
 
 def test_unpack_helpers_follow_the_documented_layout():
-    """word (P, c, h) bit i <-> token 64 P + 32 h + i, channel c;  meta word = s | z << 16."""
+    """bit i of word d of a token <-> channel 64 (d & 1) + 2 i + (d >> 1);  meta word = s | z << 16."""
     cfg = B.make_config(1, 2, 2, 128)
     lib = B.lib()
     rng = np.random.default_rng(0)
     bits = rng.integers(0, 2, (cfg.units, cfg.max_ctx, 128)).astype(np.uint8)
-    packed = np.zeros((cfg.units, cfg.max_ctx // 64, 128, 2), np.uint32)
-    for u in range(cfg.units):
-        for t in range(cfg.max_ctx):
-            P, h, i = t // 64, (t % 64) // 32, t % 32
-            packed[u, P, :, h] |= bits[u, t].astype(np.uint32) << np.uint32(i)
+    packed = np.zeros((cfg.units, cfg.max_ctx, 4), np.uint32)
+    for c in range(128):
+        d = (c // 64) + 2 * (c % 2)
+        i = (c % 64) // 2
+        packed[:, :, d] |= bits[:, :, c].astype(np.uint32) << np.uint32(i)
     got = np.zeros_like(bits)
     lib.fier_unpack_bits(C.byref(cfg), packed.ctypes.data_as(C.c_void_p), got.ctypes.data_as(C.c_void_p))
     assert np.array_equal(got, bits)
