@@ -74,6 +74,7 @@ Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
   w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * chunks * fier::kSegCand * sizeof(unsigned long long)));
   w.sb.seg_cnt = reinterpret_cast<uint32_t*>(take(units * chunks * sizeof(uint32_t)));
   w.sb.scores = reinterpret_cast<float*>(take(units * (size_t)c->max_ctx * sizeof(float)));
+  w.sb.newmax = reinterpret_cast<float*>(take(units * kD * sizeof(float)));
   w.sb.po = reinterpret_cast<float*>(take(heads * ranges * kD * sizeof(float)));
   w.sb.pm = reinterpret_cast<float*>(take(heads * ranges * sizeof(float)));
   w.sb.pl = reinterpret_cast<float*>(take(heads * ranges * sizeof(float)));
@@ -155,8 +156,9 @@ int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, i
   if (!q || !scores || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
   if (misaligned(q) || misaligned(scores)) return FIER_EALIGN;
   return hip_status(fier::launch_score(cfg->kv_dtype, n_rep_of(cfg), cache->kbits, cache->kmeta, cache->kabsmax, q,
-                                       cache->seq_lens, extra_tokens, scores, nullptr, nullptr, 0, units_of(cfg),
-                                       cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
+                                       cache->seq_lens, extra_tokens, scores, nullptr, nullptr, 0, nullptr, nullptr,
+                                       nullptr, nullptr, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
+                                       (hipStream_t)stream));
 }
 
 int fier_topk(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
@@ -233,20 +235,15 @@ int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n
     int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : w.idx;
     int32_t* cntl = count_out ? count_out + (size_t)l * units : nullptr;
     hipError_t e;
-    if (extra) {
-      const char* kn = static_cast<const char*>(k_new) + (size_t)l * units * kD * esz;
-      const char* vn = static_cast<const char*>(v_new) + (size_t)l * units * kD * esz;
-      e = fier::launch_append(cfg->kv_dtype, c->k, c->v, c->kbits, c->kmeta, c->kabsmax, c->seq_lens, kn, vn, units,
-                              cfg->n_kv_heads, cfg->max_ctx, s);
-      if (e != hipSuccess) return FIER_EHIP;
-    }
+    const char* kn = extra ? static_cast<const char*>(k_new) + (size_t)l * units * kD * esz : nullptr;
+    const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
     e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra, w.sb.scores,
-                           &w.sb, budgets, max_budget, units, cfg->n_kv_heads, cfg->max_ctx, s);
+                           &w.sb, budgets, max_budget, c->k, c->v, kn, vn, units, cfg->n_kv_heads, cfg->max_ctx, s);
     if (e != hipSuccess) return FIER_EHIP;
     e = fier::launch_threshold(w.sb, c->seq_lens, extra, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
     if (e != hipSuccess) return FIER_EHIP;
     e = fier::launch_select_attend(cfg->kv_dtype, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
-                                   cfg->sm_scale, idx_out ? idxl : nullptr, outl, units, cfg->n_kv_heads,
+                                   cfg->sm_scale, idx_out ? idxl : nullptr, outl, c->kabsmax, units, cfg->n_kv_heads,
                                    cfg->max_ctx, s);
     if (e != hipSuccess) return FIER_EHIP;
   }

@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ q,
     const int32_t* __restrict__ seq_lens, int extra, int max_budget, float scale_log2e, float* __restrict__ po,
     float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
-    int n_ranges, int n_kv_heads, int max_ctx) {
+    float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx) {
   __shared__ float sh_o[16][16][8 + 2];
   __shared__ int32_t rows[kRangeTokens];
   __shared__ uint32_t scan_tmp[4];
@@ -310,6 +310,12 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   for (int h = 0; h < NREP; ++h)
     merge_head(po, pm, pl, ((size_t)unit * NREP + h) * n_ranges, nr, sh, out + ((size_t)unit * NREP + h) * kD);
   if (tid == 0) c->arrive[2] = 0;
+  // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
+  if (extra && seq_lens[b] < max_ctx && tid < kD) {
+    float* slot = kabsmax + (size_t)unit * kD + tid;
+    const float a = newmax[(size_t)unit * kD + tid];
+    if (a > *slot) *slot = a;
+  }
 }
 
 // grid (units * n_rep), block 128: thread c merges channel c of one query head over the splits in use.
@@ -380,8 +386,8 @@ static hipError_t launch_attn_dt(int n_rep, const void* K, const void* V, const 
 template <int DT>
 static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                           const void* q, const int32_t* seq_lens, int extra, int max_budget,
-                                          float sm_scale, int32_t* idx_out, float* out, int units, int n_kv_heads,
-                                          int max_ctx, hipStream_t st) {
+                                          float sm_scale, int32_t* idx_out, float* out, float* kabsmax, int units,
+                                          int n_kv_heads, int max_ctx, hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   dim3 grid(n_ranges, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
@@ -389,8 +395,8 @@ static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, cons
   case R:                                                                                                           \
     select_attend_kernel<DT, R><<<grid, 256, 0, st>>>(sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K,             \
                                                       (const uint4*)V, (const uint4*)q, seq_lens, extra, max_budget, \
-                                                      sl2, sb.po, sb.pm, sb.pl, idx_out, out, n_ranges, n_kv_heads, \
-                                                      max_ctx);                                                     \
+                                                      sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax,   \
+                                                      n_ranges, n_kv_heads, max_ctx);                               \
     break;
   switch (n_rep) {
     FIER_SA_CASE(1)
@@ -410,12 +416,13 @@ static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, cons
 
 hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
-                                int32_t* idx_out, float* out, int units, int n_kv_heads, int max_ctx, hipStream_t st) {
+                                int32_t* idx_out, float* out, float* kabsmax, int units, int n_kv_heads, int max_ctx,
+                                hipStream_t st) {
   if (dtype == DT_F16)
     return launch_select_attend_dt<DT_F16>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out,
-                                           units, n_kv_heads, max_ctx, st);
+                                           kabsmax, units, n_kv_heads, max_ctx, st);
   return launch_select_attend_dt<DT_BF16>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out,
-                                          units, n_kv_heads, max_ctx, st);
+                                          kabsmax, units, n_kv_heads, max_ctx, st);
 }
 
 hipError_t launch_attn(int dtype, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,

@@ -44,6 +44,7 @@ struct StepBuffers {    // carved from the caller's workspace
   unsigned long long* cand;  // [units][n_chunks][kSegCand] (key << 32 | token index), one segment per workgroup
   uint32_t* seg_cnt;    // [units][n_chunks] candidates found by each threshold-kernel workgroup
   float* scores;        // [units][max_ctx]
+  float* newmax;        // [units][128]: |dequantized key| bound of the group re-quantized by this step's append
   float* po;            // attention partials, n_slots per (unit, query head)
   float* pm;
   float* pl;
@@ -57,18 +58,20 @@ hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t*
                          int max_ctx, hipStream_t st);
 
 // With sb != nullptr the kernel also builds the per-unit score histogram and its last workgroup per unit
-// finds the threshold bin for budgets[b] (first kernel of the fused step).
+// finds the threshold bin for budgets[b] (first kernel of the fused step); with k_new != nullptr as well it
+// appends the new K/V rows first (extra must then be 1).
 hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
-                        const int32_t* budgets, int max_budget, int units, int n_kv_heads, int max_ctx,
-                        hipStream_t st);
+                        const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
+                        const void* v_new, int units, int n_kv_heads, int max_ctx, hipStream_t st);
 
 hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, int32_t* count_out, int units,
                             int n_kv_heads, int max_ctx, hipStream_t st);
 
 hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
-                                int32_t* idx_out, float* out, int units, int n_kv_heads, int max_ctx, hipStream_t st);
+                                int32_t* idx_out, float* out, float* kabsmax, int units, int n_kv_heads, int max_ctx,
+                                hipStream_t st);
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
                        int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,

@@ -22,6 +22,7 @@
 // position 27 + ((i - 27) mod 4).
 #include "fier_dev.h"
 #include "fier_kernels.h"
+#include "fier_quant_dev.h"
 
 namespace fier {
 
@@ -70,21 +71,36 @@ __device__ __forceinline__ void accumulate_from(const uint32_t (&V)[4][8], const
   }
 }
 
-// grid (ceil(max_ctx / 1024), units), block 256: workgroup x owns tokens [1024 x, 1024 x + 1024) of its unit,
-// wave w the pair blocks 16 x + w, + 4, + 8, + 12.
+__device__ __forceinline__ float wave_allsum(float x) {
+  x = row_allsum(x);
+  x += __shfl_xor(x, 16, 64);
+  x += __shfl_xor(x, 32, 64);
+  return x;
+}
+
+// grid (ceil(max_ctx / 1024) [+ 1 if HIST], units), block 256: workgroup x owns tokens [1024 x, 1024 x + 1024) of
+// its unit, wave w the pair blocks 16 x + w, + 4, + 8, + 12.
 //
 // HIST (first kernel of the fused step): every score is also counted in an equal-width histogram of kSelBins
 // bins over [-R, R], R = sum_c |q_c| * absmax_c >= |score| -- a bound known before any score exists, so that
 // scoring and histogramming are one pass.  The workgroup's LDS histogram is added to the unit's histogram in
 // memory; the unit's last workgroup reads the total, finds the bin that holds the budget-th largest score,
 // publishes it and clears the histogram for the next call.
+// The extra workgroup of a unit performs the decode-stage append (Sec. 3.1) when k_new is given: one wavefront
+// writes the new K/V rows, re-quantizes the group the row falls in and scores that group's tokens straight from
+// its registers; the other workgroups leave those tokens alone.  The bound R uses the absmax of before the
+// append (every workgroup must bin with the same R); the new group's contribution is handed to the last kernel
+// of the step through `newmax`.  A score outside [-R, R] simply lands in the outermost bin.
 template <int DT, int NREP, bool HIST>
-__global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kbits, const uint4* __restrict__ kmeta,
+__global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const uint4* kmeta,
                                                     const float* __restrict__ kabsmax, const uint16_t* __restrict__ q,
                                                     const int32_t* __restrict__ seq_lens, int extra,
                                                     float* __restrict__ scores, UnitCtl* __restrict__ ctl,
                                                     uint32_t* __restrict__ ghist, const int32_t* __restrict__ budgets,
-                                                    int max_budget, int n_kv_heads, int max_ctx) {
+                                                    int max_budget, uint32_t* K, uint32_t* V,
+                                                    const uint32_t* __restrict__ k_new,
+                                                    const uint32_t* __restrict__ v_new, float* __restrict__ newmax,
+                                                    int n_kv_heads, int max_ctx) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
   __shared__ uint32_t scan_tmp[4];
   __shared__ uint32_t flag;
@@ -95,10 +111,20 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kb
   const int wave = tid >> 6;
   const int unit = blockIdx.y;
   const int b = unit / n_kv_heads;
-  int L = seq_lens[b] + extra;
-  L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
-  // workgroup 0 of a unit always runs so that an empty unit still gets its control block written
-  if ((int)blockIdx.x * kRangeTokens >= L && !(HIST && blockIdx.x == 0)) return;
+  int Lold = seq_lens[b];
+  Lold = Lold < 0 ? 0 : (Lold > max_ctx ? max_ctx : Lold);
+  const bool app = HIST && k_new != nullptr && Lold < max_ctx;  // this unit receives a new row in this step
+  int L = HIST ? Lold + (app ? 1 : 0) : Lold + extra;
+  L = L > max_ctx ? max_ctx : L;
+  const int tail_start = app ? (Lold / kG) * kG : L;  // tokens from here on are scored by the appending wave
+  const int n_score_wgs = (int)gridDim.x - (HIST ? 1 : 0);
+  const bool append_wg = HIST && (int)blockIdx.x == n_score_wgs;
+  if (append_wg) {
+    if (!app) return;
+  } else {
+    // workgroup 0 of a unit always runs so that an empty unit still gets its control block written
+    if ((int)blockIdx.x * kRangeTokens >= L && !(HIST && blockIdx.x == 0)) return;
+  }
   const int n_groups = max_ctx / kG;
   const int row = lane >> 4, n = lane & 15;
 
@@ -106,8 +132,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kb
   // 2^-16: qz for the offsets, qx additionally times the inverse of the power of two its bit is tested at.
   float qx[8], qz[8];
   float R = 0.f, hscale = 0.f;
+  const uint16_t* qb = q + (size_t)unit * NREP * kD;
   {
-    const uint16_t* qb = q + (size_t)unit * NREP * kD;
     float rpart = 0.f;
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
@@ -131,8 +157,43 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kb
     }
   }
 
+  if (append_wg) {
+    if constexpr (HIST) {
+      if (wave == 0) {  // lane = channel pair (2 lane, 2 lane + 1)
+        const uint32_t kn = k_new[(size_t)unit * (kD / 2) + lane];
+        const uint32_t vn = v_new[(size_t)unit * (kD / 2) + lane];
+        GroupCode gc;
+        int t0, ntok;
+        append_row<DT>(K, V, const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
+                       const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kmeta)), unit, Lold, max_ctx, kn, vn,
+                       lane, gc, t0, ntok);
+        newmax[(size_t)unit * kD + 2 * lane] = gc.amax_lo;
+        newmax[(size_t)unit * kD + 2 * lane + 1] = gc.amax_hi;
+        float q0 = 0.f, q1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+          q0 += w2f<DT>(qb[r * kD + 2 * lane]);
+          q1 += w2f<DT>(qb[r * kD + 2 * lane + 1]);
+        }
+        const float w0 = q0 * gc.s_lo, w1 = q1 * gc.s_hi;
+        const float base = wave_allsum(q0 * gc.z_lo + q1 * gc.z_hi);
+        float mine = 0.f;
+#pragma unroll
+        for (int t = 0; t < kG; ++t) {
+          float v = ((gc.bits_lo >> t) & 1u ? w0 : 0.f) + ((gc.bits_hi >> t) & 1u ? w1 : 0.f);
+          v = wave_allsum(v);
+          if (lane == t) mine = v + base;
+        }
+        if (lane < ntok) {
+          scores[(size_t)unit * max_ctx + t0 + lane] = mine;
+          atomicAdd(&lhist[sel_bin(mine, R, hscale, kSelBins)], 1u);
+        }
+      }
+    }
+  }
+
   const int P0 = blockIdx.x * (4 * kScorePairsPerWave) + wave;  // this wave's blocks: P0, P0 + 4, ...
-  if (P0 * kPair < L) {
+  if (!append_wg && P0 * kPair < L) {
     const uint4* __restrict__ bits_u = kbits + (size_t)unit * max_ctx;
     const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
     const int gsel = row >> 1;
@@ -177,7 +238,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kb
       accumulate_from<0, 0>(V, X, acc);
       const float sc = (((acc[0] + acc[1]) + (acc[2] + acc[3])) + base) * 65536.0f;
       const int tok = P * kPair + lane;
-      if (tok < L) {
+      if (tok < L && tok < tail_start) {
         scores[(size_t)unit * max_ctx + tok] = sc;
         if (HIST) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
       }
@@ -194,7 +255,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kb
       const uint32_t c = lhist[i];
       if (c) atomicAdd(&gh[i], c);
     }
-    const uint32_t expected = L > 0 ? (uint32_t)((L + kRangeTokens - 1) / kRangeTokens) : 1u;
+    const uint32_t expected = (L > 0 ? (uint32_t)((L + kRangeTokens - 1) / kRangeTokens) : 1u) + (app ? 1u : 0u);
     if (!last_arriver(&ctl[unit].arrive[0], expected, &flag)) return;
     // ---- the unit's last workgroup: threshold bin for the budget ---------------------------------------
     int B = budgets[b];
@@ -243,15 +304,17 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* __restrict__ kb
 
 template <int DT, bool HIST>
 static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
-                                  const void* q, const int32_t* seq_lens, int extra, float* scores, UnitCtl* ctl,
-                                  uint32_t* ghist, const int32_t* budgets, int max_budget, int units, int n_kv_heads,
-                                  int max_ctx, hipStream_t st) {
-  dim3 grid((max_ctx + kRangeTokens - 1) / kRangeTokens, units);
-#define FIER_SCORE_CASE(R)                                                                                        \
-  case R:                                                                                                         \
-    score_kernel<DT, R, HIST><<<grid, 256, 0, st>>>((const uint4*)kbits, (const uint4*)kmeta, kabsmax,            \
-                                                    (const uint16_t*)q, seq_lens, extra, scores, ctl, ghist,      \
-                                                    budgets, max_budget, n_kv_heads, max_ctx);                    \
+                                  const void* q, const int32_t* seq_lens, int extra, float* scores,
+                                  const StepBuffers* sb, const int32_t* budgets, int max_budget, void* K, void* V,
+                                  const void* k_new, const void* v_new, int units, int n_kv_heads, int max_ctx,
+                                  hipStream_t st) {
+  dim3 grid((max_ctx + kRangeTokens - 1) / kRangeTokens + (HIST ? 1 : 0), units);
+#define FIER_SCORE_CASE(R)                                                                                         \
+  case R:                                                                                                          \
+    score_kernel<DT, R, HIST><<<grid, 256, 0, st>>>(                                                               \
+        (const uint4*)kbits, (const uint4*)kmeta, kabsmax, (const uint16_t*)q, seq_lens, extra, scores,            \
+        sb ? sb->ctl : nullptr, sb ? sb->hist : nullptr, budgets, max_budget, (uint32_t*)K, (uint32_t*)V,          \
+        (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx);           \
     break;
   switch (n_rep) {
     FIER_SCORE_CASE(1)
@@ -271,20 +334,20 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
 
 hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
-                        const int32_t* budgets, int max_budget, int units, int n_kv_heads, int max_ctx,
-                        hipStream_t st) {
+                        const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
+                        const void* v_new, int units, int n_kv_heads, int max_ctx, hipStream_t st) {
   if (sb) {
     if (dtype == DT_F16)
-      return launch_score_dt<DT_F16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb->ctl, sb->hist,
-                                           budgets, max_budget, units, n_kv_heads, max_ctx, st);
-    return launch_score_dt<DT_BF16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb->ctl, sb->hist,
-                                          budgets, max_budget, units, n_kv_heads, max_ctx, st);
+      return launch_score_dt<DT_F16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
+                                           max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, st);
+    return launch_score_dt<DT_BF16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
+                                          max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, st);
   }
   if (dtype == DT_F16)
     return launch_score_dt<DT_F16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
-                                          nullptr, 0, units, n_kv_heads, max_ctx, st);
-  return launch_score_dt<DT_BF16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
-                                         nullptr, 0, units, n_kv_heads, max_ctx, st);
+                                          0, nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, st);
+  return launch_score_dt<DT_BF16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr, 0,
+                                         nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, st);
 }
 
 }  // namespace fier

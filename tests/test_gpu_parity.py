@@ -305,3 +305,93 @@ def test_results_are_deterministic(gu):
         outs.append((out.clone(), idx.clone(), dw.cache.kbits.clone()))
     for o, i, kb in outs[1:]:
         assert torch.equal(o, outs[0][0]) and torch.equal(i, outs[0][1]) and torch.equal(kb, outs[0][2])
+
+
+def _fused(gu, wl, append=False):
+    import gpu_util
+
+    dw = gpu_util.DeviceWorkload(wl)
+    B.quantize_keys(dw.cfg, dw.cache)
+    mb = int(wl.budgets.max())
+    out = torch.full((1, wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1, wl.units), -1, dtype=torch.int32, device="cuda")
+    kn = dw.k_new[None].contiguous() if append else None
+    vn = dw.v_new[None].contiguous() if append else None
+    ws = dw.workspace(mb)
+    for _ in range(2):      # twice on the same workspace: the counters inside it must come back to zero
+        B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt, ws)
+    torch.cuda.synchronize()
+    return dw, out.cpu().numpy()[0], idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
+
+
+@pytest.mark.parametrize("kind", ["constant", "two_rows", "tight_cluster", "one_outlier_token"])
+def test_fused_step_adversarial_score_distributions(gu, oracle, kind):
+    """Score distributions the a-priori histogram range cannot resolve: every token ties, two score values,
+    scores clustered in one bin (radix fallback of the threshold kernel), one token that dwarfs the range."""
+    rng = np.random.default_rng(17)
+    L = 21000
+    wl = synth.make_workload(kind, 5, 1, 2, 2, [L], [2311], F16, max_ctx=21056, plant=False)
+    row = rng.standard_normal((2, 1, 128)).astype(np.float32)
+    if kind == "constant":
+        x = np.broadcast_to(row, (2, L, 128)).copy()
+    elif kind == "two_rows":
+        other = rng.standard_normal((2, 1, 128)).astype(np.float32)
+        pick = rng.integers(0, 2, (2, L, 1)).astype(np.float32)
+        x = row * pick + other * (1 - pick)
+    elif kind == "tight_cluster":
+        x = row + 1e-3 * rng.standard_normal((2, L, 128)).astype(np.float32)
+    else:
+        x = rng.standard_normal((2, L, 128)).astype(np.float32)
+        x[:, 777] = 3000.0
+    wl.K[:, :L] = synth.f32_to_words(x, F16)
+    dw, out, idx, cnt = _fused(gu, wl)
+    r = oracle_step(oracle, wl, append=False)
+    swapped = check_index_sets(idx, cnt, r["idx"], r["count"], r["scores"], r["L"])
+    if kind in ("constant", "two_rows"):
+        assert swapped == 0                     # exact two-level keys: scores agree bit for bit in ordering
+    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                            np.ascontiguousarray(np.where(idx < 0, 0, idx)), cnt, 2)
+    assert np.abs(out - want).max() <= 2e-3
+
+
+def test_fused_step_long_context_gqa_bf16(gu, oracle):
+    """Several threshold-kernel workgroups per unit, grouped queries, ragged batch, with the append."""
+    wl = synth.make_workload("long", 9, 2, 8, 2, [40000, 9001], [4400, 990], BF16, chan="lognormal", n_planted=32)
+    dw, out, idx, cnt = _fused(gu, wl, append=True)
+    # the second call appended the same row again at the same position: state equals one append
+    r = oracle_step(oracle, wl, append=True)
+    check_index_sets(idx, cnt, r["idx"], r["count"], r["scores"], r["L"])
+    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                            np.ascontiguousarray(np.where(idx < 0, 0, idx)), cnt, 4)
+    assert np.abs(out - want).max() <= 2e-3
+    _compare_packed(dw, r["L"], r["bits"], r["s"], r["z"])
+    for u in range(wl.units):
+        assert set(wl.planted[u].tolist()) <= set(idx[u, :cnt[u]].tolist())
+
+
+def test_fused_step_multi_layer(gu, oracle):
+    """n_layers > 1 in one call: every layer's selection and output match the oracle."""
+    import gpu_util
+
+    wls = [synth.make_workload(f"layer{l}", 100 + l, 2, 4, 2, [1500, 700], [160, 80], F16, max_ctx=1536,
+                               n_planted=4) for l in range(3)]
+    dws = [gpu_util.DeviceWorkload(w) for w in wls]
+    for dw in dws:
+        B.quantize_keys(dw.cfg, dw.cache)
+    cfg = dws[0].cfg
+    q = torch.stack([dw.q.reshape(2, 4, 128) for dw in dws]).contiguous()
+    kn = torch.stack([dw.k_new for dw in dws]).contiguous()
+    vn = torch.stack([dw.v_new for dw in dws]).contiguous()
+    out = torch.zeros((3, 4, 2, 128), dtype=torch.float32, device="cuda")
+    idx = torch.full((3, 4, 160), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((3, 4), dtype=torch.int32, device="cuda")
+    B.decode_step(cfg, [dw.cache for dw in dws], q, kn, vn, dws[0].budgets, 160, out, idx, cnt, dws[0].workspace(160))
+    torch.cuda.synchronize()
+    for l, wl in enumerate(wls):
+        r = oracle_step(oracle, wl, append=True)
+        ig, cg = idx.cpu().numpy()[l], cnt.cpu().numpy()[l]
+        check_index_sets(ig, cg, r["idx"], r["count"], r["scores"], r["L"])
+        want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                                np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 2)
+        assert np.abs(out.cpu().numpy()[l] - want).max() <= 2e-3
