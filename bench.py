@@ -96,7 +96,8 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
-    ws = B.make_workspace(cfg, budget)
+    # one workspace per cache, so that a phase of the fused step can be timed alone on rotating caches
+    wss = [B.make_workspace(cfg, budget) for _ in range(R)]
     ws_dense = B.make_workspace(cfg, max_ctx)
     out = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
     idx = torch.zeros((1, units, budget), dtype=torch.int32, device="cuda")
@@ -105,7 +106,7 @@ def main():
 
     def step(i):
         r = i % R
-        B.decode_step(cfg, [caches[r]], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, ws)
+        B.decode_step(cfg, [caches[r]], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r])
 
     def timed(fn, n, warm):
         for i in range(warm):
@@ -123,42 +124,48 @@ def main():
     # ---- the timed region: K whole steps ----------------------------------------------------------------
     us_step, us_wall = timed(step, args.steps, args.warmup)
 
-    # ---- per-stage timing, each entry point launched alone (events on the launch stream) ----------------
+    # ---- each kernel of the fused step alone (HIP events on the launch stream, rotating caches) ----------
     ns = args.stage_steps
-    step(0)
+    for r in range(R):
+        step(r)
     torch.cuda.synchronize()
 
-    def st_append(i):
-        r = i % R
-        B.append_key(cfg, caches[r], kns[r], vns[r])
+    def phase(p):
+        def run(i):
+            r = i % R
+            B.decode_step_phase(cfg, [caches[r]], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r], p)
+        return run
 
-    def st_score(i):
-        r = i % R
-        B.score(cfg, caches[r], qs[r], 1, scores)
-
-    def st_topk(i):
-        B.topk(cfg, scores, seq_lens, 1, budgets, budget, idx, cnt)
-
-    def st_attn(i):
-        r = i % R
-        B.sparse_attn(cfg, caches[r], qs[r], idx, cnt, budget, out, ws)
+    us_k1, _ = timed(phase(1), ns, 12)
+    us_k2, _ = timed(phase(2), ns, 12)
+    us_k3, _ = timed(phase(3), ns, 12)
 
     def st_dense(i):
         r = i % R
         B.dense_attn(cfg, caches[r], qs[r], 1, out, ws_dense)
 
-    us_append, _ = timed(st_append, ns, 10)
-    us_score, _ = timed(st_score, ns, 10)
-    us_topk, _ = timed(st_topk, ns, 10)
-    us_attn, _ = timed(st_attn, ns, 10)
     us_dense, _ = timed(st_dense, max(24, ns // 10), 4)
+
+    # ---- stand-alone entry points (separate kernels, index list through memory) --------------------------
+    def st_score(i):
+        B.score(cfg, caches[i % R], qs[i % R], 1, scores)
+
+    def st_topk(i):
+        B.topk(cfg, scores, seq_lens, 1, budgets, budget, idx, cnt)
+
+    def st_attn(i):
+        B.sparse_attn(cfg, caches[i % R], qs[i % R], idx, cnt, budget, out, wss[0])
+
+    us_score, _ = timed(st_score, max(24, ns // 4), 4)
+    us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
+    us_attn, _ = timed(st_attn, max(24, ns // 4), 4)
 
     ab = algorithmic_bytes(w)
     achieved = ab["total"] / (us_step * 1e-6) / 1e9
-    # dominant kernel by algorithmic bytes: the gather attention (selected K/V rows + q + out)
-    attn_bytes = ab["selected_kv"] + ab["q_out"]
-    attn_gbps = attn_bytes / (us_attn * 1e-6) / 1e9
-    score_gbps = ab["packed"] / (us_score * 1e-6) / 1e9
+    # dominant kernel by algorithmic bytes: select + attend (selected K/V rows + q + out)
+    k3_bytes = ab["selected_kv"] + ab["q_out"]
+    k3_gbps = k3_bytes / (us_k3 * 1e-6) / 1e9
+    k1_gbps = ab["packed"] / (us_k1 * 1e-6) / 1e9
     dense_bytes = units * (L + 1) * 512 + ab["q_out"]
 
     res = {
@@ -180,16 +187,18 @@ def main():
         "achieved_GBps": round(achieved, 1),
         "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_step_wall": round(us_wall, 3),
-        "stages_us": {"append": round(us_append, 3), "score": round(us_score, 3), "topk": round(us_topk, 3),
-                      "sparse_attn": round(us_attn, 3), "sum": round(us_append + us_score + us_topk + us_attn, 3)},
-        "stage_GBps": {"score": round(score_gbps, 1), "sparse_attn": round(attn_gbps, 1)},
+        "kernels_us": {"append_score_hist": round(us_k1, 3), "threshold": round(us_k2, 3),
+                       "select_attend_merge": round(us_k3, 3), "sum": round(us_k1 + us_k2 + us_k3, 3)},
+        "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "select_attend_merge": round(k3_gbps, 1)},
+        "standalone_calls_us": {"fier_score": round(us_score, 3), "fier_topk": round(us_topk, 3),
+                                "fier_sparse_attn": round(us_attn, 3)},
         "dense_attn_us": round(us_dense, 3),
         "dense_attn_GBps": round(dense_bytes / (us_dense * 1e-6) / 1e9, 1),
         "speedup_vs_dense_attn": round(us_dense / us_step, 3),
-        "roofline": {"bound": "hbm", "kernel": "fier_sparse_attn (attn_split_kernel + attn_merge_kernel)",
-                     "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "bytes_per_launch": attn_bytes, "us_per_launch": round(us_attn, 3)},
+        "roofline": {"bound": "hbm", "kernel": "select_attend_kernel (selection, gather attention, merge)",
+                     "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": k3_bytes, "us_per_launch": round(us_k3, 3)},
         "setup_s": round(t_setup, 1),
     }
 

@@ -168,6 +168,17 @@ int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n
                      const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
                      float *out, int32_t *idx_out, int32_t *count_out, void *workspace, void *stream);
 
+/*
+ * One of the three kernels of fier_decode_step alone, for measurement: phase 1 = append + score + score
+ * histogram, 2 = exact threshold, 3 = selection + attention over the selected rows + merge.  Same arguments
+ * as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and these
+ * layers left behind, so the sequence 1, 2, 3 equals fier_decode_step and any phase may be repeated.
+ */
+int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
+                           const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
+                           float *out, int32_t *idx_out, int32_t *count_out, void *workspace, int32_t phase,
+                           void *stream);
+
 /* Host helpers for inspection: physical packed layout -> logical arrays, all host memory.
  * bits [units][max_ctx][D] one byte (0/1) per element; s, z [units][max_ctx/32][D] raw 16-bit words. */
 void fier_unpack_bits(const fier_config *cfg, const uint32_t *kbits_host, uint8_t *bits_host);

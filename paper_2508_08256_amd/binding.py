@@ -19,7 +19,8 @@ EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = -1, -2, -3, -4, -5, -6
 
 SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_status_string",
            "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk",
-           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_unpack_bits", "fier_unpack_meta"]
+           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_phase", "fier_unpack_bits",
+           "fier_unpack_meta"]
 
 
 class FierError(RuntimeError):
@@ -90,6 +91,8 @@ def lib():
         L.fier_dense_attn.argtypes = [cfgp, cachep, vp, i32, vp, vp, vp]
         L.fier_decode_step.restype = C.c_int
         L.fier_decode_step.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.fier_decode_step_phase.restype = C.c_int
+        L.fier_decode_step_phase.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp]
         L.fier_unpack_bits.restype = None
         L.fier_unpack_bits.argtypes = [cfgp, vp, vp]
         L.fier_unpack_meta.restype = None
@@ -209,3 +212,12 @@ def decode_step(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, 
     _check(lib().fier_decode_step(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(budgets),
                                   int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out), _ptr(workspace),
                                   _stream()), "fier_decode_step")
+
+
+def decode_step_phase(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, out, idx_out, count_out,
+                      workspace, phase: int):
+    """One kernel of the fused step alone (1 = score, 2 = threshold, 3 = select + attend); for measurement."""
+    arr = (Cache * len(caches))(*[c.c for c in caches])
+    _check(lib().fier_decode_step_phase(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                        _ptr(budgets), int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
+                                        _ptr(workspace), int(phase), _stream()), "fier_decode_step_phase")

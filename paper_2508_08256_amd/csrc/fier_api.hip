@@ -206,15 +206,16 @@ int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void*
                                       cfg->max_ctx, (hipStream_t)stream));
 }
 
-int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
-                     const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget, float* out,
-                     int32_t* idx_out, int32_t* count_out, void* workspace, void* stream) {
+static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
+                            const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget,
+                            float* out, int32_t* idx_out, int32_t* count_out, void* workspace, int32_t phase,
+                            void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
   if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
-  if (max_budget > cfg->max_ctx) return FIER_EINVAL;
+  if (max_budget > cfg->max_ctx || phase < 0 || phase > 3) return FIER_EINVAL;
   if (!workspace) return FIER_EWORKSPACE;
   if (misaligned(q) || misaligned(out) || misaligned(workspace) || misaligned(k_new) || misaligned(v_new) ||
       misaligned(idx_out))
@@ -232,22 +233,44 @@ int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n
     const fier_cache* c = &layers[l];
     const char* ql = static_cast<const char*>(q) + (size_t)l * cfg->batch * cfg->n_q_heads * kD * esz;
     float* outl = out + (size_t)l * cfg->batch * cfg->n_q_heads * kD;
-    int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : w.idx;
+    int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : nullptr;
     int32_t* cntl = count_out ? count_out + (size_t)l * units : nullptr;
     hipError_t e;
-    const char* kn = extra ? static_cast<const char*>(k_new) + (size_t)l * units * kD * esz : nullptr;
-    const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
-    e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra, w.sb.scores,
-                           &w.sb, budgets, max_budget, c->k, c->v, kn, vn, units, cfg->n_kv_heads, cfg->max_ctx, s);
-    if (e != hipSuccess) return FIER_EHIP;
-    e = fier::launch_threshold(w.sb, c->seq_lens, extra, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
-    if (e != hipSuccess) return FIER_EHIP;
-    e = fier::launch_select_attend(cfg->kv_dtype, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
-                                   cfg->sm_scale, idx_out ? idxl : nullptr, outl, c->kabsmax, units, cfg->n_kv_heads,
-                                   cfg->max_ctx, s);
-    if (e != hipSuccess) return FIER_EHIP;
+    if (phase == 0 || phase == 1) {
+      const char* kn = extra ? static_cast<const char*>(k_new) + (size_t)l * units * kD * esz : nullptr;
+      const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
+      e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra,
+                             w.sb.scores, &w.sb, budgets, max_budget, c->k, c->v, kn, vn, units, cfg->n_kv_heads,
+                             cfg->max_ctx, s);
+      if (e != hipSuccess) return FIER_EHIP;
+    }
+    if (phase == 0 || phase == 2) {
+      e = fier::launch_threshold(w.sb, c->seq_lens, extra, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
+      if (e != hipSuccess) return FIER_EHIP;
+    }
+    if (phase == 0 || phase == 3) {
+      e = fier::launch_select_attend(cfg->kv_dtype, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
+                                     cfg->sm_scale, idxl, outl, c->kabsmax, units, cfg->n_kv_heads, cfg->max_ctx, s);
+      if (e != hipSuccess) return FIER_EHIP;
+    }
   }
   return FIER_OK;
+}
+
+int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
+                     const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget, float* out,
+                     int32_t* idx_out, int32_t* count_out, void* workspace, void* stream) {
+  return decode_step_impl(cfg, layers, n_layers, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
+                          workspace, 0, stream);
+}
+
+int fier_decode_step_phase(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
+                           const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget,
+                           float* out, int32_t* idx_out, int32_t* count_out, void* workspace, int32_t phase,
+                           void* stream) {
+  if (phase < 1) return FIER_EINVAL;
+  return decode_step_impl(cfg, layers, n_layers, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
+                          workspace, phase, stream);
 }
 
 void fier_unpack_bits(const fier_config* cfg, const uint32_t* kbits_host, uint8_t* bits_host) {

@@ -181,26 +181,28 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
 }
 
-// Merge n_used partial slots of one (unit, query head) into out[128]; 256 threads: thread (c, half) folds the
-// slots of its parity for channel c with a running maximum, eight independent coherent loads at a time so
-// that the round trips to memory overlap; the two halves meet in LDS.  sh: 2 * 130 floats.  Has barriers.
+// Merge n_used partial slots of one (unit, query head) into out[128].  256 threads: thread (g, k) folds the
+// slots s = g, g + 4, ... for channels 2k, 2k + 1 with a running maximum, sixteen independent coherent loads
+// at a time so that the round trips to memory overlap; the four groups meet in LDS.
+// sh: 4 * 130 floats.  Has barriers.
 __device__ __forceinline__ void merge_head(const float* __restrict__ po, const float* __restrict__ pm,
                                            const float* __restrict__ pl, size_t base, int n_used, float* sh,
                                            float* __restrict__ out_head) {
-  constexpr int BATCH = 8;
+  constexpr int BATCH = 16;
   const int tid = threadIdx.x;
-  const int c = tid & 127, half = tid >> 7;
-  float M = -INFINITY, acc = 0.f, lsum = 0.f;
-  for (int s0 = half; s0 < n_used; s0 += 2 * BATCH) {
-    float ms[BATCH], ls[BATCH], os[BATCH];
+  const int k2 = (tid & 63) * 2, g = tid >> 6;
+  float M = -INFINITY, acc0 = 0.f, acc1 = 0.f, lsum = 0.f;
+  for (int s0 = g; s0 < n_used; s0 += 4 * BATCH) {
+    float ms[BATCH], ls[BATCH];
+    unsigned long long os[BATCH];
 #pragma unroll
     for (int k = 0; k < BATCH; ++k) {
-      const int s = s0 + 2 * k;
+      const int s = s0 + 4 * k;
       const bool ok = s < n_used;
       const size_t slot = base + (ok ? s : s0);
       ms[k] = load_coherent(&pm[slot]);
       ls[k] = load_coherent(&pl[slot]);
-      os[k] = load_coherent(&po[slot * kD + c]);
+      os[k] = load_coherent(reinterpret_cast<const unsigned long long*>(&po[slot * kD + k2]));
       if (!ok) ms[k] = -INFINITY;
     }
     float mx = M;
@@ -208,31 +210,39 @@ __device__ __forceinline__ void merge_head(const float* __restrict__ po, const f
     for (int k = 0; k < BATCH; ++k) mx = fmaxf(mx, ms[k]);
     const float mref = mx == -INFINITY ? 0.f : mx;
     const float alpha = __builtin_amdgcn_exp2f(M - mref);
-    acc *= alpha;
+    acc0 *= alpha;
+    acc1 *= alpha;
     lsum *= alpha;
 #pragma unroll
     for (int k = 0; k < BATCH; ++k) {
       const float w = __builtin_amdgcn_exp2f(ms[k] - mref);  // 0 for an empty slot
-      acc += w * os[k];
+      acc0 += w * __uint_as_float((uint32_t)os[k]);
+      acc1 += w * __uint_as_float((uint32_t)(os[k] >> 32));
       lsum += w * ls[k];
     }
     M = mx;
   }
   __syncthreads();
-  sh[half * 130 + c] = acc;
-  if (c == 0) {
-    sh[half * 130 + 128] = lsum;
-    sh[half * 130 + 129] = M;
+  sh[g * 130 + k2] = acc0;
+  sh[g * 130 + k2 + 1] = acc1;
+  if (k2 == 0) {
+    sh[g * 130 + 128] = lsum;
+    sh[g * 130 + 129] = M;
   }
   __syncthreads();
-  if (half == 0) {
-    const float m0 = sh[129], m1 = sh[130 + 129];
-    const float mx = fmaxf(m0, m1);
+  if (tid < kD) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) mx = fmaxf(mx, sh[j * 130 + 129]);
     const float mref = mx == -INFINITY ? 0.f : mx;
-    const float w0 = __builtin_amdgcn_exp2f(m0 - mref), w1 = __builtin_amdgcn_exp2f(m1 - mref);
-    const float l = w0 * sh[128] + w1 * sh[130 + 128];
-    const float a = w0 * sh[c] + w1 * sh[130 + c];
-    out_head[c] = l > 0.f ? a / l : 0.f;
+    float l = 0.f, a = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float w = __builtin_amdgcn_exp2f(sh[j * 130 + 129] - mref);
+      l += w * sh[j * 130 + 128];
+      a += w * sh[j * 130 + tid];
+    }
+    out_head[tid] = l > 0.f ? a / l : 0.f;
   }
 }
 
@@ -259,6 +269,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
   if (r * kRangeTokens >= n && r != 0) return;
+  FIER_PROF(20, unit == 0 && r == 3)
   UnitCtl* __restrict__ c = &ctl[unit];
   const int tbin = c->tbin;
   const float R = c->R, hscale = c->scale;
@@ -290,6 +301,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
       ++pos;
     }
   __syncthreads();
+  FIER_PROF(21, unit == 0 && r == 3)
 
   // ---- attention over the selected rows of this range ----------------------------------------------------
   const uint4* __restrict__ Ku = K + (size_t)unit * max_ctx * (kD / 8);
@@ -300,16 +312,20 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   AttnState<NREP> st;
   st.init();
   attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return rows[j]; }, 0, (int)n_sel, max_ctx, scale_log2e, st);
+  FIER_PROF(22, unit == 0 && r == 3)
   store_partials<NREP, true>(st, sh_o, unit, n_ranges, r, po, pm, pl);
+  FIER_PROF(23, unit == 0 && r == 3)
 
   const int nr = (n + kRangeTokens - 1) / kRangeTokens;
   if (!last_arriver(&c->arrive[2], nr > 0 ? (uint32_t)nr : 1u, &flag)) return;
+  FIER_PROF(24, unit == 0)
   // ---- the unit's last workgroup merges the partials of all ranges ------------------------------------------
   float* sh = &sh_o[0][0][0];
 #pragma unroll 1
   for (int h = 0; h < NREP; ++h)
     merge_head(po, pm, pl, ((size_t)unit * NREP + h) * n_ranges, nr, sh, out + ((size_t)unit * NREP + h) * kD);
   if (tid == 0) c->arrive[2] = 0;
+  FIER_PROF(25, unit == 0)
   // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
   if (extra && seq_lens[b] < max_ctx && tid < kD) {
     float* slot = kabsmax + (size_t)unit * kD + tid;

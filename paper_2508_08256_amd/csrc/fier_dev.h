@@ -4,6 +4,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Optional time stamps for kernel tuning (a tuning build defines FIER_PROF_ENABLE); compiled out of the library.
+#ifdef FIER_PROF_ENABLE
+extern __device__ unsigned long long fier_prof_slots[64];
+#define FIER_PROF(slot, cond) \
+  if ((cond) && threadIdx.x == 0) fier_prof_slots[slot] = wall_clock64();
+#else
+#define FIER_PROF(slot, cond)
+#endif
+
 namespace fier {
 
 constexpr int kD = 128;        // head_dim

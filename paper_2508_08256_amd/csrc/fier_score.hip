@@ -117,16 +117,20 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   int L = HIST ? Lold + (app ? 1 : 0) : Lold + extra;
   L = L > max_ctx ? max_ctx : L;
   const int tail_start = app ? (Lold / kG) * kG : L;  // tokens from here on are scored by the appending wave
-  const int n_score_wgs = (int)gridDim.x - (HIST ? 1 : 0);
-  const bool append_wg = HIST && (int)blockIdx.x == n_score_wgs;
+  // HIST: workgroup 0 is the appending one (dispatched first: its single wavefront has the longest chain of
+  // dependent loads), workgroups 1.. score the ranges 0..
+  const bool append_wg = HIST && blockIdx.x == 0;
+  const int range = (int)blockIdx.x - (HIST ? 1 : 0);
   if (append_wg) {
     if (!app) return;
   } else {
-    // workgroup 0 of a unit always runs so that an empty unit still gets its control block written
-    if ((int)blockIdx.x * kRangeTokens >= L && !(HIST && blockIdx.x == 0)) return;
+    // range 0 of a unit always runs so that an empty unit still gets its control block written
+    if (range * kRangeTokens >= L && !(HIST && range == 0)) return;
   }
   const int n_groups = max_ctx / kG;
   const int row = lane >> 4, n = lane & 15;
+  FIER_PROF(0, HIST && unit == 0 && range == 3)
+  FIER_PROF(7, HIST && unit == 0 && append_wg)
 
   // The lane's 8 query channels, summed over the query heads that share this kv head (binary32), times
   // 2^-16: qz for the offsets, qx additionally times the inverse of the power of two its bit is tested at.
@@ -157,6 +161,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     }
   }
 
+  FIER_PROF(1, HIST && unit == 0 && range == 3)
   if (append_wg) {
     if constexpr (HIST) {
       if (wave == 0) {  // lane = channel pair (2 lane, 2 lane + 1)
@@ -192,7 +197,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     }
   }
 
-  const int P0 = blockIdx.x * (4 * kScorePairsPerWave) + wave;  // this wave's blocks: P0, P0 + 4, ...
+  const int P0 = range * (4 * kScorePairsPerWave) + wave;  // this wave's blocks: P0, P0 + 4, ...
   if (!append_wg && P0 * kPair < L) {
     const uint4* __restrict__ bits_u = kbits + (size_t)unit * max_ctx;
     const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
@@ -248,6 +253,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     }
   }
 
+  FIER_PROF(2, HIST && unit == 0 && range == 3)
+  FIER_PROF(8, HIST && unit == 0 && append_wg)
   if constexpr (HIST) {
     __syncthreads();
     uint32_t* __restrict__ gh = ghist + (size_t)unit * kSelBins;
@@ -256,7 +263,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       if (c) atomicAdd(&gh[i], c);
     }
     const uint32_t expected = (L > 0 ? (uint32_t)((L + kRangeTokens - 1) / kRangeTokens) : 1u) + (app ? 1u : 0u);
+    FIER_PROF(3, unit == 0 && range == 3)
     if (!last_arriver(&ctl[unit].arrive[0], expected, &flag)) return;
+    FIER_PROF(4, unit == 0)
     // ---- the unit's last workgroup: threshold bin for the budget ---------------------------------------
     int B = budgets[b];
     B = B > max_budget ? max_budget : B;
@@ -299,6 +308,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       c->scale = hscale;
       c->arrive[0] = 0;
     }
+    FIER_PROF(5, unit == 0)
   }
 }
 

@@ -46,6 +46,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   __shared__ unsigned long long sub_list[kSubCandMax];
   __shared__ uint32_t rsel[kMaxRanges];
   __shared__ uint32_t seg_base[kThrThreads];  // one workgroup per 4096 tokens: at most 256 segments
+  __shared__ uint32_t seg_size[kThrThreads];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -54,6 +55,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
   if (chunk * kClassifyTokens >= n && chunk != 0) return;
+  FIER_PROF(10, unit == 0 && chunk == 1)
   UnitCtl* __restrict__ c = &ctl[unit];
   const int tbin = c->tbin;
   const float R = c->R, scale = c->scale;
@@ -68,6 +70,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   if (i < n) v = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx; entries >= n are masked below
   if (tid == 0) n_local = 0;
   __syncthreads();
+  FIER_PROF(11, unit == 0 && chunk == 1)
   const float vv[4] = {v.x, v.y, v.z, v.w};
   uint32_t n_gt = 0, n_c = 0;
   bool is_c[4];
@@ -104,7 +107,9 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   }
   if (tid == 4) store_coherent(&useg[chunk], n_local);
   const int nc = n > 0 ? (n + kClassifyTokens - 1) / kClassifyTokens : 1;  // workgroups of this unit
+  FIER_PROF(12, unit == 0 && chunk == 1)
   if (!last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) return;
+  FIER_PROF(13, unit == 0)
 
   // ---- the unit's last workgroup: exact threshold ------------------------------------------------------
   const int nr = (n + kRangeTokens - 1) / kRangeTokens;  // ranges in use (<= n_ranges)
@@ -113,6 +118,8 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   // segment sizes, and the first candidates of every segment in the same round trip
   uint32_t my_cnt = 0;
   if (tid < nc) my_cnt = load_coherent(&useg[tid]);
+  uint32_t my_range = 0;  // ranges tid, tid + 1024, ...: the first one is fetched in the same round trip
+  if (tid < nr) my_range = load_coherent(&urange[tid]);
   unsigned long long spec = 0;
   const int sseg = tid / kSpecCand, sk = tid % kSpecCand;
   if (need_threshold && sseg < nc) spec = load_coherent(&ucand[(size_t)sseg * kSegCand + sk]);
@@ -123,9 +130,13 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   {
     const uint32_t capped = my_cnt > (uint32_t)kSegCand ? (uint32_t)kSegCand : my_cnt;
     const uint32_t before = block_excl_scan_u32<kThrWaves>(capped, scan_tmp, total_cand);
-    if (tid < nc) seg_base[tid] = before;
+    if (tid < nc) {
+      seg_base[tid] = before;
+      seg_size[tid] = capped;
+    }
     overflow = __syncthreads_or(my_cnt > (uint32_t)kSegCand) || total_cand > (uint32_t)kSelCandMax;
   }
+  FIER_PROF(14, unit == 0)
   uint32_t T = 0;
   int32_t idxT = -1;
   if (need_threshold) {
@@ -134,11 +145,10 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     if (!overflow) {
       // gather the segments into LDS
       if (sseg < nc) {
-        const uint32_t cnt_s = load_coherent(&useg[sseg]);  // hits the line fetched above
-        if ((uint32_t)sk < cnt_s) lcand[seg_base[sseg] + sk] = spec;
+        if ((uint32_t)sk < seg_size[sseg]) lcand[seg_base[sseg] + sk] = spec;
       }
       for (int sg = 0; sg < nc; ++sg) {
-        const uint32_t cnt_s = load_coherent(&useg[sg]);
+        const uint32_t cnt_s = seg_size[sg];
         const bool prefetched = sg < kThrThreads / kSpecCand;  // its first kSpecCand entries are already in LDS
         for (uint32_t k = (prefetched ? kSpecCand : 0) + tid; k < cnt_s; k += kThrThreads)
           lcand[seg_base[sg] + k] = load_coherent(&ucand[(size_t)sg * kSegCand + k]);
@@ -252,11 +262,12 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     }
   }
   __syncthreads();
+  FIER_PROF(15, unit == 0)
   // ---- offsets of the ranges in the ascending index list ------------------------------------------------
   uint32_t run = 0;
   for (int r0 = 0; r0 < nr; r0 += kThrThreads) {
     const int r = r0 + tid;
-    const uint32_t cnt = r < nr ? load_coherent(&urange[r]) + rsel[r] : 0;
+    const uint32_t cnt = r < nr ? (r0 == 0 ? my_range : load_coherent(&urange[r])) + rsel[r] : 0;
     uint32_t total;
     const uint32_t before = run + block_excl_scan_u32<kThrWaves>(cnt, scan_tmp, total);
     if (r < nr) urange[r] = before;
@@ -268,6 +279,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     c->arrive[1] = 0;
     if (count_out) count_out[unit] = B;
   }
+  FIER_PROF(16, unit == 0)
 }
 
 hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, int32_t* count_out, int units,

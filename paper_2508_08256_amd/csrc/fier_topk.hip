@@ -15,11 +15,6 @@
 #include "fier_dev.h"
 #include "fier_kernels.h"
 
-// Optional phase time stamps for kernel tuning; compiled out of the library.
-#ifndef FIER_PROF
-#define FIER_PROF(k)
-#endif
-
 namespace fier {
 
 constexpr int kTkThreads = 1024;
@@ -159,7 +154,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     return;
   }
 
-  FIER_PROF(0)
   float4 regs[NVR];
   if constexpr (NV > 0) {
 #pragma unroll
@@ -170,7 +164,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     }
   }
 
-  FIER_PROF(1)
   // ---- 1. range of the scores ----------------------------------------------------------------
   float lo = INFINITY, hi = -INFINITY;
   for_chunks<NV>(regs, s, n, max_ctx, [&](int, const float4 v, int i) {
@@ -185,7 +178,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
   lo = block_minmax<false>(lo, red_tmp);
   hi = block_minmax<true>(hi, red_tmp);
 
-  FIER_PROF(2)
   uint32_t T;      // threshold key
   uint32_t r_eq;   // how many tokens with key == T are selected (the lowest indices)
   if (!(hi > lo)) {
@@ -204,7 +196,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
         if (i + j < n) atomicAdd(&hist[value_bin(vv[j], lo, scale)], 1u);
     });
     __syncthreads();
-    FIER_PROF(3)
     // ---- 3. threshold bin and its candidates -------------------------------------------------
     int tbin;
     uint32_t above;
@@ -213,7 +204,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     const uint32_t n_cand = hist[tbin];
     const bool in_lds = n_cand <= (uint32_t)kTkCandMax;
     __syncthreads();
-    FIER_PROF(4)
     if (in_lds) {
       for_chunks<NV>(regs, s, n, max_ctx, [&](int, const float4 v, int i) {
         const float vv[4] = {v.x, v.y, v.z, v.w};
@@ -233,7 +223,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
       });
       __syncthreads();
     }
-    FIER_PROF(5)
     if (n_cand <= 512u) {
       // ---- 4a. few candidates: rank each one against all others ------------------------------
       if ((uint32_t)tid < n_cand) {
@@ -287,7 +276,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
     }
   }
 
-  FIER_PROF(6)
   // ---- 5. ordered emission ---------------------------------------------------------------------
   // token order = (chunk, thread, element).  A token is selected iff key > T, or key == T and fewer than
   // r_eq equal keys precede it; its output slot is the number of selected tokens before it.
@@ -389,7 +377,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_kernel(const float* __restric
       run_eq += total >> 16;
     }
   }
-  FIER_PROF(7)
 }
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
