@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-steps", type=int, default=240, help="launches per stage for the per-stage timing")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain element-wise copy of 256 MiB (read 256 MiB, write 256 MiB) three times, "
+                         "so that a rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -160,6 +163,14 @@ def main():
     us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
     us_attn, _ = timed(st_attn, max(24, ns // 4), 4)
 
+    if args.pmc_calibration:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        bq = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=bq)
+        torch.cuda.synchronize()
+        del a, bq
+
     ab = algorithmic_bytes(w)
     achieved = ab["total"] / (us_step * 1e-6) / 1e9
     # dominant kernel by algorithmic bytes: select + attend (selected K/V rows + q + out)
@@ -167,6 +178,14 @@ def main():
     k3_gbps = k3_bytes / (us_k3 * 1e-6) / 1e9
     k1_gbps = ab["packed"] / (us_k1 * 1e-6) / 1e9
     dense_bytes = units * (L + 1) * 512 + ab["q_out"]
+
+    # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE runs,
+    # scaled by what the same counters read for a plain copy of known size); None for other workloads
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"decode_step_{args.workload}_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("traffic_bytes_per_launch")
 
     res = {
         "metric": "per-layer decode-step latency (us) + achieved HBM GB/s vs peak",
@@ -197,7 +216,7 @@ def main():
         "speedup_vs_dense_attn": round(us_dense / us_step, 3),
         "roofline": {"bound": "hbm", "kernel": "select_attend_kernel (selection, gather attention, merge)",
                      "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": k3_bytes, "us_per_launch": round(us_k3, 3)},
         "setup_s": round(t_setup, 1),
     }
