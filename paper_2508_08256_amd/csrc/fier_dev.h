@@ -101,13 +101,24 @@ __device__ __forceinline__ int sel_bin(float v, float R, float scale, int n_bins
   return bin > n_bins - 1 ? n_bins - 1 : (bin < 0 ? 0 : bin);
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    uint32_t o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
-  }
+// Inclusive prefix sum over the 64 lanes with DPP (row shifts inside each row of 16 lanes, then the last lane of
+// a row broadcast into the following rows): six dependent ALU ops instead of six LDS-crossbar shuffles.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add_u32(uint32_t v) {
+  return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
+}
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int /*lane*/) {
+  v = dpp_add_u32<0x111, 0xf>(v);  // row_shr:1
+  v = dpp_add_u32<0x112, 0xf>(v);  // row_shr:2
+  v = dpp_add_u32<0x114, 0xf>(v);  // row_shr:4
+  v = dpp_add_u32<0x118, 0xf>(v);  // row_shr:8
+  v = dpp_add_u32<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+  v = dpp_add_u32<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
   return v;
+}
+// Sum over the 64 lanes, the same value in every lane.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan_u32(v, 0), 63);
 }
 
 // Exclusive scan over the threads of a workgroup of NW wavefronts (thread order) and the total.
@@ -121,8 +132,10 @@ __device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t* tm
   __syncthreads();
   const uint32_t wsum = lane < NW ? tmp[lane] : 0;
   const uint32_t wincl = wave_incl_scan_u32(wsum, lane);
-  const uint32_t wave_off = __shfl(wincl, wave, 64) - __shfl(wsum, wave, 64);
-  total = __shfl(wincl, NW - 1, 64);
+  const int w = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t wave_off =
+      (uint32_t)__builtin_amdgcn_readlane((int)wincl, w) - (uint32_t)__builtin_amdgcn_readlane((int)wsum, w);
+  total = (uint32_t)__builtin_amdgcn_readlane((int)wincl, NW - 1);
   return wave_off + incl - v;
 }
 

@@ -13,6 +13,7 @@
 // range resolves), the last workgroup falls back to a radix selection streamed over the unit's scores.
 #include "fier_dev.h"
 #include "fier_kernels.h"
+#include "fier_select_dev.h"
 
 namespace fier {
 
@@ -20,11 +21,6 @@ constexpr int kThrThreads = 1024;
 constexpr int kThrWaves = kThrThreads / 64;
 constexpr int kMaxRanges = (1 << 20) / kRangeTokens;  // max_ctx <= 2^20
 constexpr int kSpecCand = 64;                          // candidates per segment fetched before its count is known
-
-__device__ __forceinline__ float key_score(uint32_t key) {
-  const uint32_t u = key ^ ((key >> 31) ? 0x80000000u : 0xffffffffu);
-  return __uint_as_float(u);
-}
 
 // grid (ceil(max_ctx / 4096), units), block 1024
 __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __restrict__ scores,
@@ -83,9 +79,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     n_c += is_c[j];
   }
   // selected-for-certain count of each 1024-token range (4 wavefronts per range)
-  uint32_t g = n_gt;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) g += __shfl_xor(g, d, 64);
+  const uint32_t g = wave_sum_u32(n_gt);
   if (lane == 0) wsum[wave] = g;
   // candidates go to this workgroup's own segment; the slot comes from an LDS counter
   if (n_c) {
@@ -153,112 +147,15 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
         for (uint32_t k = (prefetched ? kSpecCand : 0) + tid; k < cnt_s; k += kThrThreads)
           lcand[seg_base[sg] + k] = load_coherent(&ucand[(size_t)sg * kSegCand + k]);
       }
-      for (int k = tid; k < kSubBins; k += kThrThreads) hist[k] = 0;
-      if (tid == 0) n_sub = 0;
       __syncthreads();
-      // second-level histogram inside the threshold bin
-      const float lo_b = (float)tbin / scale - R;
-      const float scale2 = scale * (float)kSubBins;
-      for (uint32_t k = tid; k < total_cand; k += kThrThreads) {
-        const float x = key_score((uint32_t)(lcand[k] >> 32));
-        atomicAdd(&hist[sel_bin(x, -lo_b, scale2, kSubBins)], 1u);
-      }
-      __syncthreads();
-      // sub-bin t with (count in sub-bins > t) < r_want <= (count in sub-bins >= t); thread t owns sub-bin 1023 - t
-      {
-        const uint32_t cnt = hist[kSubBins - 1 - tid];
-        uint32_t total;
-        const uint32_t before = block_excl_scan_u32<kThrWaves>(cnt, scan_tmp, total);
-        if (before < r_want && r_want <= before + cnt) {
-          res[0] = (uint32_t)(kSubBins - 1 - tid);
-          res[1] = before;
-        }
-        __syncthreads();
-      }
-      const int tsub = (int)res[0];
-      const uint32_t r2 = r_want - res[1];  // rank wanted inside the sub-bin, 1-based
-      const uint32_t n_in_sub = hist[tsub];
-      if (n_in_sub <= (uint32_t)kSubCandMax) {
-        for (uint32_t k = tid; k < total_cand; k += kThrThreads) {
-          const unsigned long long e = lcand[k];
-          const int sb = sel_bin(key_score((uint32_t)(e >> 32)), -lo_b, scale2, kSubBins);
-          if (sb > tsub) atomicAdd(&rsel[(uint32_t)e / kRangeTokens], 1u);
-          if (sb == tsub) sub_list[atomicAdd(&n_sub, 1u)] = e;
-        }
-        __syncthreads();
-        // rank the members of the decisive sub-bin: larger key first, equal keys by lower index
-        if ((uint32_t)tid < n_in_sub) {
-          const unsigned long long me = sub_list[tid];
-          const uint32_t mk = (uint32_t)(me >> 32), mi = (uint32_t)me;
-          uint32_t rank = 0;
-          for (uint32_t j = 0; j < n_in_sub; ++j) {
-            const unsigned long long o = sub_list[j];
-            const uint32_t ok = (uint32_t)(o >> 32), oi = (uint32_t)o;
-            rank += (ok > mk) || (ok == mk && oi < mi);
-          }
-          if (rank < r2) atomicAdd(&rsel[mi / kRangeTokens], 1u);
-          if (rank == r2 - 1) {
-            res[0] = mk;
-            res[1] = mi;
-          }
-        }
-        __syncthreads();
-        T = res[0];
-        idxT = (int32_t)res[1];
-        done = true;
-      }
+      done = exact_select_lds<kThrThreads, kSubBins, kSubCandMax>(lcand, total_cand, r_want, tbin, R, scale, hist,
+                                                                  sub_list, &n_sub, res, scan_tmp, rsel, T, idxT);
     }
     if (!done) {
-      // ---- fallback: radix select over the unit's scores restricted to the threshold bin ------------
       for (int r = tid; r < nr; r += kThrThreads) rsel[r] = 0;
-      uint32_t prefix = 0, mask = 0, r = r_want;
-#pragma unroll 1
-      for (int pass = 3; pass >= 0; --pass) {
-        const int shift = 8 * pass;
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        for (int k = tid; k < n; k += kThrThreads) {
-          const float x = s[k];
-          const uint32_t key = score_key(x);
-          if (sel_bin(x, R, scale, kSelBins) == tbin && (key & mask) == prefix)
-            atomicAdd(&hist[(key >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        // digit d with (count of digits > d) < r <= (count of digits >= d): thread t owns digit 255 - t
-        const uint32_t cnt = tid < 256 ? hist[255 - tid] : 0;
-        uint32_t total;
-        const uint32_t before = block_excl_scan_u32<kThrWaves>(cnt, scan_tmp, total);
-        if (tid < 256 && before < r && r <= before + cnt) {
-          res[0] = 255u - (uint32_t)tid;
-          res[1] = before;
-        }
-        __syncthreads();
-        prefix |= res[0] << shift;
-        mask |= 0xffu << shift;
-        r -= res[1];
-        __syncthreads();
-      }
-      T = prefix;  // r = how many tokens with key == T (inside tbin) are selected: the lowest indices
-      // ordered pass: idxT = index of the r-th token with key == T; count selected candidates per range
-      uint32_t run_eq = 0;
-      for (int k0 = 0; k0 < n; k0 += kThrThreads) {
-        const int k = k0 + tid;
-        bool eq = false, gt = false;
-        if (k < n) {
-          const float x = s[k];
-          const uint32_t key = score_key(x);
-          const bool in_bin = sel_bin(x, R, scale, kSelBins) == tbin;
-          eq = in_bin && key == T;
-          gt = in_bin && key > T;
-        }
-        uint32_t total;
-        const uint32_t before = run_eq + block_excl_scan_u32<kThrWaves>(eq ? 1u : 0u, scan_tmp, total);
-        if (gt || (eq && before < r)) atomicAdd(&rsel[k / kRangeTokens], 1u);
-        if (eq && before == r - 1) res[1] = (uint32_t)k;
-        run_eq += total;
-      }
       __syncthreads();
-      idxT = (int32_t)res[1];
+      stream_select<kThrThreads>([&](int k) { return s[k]; }, n, tbin, R, scale, r_want, hist, scan_tmp, res, rsel,
+                                 T, idxT);
     }
   }
   __syncthreads();

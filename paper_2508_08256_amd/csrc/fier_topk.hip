@@ -22,28 +22,12 @@ constexpr int kTkWaves = kTkThreads / 64;
 constexpr int kTkBins = 2048;
 constexpr int kTkCandMax = 8192;
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    uint32_t o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
-  }
-  return v;
-}
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) { return wave_incl_scan_u32(v, lane); }
 
 // Exclusive scan of one value per thread over the workgroup (thread order); also returns the total.
-// `tmp` is kTkWaves + 1 words of LDS; contains two barriers.
+// `tmp` is kTkWaves words of LDS; contains two barriers.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* tmp, uint32_t& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t incl = wave_incl_scan(v, lane);
-  __syncthreads();  // tmp may still be read by a previous call
-  if (lane == 63) tmp[wave] = incl;
-  __syncthreads();
-  uint32_t wsum = lane < kTkWaves ? tmp[lane] : 0;
-  uint32_t wincl = wave_incl_scan(wsum, lane);
-  uint32_t wave_off = __shfl(wincl, wave, 64) - __shfl(wsum, wave, 64);
-  total = __shfl(wincl, kTkWaves - 1, 64);
-  return wave_off + incl - v;
+  return block_excl_scan_u32<kTkWaves>(v, tmp, total);
 }
 
 template <bool IsMax>
