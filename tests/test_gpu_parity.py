@@ -395,3 +395,102 @@ def test_fused_step_multi_layer(gu, oracle):
         want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
                                 np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 2)
         assert np.abs(out.cpu().numpy()[l] - want).max() <= 2e-3
+
+
+def _full_size_case(gu, oracle, shape, seed, sample_units):
+    """A full-size workload generated on the GPU exactly as bench.py does, run through fier_decode_step in the
+    launch configuration bench.py times, and checked against the oracle on a sample of units."""
+    d = synth.make_workload_device("full", seed, shape["batch"], shape["n_q_heads"], shape["n_kv_heads"],
+                                   [shape["L"]] * shape["batch"], [shape["budget"]] * shape["batch"], shape["dtype"],
+                                   max_ctx=-(-(shape["L"] + 1) // 64) * 64, chan=shape["chan"],
+                                   n_planted=shape["n_planted"])
+    batch, Hq, Hkv, L, budget, dtype = (shape[k] for k in ("batch", "n_q_heads", "n_kv_heads", "L", "budget", "dtype"))
+    max_ctx = d["max_ctx"]
+    cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype)
+    n_rep = cfg.n_rep
+    # host copies of the sampled units BEFORE the step (the step appends in place)
+    K0 = {u: synth.words_of(d["K"][u]) for u in sample_units}
+    V0 = {u: synth.words_of(d["V"][u]) for u in sample_units}
+    cache = B.DeviceCache(cfg, d["K"], d["V"], d["seq_lens"])
+    B.quantize_keys(cfg, cache)
+    out = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, cfg.units, budget), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1, cfg.units), dtype=torch.int32, device="cuda")
+    B.decode_step(cfg, [cache], d["q"].reshape(1, batch, Hq, 128).contiguous(),
+                  d["k_new"].reshape(1, cfg.units, 128).contiguous(), d["v_new"].reshape(1, cfg.units, 128).contiguous(),
+                  d["budgets"], budget, out, idx, cnt, B.make_workspace(cfg, budget))
+    torch.cuda.synchronize()
+    bits_g, s_g, z_g = None, None, None
+    q_all = synth.words_of(d["q"]).reshape(cfg.units, n_rep, 128)
+    kn_all, vn_all = synth.words_of(d["k_new"]), synth.words_of(d["v_new"])
+    out_g = out.cpu().numpy().reshape(cfg.units, n_rep, 128)
+    idx_g, cnt_g = idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
+    kb = cache.kbits.view(cfg.units, max_ctx, 4)
+    km = cache.kmeta.view(cfg.units, max_ctx // 32, 128)
+    for u in sample_units:
+        wl = synth.Workload("unit", 1, n_rep, 1, 128, max_ctx, dtype, np.array([L], np.int32),
+                            np.array([budget], np.int32), K0[u][None].copy(), V0[u][None].copy(), q_all[u][None].copy(),
+                            kn_all[u][None].copy(), vn_all[u][None].copy(), [d["planted"][u]])
+        r = oracle_step(oracle, wl, append=True, n_threads=8)
+        swapped = check_index_sets(idx_g[u:u + 1], cnt_g[u:u + 1], r["idx"], r["count"], r["scores"], r["L"])
+        want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], dtype,
+                                np.ascontiguousarray(np.where(idx_g[u:u + 1] < 0, 0, idx_g[u:u + 1])), cnt_g[u:u + 1], 8)
+        err = np.abs(out_g[u] - want[0]).max()
+        assert err <= 2e-3, (u, err)
+        # packed state of the unit after the append, bit for bit
+        sub = B.make_config(1, n_rep, 1, max_ctx, dtype)
+        bits = np.zeros((1, max_ctx, 128), np.uint8)
+        s = np.zeros((1, max_ctx // 32, 128), np.uint16)
+        z = np.zeros_like(s)
+        import ctypes as C
+        kbu = kb[u].cpu().numpy().view(np.uint32)
+        kmu = km[u].cpu().numpy().view(np.uint32)
+        B.lib().fier_unpack_bits(C.byref(sub), kbu.ctypes.data_as(C.c_void_p), bits.ctypes.data_as(C.c_void_p))
+        B.lib().fier_unpack_meta(C.byref(sub), kmu.ctypes.data_as(C.c_void_p), s.ctypes.data_as(C.c_void_p),
+                                 z.ctypes.data_as(C.c_void_p))
+        n = L + 1
+        assert np.array_equal(bits[0, :n], r["bits"][0, :n])
+        ng = -(-n // 32)
+        assert np.array_equal(s[0, :ng], r["s"][0, :ng]) and np.array_equal(z[0, :ng], r["z"][0, :ng])
+        assert set(d["planted"][u].tolist()) <= set(idx_g[u, :cnt_g[u]].tolist())
+        print(f"[full-size] unit {u}: swapped near-ties {swapped}, attention max err {err:.2e}", flush=True)
+    # properties that hold for every unit at any size
+    assert np.all(cnt_g == budget)
+    assert np.all(np.diff(idx_g, axis=1) > 0) and idx_g.min() >= 0 and idx_g.max() <= L
+    assert np.all(np.isfinite(out_g))
+
+
+def test_full_size_config2_sampled_units(gu, oracle):
+    """LLaMA-7B-shaped layer: 32 MHA heads, 32768 tokens + 1 appended, budget 3604 (the bench configuration)."""
+    _full_size_case(gu, oracle, dict(batch=1, n_q_heads=32, n_kv_heads=32, L=32768, budget=3604, dtype=F16,
+                                     chan="ones", n_planted=64), 2000, [0, 13, 31])
+
+
+def test_full_size_config3_sampled_units(gu, oracle):
+    """Llama-3-8B-shaped GQA layer: batch 4, 32 q / 8 kv heads, 131072 tokens, bf16, budget 4096."""
+    _full_size_case(gu, oracle, dict(batch=4, n_q_heads=32, n_kv_heads=8, L=131072, budget=4096, dtype=BF16,
+                                     chan="lognormal", n_planted=64), 3000, [5, 30])
+
+
+def test_decode_step_phases_equal_the_fused_call(gu):
+    wl = synth.config1()
+    import gpu_util
+
+    outs = []
+    for mode in ("fused", "phases"):
+        dw = gpu_util.DeviceWorkload(wl)
+        B.quantize_keys(dw.cfg, dw.cache)
+        out = torch.zeros((1, wl.units, 1, 128), dtype=torch.float32, device="cuda")
+        idx = torch.zeros((1, wl.units, 512), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+        args = (dw.cfg, [dw.cache], dw.q[None].contiguous(), dw.k_new[None].contiguous(), dw.v_new[None].contiguous(),
+                dw.budgets, 512, out, idx, cnt, dw.workspace(512))
+        if mode == "fused":
+            B.decode_step(*args)
+        else:
+            for p in (1, 2, 3, 3, 2, 3):      # later phases may be repeated on what the earlier ones left behind
+                B.decode_step_phase(*args, p)
+        torch.cuda.synchronize()
+        outs.append((out.clone(), idx.clone(), cnt.clone(), dw.cache.kbits.clone()))
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
