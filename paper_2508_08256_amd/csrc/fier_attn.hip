@@ -181,76 +181,90 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
 }
 
-// Merge n_used partial slots of one (unit, query head) into out[128].  256 threads: thread (g, k) folds the
-// slots s = g, g + 4, ... for channels 2k, 2k + 1 with a running maximum, sixteen independent coherent loads
-// at a time so that the round trips to memory overlap; the four groups meet in LDS.
+// Merge the partial slots [0, n_used) of all NREP query heads of a unit into out[NREP][128].  256 threads form
+// four groups of 64 (thread k of a group owns channels 2k, 2k+1).  Each group folds the slots s = sub, sub + GPH,
+// ... of one head with a running maximum, sixteen independent coherent loads at a time so that the round trips
+// to memory overlap; with fewer than four heads several groups share a head and meet in LDS.
 // sh: 4 * 130 floats.  Has barriers.
-__device__ __forceinline__ void merge_head(const float* __restrict__ po, const float* __restrict__ pm,
-                                           const float* __restrict__ pl, size_t base, int n_used, float* sh,
-                                           float* __restrict__ out_head) {
+template <int NREP>
+__device__ __forceinline__ void merge_heads(const float* __restrict__ po, const float* __restrict__ pm,
+                                            const float* __restrict__ pl, int unit, int n_slots, int n_used,
+                                            float* sh, float* __restrict__ out_unit) {
   constexpr int BATCH = 16;
+  constexpr int GPH = NREP == 1 ? 4 : (NREP == 2 ? 2 : 1);  // groups per head
+  constexpr int HPP = 4 / GPH;                              // heads per pass
   const int tid = threadIdx.x;
   const int k2 = (tid & 63) * 2, g = tid >> 6;
-  float M = -INFINITY, acc0 = 0.f, acc1 = 0.f, lsum = 0.f;
-  for (int s0 = g; s0 < n_used; s0 += 4 * BATCH) {
-    float ms[BATCH], ls[BATCH];
-    unsigned long long os[BATCH];
+#pragma unroll 1
+  for (int h0 = 0; h0 < NREP; h0 += HPP) {
+    const int h = h0 + g / GPH, sub = g % GPH;
+    const bool head_ok = h < NREP;
+    const size_t base = ((size_t)unit * NREP + (head_ok ? h : 0)) * n_slots;
+    float M = -INFINITY, acc0 = 0.f, acc1 = 0.f, lsum = 0.f;
+    for (int s0 = sub; s0 < n_used && head_ok; s0 += GPH * BATCH) {
+      float ms[BATCH], ls[BATCH];
+      unsigned long long os[BATCH];
 #pragma unroll
-    for (int k = 0; k < BATCH; ++k) {
-      const int s = s0 + 4 * k;
-      const bool ok = s < n_used;
-      const size_t slot = base + (ok ? s : s0);
-      ms[k] = load_coherent(&pm[slot]);
-      ls[k] = load_coherent(&pl[slot]);
-      os[k] = load_coherent(reinterpret_cast<const unsigned long long*>(&po[slot * kD + k2]));
-      if (!ok) ms[k] = -INFINITY;
+      for (int k = 0; k < BATCH; ++k) {
+        const int s = s0 + GPH * k;
+        const bool ok = s < n_used;
+        const size_t slot = base + (ok ? s : s0);
+        ms[k] = load_coherent(&pm[slot]);
+        ls[k] = load_coherent(&pl[slot]);
+        os[k] = load_coherent(reinterpret_cast<const unsigned long long*>(&po[slot * kD + k2]));
+        if (!ok) ms[k] = -INFINITY;
+      }
+      float mx = M;
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k) mx = fmaxf(mx, ms[k]);
+      const float mref = mx == -INFINITY ? 0.f : mx;
+      const float alpha = __builtin_amdgcn_exp2f(M - mref);
+      acc0 *= alpha;
+      acc1 *= alpha;
+      lsum *= alpha;
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k) {
+        const float w = __builtin_amdgcn_exp2f(ms[k] - mref);  // 0 for an empty slot
+        acc0 += w * __uint_as_float((uint32_t)os[k]);
+        acc1 += w * __uint_as_float((uint32_t)(os[k] >> 32));
+        lsum += w * ls[k];
+      }
+      M = mx;
     }
-    float mx = M;
-#pragma unroll
-    for (int k = 0; k < BATCH; ++k) mx = fmaxf(mx, ms[k]);
-    const float mref = mx == -INFINITY ? 0.f : mx;
-    const float alpha = __builtin_amdgcn_exp2f(M - mref);
-    acc0 *= alpha;
-    acc1 *= alpha;
-    lsum *= alpha;
-#pragma unroll
-    for (int k = 0; k < BATCH; ++k) {
-      const float w = __builtin_amdgcn_exp2f(ms[k] - mref);  // 0 for an empty slot
-      acc0 += w * __uint_as_float((uint32_t)os[k]);
-      acc1 += w * __uint_as_float((uint32_t)(os[k] >> 32));
-      lsum += w * ls[k];
+    __syncthreads();
+    sh[g * 130 + k2] = acc0;
+    sh[g * 130 + k2 + 1] = acc1;
+    if (k2 == 0) {
+      sh[g * 130 + 128] = lsum;
+      sh[g * 130 + 129] = M;
     }
-    M = mx;
-  }
-  __syncthreads();
-  sh[g * 130 + k2] = acc0;
-  sh[g * 130 + k2 + 1] = acc1;
-  if (k2 == 0) {
-    sh[g * 130 + 128] = lsum;
-    sh[g * 130 + 129] = M;
-  }
-  __syncthreads();
-  if (tid < kD) {
-    float mx = -INFINITY;
+    __syncthreads();
+    for (int o = tid; o < HPP * kD; o += 256) {
+      const int hh = o / kD, c = o % kD;
+      if (h0 + hh < NREP) {
+        float mx = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) mx = fmaxf(mx, sh[j * 130 + 129]);
-    const float mref = mx == -INFINITY ? 0.f : mx;
-    float l = 0.f, a = 0.f;
+        for (int j = 0; j < GPH; ++j) mx = fmaxf(mx, sh[(hh * GPH + j) * 130 + 129]);
+        const float mref = mx == -INFINITY ? 0.f : mx;
+        float l = 0.f, a = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float w = __builtin_amdgcn_exp2f(sh[j * 130 + 129] - mref);
-      l += w * sh[j * 130 + 128];
-      a += w * sh[j * 130 + tid];
+        for (int j = 0; j < GPH; ++j) {
+          const float w = __builtin_amdgcn_exp2f(sh[(hh * GPH + j) * 130 + 129] - mref);
+          l += w * sh[(hh * GPH + j) * 130 + 128];
+          a += w * sh[(hh * GPH + j) * 130 + c];
+        }
+        out_unit[(size_t)(h0 + hh) * kD + c] = l > 0.f ? a / l : 0.f;
+      }
     }
-    out_head[tid] = l > 0.f ? a / l : 0.f;
   }
 }
 
-// Third kernel of the fused decode step.  grid (n_ranges, units), block 256: the workgroup owns tokens
-// [1024 r, 1024 r + 1024) of its unit.  It re-reads their scores, applies the exact selection rule fixed by the
-// threshold kernel, writes its part of the ascending index list, and attends over its selected rows straight
-// from an LDS list -- the index list never has to be read back.  The unit's last workgroup merges the partials.
-template <int DT, int NREP>
+// Third kernel of the fused decode step.  grid (ceil(n_ranges / RPW), units), block 256: the workgroup owns RPW
+// consecutive 1024-token ranges of its unit (RPW is chosen by the host so that a workgroup has on the order of a
+// hundred selected rows).  It re-reads their scores, applies the exact selection rule fixed by the threshold
+// kernel, writes its part of the ascending index list, and attends over its selected rows straight from an LDS
+// list -- the index list never has to be read back.  The unit's last workgroup merges the partials.
+template <int DT, int NREP, int RPW>
 __global__ __launch_bounds__(256) void select_attend_kernel(
     const float* __restrict__ scores, UnitCtl* __restrict__ ctl, const uint32_t* __restrict__ range_off,
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ q,
@@ -258,52 +272,67 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
     float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx) {
   __shared__ float sh_o[16][16][8 + 2];
-  __shared__ int32_t rows[kRangeTokens];
+  __shared__ uint16_t rows[kRangeTokens * RPW];  // selected tokens, relative to the workgroup's first token
   __shared__ uint32_t scan_tmp[4];
   __shared__ uint32_t flag;
 
   const int tid = threadIdx.x;
   const int cn = tid & 15;
-  const int unit = blockIdx.y, r = blockIdx.x;
+  const int unit = blockIdx.y, wg = blockIdx.x;
   const int b = unit / n_kv_heads;
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
-  if (r * kRangeTokens >= n && r != 0) return;
-  FIER_PROF(20, unit == 0 && r == 3)
+  const int tok0 = wg * RPW * kRangeTokens;
+  if (tok0 >= n && wg != 0) return;
+  FIER_PROF(20, unit == 0 && wg == 3)
   UnitCtl* __restrict__ c = &ctl[unit];
   const int tbin = c->tbin;
   const float R = c->R, hscale = c->scale;
   const uint32_t T = c->T;
   const int32_t idxT = c->idxT;
+  const int n_slots = (int)gridDim.x;
 
-  // ---- exact selection inside this range, in token order -------------------------------------------------
-  const int i = r * kRangeTokens + 4 * tid;
-  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (i < n) v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
-  const float vv[4] = {v.x, v.y, v.z, v.w};
-  bool sel[4];
-  uint32_t cnt = 0;
+  // ---- exact selection inside this workgroup's ranges, in token order ---------------------------------------
+  float4 v[RPW];
+  uint32_t off[RPW];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int bin = sel_bin(vv[j], R, hscale, kSelBins);
-    const uint32_t key = score_key(vv[j]);
-    sel[j] = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
-    cnt += sel[j];
+  for (int rr = 0; rr < RPW; ++rr) {
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
+    v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n) v[rr] = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
+    const int r = wg * RPW + rr;
+    off[rr] = r < n_ranges ? range_off[(size_t)unit * n_ranges + r] : 0;
   }
-  uint32_t n_sel;
-  uint32_t pos = block_excl_scan_u32<4>(cnt, scan_tmp, n_sel);
-  const uint32_t off = r < n_ranges ? range_off[(size_t)unit * n_ranges + r] : 0;
+  uint32_t n_sel_total = 0;
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    if (sel[j]) {
-      rows[pos] = i + j;
-      if (idx_out && off + pos < (uint32_t)max_budget) idx_out[(size_t)unit * max_budget + off + pos] = i + j;
-      ++pos;
+  for (int rr = 0; rr < RPW; ++rr) {
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
+    const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
+    bool sel[4];
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int bin = sel_bin(vv[j], R, hscale, kSelBins);
+      const uint32_t key = score_key(vv[j]);
+      sel[j] = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
+      cnt += sel[j];
     }
+    uint32_t n_sel;
+    uint32_t pos = block_excl_scan_u32<4>(cnt, scan_tmp, n_sel);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (sel[j]) {
+        rows[n_sel_total + pos] = (uint16_t)(i + j - tok0);
+        if (idx_out && off[rr] + pos < (uint32_t)max_budget)
+          idx_out[(size_t)unit * max_budget + off[rr] + pos] = i + j;
+        ++pos;
+      }
+    n_sel_total += n_sel;
+  }
   __syncthreads();
-  FIER_PROF(21, unit == 0 && r == 3)
+  FIER_PROF(21, unit == 0 && wg == 3)
 
-  // ---- attention over the selected rows of this range ----------------------------------------------------
+  // ---- attention over the selected rows of these ranges --------------------------------------------------------
   const uint4* __restrict__ Ku = K + (size_t)unit * max_ctx * (kD / 8);
   const uint4* __restrict__ Vu = V + (size_t)unit * max_ctx * (kD / 8);
   uint4 qr[NREP];
@@ -311,19 +340,17 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   for (int h = 0; h < NREP; ++h) qr[h] = q[((size_t)unit * NREP + h) * (kD / 8) + cn];
   AttnState<NREP> st;
   st.init();
-  attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return rows[j]; }, 0, (int)n_sel, max_ctx, scale_log2e, st);
-  FIER_PROF(22, unit == 0 && r == 3)
-  store_partials<NREP, true>(st, sh_o, unit, n_ranges, r, po, pm, pl);
-  FIER_PROF(23, unit == 0 && r == 3)
+  attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return tok0 + (int)rows[j]; }, 0, (int)n_sel_total, max_ctx,
+                        scale_log2e, st);
+  FIER_PROF(22, unit == 0 && wg == 3)
+  store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, po, pm, pl);
+  FIER_PROF(23, unit == 0 && wg == 3)
 
-  const int nr = (n + kRangeTokens - 1) / kRangeTokens;
-  if (!last_arriver(&c->arrive[2], nr > 0 ? (uint32_t)nr : 1u, &flag)) return;
+  const int n_wgs = (n + RPW * kRangeTokens - 1) / (RPW * kRangeTokens);  // workgroups of this unit in use
+  if (!last_arriver(&c->arrive[2], n_wgs > 0 ? (uint32_t)n_wgs : 1u, &flag)) return;
   FIER_PROF(24, unit == 0)
-  // ---- the unit's last workgroup merges the partials of all ranges ------------------------------------------
-  float* sh = &sh_o[0][0][0];
-#pragma unroll 1
-  for (int h = 0; h < NREP; ++h)
-    merge_head(po, pm, pl, ((size_t)unit * NREP + h) * n_ranges, nr, sh, out + ((size_t)unit * NREP + h) * kD);
+  // ---- the unit's last workgroup merges the partials of all workgroups --------------------------------------
+  merge_heads<NREP>(po, pm, pl, unit, n_slots, n_wgs, &sh_o[0][0][0], out + (size_t)unit * NREP * kD);
   if (tid == 0) c->arrive[2] = 0;
   FIER_PROF(25, unit == 0)
   // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
@@ -399,20 +426,19 @@ static hipError_t launch_attn_dt(int n_rep, const void* K, const void* V, const 
   return hipGetLastError();
 }
 
-template <int DT>
+template <int DT, int RPW>
 static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                           const void* q, const int32_t* seq_lens, int extra, int max_budget,
                                           float sm_scale, int32_t* idx_out, float* out, float* kabsmax, int units,
                                           int n_kv_heads, int max_ctx, hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  dim3 grid(n_ranges, units);
+  dim3 grid((n_ranges + RPW - 1) / RPW, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
-#define FIER_SA_CASE(R)                                                                                             \
-  case R:                                                                                                           \
-    select_attend_kernel<DT, R><<<grid, 256, 0, st>>>(sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K,             \
-                                                      (const uint4*)V, (const uint4*)q, seq_lens, extra, max_budget, \
-                                                      sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax,   \
-                                                      n_ranges, n_kv_heads, max_ctx);                               \
+#define FIER_SA_CASE(R)                                                                                            \
+  case R:                                                                                                          \
+    select_attend_kernel<DT, R, RPW><<<grid, 256, 0, st>>>(                                                        \
+        sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K, (const uint4*)V, (const uint4*)q, seq_lens, extra,       \
+        max_budget, sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax, n_ranges, n_kv_heads, max_ctx);    \
     break;
   switch (n_rep) {
     FIER_SA_CASE(1)
@@ -430,15 +456,33 @@ static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, cons
   return hipGetLastError();
 }
 
+int select_attend_ranges_per_wg(int max_budget, int max_ctx) {
+  // about a hundred selected rows per workgroup: rows per 1024-token range = 1024 * budget / context
+  const double per_range = 1024.0 * (double)max_budget / (double)max_ctx;
+  int rpw = 1;
+  while (rpw < 8 && per_range * rpw < 96.0) rpw *= 2;
+  return rpw;
+}
+
 hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
                                 int32_t* idx_out, float* out, float* kabsmax, int units, int n_kv_heads, int max_ctx,
                                 hipStream_t st) {
-  if (dtype == DT_F16)
-    return launch_select_attend_dt<DT_F16>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out,
-                                           kabsmax, units, n_kv_heads, max_ctx, st);
-  return launch_select_attend_dt<DT_BF16>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out,
-                                          kabsmax, units, n_kv_heads, max_ctx, st);
+#define FIER_SA_RPW(DT, RPW)                                                                                        \
+  return launch_select_attend_dt<DT, RPW>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out, \
+                                          kabsmax, units, n_kv_heads, max_ctx, st)
+  const int rpw = select_attend_ranges_per_wg(max_budget, max_ctx);
+  if (dtype == DT_F16) {
+    if (rpw == 1) FIER_SA_RPW(DT_F16, 1);
+    if (rpw == 2) FIER_SA_RPW(DT_F16, 2);
+    if (rpw == 4) FIER_SA_RPW(DT_F16, 4);
+    FIER_SA_RPW(DT_F16, 8);
+  }
+  if (rpw == 1) FIER_SA_RPW(DT_BF16, 1);
+  if (rpw == 2) FIER_SA_RPW(DT_BF16, 2);
+  if (rpw == 4) FIER_SA_RPW(DT_BF16, 4);
+  FIER_SA_RPW(DT_BF16, 8);
+#undef FIER_SA_RPW
 }
 
 hipError_t launch_attn(int dtype, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,

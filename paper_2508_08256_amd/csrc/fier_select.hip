@@ -141,11 +141,16 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
       if (sseg < nc) {
         if ((uint32_t)sk < seg_size[sseg]) lcand[seg_base[sseg] + sk] = spec;
       }
-      for (int sg = 0; sg < nc; ++sg) {
-        const uint32_t cnt_s = seg_size[sg];
-        const bool prefetched = sg < kThrThreads / kSpecCand;  // its first kSpecCand entries are already in LDS
-        for (uint32_t k = (prefetched ? kSpecCand : 0) + tid; k < cnt_s; k += kThrThreads)
-          lcand[seg_base[sg] + k] = load_coherent(&ucand[(size_t)sg * kSegCand + k]);
+      // the rest in one batch of independent loads: flat entry e -> (segment, slot) by binary search of seg_base
+      for (uint32_t e = tid; e < total_cand; e += kThrThreads) {
+        int lo = 0, hi = nc - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (seg_base[mid] <= e) lo = mid; else hi = mid - 1;
+        }
+        const uint32_t k = e - seg_base[lo];
+        const bool prefetched = lo < kThrThreads / kSpecCand && k < (uint32_t)kSpecCand;
+        if (!prefetched) lcand[e] = load_coherent(&ucand[(size_t)lo * kSegCand + k]);
       }
       __syncthreads();
       done = exact_select_lds<kThrThreads, kSubBins, kSubCandMax>(lcand, total_cand, r_want, tbin, R, scale, hist,
