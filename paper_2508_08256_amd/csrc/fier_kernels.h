@@ -19,7 +19,7 @@ constexpr int kSelBins = 512;          // equal-width score histogram bins over 
 constexpr int kRangeTokens = 1024;     // tokens per workgroup in the score and the select+attend kernels
 constexpr int kClassifyTokens = 4096;  // tokens per workgroup in the threshold kernel
 constexpr int kSegCand = 1024;         // candidate slots per threshold-kernel workgroup
-constexpr int kSelCandMax = 8192;      // candidates per unit the exact selection handles in LDS
+constexpr int kSelCandMax = 4096;      // candidates per unit the exact selection handles in LDS
 constexpr int kSubBins = 1024;         // second-level bins inside the threshold bin
 constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 

@@ -24,7 +24,26 @@
 #include "fier_kernels.h"
 #include "fier_quant_dev.h"
 
+// MFMA variant of the inner product (the default).  The contraction over the 128 channels runs on the matrix
+// cores with the 1-bit codes as the B operand and the per-group weights as the A operand of
+// v_mfma_f32_16x16x32_bf16:
+//   * B (bits): a bfloat16 whose only set bit is exponent bit e IS the number 2^(2^e - 127); one v_and of the code
+//     word with a two-bit mask therefore yields two B elements (one per 16-bit half), eight masks cover bits
+//     7..14 / 23..30 of a word and one rotation by 8 the other sixteen bits: 17 vector ops per 32 elements instead
+//     of 2.2 per element.  Lane (n, kq) of the wavefront owns word kq of token n of a 16-token tile;
+//   * A (weights): w = q_c s_c times the inverse of its bit's power of two (and 2^-32 against overflow), split
+//     exactly into three bfloat16 terms (8 + 8 + 8 significand bits), one matrix row per term: rows 0-2 carry the
+//     first group of the pair block, rows 8-10 the second.  The rows are built once per pair block by the lanes
+//     that hold the group's (s, z) and handed to the A layout through 4 KiB of LDS per wavefront;
+//   * every product is exact (one factor is a power of two), the matrix core accumulates in binary32, and the
+//     three rows of a group are added at the end: the result is the same fp32 sum, in another order.
 namespace fier {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr bool kScoreUseMfma = true;
 
 constexpr int kScorePairsPerWave = kRangeTokens / 256;  // pair blocks per wavefront (4 wavefronts per workgroup)
 
@@ -92,7 +111,7 @@ __device__ __forceinline__ float wave_allsum(float x) {
 // append (every workgroup must bin with the same R); the new group's contribution is handed to the last kernel
 // of the step through `newmax`.  A score outside [-R, R] simply lands in the outermost bin.
 template <int DT, int NREP, bool HIST>
-__global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const uint4* kmeta,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HIST ? 5 : 4))) void score_kernel(const uint4* kbits, const uint4* kmeta,
                                                     const float* __restrict__ kabsmax, const uint16_t* __restrict__ q,
                                                     const int32_t* __restrict__ seq_lens, int extra,
                                                     float* __restrict__ scores, UnitCtl* __restrict__ ctl,
@@ -102,6 +121,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
                                                     const uint32_t* __restrict__ v_new, float* __restrict__ newmax,
                                                     int n_kv_heads, int max_ctx) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
+  __shared__ __attribute__((aligned(16))) uint16_t a_lds[kScoreUseMfma ? 4 * 4 * 16 * 32 : 8];  // [wave][j][row][k]
   __shared__ uint32_t scan_tmp[4];
   __shared__ uint32_t flag;
   __shared__ int found[2];
@@ -131,6 +151,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const int row = lane >> 4, n = lane & 15;
   FIER_PROF(0, HIST && unit == 0 && range == 3)
   FIER_PROF(7, HIST && unit == 0 && append_wg)
+  FIER_PROF(26, HIST && unit == (int)gridDim.y - 1 && range == 30)
+  FIER_PROF(28, HIST && unit == (int)gridDim.y / 2 && range == 16)
 
   // The lane's 8 query channels, summed over the query heads that share this kv head (binary32), times
   // 2^-16: qz for the offsets, qx additionally times the inverse of the power of two its bit is tested at.
@@ -198,6 +220,135 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   }
 
   const int P0 = range * (4 * kScorePairsPerWave) + wave;  // this wave's blocks: P0, P0 + 4, ...
+  if constexpr (kScoreUseMfma) {
+    // zero this wave's A buffer once: the rows that carry no weights must read as zero
+    {
+      uint4* az = reinterpret_cast<uint4*>(a_lds) + wave * 256;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) az[lane + 64 * k] = make_uint4(0, 0, 0, 0);
+    }
+    if (!append_wg && P0 * kPair < L) {
+      const uint32_t* __restrict__ bits_u = reinterpret_cast<const uint32_t*>(kbits) + (size_t)unit * max_ctx * 4;
+      const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
+      const int gsel = row >> 1;   // the group whose (s, z) this row of lanes holds
+      const int hsel = row & 1;    // the 64-channel half whose weights this row converts
+      // per-lane constants of the weight rows: channel c_e = 64 hsel + 4n + e sits in word kq_c at bit i_c
+      float qf[4];
+      int a_off[4];  // byte offset of the first (most significant) term of channel e in this wave's A buffer
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int kq_c = hsel + 2 * (e & 1);
+        const int i_c = 2 * n + (e >> 1);
+        int v, hf, p;
+        if (i_c >= 7 && i_c <= 14) {
+          v = 0, hf = 0, p = i_c;
+        } else if (i_c >= 23 && i_c <= 30) {
+          v = 0, hf = 1, p = i_c - 16;
+        } else if (i_c >= 15 && i_c <= 22) {
+          v = 1, hf = 0, p = i_c - 8;
+        } else {
+          v = 1, hf = 1, p = (i_c + 8) & 31;
+        }
+        const int j = 2 * v + ((p - 7) >> 2), r = (p - 7) & 3, k = 8 * kq_c + 2 * r + hf;
+        // 2^-32 / (value of a bfloat16 whose only set bit is bit p) = 2^(95 - 2^(p-7))
+        const float comp = __uint_as_float((uint32_t)(127 + 95 - (1 << (p - 7))) << 23);
+        qf[e] = qz[4 * hsel + e] * 65536.0f * comp;  // qz holds q * 2^-16
+        a_off[e] = wave * 4096 + j * 1024 + (8 * gsel) * 64 + k * 2;
+      }
+      float qb8[8];  // q * 2^-32 for the offsets z
+#pragma unroll
+      for (int m = 0; m < 8; ++m) qb8[m] = qz[m] * 1.52587890625e-05f;
+
+      uint32_t w_cur[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) w_cur[t] = bits_u[(size_t)(P0 * kPair + 16 * t + n) * 4 + row];
+      uint4 ma_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + n];
+      uint4 mb_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + 16 + n];
+      char* a_bytes = reinterpret_cast<char*>(a_lds);
+
+#pragma unroll 1
+      for (int it = 0; it < kScorePairsPerWave; ++it) {
+        const int P = P0 + 4 * it;
+        if (P * kPair >= L) break;
+        int Pn = P + 4;
+        Pn = (it + 1 < kScorePairsPerWave && Pn * kPair < L) ? Pn : P;
+        uint32_t w_nxt[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w_nxt[t] = bits_u[(size_t)(Pn * kPair + 16 * t + n) * 4 + row];
+        const uint4 ma_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + n];
+        const uint4 mb_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + 16 + n];
+
+        // ---- weight rows of this row's group and channel half -> LDS ----------------------------------------
+        const uint32_t mwa[4] = {ma_cur.x, ma_cur.y, ma_cur.z, ma_cur.w};
+        const uint32_t mwb[4] = {mb_cur.x, mb_cur.y, mb_cur.z, mb_cur.w};
+        float basep = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          basep += qb8[e] * hi16f<DT>(mwa[e]);
+          basep += qb8[4 + e] * hi16f<DT>(mwb[e]);
+          const float sv = lo16f<DT>(hsel ? mwb[e] : mwa[e]);
+          const float w = qf[e] * sv;
+          const uint32_t wb = __float_as_uint(w);
+          const float r1 = w - __uint_as_float(wb & 0xffff0000u);
+          const uint32_t r1b = __float_as_uint(r1);
+          const float r2 = r1 - __uint_as_float(r1b & 0xffff0000u);
+          *reinterpret_cast<uint16_t*>(a_bytes + a_off[e]) = (uint16_t)(wb >> 16);
+          *reinterpret_cast<uint16_t*>(a_bytes + a_off[e] + 64) = (uint16_t)(r1b >> 16);
+          *reinterpret_cast<uint16_t*>(a_bytes + a_off[e] + 128) = (uint16_t)(__float_as_uint(r2) >> 16);
+        }
+        const float base = row_allsum(basep);  // every row holds all 128 offsets of its group
+        // the writes above come from other lanes of this same wavefront: LDS operations of a wavefront complete
+        // in order, the fence keeps the compiler from moving the reads above them
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        bf16x8_t areg[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          areg[j] = __builtin_bit_cast(
+              bf16x8_t, *reinterpret_cast<const u32x4_t*>(a_bytes + wave * 4096 + j * 1024 + n * 64 + row * 16));
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // reads done before the next block's writes
+
+        // ---- four 16-token tiles: bits -> B operand, 4 MFMAs each -------------------------------------------
+        floatx4_t acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint32_t word = (j >> 1) ? rotr32(w_cur[t], 8) : w_cur[t];
+            u32x4_t b;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int p = 7 + 4 * (j & 1) + r;
+              b[r] = word & ((1u << p) | (1u << (p + 16)));
+            }
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[j], __builtin_bit_cast(bf16x8_t, b), acc[t], 0, 0, 0);
+          }
+        }
+        // rows 0-2 (lanes 0-15) hold the first group's tiles 0, 1; rows 8-10 (lanes 32-47) the second group's 2, 3
+        const bool second = row == 2;
+        const floatx4_t da = second ? acc[2] : acc[0], db = second ? acc[3] : acc[1];
+        const float sa = (((da[0] + da[1]) + da[2]) + base) * 4294967296.0f;
+        const float sb = (((db[0] + db[1]) + db[2]) + base) * 4294967296.0f;
+        if ((row & 1) == 0) {
+          const int tok = P * kPair + 16 * row + n;  // row 0: tokens n, 16 + n; row 2: 32 + n, 48 + n
+          if (tok < L && tok < tail_start) {
+            scores[(size_t)unit * max_ctx + tok] = sa;
+            if (HIST) atomicAdd(&lhist[sel_bin(sa, R, hscale, kSelBins)], 1u);
+          }
+          if (tok + 16 < L && tok + 16 < tail_start) {
+            scores[(size_t)unit * max_ctx + tok + 16] = sb;
+            if (HIST) atomicAdd(&lhist[sel_bin(sb, R, hscale, kSelBins)], 1u);
+          }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w_cur[t] = w_nxt[t];
+        ma_cur = ma_nxt;
+        mb_cur = mb_nxt;
+      }
+    }
+  } else {
   if (!append_wg && P0 * kPair < L) {
     const uint4* __restrict__ bits_u = kbits + (size_t)unit * max_ctx;
     const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
@@ -253,8 +404,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     }
   }
 
+  }
+
   FIER_PROF(2, HIST && unit == 0 && range == 3)
   FIER_PROF(8, HIST && unit == 0 && append_wg)
+  FIER_PROF(27, HIST && unit == (int)gridDim.y - 1 && range == 30)
+  FIER_PROF(29, HIST && unit == (int)gridDim.y / 2 && range == 16)
   if constexpr (HIST) {
     __syncthreads();
     uint32_t* __restrict__ gh = ghist + (size_t)unit * kSelBins;

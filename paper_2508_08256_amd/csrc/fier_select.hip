@@ -20,6 +20,7 @@ namespace fier {
 constexpr int kThrThreads = 1024;
 constexpr int kThrWaves = kThrThreads / 64;
 constexpr int kMaxRanges = (1 << 20) / kRangeTokens;  // max_ctx <= 2^20
+constexpr int kMaxChunks = (1 << 20) / kClassifyTokens;
 constexpr int kSpecCand = 64;                          // candidates per segment fetched before its count is known
 
 // grid (ceil(max_ctx / 4096), units), block 1024
@@ -41,8 +42,8 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   __shared__ unsigned long long lcand[kSelCandMax];
   __shared__ unsigned long long sub_list[kSubCandMax];
   __shared__ uint32_t rsel[kMaxRanges];
-  __shared__ uint32_t seg_base[kThrThreads];  // one workgroup per 4096 tokens: at most 256 segments
-  __shared__ uint32_t seg_size[kThrThreads];
+  __shared__ uint32_t seg_base[kMaxChunks];  // one segment per classifying workgroup
+  __shared__ uint32_t seg_size[kMaxChunks];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
