@@ -14,6 +14,7 @@ SOURCES = ["fier_api.hip", "fier_quantize.hip", "fier_score.hip", "fier_select.h
            "fier_attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",  # matrix-core results stay in ordinary vector registers
          "-I", INCLUDE, "-I", CSRC]
 
 

@@ -1,94 +1,44 @@
 // Approximate scores from the 1-bit key cache (Alg. 1 step 2):
 //   score[j] = sum_c q_c * (z[G(j)][c] + bit[j][c] * s[G(j)][c]),  q = sum of the unit's query heads.
 //
-// Lane = token.  One wavefront owns one pair block (64 tokens = groups 2P and 2P+1) at a time:
-//   * each lane loads the 16-byte code word of its own token (one coalesced 1 KiB request per block);
-//   * the per-group weights w[c] = q_c * s[G][c] differ between the two halves of the wavefront.  They
-//     stay distributed: each row of 16 lanes holds all 128 weights of its own group in 8 registers
-//     (lane n of the row holds 8 channels), and a DPP row broadcast inside the multiply-add hands weight
-//     (m, n) to the 16 lanes of the row.  No LDS and no replication through memory;
-//   * "bit ? w : 0" costs no select: a code word ANDed with a single-bit mask in the exponent field of a
-//     binary32 IS the number 2^k or 0 (bit 30 -> 2, 29 -> 2^-63, 28 -> 2^-95, 27 -> 2^-111).  The weight
-//     register carries the inverse power of two (folded into q once per kernel), so one v_and and one
-//     v_fmac with a DPP source accumulate bit * w exactly.  Eight rotations of each code word bring every
-//     bit to one of the four usable positions: 2 + 7/32 vector ops per (token, channel);
-//   * q is pre-scaled by 2^-16 so that w * 2^111 stays finite for |q_c s_c| < 2^32 (any binary16 data);
-//     the final score is scaled back by 2^16.  All scalings are powers of two: no rounding is added;
-//   * base[G] = sum_c q_c * z[G][c] is reduced inside each row with DPP rotates.
+// The contraction over the 128 channels runs on the matrix cores as an int8 product
+// (v_mfma_i32_16x16x64_i8), one wavefront per pair block (64 tokens = groups 2P and 2P+1) at a time:
+//   * B operand = the codes.  A byte with a single bit k set IS the integer 2^k (bit 7: -128), so one v_and of a
+//     code word with 0x01010101 << k yields four B elements: 8 vector ops expand 32 codes.  Lane (n, kq) of the
+//     wavefront owns word kq of token n of a 16-token tile, which is exactly the B layout (k = 16 kq + 0..15);
+//   * A operand = the weights.  w = q_c s_c (binary32 product), divided by its bit's power of two and turned
+//     into a 31-bit fixed-point number relative to the largest |w| of its own group (the scale is a power of
+//     two, found per group with a DPP max), then cut into four signed bytes: F = d0 + 2^8 d1 + 2^16 d2 + 2^24 d3.
+//     The four digits are four rows of A.  The rows are built once per pair block by the lanes that hold the
+//     group's (s, z) and reach the A layout through 1.3 KiB of LDS per wavefront;
+//   * the digit rows are read back as two A operands, one with the digits in rows 0-3 / 8-11 and zeros elsewhere
+//     for the first tile of each group, one with them in rows 4-7 / 12-15 for the second tile: both tiles of a
+//     group accumulate into one 16x16 result that holds tile t in rows 4t..4t+3, the rows lane row t receives.
+//     Lane l ends up with the four digit sums of token l of the block, recombines them in binary32 and adds
+//     base[G] = sum_c q_c z[G][c];
+//   * the integer accumulation is exact; the only rounding is the fixed-point step of the weights,
+//     <= 2^(k-1) * 2^-30 * 2 max_c|w_c| per channel, about 4e-6 max|w| in the worst case over 128 channels.
 //
-// Channel bookkeeping.  Meta: lane n of a row loads (s,z) of channels 4n..4n+3 and 64+4n..64+4n+3 as two
-// 16-byte requests: register m = 4h + e holds channel c = 64h + 4n + e.  Bits: channel c sits in word
-// d = h + 2(e & 1) at bit i = 2n + (e >> 1).  Bit i is tested in rotation a = ((i - 27) mod 32) / 4 at
-// position 27 + ((i - 27) mod 4).
+// Channel bookkeeping.  Row r = lane / 16 works for group g = r / 2 and channel half h = r % 2; lane n of the row
+// loads (s, z) of channels c = 64h + 4n + e, e = 0..3, as one 16-byte request.  Channel c sits in code word
+// kq = h + 2(e & 1) at bit i = 2n + (e >> 1), i.e. byte y = i / 8, bit k = i % 8: MFMA j = k / 4, B register
+// r = k % 4, contraction index K = 16 kq + 4r + y.
 #include "fier_dev.h"
 #include "fier_kernels.h"
 #include "fier_quant_dev.h"
 
-// MFMA variant of the inner product (the default).  The contraction over the 128 channels runs on the matrix
-// cores with the 1-bit codes as the B operand and the per-group weights as the A operand of
-// v_mfma_f32_16x16x32_bf16:
-//   * B (bits): a bfloat16 whose only set bit is exponent bit e IS the number 2^(2^e - 127); one v_and of the code
-//     word with a two-bit mask therefore yields two B elements (one per 16-bit half), eight masks cover bits
-//     7..14 / 23..30 of a word and one rotation by 8 the other sixteen bits: 17 vector ops per 32 elements instead
-//     of 2.2 per element.  Lane (n, kq) of the wavefront owns word kq of token n of a 16-token tile;
-//   * A (weights): w = q_c s_c times the inverse of its bit's power of two (and 2^-32 against overflow), split
-//     exactly into three bfloat16 terms (8 + 8 + 8 significand bits), one matrix row per term: rows 0-2 carry the
-//     first group of the pair block, rows 8-10 the second.  The rows are built once per pair block by the lanes
-//     that hold the group's (s, z) and handed to the A layout through 4 KiB of LDS per wavefront;
-//   * every product is exact (one factor is a power of two), the matrix core accumulates in binary32, and the
-//     three rows of a group are added at the end: the result is the same fp32 sum, in another order.
 namespace fier {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float floatx4_t __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr bool kScoreUseMfma = true;
 
-constexpr int kScorePairsPerWave = kRangeTokens / 256;  // pair blocks per wavefront (4 wavefronts per workgroup)
-
-__device__ __forceinline__ uint32_t rotr32(uint32_t x, int r) { return __builtin_amdgcn_alignbit(x, x, r); }
-
-// 2^-16 / (value of a binary32 whose only set bit is bit 27 + j)
-__device__ __forceinline__ float position_scale(int j) {
-  // j = 0: 2^111, 1: 2^95, 2: 2^63, 3: 2^-1, each times 2^-16
-  const uint32_t e = j == 0 ? (127u + 95u) : j == 1 ? (127u + 79u) : j == 2 ? (127u + 47u) : (127u - 17u);
-  return __uint_as_float(e << 23);
-}
-
-// Four channels (h, n, e = 0..3):  acc_e += bit ? X[4h+e] broadcast from row lane n : 0
-template <int H, int N>
-__device__ __forceinline__ void accumulate_4(const uint32_t (&V)[4][8], const float (&X)[8], float (&acc)[4]) {
-  constexpr int I0 = 2 * N, I1 = 2 * N + 1;
-  constexpr int R0 = (I0 + 32 - 27) % 32, R1 = (I1 + 32 - 27) % 32;
-  constexpr int A0 = R0 / 4, A1 = R1 / 4;
-  constexpr uint32_t M0 = 1u << (27 + R0 % 4), M1 = 1u << (27 + R1 % 4);
-  uint32_t t0, t1;
-  asm("v_and_b32 %[t0], %[m0], %[va]\n\t"
-      "v_and_b32 %[t1], %[m0], %[vb]\n\t"
-      "v_fmac_f32_dpp %[a0], %[x0], %[t0] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "v_and_b32 %[t0], %[m1], %[vc]\n\t"
-      "v_fmac_f32_dpp %[a1], %[x1], %[t1] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "v_and_b32 %[t1], %[m1], %[vd]\n\t"
-      "v_fmac_f32_dpp %[a2], %[x2], %[t0] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf\n\t"
-      "v_fmac_f32_dpp %[a3], %[x3], %[t1] row_newbcast:%[bc] row_mask:0xf bank_mask:0xf"
-      : [t0] "=&v"(t0), [t1] "=&v"(t1), [a0] "+&v"(acc[0]), [a1] "+&v"(acc[1]), [a2] "+&v"(acc[2]),
-        [a3] "+&v"(acc[3])
-      : [va] "v"(V[H][A0]), [vb] "v"(V[H + 2][A0]), [vc] "v"(V[H][A1]), [vd] "v"(V[H + 2][A1]), [x0] "v"(X[4 * H]),
-        [x1] "v"(X[4 * H + 1]), [x2] "v"(X[4 * H + 2]), [x3] "v"(X[4 * H + 3]), [m0] "s"(M0), [m1] "s"(M1),
-        [bc] "n"(N));
-}
-
-template <int H, int N>
-__device__ __forceinline__ void accumulate_from(const uint32_t (&V)[4][8], const float (&X)[8], float (&acc)[4]) {
-  if constexpr (H < 2) {
-    accumulate_4<H, N>(V, X, acc);
-    if constexpr (N + 1 < 16)
-      accumulate_from<H, N + 1>(V, X, acc);
-    else
-      accumulate_from<H + 1, 0>(V, X, acc);
-  }
-}
+// LDS image of one wavefront's A operand: [j (K half)][group][digit][64 bytes], a zero row per j, padded so that
+// the (group, j) sub-blocks start in different banks.
+constexpr int kADigit = 64;
+constexpr int kAGroup = 320;
+constexpr int kAZeroRow = 576;
+constexpr int kAPlane = 672;
+constexpr int kAWave = 2 * kAPlane;
 
 __device__ __forceinline__ float wave_allsum(float x) {
   x = row_allsum(x);
@@ -97,8 +47,26 @@ __device__ __forceinline__ float wave_allsum(float x) {
   return x;
 }
 
-// grid (ceil(max_ctx / 1024) [+ 1 if HIST], units), block 256: workgroup x owns tokens [1024 x, 1024 x + 1024) of
-// its unit, wave w the pair blocks 16 x + w, + 4, + 8, + 12.
+// value of the lane 16 away (rows 0 <-> 1, 2 <-> 3)
+__device__ __forceinline__ float swap_rows(float x) {
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401f));  // bit mode: xor 16
+}
+// max over the 16 lanes of a row of non-negative floats, as unsigned integers (their bit patterns order alike)
+template <int N>
+__device__ __forceinline__ uint32_t row_ror_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + N, 0xf, 0xf, true);
+}
+__device__ __forceinline__ uint32_t row_allmax_u32(uint32_t x) {
+  x = max(x, row_ror_u32<8>(x));
+  x = max(x, row_ror_u32<4>(x));
+  x = max(x, row_ror_u32<2>(x));
+  x = max(x, row_ror_u32<1>(x));
+  return x;
+}
+
+// grid (ceil(max_ctx / (256 bpw)) [+ 1 if HIST], units), block 256: workgroup x owns 4 bpw consecutive pair blocks
+// of its unit, wave w the blocks 4 bpw x + w, + 4, + 8, ...  The launcher picks bpw so that the whole grid is
+// resident at once: the per-workgroup prologue (q, R) and epilogue (histogram flush, arrival) are then paid once.
 //
 // HIST (first kernel of the fused step): every score is also counted in an equal-width histogram of kSelBins
 // bins over [-R, R], R = sum_c |q_c| * absmax_c >= |score| -- a bound known before any score exists, so that
@@ -111,17 +79,17 @@ __device__ __forceinline__ float wave_allsum(float x) {
 // append (every workgroup must bin with the same R); the new group's contribution is handed to the last kernel
 // of the step through `newmax`.  A score outside [-R, R] simply lands in the outermost bin.
 template <int DT, int NREP, bool HIST>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HIST ? 5 : 4))) void score_kernel(const uint4* kbits, const uint4* kmeta,
+__global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const uint4* kmeta,
                                                     const float* __restrict__ kabsmax, const uint16_t* __restrict__ q,
                                                     const int32_t* __restrict__ seq_lens, int extra,
                                                     float* __restrict__ scores, UnitCtl* __restrict__ ctl,
                                                     uint32_t* __restrict__ ghist, const int32_t* __restrict__ budgets,
-                                                    int max_budget, uint32_t* K, uint32_t* V,
+                                                    int max_budget, uint32_t* __restrict__ K, uint32_t* __restrict__ V,
                                                     const uint32_t* __restrict__ k_new,
                                                     const uint32_t* __restrict__ v_new, float* __restrict__ newmax,
-                                                    int n_kv_heads, int max_ctx) {
+                                                    int n_kv_heads, int max_ctx, int bpw) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
-  __shared__ __attribute__((aligned(16))) uint16_t a_lds[kScoreUseMfma ? 4 * 4 * 16 * 32 : 8];  // [wave][j][row][k]
+  __shared__ __attribute__((aligned(16))) unsigned char a_lds[4 * kAWave];
   __shared__ uint32_t scan_tmp[4];
   __shared__ uint32_t flag;
   __shared__ int found[2];
@@ -145,38 +113,69 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HIST ? 5 : 
     if (!app) return;
   } else {
     // range 0 of a unit always runs so that an empty unit still gets its control block written
-    if (range * kRangeTokens >= L && !(HIST && range == 0)) return;
+    if (range * (4 * kPair) * bpw >= L && !(HIST && range == 0)) return;
   }
   const int n_groups = max_ctx / kG;
   const int row = lane >> 4, n = lane & 15;
+  const int gsel = row >> 1;  // the group of the pair block whose (s, z) this row of lanes holds
+  const int hsel = row & 1;   // the 64-channel half it holds
   FIER_PROF(0, HIST && unit == 0 && range == 3)
   FIER_PROF(7, HIST && unit == 0 && append_wg)
-  FIER_PROF(26, HIST && unit == (int)gridDim.y - 1 && range == 30)
-  FIER_PROF(28, HIST && unit == (int)gridDim.y / 2 && range == 16)
 
-  // The lane's 8 query channels, summed over the query heads that share this kv head (binary32), times
-  // 2^-16: qz for the offsets, qx additionally times the inverse of the power of two its bit is tested at.
-  float qx[8], qz[8];
+  // ---- first block's loads go out before anything else (their addresses do not depend on q) ----------------
+  const int P0 = range * (4 * bpw) + wave;  // this wave's blocks: P0, P0 + 4, ...
+  const bool scoring = !append_wg && P0 * kPair < L;
+  const uint32_t* __restrict__ bits_u = reinterpret_cast<const uint32_t*>(kbits) + (size_t)unit * max_ctx * 4;
+  const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
+  // word `row` of token 16 t + n of block P sits at pb[64 t], pb = bits_u + P * 256 + 4 n + row;
+  // the lane's (s, z) quad of block P at pm = meta_u + (2 P + gsel) * 32 + 16 hsel + n
+  const uint32_t* const pb = bits_u + ((size_t)P0 * 256 + 4 * n + row);
+  const uint4* const pm = meta_u + ((size_t)(2 * P0 + gsel) * 32 + 16 * hsel + n);
+  // blocks of this wave that hold tokens: P0, P0 + 4, ... below ceil(L / 64), at most bpw
+  int nb = scoring ? ((L + kPair - 1) / kPair - P0 + 3) / 4 : 0;
+  nb = nb > bpw ? bpw : nb;
+  // three register buffers rotate: the block being scored and the next two already on their way
+  uint32_t wA[4] = {0, 0, 0, 0}, wB[4] = {0, 0, 0, 0}, wC[4] = {0, 0, 0, 0};
+  uint4 mA = make_uint4(0, 0, 0, 0), mB = mA, mC = mA;
+  // block P0 + 4 i of this wave; past the wave's last block the last one is fetched again (unconditional loads
+  // keep the count of outstanding requests the same on every path)
+  auto fetch = [&](uint32_t (&w)[4], uint4& m, int i) {
+    i = i < nb ? i : nb - 1;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) w[t] = pb[(size_t)i * 1024 + 64 * t];
+    m = pm[(size_t)i * 256];
+  };
+  if (scoring) {
+    fetch(wA, mA, 0);
+    fetch(wB, mB, 1);
+  }
+
+  // ---- the lane's 4 query channels c = 64 hsel + 4 n + e, summed over the query heads of this kv head ------
+  float qs[4];
   float R = 0.f, hscale = 0.f;
   const uint16_t* qb = q + (size_t)unit * NREP * kD;
   {
-    float rpart = 0.f;
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      const int e = m & 3;
-      const int c = 64 * (m >> 2) + 4 * n + e;
-      float s = 0.f;
+    for (int e = 0; e < 4; ++e) qs[e] = 0.f;
 #pragma unroll
-      for (int r = 0; r < NREP; ++r) s += w2f<DT>(qb[r * kD + c]);
-      const int i = 2 * n + (e >> 1);
-      qz[m] = s * 1.52587890625e-05f;
-      qx[m] = s * position_scale((i + 32 - 27) & 3);
-      if (HIST) rpart += fabsf(s) * kabsmax[(size_t)unit * kD + c];
+    for (int r = 0; r < NREP; ++r) {
+      const uint2 qq = *reinterpret_cast<const uint2*>(qb + r * kD + 64 * hsel + 4 * n);
+      qs[0] += lo16f<DT>(qq.x);
+      qs[1] += hi16f<DT>(qq.x);
+      qs[2] += lo16f<DT>(qq.y);
+      qs[3] += hi16f<DT>(qq.y);
     }
     if (HIST) {
-      // every row holds all 128 channels; lane 0's sum is taken so that R is bit-identical in every lane, wave
-      // and workgroup (the binning must be the same function everywhere)
-      R = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(row_allsum(rpart))));
+      const float4 am = *reinterpret_cast<const float4*>(kabsmax + (size_t)unit * kD + 64 * hsel + 4 * n);
+      float rpart = fabsf(qs[0]) * am.x;
+      rpart += fabsf(qs[1]) * am.y;
+      rpart += fabsf(qs[2]) * am.z;
+      rpart += fabsf(qs[3]) * am.w;
+      rpart = row_allsum(rpart);   // this half of the channels
+      rpart += swap_rows(rpart);   // both halves
+      // lane 0's sum is taken so that R is bit-identical in every lane, wave and workgroup (the binning must be
+      // the same function everywhere)
+      R = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(rpart)));
       hscale = (float)kSelBins / (R + R);
       for (int i = tid; i < kSelBins; i += 256) lhist[i] = 0;
       __syncthreads();
@@ -219,197 +218,114 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HIST ? 5 : 
     }
   }
 
-  const int P0 = range * (4 * kScorePairsPerWave) + wave;  // this wave's blocks: P0, P0 + 4, ...
-  if constexpr (kScoreUseMfma) {
-    // zero this wave's A buffer once: the rows that carry no weights must read as zero
-    {
-      uint4* az = reinterpret_cast<uint4*>(a_lds) + wave * 256;
+  if (scoring) {
+    // per-lane constants of the weight rows
+    float qk[4];   // q_c divided by the integer its code bit stands for in B
+    int a_wr[4];   // LDS byte offset of digit 0 of channel e
 #pragma unroll
-      for (int k = 0; k < 4; ++k) az[lane + 64 * k] = make_uint4(0, 0, 0, 0);
+    for (int e = 0; e < 4; ++e) {
+      const int kq_c = hsel + 2 * (e & 1);
+      const int i_c = 2 * n + (e >> 1);
+      const int y = i_c >> 3, k = i_c & 7;
+      // 2^-k, negative for k = 7 (a byte with only bit 7 set is -128)
+      const float inv_bit = __uint_as_float(((uint32_t)(127 - k) << 23) | (k == 7 ? 0x80000000u : 0u));
+      qk[e] = qs[e] * inv_bit;
+      a_wr[e] = wave * kAWave + (k >> 2) * kAPlane + gsel * kAGroup + 16 * kq_c + 4 * (k & 3) + y;
     }
-    if (!append_wg && P0 * kPair < L) {
-      const uint32_t* __restrict__ bits_u = reinterpret_cast<const uint32_t*>(kbits) + (size_t)unit * max_ctx * 4;
-      const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
-      const int gsel = row >> 1;   // the group whose (s, z) this row of lanes holds
-      const int hsel = row & 1;    // the 64-channel half whose weights this row converts
-      // per-lane constants of the weight rows: channel c_e = 64 hsel + 4n + e sits in word kq_c at bit i_c
-      float qf[4];
-      int a_off[4];  // byte offset of the first (most significant) term of channel e in this wave's A buffer
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int kq_c = hsel + 2 * (e & 1);
-        const int i_c = 2 * n + (e >> 1);
-        int v, hf, p;
-        if (i_c >= 7 && i_c <= 14) {
-          v = 0, hf = 0, p = i_c;
-        } else if (i_c >= 23 && i_c <= 30) {
-          v = 0, hf = 1, p = i_c - 16;
-        } else if (i_c >= 15 && i_c <= 22) {
-          v = 1, hf = 0, p = i_c - 8;
-        } else {
-          v = 1, hf = 1, p = (i_c + 8) & 31;
-        }
-        const int j = 2 * v + ((p - 7) >> 2), r = (p - 7) & 3, k = 8 * kq_c + 2 * r + hf;
-        // 2^-32 / (value of a bfloat16 whose only set bit is bit p) = 2^(95 - 2^(p-7))
-        const float comp = __uint_as_float((uint32_t)(127 + 95 - (1 << (p - 7))) << 23);
-        qf[e] = qz[4 * hsel + e] * 65536.0f * comp;  // qz holds q * 2^-16
-        a_off[e] = wave * 4096 + j * 1024 + (8 * gsel) * 64 + k * 2;
-      }
-      float qb8[8];  // q * 2^-32 for the offsets z
-#pragma unroll
-      for (int m = 0; m < 8; ++m) qb8[m] = qz[m] * 1.52587890625e-05f;
+    // Two A operands.  "Even" serves the first tile of each group and carries the digits of the first group in
+    // rows 0-3, of the second in rows 8-11; "odd" serves the second tiles with the same digits in rows 4-7 and
+    // 12-15; all other rows read the zero row.  The two tiles of a group then accumulate into one 16x16 result
+    // that holds tile t in rows 4t..4t+3, the rows lane row t receives.
+    if (lane < 32) *reinterpret_cast<uint32_t*>(a_lds + wave * kAWave + (lane >> 4) * kAPlane + kAZeroRow + 4 * n) = 0u;
+    const int a_real = (n >> 3) * kAGroup + (n & 3) * kADigit;
+    const int a_even = wave * kAWave + ((n & 4) ? kAZeroRow : a_real) + 16 * row;
+    const int a_odd = wave * kAWave + ((n & 4) ? a_real : kAZeroRow) + 16 * row;
 
-      uint32_t w_cur[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) w_cur[t] = bits_u[(size_t)(P0 * kPair + 16 * t + n) * 4 + row];
-      uint4 ma_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + n];
-      uint4 mb_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + 16 + n];
-      char* a_bytes = reinterpret_cast<char*>(a_lds);
-
-#pragma unroll 1
-      for (int it = 0; it < kScorePairsPerWave; ++it) {
-        const int P = P0 + 4 * it;
-        if (P * kPair >= L) break;
-        int Pn = P + 4;
-        Pn = (it + 1 < kScorePairsPerWave && Pn * kPair < L) ? Pn : P;
-        uint32_t w_nxt[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) w_nxt[t] = bits_u[(size_t)(Pn * kPair + 16 * t + n) * 4 + row];
-        const uint4 ma_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + n];
-        const uint4 mb_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + 16 + n];
-
-        // ---- weight rows of this row's group and channel half -> LDS ----------------------------------------
-        const uint32_t mwa[4] = {ma_cur.x, ma_cur.y, ma_cur.z, ma_cur.w};
-        const uint32_t mwb[4] = {mb_cur.x, mb_cur.y, mb_cur.z, mb_cur.w};
-        float basep = 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          basep += qb8[e] * hi16f<DT>(mwa[e]);
-          basep += qb8[4 + e] * hi16f<DT>(mwb[e]);
-          const float sv = lo16f<DT>(hsel ? mwb[e] : mwa[e]);
-          const float w = qf[e] * sv;
-          const uint32_t wb = __float_as_uint(w);
-          const float r1 = w - __uint_as_float(wb & 0xffff0000u);
-          const uint32_t r1b = __float_as_uint(r1);
-          const float r2 = r1 - __uint_as_float(r1b & 0xffff0000u);
-          *reinterpret_cast<uint16_t*>(a_bytes + a_off[e]) = (uint16_t)(wb >> 16);
-          *reinterpret_cast<uint16_t*>(a_bytes + a_off[e] + 64) = (uint16_t)(r1b >> 16);
-          *reinterpret_cast<uint16_t*>(a_bytes + a_off[e] + 128) = (uint16_t)(__float_as_uint(r2) >> 16);
-        }
-        const float base = row_allsum(basep);  // every row holds all 128 offsets of its group
-        // the writes above come from other lanes of this same wavefront: LDS operations of a wavefront complete
-        // in order, the fence keeps the compiler from moving the reads above them
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        bf16x8_t areg[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          areg[j] = __builtin_bit_cast(
-              bf16x8_t, *reinterpret_cast<const u32x4_t*>(a_bytes + wave * 4096 + j * 1024 + n * 64 + row * 16));
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // reads done before the next block's writes
-
-        // ---- four 16-token tiles: bits -> B operand, 4 MFMAs each -------------------------------------------
-        floatx4_t acc[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const uint32_t word = (j >> 1) ? rotr32(w_cur[t], 8) : w_cur[t];
-            u32x4_t b;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int p = 7 + 4 * (j & 1) + r;
-              b[r] = word & ((1u << p) | (1u << (p + 16)));
-            }
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[j], __builtin_bit_cast(bf16x8_t, b), acc[t], 0, 0, 0);
-          }
-        }
-        // rows 0-2 (lanes 0-15) hold the first group's tiles 0, 1; rows 8-10 (lanes 32-47) the second group's 2, 3
-        const bool second = row == 2;
-        const floatx4_t da = second ? acc[2] : acc[0], db = second ? acc[3] : acc[1];
-        const float sa = (((da[0] + da[1]) + da[2]) + base) * 4294967296.0f;
-        const float sb = (((db[0] + db[1]) + db[2]) + base) * 4294967296.0f;
-        if ((row & 1) == 0) {
-          const int tok = P * kPair + 16 * row + n;  // row 0: tokens n, 16 + n; row 2: 32 + n, 48 + n
-          if (tok < L && tok < tail_start) {
-            scores[(size_t)unit * max_ctx + tok] = sa;
-            if (HIST) atomicAdd(&lhist[sel_bin(sa, R, hscale, kSelBins)], 1u);
-          }
-          if (tok + 16 < L && tok + 16 < tail_start) {
-            scores[(size_t)unit * max_ctx + tok + 16] = sb;
-            if (HIST) atomicAdd(&lhist[sel_bin(sb, R, hscale, kSelBins)], 1u);
-          }
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) w_cur[t] = w_nxt[t];
-        ma_cur = ma_nxt;
-        mb_cur = mb_nxt;
-      }
-    }
-  } else {
-  if (!append_wg && P0 * kPair < L) {
-    const uint4* __restrict__ bits_u = kbits + (size_t)unit * max_ctx;
-    const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
-    const int gsel = row >> 1;
-
-    uint4 w_cur = bits_u[P0 * kPair + lane];
-    uint4 ma_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + n];
-    uint4 mb_cur = meta_u[(size_t)(2 * P0 + gsel) * (kD / 4) + 16 + n];
-
-#pragma unroll 1
-    for (int it = 0; it < kScorePairsPerWave; ++it) {
+    auto score_block = [&](const uint32_t (&w_cur)[4], const uint4& m_cur, int it) {
       const int P = P0 + 4 * it;
-      if (P * kPair >= L) break;
-      // prefetch the next block of this wave (clamped to stay inside the unit's buffers)
-      int Pn = P + 4;
-      Pn = (it + 1 < kScorePairsPerWave && Pn * kPair < L) ? Pn : P;
-      const uint4 w_nxt = bits_u[Pn * kPair + lane];
-      const uint4 ma_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + n];
-      const uint4 mb_nxt = meta_u[(size_t)(2 * Pn + gsel) * (kD / 4) + 16 + n];
 
-      const uint32_t mw[8] = {ma_cur.x, ma_cur.y, ma_cur.z, ma_cur.w, mb_cur.x, mb_cur.y, mb_cur.z, mb_cur.w};
-      float X[8];
+      // ---- this row's weights -> fixed point relative to the group's largest -> digit rows in LDS ----------
+      const uint32_t mw[4] = {m_cur.x, m_cur.y, m_cur.z, m_cur.w};
+      float wv[4];
       float basep = 0.f;
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        X[m] = qx[m] * lo16f<DT>(mw[m]);
-        basep += qz[m] * hi16f<DT>(mw[m]);
+      for (int e = 0; e < 4; ++e) {
+        wv[e] = qk[e] * lo16f<DT>(mw[e]);
+        basep += qs[e] * hi16f<DT>(mw[e]);
       }
-      const uint32_t ww[4] = {w_cur.x, w_cur.y, w_cur.z, w_cur.w};
-      uint32_t V[4][8];
+      uint32_t mx = __float_as_uint(fmaxf(fmaxf(fabsf(wv[0]), fabsf(wv[1])), fmaxf(fabsf(wv[2]), fabsf(wv[3]))));
+      mx = row_allmax_u32(mx);
+      mx = max(mx, (uint32_t)__builtin_amdgcn_ds_swizzle((int)mx, 0x401f));  // over all 128 channels of the group
+      // max|w| < 2^(ex - 126), ex its biased exponent: scale = 2^(156 - ex) keeps |w * scale| < 2^30
+      uint32_t exb = mx & 0x7f800000u;
+      exb = exb < (29u << 23) ? (29u << 23) : exb;
+      const float scale = __uint_as_float(0x8d800000u - exb);      // (283 - ex) << 23
+      const float inv_scale = __uint_as_float(exb - (29u << 23));  // 2^(ex - 156); 0 when the group carries nothing
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        V[d][0] = ww[d];
-#pragma unroll
-        for (int a = 1; a < 8; ++a) V[d][a] = rotr32(ww[d], 4 * a);
+      for (int e = 0; e < 4; ++e) {
+        const int F = (int)rintf(wv[e] * scale);
+        // signed digits: the bytes of (F + 0x808080) ^ 0x808080, the top one as it is
+        const uint32_t X = ((uint32_t)F + 0x00808080u) ^ 0x00808080u;
+        unsigned char* dst = a_lds + a_wr[e];
+        dst[0] = (unsigned char)X;
+        dst[kADigit] = (unsigned char)(X >> 8);
+        dst[2 * kADigit] = (unsigned char)(X >> 16);
+        dst[3 * kADigit] = (unsigned char)(X >> 24);
       }
-      const float base = row_allsum(basep);
-      // A DPP source must not be read within two issue slots of the VALU write that produced it.  The weights
-      // pass through this fence so that every later DPP read of them is at least that far from their writes.
-      asm volatile("s_nop 1"
-                   : "+v"(X[0]), "+v"(X[1]), "+v"(X[2]), "+v"(X[3]), "+v"(X[4]), "+v"(X[5]), "+v"(X[6]), "+v"(X[7]));
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
-      accumulate_from<0, 0>(V, X, acc);
-      const float sc = (((acc[0] + acc[1]) + (acc[2] + acc[3])) + base) * 65536.0f;
+      float base = row_allsum(basep);
+      base += swap_rows(base);  // every lane of rows 2g, 2g + 1: base of group g
+      // the writes above come from other lanes of this same wavefront: LDS operations of a wavefront complete
+      // in order, the fences keep the compiler from moving the reads above them
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+      // ---- 4 tiles x 2 K-halves ----------------------------------------------------------------------------
+      const i32x4_t ae0 = *reinterpret_cast<const i32x4_t*>(a_lds + a_even);
+      const i32x4_t ae1 = *reinterpret_cast<const i32x4_t*>(a_lds + a_even + kAPlane);
+      const i32x4_t ao0 = *reinterpret_cast<const i32x4_t*>(a_lds + a_odd);
+      const i32x4_t ao1 = *reinterpret_cast<const i32x4_t*>(a_lds + a_odd + kAPlane);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // reads done before the next block's writes
+      i32x4_t acc[2];
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        i32x4_t b[2][2];  // [tile of the group][K half]
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            b[u][0][r] = (int)(w_cur[2 * g + u] & (0x01010101u << r));
+            b[u][1][r] = (int)(w_cur[2 * g + u] & (0x01010101u << (4 + r)));
+          }
+        acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ae0, b[0][0], i32x4_t{0, 0, 0, 0}, 0, 0, 0);
+        acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ae1, b[0][1], acc[g], 0, 0, 0);
+        acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ao0, b[1][0], acc[g], 0, 0, 0);
+        acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ao1, b[1][1], acc[g], 0, 0, 0);
+      }
+      // lane l = 16 row + n is token l of the block: its digit sums are registers 0..3 of its group's result
+      const i32x4_t dg = gsel ? acc[1] : acc[0];
+      float f = (float)dg[0];
+      f = fmaf((float)dg[1], 256.0f, f);
+      f = fmaf((float)dg[2], 65536.0f, f);
+      f = fmaf((float)dg[3], 16777216.0f, f);
+      const float sc = fmaf(f, inv_scale, base);
       const int tok = P * kPair + lane;
       if (tok < L && tok < tail_start) {
         scores[(size_t)unit * max_ctx + tok] = sc;
         if (HIST) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
       }
-      w_cur = w_nxt;
-      ma_cur = ma_nxt;
-      mb_cur = mb_nxt;
+    };
+    for (int it = 0; it < nb; it += 3) {
+      fetch(wC, mC, it + 2);
+      score_block(wA, mA, it);
+      fetch(wA, mA, it + 3);
+      if (it + 1 < nb) score_block(wB, mB, it + 1);
+      fetch(wB, mB, it + 4);
+      if (it + 2 < nb) score_block(wC, mC, it + 2);
     }
-  }
-
   }
 
   FIER_PROF(2, HIST && unit == 0 && range == 3)
   FIER_PROF(8, HIST && unit == 0 && append_wg)
-  FIER_PROF(27, HIST && unit == (int)gridDim.y - 1 && range == 30)
-  FIER_PROF(29, HIST && unit == (int)gridDim.y / 2 && range == 16)
   if constexpr (HIST) {
     __syncthreads();
     uint32_t* __restrict__ gh = ghist + (size_t)unit * kSelBins;
@@ -417,7 +333,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HIST ? 5 : 
       const uint32_t c = lhist[i];
       if (c) atomicAdd(&gh[i], c);
     }
-    const uint32_t expected = (L > 0 ? (uint32_t)((L + kRangeTokens - 1) / kRangeTokens) : 1u) + (app ? 1u : 0u);
+    const int span = 4 * kPair * bpw;  // tokens per workgroup
+    const uint32_t expected = (L > 0 ? (uint32_t)((L + span - 1) / span) : 1u) + (app ? 1u : 0u);
     FIER_PROF(3, unit == 0 && range == 3)
     if (!last_arriver(&ctl[unit].arrive[0], expected, &flag)) return;
     FIER_PROF(4, unit == 0)
@@ -473,13 +390,20 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
                                   const StepBuffers* sb, const int32_t* budgets, int max_budget, void* K, void* V,
                                   const void* k_new, const void* v_new, int units, int n_kv_heads, int max_ctx,
                                   hipStream_t st) {
-  dim3 grid((max_ctx + kRangeTokens - 1) / kRangeTokens + (HIST ? 1 : 0), units);
+  // blocks per wavefront: the smallest that lets every workgroup be resident at once (256 CUs; the registers
+  // allow 4 workgroups per CU for the fused kernel, 8 for the score-only one), at least 4
+  const int n_blocks = (max_ctx + kPair - 1) / kPair;
+  const int wg_slots = HIST ? 256 * 4 - units : 256 * 8;
+  const int per_unit = wg_slots / units > 0 ? wg_slots / units : 1;
+  int bpw = (n_blocks + 4 * per_unit - 1) / (4 * per_unit);
+  bpw = bpw < 4 ? 4 : bpw;
+  dim3 grid((n_blocks + 4 * bpw - 1) / (4 * bpw) + (HIST ? 1 : 0), units);
 #define FIER_SCORE_CASE(R)                                                                                         \
   case R:                                                                                                          \
     score_kernel<DT, R, HIST><<<grid, 256, 0, st>>>(                                                               \
         (const uint4*)kbits, (const uint4*)kmeta, kabsmax, (const uint16_t*)q, seq_lens, extra, scores,            \
         sb ? sb->ctl : nullptr, sb ? sb->hist : nullptr, budgets, max_budget, (uint32_t*)K, (uint32_t*)V,          \
-        (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx);           \
+        (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx, bpw);      \
     break;
   switch (n_rep) {
     FIER_SCORE_CASE(1)
