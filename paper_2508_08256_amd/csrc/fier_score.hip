@@ -134,9 +134,6 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   // blocks of this wave that hold tokens: P0, P0 + 4, ... below ceil(L / 64), at most bpw
   int nb = scoring ? ((L + kPair - 1) / kPair - P0 + 3) / 4 : 0;
   nb = nb > bpw ? bpw : nb;
-  // three register buffers rotate: the block being scored and the next two already on their way
-  uint32_t wA[4] = {0, 0, 0, 0}, wB[4] = {0, 0, 0, 0}, wC[4] = {0, 0, 0, 0};
-  uint4 mA = make_uint4(0, 0, 0, 0), mB = mA, mC = mA;
   // block P0 + 4 i of this wave; past the wave's last block the last one is fetched again (unconditional loads
   // keep the count of outstanding requests the same on every path)
   auto fetch = [&](uint32_t (&w)[4], uint4& m, int i) {
@@ -145,10 +142,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     for (int t = 0; t < 4; ++t) w[t] = pb[(size_t)i * 1024 + 64 * t];
     m = pm[(size_t)i * 256];
   };
-  if (scoring) {
-    fetch(wA, mA, 0);
-    fetch(wB, mB, 1);
-  }
+  uint32_t w_cur[4] = {0, 0, 0, 0};
+  uint4 m_cur = make_uint4(0, 0, 0, 0);
+  if (scoring) fetch(w_cur, m_cur, 0);
 
   // ---- the lane's 4 query channels c = 64 hsel + 4 n + e, summed over the query heads of this kv head ------
   float qs[4];
@@ -241,8 +237,11 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     const int a_even = wave * kAWave + ((n & 4) ? kAZeroRow : a_real) + 16 * row;
     const int a_odd = wave * kAWave + ((n & 4) ? a_real : kAZeroRow) + 16 * row;
 
-    auto score_block = [&](const uint32_t (&w_cur)[4], const uint4& m_cur, int it) {
+    for (int it = 0; it < nb; ++it) {
       const int P = P0 + 4 * it;
+      uint32_t w_nxt[4];
+      uint4 m_nxt;
+      fetch(w_nxt, m_nxt, it + 1);  // the next block is on its way while this one is scored
 
       // ---- this row's weights -> fixed point relative to the group's largest -> digit rows in LDS ----------
       const uint32_t mw[4] = {m_cur.x, m_cur.y, m_cur.z, m_cur.w};
@@ -313,14 +312,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
         scores[(size_t)unit * max_ctx + tok] = sc;
         if (HIST) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
       }
-    };
-    for (int it = 0; it < nb; it += 3) {
-      fetch(wC, mC, it + 2);
-      score_block(wA, mA, it);
-      fetch(wA, mA, it + 3);
-      if (it + 1 < nb) score_block(wB, mB, it + 1);
-      fetch(wB, mB, it + 4);
-      if (it + 2 < nb) score_block(wC, mC, it + 2);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) w_cur[t] = w_nxt[t];
+      m_cur = m_nxt;
     }
   }
 
