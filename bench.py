@@ -33,17 +33,39 @@ WORKLOADS = {
                     n_planted=64, rotate=5, label="llama3_8b_gqa32x8_b4_ctx131072_budget4096_bf16_append1"),
     "config1": dict(batch=1, n_q_heads=8, n_kv_heads=8, L=4096, budget=512, dtype=0, chan="ones",
                     n_planted=16, rotate=4, label="small_mha8_ctx4096_budget512_fp16_append1"),
+    # budget sweep at 64k context: --budget picks the point (256, 1024, 4096, 7209, 16384)
+    "config4": dict(batch=1, n_q_heads=32, n_kv_heads=32, L=65536, budget=7209, dtype=0, chan="ones",
+                    n_planted=64, rotate=16, label="mha32_ctx65536_fp16_append1"),
+    # batched ragged serving step: 16 sequences, lengths U{8192..65536}, budget 11 % of each, 32 layers per step
+    "config5": dict(batch=16, n_q_heads=32, n_kv_heads=8, L="ragged", L_lo=8192, L_hi=65536, budget="11%",
+                    dtype=1, chan="lognormal", n_planted=64, rotate=1, layers=32,
+                    label="llama3_8b_gqa32x8_b16_ragged8k-64k_budget11pct_bf16_32layers_append1"),
 }
 
 
-def algorithmic_bytes(w):
+def shape_of(w, seed):
+    """Per-sequence context lengths and budgets of a workload (ragged ones are drawn from the seed)."""
+    batch = w["batch"]
+    if w["L"] == "ragged":
+        rng = np.random.default_rng(seed)
+        lens = rng.integers(w["L_lo"], w["L_hi"] + 1, size=batch).astype(np.int64)
+    else:
+        lens = np.full(batch, w["L"], np.int64)
+    if w["budget"] == "11%":
+        buds = np.array([int(round(0.11 * int(l))) for l in lens], np.int64)
+    else:
+        buds = np.full(batch, w["budget"], np.int64)
+    return lens, buds
+
+
+def algorithmic_bytes(w, lens, buds):
     """Bytes the method has to move per layer step: packed keys + (s, z) metadata (32 B per cached token and
     unit), the selected K and V rows (512 B per selected token and unit), query in and fp32 output out."""
-    units = w["batch"] * w["n_kv_heads"]
+    hkv = w["n_kv_heads"]
     heads = w["batch"] * w["n_q_heads"]
-    n_tok = w["L"] + 1
-    packed = units * n_tok * 32
-    kv = units * min(w["budget"], n_tok) * 512
+    n_tok = lens + 1
+    packed = int(hkv * n_tok.sum() * 32)
+    kv = int(hkv * np.minimum(buds, n_tok).sum() * 512)
     qo = heads * (256 + 512)
     return dict(packed=packed, selected_kv=kv, q_out=qo, total=packed + kv + qo)
 
@@ -54,6 +76,7 @@ def main():
     ap.add_argument("--steps", type=int, default=600)
     ap.add_argument("--warmup", type=int, default=60)
     ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
+    ap.add_argument("--budget", type=int, default=None, help="token budget (config4's sweep point)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-steps", type=int, default=240, help="launches per stage for the per-stage timing")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -71,45 +94,62 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     B.lib()  # fail loudly if the HIP library is missing
-    w = WORKLOADS[args.workload]
-    R = w["rotate"]
-    batch, Hq, Hkv, L, budget, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["L"], w["budget"], w["dtype"]
+    w = dict(WORKLOADS[args.workload])
+    if args.budget is not None:
+        w["budget"] = args.budget
+        w["label"] += f"_budget{args.budget}"
+    elif args.workload == "config4":
+        w["label"] += f"_budget{w['budget']}"
+    R, NL = w["rotate"], w.get("layers", 1)
+    batch, Hq, Hkv, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["dtype"]
+    lens, buds = shape_of(w, 5000)
+    L, budget = int(lens.max()), int(buds.max())   # the largest context and budget (all of them when not ragged)
     max_ctx = -(-(L + 1) // 64) * 64
     cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype)
     units, n_rep = cfg.units, cfg.n_rep
-    tdt = torch.float16 if dtype == 0 else torch.bfloat16
+    if NL > 1 and args.steps == 600:
+        args.steps, args.warmup, args.stage_steps = 40, 4, 16   # a step is NL layers
 
-    # ---- resident inputs: R layer caches, quantized once (prefill), fresh q / k_new / v_new per cache ------
+    # ---- resident inputs: R sets of NL layer caches, quantized once (prefill), fresh q / k_new / v_new each ---
     t0 = time.time()
     caches, qs, kns, vns, hosts = [], [], [], [], None
-    seq_lens = torch.full((batch,), L, dtype=torch.int32, device="cuda")
-    budgets = torch.full((batch,), budget, dtype=torch.int32, device="cuda")
+    seq_lens = torch.as_tensor(lens.astype(np.int32), device="cuda")
+    budgets = torch.as_tensor(buds.astype(np.int32), device="cuda")
     for r in range(R):
-        d = synth.make_workload_device(f"{args.workload}_cache{r}", 1000 * 2 + r, batch, Hq, Hkv, [L] * batch,
-                                       [budget] * batch, dtype, max_ctx=max_ctx, chan=w["chan"],
-                                       n_planted=w["n_planted"])
-        c = B.DeviceCache(cfg, d["K"], d["V"], seq_lens)
-        B.quantize_keys(cfg, c)
-        caches.append(c)
-        qs.append(d["q"].reshape(1, batch, Hq, 128).contiguous())
-        kns.append(d["k_new"].reshape(1, units, 128).contiguous())
-        vns.append(d["v_new"].reshape(1, units, 128).contiguous())
-        if r == 0:
-            hosts = d
+        cl, ql, kl, vl = [], [], [], []
+        for layer in range(NL):
+            d = synth.make_workload_device(f"{args.workload}_cache{r}_{layer}", 1000 * 2 + r * NL + layer, batch, Hq,
+                                           Hkv, lens, buds, dtype, max_ctx=max_ctx, chan=w["chan"],
+                                           n_planted=w["n_planted"])
+            c = B.DeviceCache(cfg, d["K"], d["V"], seq_lens)
+            B.quantize_keys(cfg, c)
+            cl.append(c)
+            ql.append(d["q"].reshape(batch, Hq, 128))
+            kl.append(d["k_new"].reshape(units, 128))
+            vl.append(d["v_new"].reshape(units, 128))
+            if r == 0 and layer == 0:
+                hosts = {k: (v[:min(units, 32)].clone() if k in ("K", "V", "q", "k_new", "v_new") else v)
+                         for k, v in d.items()}
+            del d
+        caches.append(cl)
+        qs.append(torch.stack(ql).contiguous())
+        kns.append(torch.stack(kl).contiguous())
+        vns.append(torch.stack(vl).contiguous())
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
-    # one workspace per cache, so that a phase of the fused step can be timed alone on rotating caches
+    # one workspace per cache set, so that a phase of the fused step can be timed alone on rotating caches
     wss = [B.make_workspace(cfg, budget) for _ in range(R)]
     ws_dense = B.make_workspace(cfg, max_ctx)
-    out = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
-    idx = torch.zeros((1, units, budget), dtype=torch.int32, device="cuda")
-    cnt = torch.zeros((1, units), dtype=torch.int32, device="cuda")
+    out = torch.zeros((NL, batch, Hq, 128), dtype=torch.float32, device="cuda")
+    out1 = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((NL, units, budget), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((NL, units), dtype=torch.int32, device="cuda")
     scores = torch.zeros((units, max_ctx), dtype=torch.float32, device="cuda")
 
     def step(i):
         r = i % R
-        B.decode_step(cfg, [caches[r]], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r])
+        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r])
 
     def timed(fn, n, warm):
         for i in range(warm):
@@ -127,6 +167,38 @@ def main():
     # ---- the timed region: K whole steps ----------------------------------------------------------------
     us_step, us_wall = timed(step, args.steps, args.warmup)
 
+    # ---- spread of single steps: an event between consecutive steps ------------------------------------------
+    n_dist = min(args.steps, 200)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_dist + 1)]
+    evs[0].record()
+    for i in range(n_dist):
+        step(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    single = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_dist)])
+
+    # ---- the same steps replayed from one HIP graph ------------------------------------------------------------
+    us_graph = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for r in range(R):
+                step(r)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for r in range(R):
+                step(r)
+        torch.cuda.synchronize()
+        n_rep_g = max(3, min(args.steps, 240) // R)
+        us_graph, _ = timed(lambda i: graph.replay(), n_rep_g, 2)
+        us_graph /= R
+        del graph
+    except Exception as e:  # a capture problem must not lose the measurement above
+        sys.stderr.write(f"bench.py: graph replay skipped: {e}\n")
+
     # ---- each kernel of the fused step alone (HIP events on the launch stream, rotating caches) ----------
     ns = args.stage_steps
     for r in range(R):
@@ -136,28 +208,33 @@ def main():
     def phase(p):
         def run(i):
             r = i % R
-            B.decode_step_phase(cfg, [caches[r]], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r], p)
+            B.decode_step_phase(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r], p)
         return run
 
-    us_k1, _ = timed(phase(1), ns, 12)
-    us_k2, _ = timed(phase(2), ns, 12)
-    us_k3, _ = timed(phase(3), ns, 12)
+    us_k1, _ = timed(phase(1), ns, 12 if NL == 1 else 2)
+    us_k2, _ = timed(phase(2), ns, 12 if NL == 1 else 2)
+    us_k3, _ = timed(phase(3), ns, 12 if NL == 1 else 2)
+
+    # layer (r, l) of the flattened cache list, for the per-layer calls
+    flat = [(r, l) for r in range(R) for l in range(NL)]
 
     def st_dense(i):
-        r = i % R
-        B.dense_attn(cfg, caches[r], qs[r], 1, out, ws_dense)
+        r, l = flat[i % len(flat)]
+        B.dense_attn(cfg, caches[r][l], qs[r][l:l + 1], 1, out1, ws_dense)
 
     us_dense, _ = timed(st_dense, max(24, ns // 10), 4)
 
     # ---- stand-alone entry points (separate kernels, index list through memory) --------------------------
     def st_score(i):
-        B.score(cfg, caches[i % R], qs[i % R], 1, scores)
+        r, l = flat[i % len(flat)]
+        B.score(cfg, caches[r][l], qs[r][l:l + 1], 1, scores)
 
     def st_topk(i):
-        B.topk(cfg, scores, seq_lens, 1, budgets, budget, idx, cnt)
+        B.topk(cfg, scores, seq_lens, 1, budgets, budget, idx[0:1], cnt[0:1])
 
     def st_attn(i):
-        B.sparse_attn(cfg, caches[i % R], qs[i % R], idx, cnt, budget, out, wss[0])
+        r, l = flat[i % len(flat)]
+        B.sparse_attn(cfg, caches[r][l], qs[r][l:l + 1], idx[0:1], cnt[0:1], budget, out1, wss[0])
 
     us_score, _ = timed(st_score, max(24, ns // 4), 4)
     us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
@@ -171,25 +248,26 @@ def main():
         torch.cuda.synchronize()
         del a, bq
 
-    ab = algorithmic_bytes(w)
-    achieved = ab["total"] / (us_step * 1e-6) / 1e9
+    ab = algorithmic_bytes(w, lens, buds)          # per layer
+    us_layer = us_step / NL
+    achieved = ab["total"] / (us_layer * 1e-6) / 1e9
     # dominant kernel by algorithmic bytes: select + attend (selected K/V rows + q + out)
     k3_bytes = ab["selected_kv"] + ab["q_out"]
-    k3_gbps = k3_bytes / (us_k3 * 1e-6) / 1e9
-    k1_gbps = ab["packed"] / (us_k1 * 1e-6) / 1e9
-    dense_bytes = units * (L + 1) * 512 + ab["q_out"]
+    k3_gbps = k3_bytes / (us_k3 / NL * 1e-6) / 1e9
+    k1_gbps = ab["packed"] / (us_k1 / NL * 1e-6) / 1e9
+    dense_bytes = int(Hkv * (lens + 1).sum() * 512) + ab["q_out"]
 
     # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE runs,
     # scaled by what the same counters read for a plain copy of known size); None for other workloads
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"decode_step_{args.workload}_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.budget is None:
         with open(tpath) as f:
             traffic = json.load(f).get("traffic_bytes_per_launch")
 
     res = {
         "metric": "per-layer decode-step latency (us) + achieved HBM GB/s vs peak",
-        "value": round(us_step, 3),
+        "value": round(us_layer, 3),
         "unit": "us",
         "n_gpus": 1,
         "steps": args.steps,
@@ -201,64 +279,79 @@ def main():
         "dtype": "f16" if dtype == 0 else "bf16",
         "data": "synthetic",
         "config": {"workload": w["label"], "batch": batch, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128,
-                   "context": L, "budget": budget, "group_size": 32, "rotating_caches": R,
-                   "algorithmic_bytes_per_step": ab["total"]},
+                   "context": L if w["L"] != "ragged" else [int(x) for x in lens],
+                   "budget": budget if w["budget"] != "11%" else [int(x) for x in buds], "group_size": 32,
+                   "layers_per_step": NL, "rotating_caches": R * NL,
+                   "algorithmic_bytes_per_layer": ab["total"]},
         "achieved_GBps": round(achieved, 1),
         "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_step_wall": round(us_wall, 3),
-        "kernels_us": {"append_score_hist": round(us_k1, 3), "threshold": round(us_k2, 3),
-                       "select_attend_merge": round(us_k3, 3), "sum": round(us_k1 + us_k2 + us_k3, 3)},
+        "single_step_us": {"min": round(float(single.min()), 3), "median": round(float(np.median(single)), 3),
+                           "p95": round(float(np.percentile(single, 95)), 3), "n": int(n_dist)},
+        "graph_replay_us_per_step": None if us_graph is None else round(us_graph, 3),
+        "kernels_us": {"append_score_hist": round(us_k1 / NL, 3), "threshold": round(us_k2 / NL, 3),
+                       "select_attend_merge": round(us_k3 / NL, 3), "sum": round((us_k1 + us_k2 + us_k3) / NL, 3)},
         "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "select_attend_merge": round(k3_gbps, 1)},
         "standalone_calls_us": {"fier_score": round(us_score, 3), "fier_topk": round(us_topk, 3),
                                 "fier_sparse_attn": round(us_attn, 3)},
         "dense_attn_us": round(us_dense, 3),
         "dense_attn_GBps": round(dense_bytes / (us_dense * 1e-6) / 1e9, 1),
-        "speedup_vs_dense_attn": round(us_dense / us_step, 3),
+        "speedup_vs_dense_attn": round(us_dense / us_layer, 3),
         "roofline": {"bound": "hbm", "kernel": "select_attend_kernel (selection, gather attention, merge)",
                      "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "bytes_per_launch": k3_bytes, "us_per_launch": round(us_k3, 3)},
+                     "bytes_per_launch": k3_bytes, "us_per_launch": round(us_k3 / NL, 3)},
         "setup_s": round(t_setup, 1),
     }
 
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(hosts, w, max_ctx)
+        res["cpu_baseline"] = cpu_baseline(hosts, w, lens, buds)
     print(json.dumps(res), flush=True)
 
 
-def cpu_baseline(d, w, max_ctx):
+def cpu_baseline(d, w, lens, buds):
     """The CPU oracle, as it stands, timed on this machine's host cores on the same kind of layer step."""
     import oracle
     from paper_2508_08256_amd import synth
 
     oracle.build()
     threads = oracle.max_threads()
-    units = w["batch"] * w["n_kv_heads"]
-    n_rep = w["n_q_heads"] // w["n_kv_heads"]
-    # bounded sample: at most 32 units of cache 0 (all of config 2; the first 32 units of larger ones)
+    hkv = w["n_kv_heads"]
+    units = w["batch"] * hkv
+    n_rep = w["n_q_heads"] // hkv
+    # bounded sample: at most 32 units of the first layer cache (all of config 2; the first 32 units of larger ones)
     su = min(units, 32)
     K = synth.words_of(d["K"][:su])
     V = synth.words_of(d["V"][:su])
     q = synth.words_of(d["q"][:su]).reshape(su, n_rep, 128)
     kn = synth.words_of(d["k_new"][:su])
     vn = synth.words_of(d["v_new"][:su])
-    L = np.full(su, w["L"], np.int32)
-    bud = np.full(su, w["budget"], np.int32)
+    L = np.repeat(lens, hkv)[:su].astype(np.int32)
+    bud = np.repeat(buds, hkv)[:su].astype(np.int32)
+    max_budget = int(buds.max())
     bits, s, z = oracle.quantize(K, L, 32, w["dtype"], threads)        # prefill, not timed
-    reps, t_total = 0, 0.0
-    while reps < 3 or (t_total < 10.0 and reps < 20):
+
+    def layer_step(nthreads):
         t0 = time.perf_counter()
         oracle.append(K, V, L, kn, vn, bits, s, z, 32, w["dtype"])
         L1 = (L + 1).astype(np.int32)
-        sc = oracle.score(bits, s, z, q, L1, 32, w["dtype"], threads)
-        idx, cnt = oracle.topk(sc, L1, bud, w["budget"])
-        oracle.attention(K, V, q, L1, 1.0 / np.sqrt(128.0), w["dtype"], idx, cnt, threads)
-        t_total += time.perf_counter() - t0
+        sc = oracle.score(bits, s, z, q, L1, 32, w["dtype"], nthreads)
+        idx, cnt = oracle.topk(sc, L1, bud, max_budget)
+        oracle.attention(K, V, q, L1, 1.0 / np.sqrt(128.0), w["dtype"], idx, cnt, nthreads)
+        return time.perf_counter() - t0
+
+    reps, t_total = 0, 0.0
+    while reps < 3 or (t_total < 10.0 and reps < 20):
+        t_total += layer_step(threads)
         reps += 1
-    us = t_total / reps * 1e6 * (units / su)
+    t_single = layer_step(1)
+    frac = float((np.repeat(lens, hkv) + 1).sum()) / float((L + 1).sum())   # whole layer / sample, by tokens
+    us = t_total / reps * 1e6 * frac
     return {"value": round(us, 1), "unit": "us per layer step", "cores": threads, "kind": "oracle",
-            "sample": f"{reps} repetitions of the layer step on {su} of {units} units of cache 0"
-                      f"{' (scaled to all units)' if su != units else ''}, OpenMP over units"}
+            "single_thread_value": round(t_single * 1e6 * frac, 1),
+            "sample": f"{reps} repetitions of the layer step on {su} of {units} units of the first layer cache"
+                      f"{' (scaled to all units by token count)' if su != units else ''}, OpenMP over units; "
+                      f"single_thread_value: one repetition with 1 thread"}
 
 
 if __name__ == "__main__":

@@ -90,50 +90,77 @@ __device__ __forceinline__ void attend_rows(const uint4* __restrict__ Ku, const 
   }
 }
 
+// value of the lane 16 / 32 lanes away
+__device__ __forceinline__ float xor16(float x) {
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401f));
+}
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+constexpr int kPartialFloats = 4 * 16 * 10;  // LDS floats per query head: [wave][channel chunk][o[8], m, l]
+
 // Combine the 16 lane-row states of the workgroup per query head and write one partial (m, l, o[128]) per head
-// into slot `slot` of the unit's partial arrays.  Contains barriers: every thread of the workgroup calls it.
+// into slot `slot` of the unit's partial arrays.  The four lane rows of a wavefront are folded with cross-lane
+// moves first, so that only one state per wavefront and head goes through LDS and all heads share one barrier.
+// sh: NREP * kPartialFloats floats.  Contains barriers: every thread of the workgroup calls it.
 template <int NREP, bool COHERENT>
-__device__ __forceinline__ void store_partials(const AttnState<NREP>& st, float (*sh_o)[16][8 + 2], int unit,
-                                               int n_slots, int slot, float* __restrict__ po, float* __restrict__ pm,
+__device__ __forceinline__ void store_partials(const AttnState<NREP>& st, float* sh, int unit, int n_slots, int slot,
+                                               float* __restrict__ po, float* __restrict__ pm,
                                                float* __restrict__ pl) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int rs = lane >> 4, cn = lane & 15;
+  __syncthreads();  // sh may still be read as something else by a slower wavefront
 #pragma unroll
   for (int r = 0; r < NREP; ++r) {
-    __syncthreads();
-    float* dst = sh_o[wave * 4 + rs][cn];
+    float M = fmaxf(st.m[r], xor16(st.m[r]));
+    M = fmaxf(M, xor32(M));
+    const float w = st.m[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(st.m[r] - M);
+    float l = st.l[r] * w;
+    l += xor16(l);
+    l += xor32(l);
+    float o[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) dst[c] = st.o[r][c];
-    dst[8] = st.m[r];
-    dst[9] = st.l[r];
-    __syncthreads();
-    if (tid < kD) {
-      const int chunk = tid >> 3, e = tid & 7;
-      float M = -INFINITY;
+    for (int c = 0; c < 8; ++c) {
+      o[c] = st.o[r][c] * w;
+      o[c] += xor16(o[c]);
+      o[c] += xor32(o[c]);
+    }
+    if (rs == 0) {
+      float* dst = sh + r * kPartialFloats + (wave * 16 + cn) * 10;
 #pragma unroll
-      for (int s = 0; s < 16; ++s) M = fmaxf(M, sh_o[s][chunk][8]);
-      float acc = 0.f, lsum = 0.f;
+      for (int c = 0; c < 8; ++c) dst[c] = o[c];
+      dst[8] = M;
+      dst[9] = l;
+    }
+  }
+  __syncthreads();
+  // thread -> (head parity, channel): threads 0..127 take the even heads, 128..255 the odd ones
+  const int ch = tid & 127, chunk = ch >> 3, e = ch & 7;
+  for (int r = tid >> 7; r < NREP; r += 2) {
+    const float* src = sh + r * kPartialFloats + chunk * 10;
+    float M = -INFINITY;
 #pragma unroll
-      for (int s = 0; s < 16; ++s) {
-        const float ms = sh_o[s][chunk][8];
-        const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-        acc += w * sh_o[s][chunk][e];
-        lsum += w * sh_o[s][chunk][9];
+    for (int wv = 0; wv < 4; ++wv) M = fmaxf(M, src[wv * 160 + 8]);
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) {
+      const float ms = src[wv * 160 + 8];
+      const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+      acc += w * src[wv * 160 + e];
+      lsum += w * src[wv * 160 + 9];
+    }
+    const size_t ps = ((size_t)unit * NREP + r) * n_slots + slot;
+    if (COHERENT) {  // read back by another workgroup of this kernel
+      store_coherent(&po[ps * kD + ch], acc);
+      if (ch == 0) {
+        store_coherent(&pm[ps], M);
+        store_coherent(&pl[ps], lsum);
       }
-      const size_t ps = ((size_t)unit * NREP + r) * n_slots + slot;
-      if (COHERENT) {  // read back by another workgroup of this kernel
-        store_coherent(&po[ps * kD + tid], acc);
-        if (tid == 0) {
-          store_coherent(&pm[ps], M);
-          store_coherent(&pl[ps], lsum);
-        }
-      } else {
-        po[ps * kD + tid] = acc;
-        if (tid == 0) {
-          pm[ps] = M;
-          pl[ps] = lsum;
-        }
+    } else {
+      po[ps * kD + ch] = acc;
+      if (ch == 0) {
+        pm[ps] = M;
+        pl[ps] = lsum;
       }
     }
   }
@@ -148,7 +175,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
                                                          float scale_log2e, float* __restrict__ po,
                                                          float* __restrict__ pm, float* __restrict__ pl,
                                                          int n_kv_heads, int max_ctx) {
-  __shared__ float sh_o[16][16][8 + 2];  // [wave*4 + lane row][channel chunk][o[8], m, l]
+  __shared__ float sh_o[NREP * kPartialFloats];
 
   const int cn = threadIdx.x & 15;
   const int unit = blockIdx.y, split = blockIdx.x;
@@ -181,53 +208,67 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
 }
 
+__device__ __forceinline__ float wave_allsum_f(float x) {
+  x = row_allsum(x);
+  x += xor16(x);
+  x += xor32(x);
+  return x;
+}
+__device__ __forceinline__ float wave_allmax_f(float x) {
+  x = fmaxf(x, row_ror<8>(x));
+  x = fmaxf(x, row_ror<4>(x));
+  x = fmaxf(x, row_ror<2>(x));
+  x = fmaxf(x, row_ror<1>(x));
+  x = fmaxf(x, xor16(x));
+  x = fmaxf(x, xor32(x));
+  return x;
+}
+
 // Merge the partial slots [0, n_used) of all NREP query heads of a unit into out[NREP][128].  256 threads form
 // four groups of 64 (thread k of a group owns channels 2k, 2k+1).  Each group folds the slots s = sub, sub + GPH,
-// ... of one head with a running maximum, sixteen independent coherent loads at a time so that the round trips
+// ... of one head with a running maximum, 32 or 40 slots per batch: their (m, l) sit one per lane and reach the other
+// lanes as scalars, the independent 8-byte loads of o are in flight together, so that the round trips
 // to memory overlap; with fewer than four heads several groups share a head and meet in LDS.
 // sh: 4 * 130 floats.  Has barriers.
 template <int NREP>
 __device__ __forceinline__ void merge_heads(const float* __restrict__ po, const float* __restrict__ pm,
                                             const float* __restrict__ pl, int unit, int n_slots, int n_used,
                                             float* sh, float* __restrict__ out_unit) {
-  constexpr int BATCH = 16;
   constexpr int GPH = NREP == 1 ? 4 : (NREP == 2 ? 2 : 1);  // groups per head
+  constexpr int BATCH = GPH == 1 ? 40 : 32;                 // slots per batch and group (a 128k context has 33)
   constexpr int HPP = 4 / GPH;                              // heads per pass
-  const int tid = threadIdx.x;
-  const int k2 = (tid & 63) * 2, g = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int k2 = lane * 2, g = tid >> 6;
 #pragma unroll 1
   for (int h0 = 0; h0 < NREP; h0 += HPP) {
     const int h = h0 + g / GPH, sub = g % GPH;
-    const bool head_ok = h < NREP;
+    const bool head_ok = h < NREP;  // the same for the whole wavefront
     const size_t base = ((size_t)unit * NREP + (head_ok ? h : 0)) * n_slots;
     float M = -INFINITY, acc0 = 0.f, acc1 = 0.f, lsum = 0.f;
     for (int s0 = sub; s0 < n_used && head_ok; s0 += GPH * BATCH) {
-      float ms[BATCH], ls[BATCH];
+      // (m, l) of the batch's slots live one per lane; every lane loads its two channels of all the slots
+      const int sj = s0 + GPH * lane;
+      const bool okj = lane < BATCH && sj < n_used;
+      const float mj = okj ? load_coherent(&pm[base + sj]) : -INFINITY;
+      const float lj = okj ? load_coherent(&pl[base + sj]) : 0.f;
       unsigned long long os[BATCH];
 #pragma unroll
       for (int k = 0; k < BATCH; ++k) {
         const int s = s0 + GPH * k;
-        const bool ok = s < n_used;
-        const size_t slot = base + (ok ? s : s0);
-        ms[k] = load_coherent(&pm[slot]);
-        ls[k] = load_coherent(&pl[slot]);
-        os[k] = load_coherent(reinterpret_cast<const unsigned long long*>(&po[slot * kD + k2]));
-        if (!ok) ms[k] = -INFINITY;
+        os[k] = load_coherent(reinterpret_cast<const unsigned long long*>(&po[(base + (s < n_used ? s : s0)) * kD + k2]));
       }
-      float mx = M;
-#pragma unroll
-      for (int k = 0; k < BATCH; ++k) mx = fmaxf(mx, ms[k]);
+      const float mx = fmaxf(M, wave_allmax_f(mj));
       const float mref = mx == -INFINITY ? 0.f : mx;
       const float alpha = __builtin_amdgcn_exp2f(M - mref);
+      const float wj = __builtin_amdgcn_exp2f(mj - mref);  // 0 for an empty slot
       acc0 *= alpha;
       acc1 *= alpha;
-      lsum *= alpha;
+      lsum = lsum * alpha + wave_allsum_f(wj * lj);
 #pragma unroll
       for (int k = 0; k < BATCH; ++k) {
-        const float w = __builtin_amdgcn_exp2f(ms[k] - mref);  // 0 for an empty slot
+        const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wj), k));
         acc0 += w * __uint_as_float((uint32_t)os[k]);
         acc1 += w * __uint_as_float((uint32_t)(os[k] >> 32));
-        lsum += w * ls[k];
       }
       M = mx;
     }
@@ -271,7 +312,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const int32_t* __restrict__ seq_lens, int extra, int max_budget, float scale_log2e, float* __restrict__ po,
     float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
     float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx) {
-  __shared__ float sh_o[16][16][8 + 2];
+  __shared__ float sh_o[NREP * kPartialFloats > 4 * 130 ? NREP * kPartialFloats : 4 * 130];
   __shared__ uint16_t rows[kRangeTokens * RPW];  // selected tokens, relative to the workgroup's first token
   __shared__ uint32_t scan_tmp[4];
   __shared__ uint32_t flag;
@@ -303,31 +344,47 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const int r = wg * RPW + rr;
     off[rr] = r < n_ranges ? range_off[(size_t)unit * n_ranges + r] : 0;
   }
-  uint32_t n_sel_total = 0;
+  // selection flags of the thread's 4 tokens in each range, and their count
+  uint32_t selm[RPW], cnt[RPW];
 #pragma unroll
   for (int rr = 0; rr < RPW; ++rr) {
     const int i = tok0 + rr * kRangeTokens + 4 * tid;
     const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
-    bool sel[4];
-    uint32_t cnt = 0;
+    selm[rr] = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int bin = sel_bin(vv[j], R, hscale, kSelBins);
       const uint32_t key = score_key(vv[j]);
-      sel[j] = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
-      cnt += sel[j];
+      const bool sel = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
+      selm[rr] |= sel ? 1u << j : 0u;
     }
-    uint32_t n_sel;
-    uint32_t pos = block_excl_scan_u32<4>(cnt, scan_tmp, n_sel);
+    cnt[rr] = __builtin_popcount(selm[rr]);
+  }
+  // positions in token order: one workgroup scan serves two ranges (16 bits each: a range holds <= 1024 tokens)
+  uint32_t n_sel_total = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (sel[j]) {
-        rows[n_sel_total + pos] = (uint16_t)(i + j - tok0);
-        if (idx_out && off[rr] + pos < (uint32_t)max_budget)
-          idx_out[(size_t)unit * max_budget + off[rr] + pos] = i + j;
-        ++pos;
+  for (int r2 = 0; r2 < RPW; r2 += 2) {
+    const uint32_t packed = cnt[r2] | (r2 + 1 < RPW ? cnt[r2 + 1 < RPW ? r2 + 1 : r2] << 16 : 0u);
+    uint32_t total;
+    const uint32_t before = block_excl_scan_u32<4>(packed, scan_tmp, total);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int rr = r2 + h;
+      if (rr < RPW) {
+        const int i = tok0 + rr * kRangeTokens + 4 * tid;
+        uint32_t pos = (before >> (16 * h)) & 0xffffu;
+        const uint32_t n_sel = (total >> (16 * h)) & 0xffffu;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (selm[rr] >> j & 1u) {
+            rows[n_sel_total + pos] = (uint16_t)(i + j - tok0);
+            if (idx_out && off[rr] + pos < (uint32_t)max_budget)
+              idx_out[(size_t)unit * max_budget + off[rr] + pos] = i + j;
+            ++pos;
+          }
+        n_sel_total += n_sel;
       }
-    n_sel_total += n_sel;
+    }
   }
   __syncthreads();
   FIER_PROF(21, unit == 0 && wg == 3)
@@ -350,7 +407,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   if (!last_arriver(&c->arrive[2], n_wgs > 0 ? (uint32_t)n_wgs : 1u, &flag)) return;
   FIER_PROF(24, unit == 0)
   // ---- the unit's last workgroup merges the partials of all workgroups --------------------------------------
-  merge_heads<NREP>(po, pm, pl, unit, n_slots, n_wgs, &sh_o[0][0][0], out + (size_t)unit * NREP * kD);
+  merge_heads<NREP>(po, pm, pl, unit, n_slots, n_wgs, sh_o, out + (size_t)unit * NREP * kD);
   if (tid == 0) c->arrive[2] = 0;
   FIER_PROF(25, unit == 0)
   // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
