@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=60)
     ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
     ap.add_argument("--budget", type=int, default=None, help="token budget (config4's sweep point)")
+    ap.add_argument("--loop-steps", type=int, default=0,
+                    help="instead of the default measurement: this many consecutive token steps (append, growing "
+                         "context) over all the workload's layer caches in one call per token, eager and as one graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-steps", type=int, default=240, help="launches per stage for the per-stage timing")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -104,7 +107,7 @@ def main():
     batch, Hq, Hkv, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["dtype"]
     lens, buds = shape_of(w, 5000)
     L, budget = int(lens.max()), int(buds.max())   # the largest context and budget (all of them when not ragged)
-    max_ctx = -(-(L + 1) // 64) * 64
+    max_ctx = -(-(L + 1 + max(0, args.loop_steps)) // 64) * 64
     cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype)
     units, n_rep = cfg.units, cfg.n_rep
     if NL > 1 and args.steps == 600:
@@ -138,6 +141,10 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
+    if args.loop_steps > 0:
+        decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, buds, budget, t_setup)
+        return
+
     # one workspace per cache set, so that a phase of the fused step can be timed alone on rotating caches
     wss = [B.make_workspace(cfg, budget) for _ in range(R)]
     ws_dense = B.make_workspace(cfg, max_ctx)
@@ -149,7 +156,7 @@ def main():
 
     def step(i):
         r = i % R
-        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r])
+        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0])
 
     def timed(fn, n, warm):
         for i in range(warm):
@@ -306,6 +313,83 @@ def main():
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(hosts, w, lens, buds)
+    print(json.dumps(res), flush=True)
+
+
+def decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, buds, budget, t_setup):
+    """The decode loop of Sec. 3.1 on this workload: N token steps, each ONE fier_decode_step call over all the
+    layer caches (append one row per layer, score, select, attend) followed by the caller's seq_lens += 1."""
+    import torch
+
+    from paper_2508_08256_amd import binding as B
+
+    N = args.loop_steps
+    layers = [c for cl in caches for c in cl]
+    NLt = len(layers)
+    q = torch.cat(qs).contiguous()
+    kn = torch.cat(kns).contiguous()
+    vn = torch.cat(vns).contiguous()
+    batch, Hq = w["batch"], w["n_q_heads"]
+    ws = B.make_workspace(cfg, budget)
+    out = torch.zeros((NLt, batch, Hq, 128), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((NLt, cfg.units, budget), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((NLt, cfg.units), dtype=torch.int32, device="cuda")
+    lens0 = seq_lens.clone()
+
+    def tokens(n):
+        for _ in range(n):
+            B.decode_step(cfg, layers, q, kn, vn, budgets, budget, out, idx, cnt, ws)
+            seq_lens.add_(1)
+
+    def timed_tokens(fn):
+        seq_lens.copy_(lens0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / N
+
+    tokens(4)                                   # warm-up
+    us_eager = timed_tokens(lambda: tokens(N))
+    us_graph = None
+    try:
+        seq_lens.copy_(lens0)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            tokens(2)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        seq_lens.copy_(lens0)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            tokens(N)
+        torch.cuda.synchronize()
+        timed_tokens(graph.replay)
+        us_graph = timed_tokens(graph.replay)
+    except Exception as e:
+        sys.stderr.write(f"bench.py: graph replay skipped: {e}\n")
+    # bytes of the middle token step
+    ab = algorithmic_bytes(w, lens + N // 2, buds)
+    us_layer = us_eager / NLt
+    res = {
+        "metric": "per-layer decode-step latency (us) + achieved HBM GB/s vs peak",
+        "value": round(us_layer, 3), "unit": "us", "n_gpus": 1, "steps": N, "warmup": 4,
+        "ms_per_step": round(us_eager / 1e3, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if w["dtype"] == 0 else "bf16", "data": "synthetic",
+        "config": {"workload": w["label"] + f"_decode_loop{N}", "batch": batch, "n_q_heads": Hq,
+                   "n_kv_heads": w["n_kv_heads"], "head_dim": 128, "context_start": [int(x) for x in lens],
+                   "tokens_appended": N, "layers_per_token": NLt, "group_size": 32,
+                   "algorithmic_bytes_per_layer": ab["total"]},
+        "achieved_GBps": round(ab["total"] / (us_layer * 1e-6) / 1e9, 1),
+        "hbm_frac": round(ab["total"] / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "us_per_token_eager": round(us_eager, 3),
+        "us_per_token_graph": None if us_graph is None else round(us_graph, 3),
+        "us_per_layer_graph": None if us_graph is None else round(us_graph / NLt, 3),
+        "setup_s": round(t_setup, 1),
+    }
     print(json.dumps(res), flush=True)
 
 

@@ -494,3 +494,101 @@ def test_decode_step_phases_equal_the_fused_call(gu):
         outs.append((out.clone(), idx.clone(), cnt.clone(), dw.cache.kbits.clone()))
     for a, b in zip(outs[0], outs[1]):
         assert torch.equal(a, b)
+
+
+def test_decode_loop_many_steps_eager_and_graph(gu, oracle):
+    """The decode loop of Sec. 3.1: consecutive steps, each appending one row (contexts grow across group,
+    pair-block, 1024-token-range and 4096-token-chunk boundaries).  Every step's selection and output match the
+    oracle run step by step; the packed cache at the end equals a bulk quantization of the final keys bit for
+    bit; the same loop replayed from one HIP graph (twice, with eager work in between) gives the eager results."""
+    steps, batch, Hq, Hkv = 80, 2, 4, 2
+    lens0 = [4060, 1010]
+    budgets = [400, 120]
+    max_ctx = 4224
+    wl = synth.make_workload("loop", 321, batch, Hq, Hkv, lens0, budgets, F16, max_ctx=max_ctx, n_planted=8)
+    units, n_rep = wl.units, wl.n_rep
+    rng = np.random.default_rng(99)
+    q_all = synth.f32_to_words(rng.standard_normal((steps, units, n_rep, 128)).astype(np.float32), F16)
+    kn_all = synth.f32_to_words(rng.standard_normal((steps, units, 128)).astype(np.float32), F16)
+    vn_all = synth.f32_to_words(rng.standard_normal((steps, units, 128)).astype(np.float32), F16)
+    mb = max(budgets)
+
+    # ---- oracle, step by step ------------------------------------------------------------------------------
+    K, V, L = wl.K.copy(), wl.V.copy(), wl.unit_lens.copy()
+    bits, s, z = oracle.quantize(K, L, G, F16, 4)
+    want = []
+    for t in range(steps):
+        oracle.append(K, V, L, kn_all[t], vn_all[t], bits, s, z, G, F16)
+        L = (L + 1).astype(np.int32)
+        sc = oracle.score(bits, s, z, q_all[t], L, G, F16, 4)
+        idx_o, cnt_o = oracle.topk(sc, L, wl.unit_budgets, mb)
+        want.append((sc, idx_o, cnt_o, L.copy()))
+
+    # ---- GPU ---------------------------------------------------------------------------------------------------
+    dw = gu.DeviceWorkload(wl)
+    B.quantize_keys(dw.cfg, dw.cache)
+    torch.cuda.synchronize()
+    snap = [x.clone() for x in (dw.K, dw.V, dw.cache.kbits, dw.cache.kmeta, dw.cache.kabsmax, dw.seq_lens)]
+
+    def restore():
+        for dst, src in zip((dw.K, dw.V, dw.cache.kbits, dw.cache.kmeta, dw.cache.kabsmax, dw.seq_lens), snap):
+            dst.copy_(src)
+
+    q_d = gu.to_dev(q_all, F16).reshape(steps, 1, batch, Hq, 128).contiguous()
+    kn_d = gu.to_dev(kn_all, F16).reshape(steps, 1, units, 128).contiguous()
+    vn_d = gu.to_dev(vn_all, F16).reshape(steps, 1, units, 128).contiguous()
+    outs = torch.zeros((steps, 1, units, n_rep, 128), dtype=torch.float32, device="cuda")
+    idxs = torch.full((steps, 1, units, mb), -1, dtype=torch.int32, device="cuda")
+    cnts = torch.zeros((steps, 1, units), dtype=torch.int32, device="cuda")
+    ws = dw.workspace(mb)
+
+    def loop():
+        for t in range(steps):
+            B.decode_step(dw.cfg, [dw.cache], q_d[t], kn_d[t], vn_d[t], dw.budgets, mb, outs[t], idxs[t], cnts[t], ws)
+            dw.seq_lens.add_(1)   # the caller advances the lengths after each step
+
+    loop()
+    torch.cuda.synchronize()
+    out_e, idx_e, cnt_e = outs.cpu().numpy(), idxs.cpu().numpy(), cnts.cpu().numpy()
+    swapped = 0
+    for t in range(steps):
+        sc, idx_o, cnt_o, Lt = want[t]
+        swapped += check_index_sets(idx_e[t, 0], cnt_e[t, 0], idx_o, cnt_o, sc, Lt)
+    # attention on the GPU's own selections, at a few steps (the oracle's K, V hold every appended row by now;
+    # a step only looks at rows below its own length)
+    for t in (0, 35, 36, 37, steps - 1):
+        ig, cg = idx_e[t, 0], cnt_e[t, 0]
+        ref = oracle.attention(K, V, q_all[t], want[t][3], 1.0 / np.sqrt(128.0), F16,
+                               np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 4)
+        assert np.abs(out_e[t, 0] - ref).max() <= 2e-3, t
+    # the incrementally built packed cache == bulk quantization of the final keys
+    bits_b, s_b, z_b = oracle.quantize(K, L, G, F16, 4)
+    _compare_packed(dw, L, bits_b, s_b, z_b)
+    assert np.array_equal(gu.words_of(dw.K)[:, :L.max()], K[:, :L.max()])
+    print(f"[loop] {steps} steps, swapped near-ties {swapped}", flush=True)
+
+    # ---- the same loop as one graph --------------------------------------------------------------------------
+    restore()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        loop()                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    restore()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        loop()
+    for rep in range(2):
+        restore()
+        outs.zero_()
+        idxs.fill_(-1)
+        cnts.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(idxs.cpu().numpy(), idx_e), rep
+        assert np.array_equal(cnts.cpu().numpy(), cnt_e), rep
+        assert np.array_equal(outs.cpu().numpy(), out_e), rep
+        assert int(dw.seq_lens[0]) == lens0[0] + steps
