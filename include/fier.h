@@ -172,7 +172,9 @@ int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n
  * One of the three kernels of fier_decode_step alone, for measurement: phase 1 = append + score + score
  * histogram, 2 = exact threshold, 3 = selection + attention over the selected rows + merge.  Same arguments
  * as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and these
- * layers left behind, so the sequence 1, 2, 3 equals fier_decode_step and any phase may be repeated.
+ * layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
+ * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with
+ * one phase 2 before the next real step), phase 2 only after a phase 1, phase 3 may be repeated freely.
  */
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
                            const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,

@@ -245,7 +245,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
       if (e != hipSuccess) return FIER_EHIP;
     }
     if (phase == 0 || phase == 2) {
-      e = fier::launch_threshold(w.sb, c->seq_lens, extra, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
+      e = fier::launch_threshold(w.sb, c->seq_lens, extra, budgets, max_budget, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
     if (phase == 0 || phase == 3) {

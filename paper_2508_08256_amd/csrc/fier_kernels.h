@@ -24,7 +24,7 @@ constexpr int kSubBins = 1024;         // second-level bins inside the threshold
 constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 
 struct UnitCtl {        // one per unit at the head of the workspace
-  uint32_t arrive[3];   // arrival counters of the three kernels; zero between calls
+  uint32_t arrive[3];   // arrival counters of the kernels (the first one is unused); zero between calls
   uint32_t unused0;
   int32_t tbin;         // bins above are selected, bins below are not (-1: everything, kSelBins: nothing)
   uint32_t above;       // tokens in bins above tbin
@@ -39,7 +39,7 @@ static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte line");
 
 struct StepBuffers {    // carved from the caller's workspace
   UnitCtl* ctl;         // [units]
-  uint32_t* hist;       // [units][kSelBins]; zero between calls
+  uint32_t* hist;       // [units][kSelBins]: filled by the score kernel, read and cleared by the threshold kernel
   uint32_t* range_cnt;  // [units][n_ranges]: selected tokens per 1024-token range, then their exclusive scan
   unsigned long long* cand;  // [units][n_chunks][kSegCand] (key << 32 | token index), one segment per workgroup
   uint32_t* seg_cnt;    // [units][n_chunks] candidates found by each threshold-kernel workgroup
@@ -65,8 +65,9 @@ hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint3
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
                         const void* v_new, int units, int n_kv_heads, int max_ctx, hipStream_t st);
 
-hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, int32_t* count_out, int units,
-                            int n_kv_heads, int max_ctx, hipStream_t st);
+hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, const int32_t* budgets,
+                            int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,
+                            hipStream_t st);
 
 hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,

@@ -71,8 +71,8 @@ __device__ __forceinline__ uint32_t row_allmax_u32(uint32_t x) {
 // HIST (first kernel of the fused step): every score is also counted in an equal-width histogram of kSelBins
 // bins over [-R, R], R = sum_c |q_c| * absmax_c >= |score| -- a bound known before any score exists, so that
 // scoring and histogramming are one pass.  The workgroup's LDS histogram is added to the unit's histogram in
-// memory; the unit's last workgroup reads the total, finds the bin that holds the budget-th largest score,
-// publishes it and clears the histogram for the next call.
+// memory with device atomics and the workgroup is done: nobody waits or counts arrivals here; the threshold
+// kernel reads the merged histogram (and clears it for the next call).
 // The extra workgroup of a unit performs the decode-stage append (Sec. 3.1) when k_new is given: one wavefront
 // writes the new K/V rows, re-quantizes the group the row falls in and scores that group's tokens straight from
 // its registers; the other workgroups leave those tokens alone.  The bound R uses the absmax of before the
@@ -90,9 +90,6 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
                                                     int n_kv_heads, int max_ctx, int bpw) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
   __shared__ __attribute__((aligned(16))) unsigned char a_lds[4 * kAWave];
-  __shared__ uint32_t scan_tmp[4];
-  __shared__ uint32_t flag;
-  __shared__ int found[2];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -327,54 +324,13 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       const uint32_t c = lhist[i];
       if (c) atomicAdd(&gh[i], c);
     }
-    const int span = 4 * kPair * bpw;  // tokens per workgroup
-    const uint32_t expected = (L > 0 ? (uint32_t)((L + span - 1) / span) : 1u) + (app ? 1u : 0u);
-    FIER_PROF(3, unit == 0 && range == 3)
-    if (!last_arriver(&ctl[unit].arrive[0], expected, &flag)) return;
-    FIER_PROF(4, unit == 0)
-    // ---- the unit's last workgroup: threshold bin for the budget ---------------------------------------
-    int B = budgets[b];
-    B = B > max_budget ? max_budget : B;
-    B = B > L ? L : B;
-    B = B < 0 ? 0 : B;
-    constexpr int PER = kSelBins / 256;
-    // thread t owns bins kSelBins-1-PER*t down to kSelBins-PER*(t+1), i.e. descending score order
-    uint32_t cnt[PER], sum = 0;
-#pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      cnt[k] = load_coherent(&gh[kSelBins - 1 - (PER * tid + k)]);
-      sum += cnt[k];
-    }
-    uint32_t total;
-    uint32_t before = block_excl_scan_u32<4>(sum, scan_tmp, total);
-    if (tid == 0) {
-      found[0] = B >= L ? -1 : kSelBins;  // everything / nothing selected by bin alone
-      found[1] = 0;
-    }
-    __syncthreads();
-    if (B > 0 && B < L) {
-#pragma unroll
-      for (int k = 0; k < PER; ++k) {
-        if (before < (uint32_t)B && (uint32_t)B <= before + cnt[k]) {
-          found[0] = kSelBins - 1 - (PER * tid + k);
-          found[1] = (int)before;
-        }
-        before += cnt[k];
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < PER; ++k) gh[kSelBins - 1 - (PER * tid + k)] = 0;
-    if (tid == 0) {
+    // the bound the scores were binned with, for the kernels that follow (range 0 of a unit always runs)
+    if (range == 0 && tid == 0) {
       UnitCtl* c = &ctl[unit];
-      c->tbin = found[0];
-      c->above = (uint32_t)found[1];
-      c->budget = B;
       c->R = R;
       c->scale = hscale;
-      c->arrive[0] = 0;
     }
-    FIER_PROF(5, unit == 0)
+    FIER_PROF(3, unit == 0 && range == 3)
   }
 }
 

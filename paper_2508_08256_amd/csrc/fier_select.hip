@@ -1,7 +1,9 @@
 // Second kernel of the fused decode step: exact top-B threshold per unit (Alg. 1 step 3).
 //
-// The score kernel has left, per unit, the histogram bin `tbin` that contains the B-th largest score and
-// the number of scores in bins above it.  Here every workgroup re-reads 4096 scores of its unit and
+// The score kernel has left, per unit, the 512-bin histogram of its scores.  Every workgroup here first finds,
+// from that histogram, the bin `tbin` that contains the B-th largest score and the number of scores in bins
+// above it (the same few hundred integer additions in every workgroup of the unit: cheaper than a serial step at
+// the end of the score kernel plus the wait for it), then re-reads 4096 scores of its unit and
 //   * counts, per 1024-token range, the tokens in bins above tbin (they are selected for certain);
 //   * writes the tokens that fall into tbin itself -- the only candidates for the threshold, about 1 % of
 //     the tokens for bell-shaped scores -- as (key, index) pairs into its own candidate segment.
@@ -27,6 +29,8 @@ constexpr int kSpecCand = 64;                          // candidates per segment
 __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __restrict__ scores,
                                                                 const int32_t* __restrict__ seq_lens, int extra,
                                                                 UnitCtl* __restrict__ ctl,
+                                                                uint32_t* __restrict__ ghist,
+                                                                const int32_t* __restrict__ budgets, int max_budget,
                                                                 uint32_t* __restrict__ range_cnt,
                                                                 unsigned long long* __restrict__ cand,
                                                                 uint32_t* __restrict__ seg_cnt,
@@ -34,6 +38,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
                                                                 int n_chunks, int n_kv_heads, int max_ctx) {
   __shared__ uint32_t wsum[kThrWaves];
   __shared__ uint32_t flag;
+  __shared__ int found[2];
   __shared__ uint32_t scan_tmp[kThrWaves];
   __shared__ uint32_t hist[kSubBins];
   __shared__ uint32_t res[2];
@@ -54,19 +59,42 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   if (chunk * kClassifyTokens >= n && chunk != 0) return;
   FIER_PROF(10, unit == 0 && chunk == 1)
   UnitCtl* __restrict__ c = &ctl[unit];
-  const int tbin = c->tbin;
   const float R = c->R, scale = c->scale;
   const float* __restrict__ s = scores + (size_t)unit * max_ctx;
   unsigned long long* __restrict__ ucand = cand + (size_t)unit * n_chunks * kSegCand;
   uint32_t* __restrict__ useg = seg_cnt + (size_t)unit * n_chunks;
   uint32_t* __restrict__ urange = range_cnt + (size_t)unit * n_ranges;
+  uint32_t* __restrict__ gh = ghist + (size_t)unit * kSelBins;
 
-  // ---- classify this workgroup's 4096 scores -------------------------------------------------------
+  // this workgroup's 4096 scores and the unit's histogram leave in the same round trip
   const int i = chunk * kClassifyTokens + 4 * tid;
   float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
   if (i < n) v = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx; entries >= n are masked below
-  if (tid == 0) n_local = 0;
-  __syncthreads();
+  // thread t < 512 owns bin 511 - t: descending score order
+  const uint32_t hcnt = tid < kSelBins ? gh[kSelBins - 1 - tid] : 0;
+  int B = budgets[b];
+  B = B > max_budget ? max_budget : B;
+  B = B > n ? n : B;
+  B = B < 0 ? 0 : B;
+  if (tid == 0) {
+    n_local = 0;
+    found[0] = B >= n ? -1 : kSelBins;  // everything / nothing selected by bin alone
+    found[1] = 0;
+  }
+  // ---- the bin that holds the B-th largest score ---------------------------------------------------------
+  {
+    uint32_t total;
+    const uint32_t before = block_excl_scan_u32<kThrWaves>(hcnt, scan_tmp, total);  // has barriers
+    if (B > 0 && B < n && before < (uint32_t)B && (uint32_t)B <= before + hcnt) {
+      found[0] = kSelBins - 1 - tid;
+      found[1] = (int)before;
+    }
+    __syncthreads();
+  }
+  const int tbin = found[0];
+  const uint32_t above = (uint32_t)found[1];
+
+  // ---- classify this workgroup's 4096 scores -------------------------------------------------------
   FIER_PROF(11, unit == 0 && chunk == 1)
   const float vv[4] = {v.x, v.y, v.z, v.w};
   uint32_t n_gt = 0, n_c = 0;
@@ -108,7 +136,6 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
 
   // ---- the unit's last workgroup: exact threshold ------------------------------------------------------
   const int nr = (n + kRangeTokens - 1) / kRangeTokens;  // ranges in use (<= n_ranges)
-  const int B = c->budget;
   const bool need_threshold = tbin >= 0 && tbin < kSelBins && B > 0;
   // segment sizes, and the first candidates of every segment in the same round trip
   uint32_t my_cnt = 0;
@@ -135,7 +162,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   uint32_t T = 0;
   int32_t idxT = -1;
   if (need_threshold) {
-    const uint32_t r_want = (uint32_t)B - c->above;  // candidates to take, >= 1
+    const uint32_t r_want = (uint32_t)B - above;  // candidates to take, >= 1
     bool done = false;
     if (!overflow) {
       // gather the segments into LDS
@@ -176,7 +203,11 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     if (r < nr) urange[r] = before;
     run += total;
   }
+  if (tid < kSelBins) gh[tid] = 0;  // the histogram is zero between calls
   if (tid == 0) {
+    c->tbin = tbin;
+    c->above = above;
+    c->budget = B;
     c->T = T;
     c->idxT = idxT;
     c->arrive[1] = 0;
@@ -185,13 +216,15 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   FIER_PROF(16, unit == 0)
 }
 
-hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, int32_t* count_out, int units,
-                            int n_kv_heads, int max_ctx, hipStream_t st) {
+hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, const int32_t* budgets,
+                            int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,
+                            hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   const int n_chunks = (max_ctx + kClassifyTokens - 1) / kClassifyTokens;
   dim3 grid(n_chunks, units);
-  threshold_kernel<<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.range_cnt, sb.cand, sb.seg_cnt,
-                                                 count_out, n_ranges, n_chunks, n_kv_heads, max_ctx);
+  threshold_kernel<<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.hist, budgets, max_budget,
+                                                 sb.range_cnt, sb.cand, sb.seg_cnt, count_out, n_ranges, n_chunks,
+                                                 n_kv_heads, max_ctx);
   return hipGetLastError();
 }
 
