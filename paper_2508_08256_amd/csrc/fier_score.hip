@@ -6,6 +6,7 @@
 //   * B operand = the codes.  A byte with a single bit k set IS the integer 2^k (bit 7: -128), so one v_and of a
 //     code word with 0x01010101 << k yields four B elements: 8 vector ops expand 32 codes.  Lane (n, kq) of the
 //     wavefront owns word kq of token n of a 16-token tile, which is exactly the B layout (k = 16 kq + 0..15);
+//     the words arrive as one 16-byte load per token and are put into that order by four lane-row swaps;
 //   * A operand = the weights.  w = q_c s_c (binary32 product), divided by its bit's power of two and turned
 //     into a 31-bit fixed-point number relative to the largest |w| of its own group (the scale is a power of
 //     two, found per group with a DPP max), then cut into four signed bytes: F = d0 + 2^8 d1 + 2^16 d2 + 2^24 d3.
@@ -30,6 +31,7 @@
 namespace fier {
 
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 
 // LDS image of one wavefront's A operand: [j (K half)][group][digit][64 bytes], a zero row per j, padded so that
@@ -124,9 +126,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const bool scoring = !append_wg && P0 * kPair < L;
   const uint32_t* __restrict__ bits_u = reinterpret_cast<const uint32_t*>(kbits) + (size_t)unit * max_ctx * 4;
   const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
-  // word `row` of token 16 t + n of block P sits at pb[64 t], pb = bits_u + P * 256 + 4 n + row;
-  // the lane's (s, z) quad of block P at pm = meta_u + (2 P + gsel) * 32 + 16 hsel + n
-  const uint32_t* const pb = bits_u + ((size_t)P0 * 256 + 4 * n + row);
+  // lane l loads the whole 16-byte code word of token l of the block (one contiguous 1 KiB request per wavefront);
+  // the lane's (s, z) quad of block P is at meta_u[(2 P + gsel) * 32 + 16 hsel + n]
+  const uint4* const pb = reinterpret_cast<const uint4*>(bits_u) + ((size_t)P0 * kPair + lane);
   const uint4* const pm = meta_u + ((size_t)(2 * P0 + gsel) * 32 + 16 * hsel + n);
   // blocks of this wave that hold tokens: P0, P0 + 4, ... below ceil(L / 64), at most bpw
   int nb = scoring ? ((L + kPair - 1) / kPair - P0 + 3) / 4 : 0;
@@ -135,8 +137,11 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   // keep the count of outstanding requests the same on every path)
   auto fetch = [&](uint32_t (&w)[4], uint4& m, int i) {
     i = i < nb ? i : nb - 1;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) w[t] = pb[(size_t)i * 1024 + 64 * t];
+    const uint4 v = pb[(size_t)i * (4 * kPair)];
+    w[0] = v.x;
+    w[1] = v.y;
+    w[2] = v.z;
+    w[3] = v.w;
     m = pm[(size_t)i * 256];
   };
   uint32_t w_cur[4] = {0, 0, 0, 0};
@@ -239,6 +244,18 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       uint32_t w_nxt[4];
       uint4 m_nxt;
       fetch(w_nxt, m_nxt, it + 1);  // the next block is on its way while this one is scored
+      // The B layout wants, in lane (row r, n), word r of the tokens 16 t + n, t = 0..3; the load left word d of
+      // token 16 r + n in register d: a 4x4 transpose between register index and lane row, two swap stages.
+      {
+        const u32x2_t a = __builtin_amdgcn_permlane32_swap(w_cur[0], w_cur[2], false, false);
+        const u32x2_t b = __builtin_amdgcn_permlane32_swap(w_cur[1], w_cur[3], false, false);
+        const u32x2_t c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+        const u32x2_t d = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+        w_cur[0] = c[0];
+        w_cur[1] = c[1];
+        w_cur[2] = d[0];
+        w_cur[3] = d[1];
+      }
 
       // ---- this row's weights -> fixed point relative to the group's largest -> digit rows in LDS ----------
       const uint32_t mw[4] = {m_cur.x, m_cur.y, m_cur.z, m_cur.w};
