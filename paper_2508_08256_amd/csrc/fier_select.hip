@@ -25,7 +25,9 @@ constexpr int kMaxRanges = (1 << 20) / kRangeTokens;  // max_ctx <= 2^20
 constexpr int kMaxChunks = (1 << 20) / kClassifyTokens;
 constexpr int kSpecCand = 64;                          // candidates per segment fetched before its count is known
 
-// grid (ceil(max_ctx / 4096), units), block 1024
+// grid (ceil(max_ctx / (4096 NV)), units), block 1024: a workgroup classifies NV stretches of 4096 tokens (thread t
+// the tokens 4t..4t+3 of each).  The launcher picks NV so that all workgroups are resident at once if possible.
+template <int NV>
 __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __restrict__ scores,
                                                                 const int32_t* __restrict__ seq_lens, int extra,
                                                                 UnitCtl* __restrict__ ctl,
@@ -36,7 +38,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
                                                                 uint32_t* __restrict__ seg_cnt,
                                                                 int32_t* __restrict__ count_out, int n_ranges,
                                                                 int n_chunks, int n_kv_heads, int max_ctx) {
-  __shared__ uint32_t wsum[kThrWaves];
+  __shared__ uint32_t wsum[NV][kThrWaves];
   __shared__ uint32_t flag;
   __shared__ int found[2];
   __shared__ uint32_t scan_tmp[kThrWaves];
@@ -56,7 +58,8 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   const int b = unit / n_kv_heads;
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
-  if (chunk * kClassifyTokens >= n && chunk != 0) return;
+  constexpr int kChunkTokens = kClassifyTokens * NV;
+  if (chunk * kChunkTokens >= n && chunk != 0) return;
   FIER_PROF(10, unit == 0 && chunk == 1)
   UnitCtl* __restrict__ c = &ctl[unit];
   const float R = c->R, scale = c->scale;
@@ -66,10 +69,14 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   uint32_t* __restrict__ urange = range_cnt + (size_t)unit * n_ranges;
   uint32_t* __restrict__ gh = ghist + (size_t)unit * kSelBins;
 
-  // this workgroup's 4096 scores and the unit's histogram leave in the same round trip
-  const int i = chunk * kClassifyTokens + 4 * tid;
-  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (i < n) v = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx; entries >= n are masked below
+  // this workgroup's scores and the unit's histogram leave in the same round trip
+  float4 v[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = chunk * kChunkTokens + k * kClassifyTokens + 4 * tid;
+    v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n) v[k] = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx; entries >= n are masked below
+  }
   // thread t < 512 owns bin 511 - t: descending score order
   const uint32_t hcnt = tid < kSelBins ? gh[kSelBins - 1 - tid] : 0;
   int B = budgets[b];
@@ -94,42 +101,51 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   const int tbin = found[0];
   const uint32_t above = (uint32_t)found[1];
 
-  // ---- classify this workgroup's 4096 scores -------------------------------------------------------
+  // ---- classify this workgroup's scores ----------------------------------------------------------------
   FIER_PROF(11, unit == 0 && chunk == 1)
-  const float vv[4] = {v.x, v.y, v.z, v.w};
-  uint32_t n_gt = 0, n_c = 0;
-  bool is_c[4];
+  uint32_t cmask = 0;  // candidate flags: bit 4k + j = token j of stretch k
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const bool ok = i + j < n;
-    const int bin = sel_bin(vv[j], R, scale, kSelBins);
-    n_gt += ok && bin > tbin;
-    is_c[j] = ok && bin == tbin;
-    n_c += is_c[j];
+  for (int k = 0; k < NV; ++k) {
+    const int i = chunk * kChunkTokens + k * kClassifyTokens + 4 * tid;
+    const float vv[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+    uint32_t n_gt = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool ok = i + j < n;
+      const int bin = sel_bin(vv[j], R, scale, kSelBins);
+      n_gt += ok && bin > tbin;
+      cmask |= (ok && bin == tbin) ? 1u << (4 * k + j) : 0u;
+    }
+    // selected-for-certain count of each 1024-token range (4 wavefronts per range)
+    const uint32_t g = wave_sum_u32(n_gt);
+    if (lane == 0) wsum[k][wave] = g;
   }
-  // selected-for-certain count of each 1024-token range (4 wavefronts per range)
-  const uint32_t g = wave_sum_u32(n_gt);
-  if (lane == 0) wsum[wave] = g;
   // candidates go to this workgroup's own segment; the slot comes from an LDS counter
-  if (n_c) {
-    uint32_t pos = atomicAdd(&n_local, n_c);
+  if (cmask) {
+    uint32_t pos = atomicAdd(&n_local, (uint32_t)__builtin_popcount(cmask));
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (is_c[j]) {
-        if (pos < (uint32_t)kSegCand)
-          store_coherent(&ucand[(size_t)chunk * kSegCand + pos],
-                         ((unsigned long long)score_key(vv[j]) << 32) | (uint32_t)(i + j));
-        ++pos;
-      }
+    for (int k = 0; k < NV; ++k) {
+      const int i = chunk * kChunkTokens + k * kClassifyTokens + 4 * tid;
+      const float vv[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (cmask >> (4 * k + j) & 1u) {
+          if (pos < (uint32_t)kSegCand)
+            store_coherent(&ucand[(size_t)chunk * kSegCand + pos],
+                           ((unsigned long long)score_key(vv[j]) << 32) | (uint32_t)(i + j));
+          ++pos;
+        }
+    }
   }
   __syncthreads();
-  if (tid < 4) {
-    const int r = chunk * 4 + tid;
+  if (tid < 4 * NV) {
+    const int k = tid >> 2, q4 = tid & 3;
+    const int r = chunk * (4 * NV) + tid;
     if (r < n_ranges)
-      store_coherent(&urange[r], wsum[4 * tid] + wsum[4 * tid + 1] + wsum[4 * tid + 2] + wsum[4 * tid + 3]);
+      store_coherent(&urange[r], wsum[k][4 * q4] + wsum[k][4 * q4 + 1] + wsum[k][4 * q4 + 2] + wsum[k][4 * q4 + 3]);
   }
-  if (tid == 4) store_coherent(&useg[chunk], n_local);
-  const int nc = n > 0 ? (n + kClassifyTokens - 1) / kClassifyTokens : 1;  // workgroups of this unit
+  if (tid == 4 * NV) store_coherent(&useg[chunk], n_local);
+  const int nc = n > 0 ? (n + kChunkTokens - 1) / kChunkTokens : 1;  // workgroups of this unit
   FIER_PROF(12, unit == 0 && chunk == 1)
   if (!last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) return;
   FIER_PROF(13, unit == 0)
@@ -220,11 +236,23 @@ hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int 
                             int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,
                             hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  const int n_chunks = (max_ctx + kClassifyTokens - 1) / kClassifyTokens;
+  // tokens per workgroup: 4096 NV with the smallest NV in {1, 2, 4} for which the grid fits the machine at once
+  // (two workgroups of 1024 threads per CU, 256 CUs); the candidate segments are sized for NV = 1 (the most)
+  int nv = 1;
+  while (nv < 4 && (size_t)units * ((max_ctx + kClassifyTokens * nv - 1) / (kClassifyTokens * nv)) > 512) nv *= 2;
+  const int n_chunks = (max_ctx + kClassifyTokens * nv - 1) / (kClassifyTokens * nv);
   dim3 grid(n_chunks, units);
-  threshold_kernel<<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.hist, budgets, max_budget,
-                                                 sb.range_cnt, sb.cand, sb.seg_cnt, count_out, n_ranges, n_chunks,
-                                                 n_kv_heads, max_ctx);
+#define FIER_THR_CASE(NV)                                                                                            \
+  threshold_kernel<NV><<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.hist, budgets,         \
+                                                     max_budget, sb.range_cnt, sb.cand, sb.seg_cnt, count_out,      \
+                                                     n_ranges, n_chunks, n_kv_heads, max_ctx)
+  if (nv == 1)
+    FIER_THR_CASE(1);
+  else if (nv == 2)
+    FIER_THR_CASE(2);
+  else
+    FIER_THR_CASE(4);
+#undef FIER_THR_CASE
   return hipGetLastError();
 }
 
