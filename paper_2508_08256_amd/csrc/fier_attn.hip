@@ -90,13 +90,150 @@ __device__ __forceinline__ void attend_rows(const uint4* __restrict__ Ku, const 
   }
 }
 
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+template <int DT>
+__device__ __forceinline__ floatx4_t mfma_16x16x32(const uint4& a, const uint4& b, floatx4_t c) {
+  if (DT == DT_F16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0,
+                                                  0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                 0, 0, 0);
+}
+
+constexpr int kPartialFloats = 4 * 16 * 10;  // LDS floats per query head: [wave][channel chunk][o[8], m, l]
+constexpr int kAttnMfmaLds = 4 * 144;  // LDS floats attend_rows_mfma needs: per wavefront p[16 tokens][8 heads], alpha[8]
+
+// The same for 3 to 8 query heads per kv head, where q.K^T for all heads of the group is a real (if skinny) dense
+// contraction: per wavefront and 16 gathered rows, S[head][token] comes from four v_mfma_f32_16x16x32 (A = the
+// queries, one matrix row per head, B = the K rows as they lie in memory: lane (n, kq) loads channels
+// 32c + 8kq .. + 7 of row n).  The softmax runs on S where the matrix core leaves it (lane = token, register = head),
+// the probabilities go through LDS to the lanes that own the V rows (a 16-lane row owns one V row, as in
+// attend_rows) and the P.V product stays on the vector ALUs.  One running (m, l) per head and wavefront.
+// q_unit: the unit's NREP query rows; sh: kAttnMfmaLds floats of LDS.
+template <int DT, int NREP, class RowOf>
+__device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ Ku, const uint4* __restrict__ Vu,
+                                                 const uint4* __restrict__ q_unit, RowOf row_of, int start, int end,
+                                                 int max_ctx, float scale_log2e, AttnState<NREP>& st, float* sh) {
+  static_assert(NREP >= 1 && NREP <= 8, "heads per kv head");
+  static_assert(NREP * kPartialFloats >= kAttnMfmaLds || NREP < 3, "the callers lend the partials' LDS");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, kq = lane >> 4;  // matrix view: token column n, K quarter kq; result rows 4kq..4kq+3
+  float* p_sh = sh + wave * 144;            // [token][8 heads], then alpha[8]
+  uint4 qa[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    qa[c] = n < NREP ? q_unit[(size_t)n * (kD / 8) + 4 * c + kq] : make_uint4(0, 0, 0, 0);
+  // running max and sum of head 4kq + i in element i, the same in the 16 lanes of a lane row
+  float m_run[4], l_run[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    m_run[i] = -INFINITY;
+    l_run[i] = 0.f;
+  }
+  for (int j0 = start + wave * 16; j0 < end; j0 += 64) {
+    // K rows in the matrix view (token j0 + n), V rows in the row-owner view (tokens j0 + 4u + kq, channels 8n..8n+7)
+    const int jk = j0 + n;
+    const bool valid = jk < end;
+    int tk = valid ? row_of(jk) : 0;
+    tk = (tk < 0 || tk >= max_ctx) ? 0 : tk;
+    uint4 kk[4], vv[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kk[c] = Ku[(size_t)tk * (kD / 8) + 4 * c + kq];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int jv = j0 + 4 * u + kq;
+      int tv = jv < end ? row_of(jv) : 0;
+      tv = (tv < 0 || tv >= max_ctx) ? 0 : tv;
+      vv[u] = Vu[(size_t)tv * (kD / 8) + n];
+    }
+    floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sacc = mfma_16x16x32<DT>(qa[c], kk[c], sacc);
+    float p[4], alpha[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float logit = valid ? sacc[i] * scale_log2e : -INFINITY;
+      float tmax = logit;
+      tmax = fmaxf(tmax, row_ror<8>(tmax));
+      tmax = fmaxf(tmax, row_ror<4>(tmax));
+      tmax = fmaxf(tmax, row_ror<2>(tmax));
+      tmax = fmaxf(tmax, row_ror<1>(tmax));
+      const float mx = fmaxf(m_run[i], tmax);
+      const float mref = mx == -INFINITY ? 0.f : mx;
+      alpha[i] = __builtin_amdgcn_exp2f(m_run[i] - mref);
+      p[i] = __builtin_amdgcn_exp2f(logit - mref);
+      l_run[i] = l_run[i] * alpha[i] + row_allsum(p[i]);
+      m_run[i] = mx;
+    }
+    if (4 * kq < NREP) {
+      *reinterpret_cast<float4*>(p_sh + n * 8 + 4 * kq) = make_float4(p[0], p[1], p[2], p[3]);
+      if (n == 0) *reinterpret_cast<float4*>(p_sh + 128 + 4 * kq) = make_float4(alpha[0], alpha[1], alpha[2], alpha[3]);
+    }
+    // written and read by different lanes of this same wavefront: LDS operations of a wavefront complete in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float al[8], pw[4][8];
+    {
+      const float4 a0 = *reinterpret_cast<const float4*>(p_sh + 128);
+      al[0] = a0.x, al[1] = a0.y, al[2] = a0.z, al[3] = a0.w;
+      if (NREP > 4) {
+        const float4 a1 = *reinterpret_cast<const float4*>(p_sh + 132);
+        al[4] = a1.x, al[5] = a1.y, al[6] = a1.z, al[7] = a1.w;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float4 p0 = *reinterpret_cast<const float4*>(p_sh + (4 * u + kq) * 8);
+        pw[u][0] = p0.x, pw[u][1] = p0.y, pw[u][2] = p0.z, pw[u][3] = p0.w;
+        if (NREP > 4) {
+          const float4 p1 = *reinterpret_cast<const float4*>(p_sh + (4 * u + kq) * 8 + 4);
+          pw[u][4] = p1.x, pw[u][5] = p1.y, pw[u][6] = p1.z, pw[u][7] = p1.w;
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // reads done before the next tile's writes
+    float vf[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t vw[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        vf[u][2 * c] = lo16f<DT>(vw[c]);
+        vf[u][2 * c + 1] = hi16f<DT>(vw[c]);
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < NREP; ++h)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float o = st.o[h][c] * al[h];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o += pw[u][h] * vf[u][c];
+        st.o[h][c] = o;
+      }
+  }
+  // the per-wavefront (m, l) into the per-lane state: every lane row carries m, the first one also l
+  if (4 * kq < NREP && n == 0) {
+    *reinterpret_cast<float4*>(p_sh + 4 * kq) = make_float4(m_run[0], m_run[1], m_run[2], m_run[3]);
+    *reinterpret_cast<float4*>(p_sh + 8 + 4 * kq) = make_float4(l_run[0], l_run[1], l_run[2], l_run[3]);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (int h = 0; h < NREP; ++h) {
+    st.m[h] = p_sh[h];
+    st.l[h] = kq == 0 ? p_sh[8 + h] : 0.f;
+  }
+}
+
 // value of the lane 16 / 32 lanes away
 __device__ __forceinline__ float xor16(float x) {
   return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401f));
 }
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
 
-constexpr int kPartialFloats = 4 * 16 * 10;  // LDS floats per query head: [wave][channel chunk][o[8], m, l]
 
 // Combine the 16 lane-row states of the workgroup per query head and write one partial (m, l, o[128]) per head
 // into slot `slot` of the unit's partial arrays.  The four lane rows of a wavefront are folded with cross-lane
@@ -201,10 +338,19 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
 
   AttnState<NREP> st;
   st.init();
-  if (sel)
-    attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st);
-  else
-    attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st);
+  if constexpr (NREP >= 3) {
+    const uint4* q_unit = q + (size_t)unit * NREP * (kD / 8);
+    if (sel)
+      attend_rows_mfma<DT, NREP>(Ku, Vu, q_unit, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st,
+                                 sh_o);
+    else
+      attend_rows_mfma<DT, NREP>(Ku, Vu, q_unit, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st, sh_o);
+  } else {
+    if (sel)
+      attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st);
+    else
+      attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st);
+  }
   store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
 }
 
@@ -397,8 +543,12 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   for (int h = 0; h < NREP; ++h) qr[h] = q[((size_t)unit * NREP + h) * (kD / 8) + cn];
   AttnState<NREP> st;
   st.init();
-  attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return tok0 + (int)rows[j]; }, 0, (int)n_sel_total, max_ctx,
-                        scale_log2e, st);
+  if constexpr (NREP >= 3)
+    attend_rows_mfma<DT, NREP>(Ku, Vu, q + (size_t)unit * NREP * (kD / 8), [&](int j) { return tok0 + (int)rows[j]; },
+                               0, (int)n_sel_total, max_ctx, scale_log2e, st, sh_o);
+  else
+    attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return tok0 + (int)rows[j]; }, 0, (int)n_sel_total, max_ctx,
+                          scale_log2e, st);
   FIER_PROF(22, unit == 0 && wg == 3)
   store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, po, pm, pl);
   FIER_PROF(23, unit == 0 && wg == 3)
