@@ -145,8 +145,9 @@ def main():
         decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, buds, budget, t_setup)
         return
 
-    # one workspace per cache set, so that a phase of the fused step can be timed alone on rotating caches
-    wss = [B.make_workspace(cfg, budget) for _ in range(R)]
+    # the timed steps share ONE workspace (as a model's layers would); the per-kernel timing below needs every
+    # layer cache to keep its own intermediate state, hence one workspace per layer cache there
+    wss = [[B.make_workspace(cfg, budget) for _ in range(NL)] for _ in range(R)]
     ws_dense = B.make_workspace(cfg, max_ctx)
     out = torch.zeros((NL, batch, Hq, 128), dtype=torch.float32, device="cuda")
     out1 = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
@@ -156,7 +157,7 @@ def main():
 
     def step(i):
         r = i % R
-        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0])
+        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0][0])
 
     def timed(fn, n, warm):
         for i in range(warm):
@@ -208,15 +209,21 @@ def main():
 
     # ---- each kernel of the fused step alone (HIP events on the launch stream, rotating caches) ----------
     ns = args.stage_steps
-    for r in range(R):
-        step(r)
-    torch.cuda.synchronize()
+
+    # argument tuples per layer cache, prepared once (slicing tensors inside the timed loop would make it CPU-bound)
+    largs = [[(cfg, caches[r][l:l + 1], qs[r][l:l + 1], kns[r][l:l + 1], vns[r][l:l + 1], budgets, budget,
+               out[l:l + 1], idx[l:l + 1], cnt[l:l + 1], wss[r][l]) for l in range(NL)] for r in range(R)]
 
     def phase(p):
         def run(i):
-            r = i % R
-            B.decode_step_phase(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[r], p)
+            for a in largs[i % R]:
+                B.decode_step_phase(*a, p)
         return run
+
+    for r in range(R):                    # a whole step per layer cache on its own workspace
+        for p in (1, 2, 3):
+            phase(p)(r)
+    torch.cuda.synchronize()
 
     # The score kernel adds into the unit histograms that the threshold kernel consumes and clears, so the
     # threshold kernel cannot be repeated alone: it is timed as (score + threshold) - (score).  The third kernel
@@ -252,7 +259,7 @@ def main():
 
     def st_attn(i):
         r, l = flat[i % len(flat)]
-        B.sparse_attn(cfg, caches[r][l], qs[r][l:l + 1], idx[0:1], cnt[0:1], budget, out1, wss[0])
+        B.sparse_attn(cfg, caches[r][l], qs[r][l:l + 1], idx[0:1], cnt[0:1], budget, out1, wss[0][0])
 
     us_score, _ = timed(st_score, max(24, ns // 4), 4)
     us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
