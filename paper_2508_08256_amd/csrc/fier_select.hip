@@ -236,10 +236,13 @@ hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int 
                             int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,
                             hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  // tokens per workgroup: 4096 NV with the smallest NV in {1, 2, 4} for which the grid fits the machine at once
-  // (two workgroups of 1024 threads per CU, 256 CUs); the candidate segments are sized for NV = 1 (the most)
+  // tokens per workgroup: 4096 NV.  One stretch per thread while the grid fits the machine at once (two workgroups
+  // of 1024 threads per CU, 256 CUs), two beyond that (measured best at 1000 to 2000 workgroups), four for more
+  // than 2048 workgroups of two; the candidate segments are sized for NV = 1 (the most)
+  auto wgs = [&](int v) { return (size_t)units * ((max_ctx + kClassifyTokens * v - 1) / (kClassifyTokens * v)); };
   int nv = 1;
-  while (nv < 4 && (size_t)units * ((max_ctx + kClassifyTokens * nv - 1) / (kClassifyTokens * nv)) > 512) nv *= 2;
+  if (wgs(1) > 512) nv = 2;
+  if (wgs(2) > 2048) nv = 4;
   const int n_chunks = (max_ctx + kClassifyTokens * nv - 1) / (kClassifyTokens * nv);
   dim3 grid(n_chunks, units);
 #define FIER_THR_CASE(NV)                                                                                            \
