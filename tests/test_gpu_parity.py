@@ -77,6 +77,8 @@ def test_quantize_special_values(gu, oracle):
         x[0, 32:64, :] = np.where(rng.integers(0, 2, (32, D)) == 1, -0.0, 0.0)
         x[0, 64:96, 0:32] = rng.integers(-4, 5, (32, 32))           # many exact midpoints
         x[1, :64, :] *= 20000.0 if dtype == F16 else 1e30          # ranges near the top of the format
+        if dtype == F16:
+            x = np.clip(x, -65000.0, 65000.0)                       # inputs are finite (the range may still saturate s)
         x[1, 64:, :] *= 1e-6                                        # subnormal binary16 inputs
         wl = synth.make_workload("special", 1, 1, 2, 2, [L], [8], dtype, max_ctx=L, plant=False)
         wl.K[:] = synth.f32_to_words(x, dtype)
@@ -154,7 +156,7 @@ def _run_topk(gu, cfg, scores_np, lens, budgets, max_budget, extra=0):
 @pytest.mark.parametrize("kind", ["gauss", "equal", "ties", "two_values", "clustered", "signed_zero", "tiny_range"])
 def test_topk_exact_on_identical_scores(gu, oracle, kind):
     """Same binary32 scores on both sides: the selected sets must be identical, ties to the lower index."""
-    rng = np.random.default_rng(hash(kind) % 1000)
+    rng = np.random.default_rng(sum(kind.encode()))   # a fixed seed per kind (hash() differs between processes)
     batch, H, Lcap = 3, 2, 40960
     lens = np.array([40960, 12345, 70], np.int32)
     budgets = np.array([4505, 1, 69], np.int32)
