@@ -59,12 +59,13 @@ def shape_of(w, seed):
 
 
 def algorithmic_bytes(w, lens, buds):
-    """Bytes the method has to move per layer step: packed keys + (s, z) metadata (32 B per cached token and
-    unit), the selected K and V rows (512 B per selected token and unit), query in and fp32 output out."""
+    """Bytes the method has to move per layer step: packed keys + (s, z) metadata (16 + 512/g B per cached token
+    and unit: 32 B at g = 32), the selected K and V rows (512 B per selected token and unit), query in and fp32
+    output out."""
     hkv = w["n_kv_heads"]
     heads = w["batch"] * w["n_q_heads"]
     n_tok = lens + 1
-    packed = int(hkv * n_tok.sum() * 32)
+    packed = int(hkv * n_tok.sum() * (16 + 512 // w.get("group_size", 32)))
     kv = int(hkv * np.minimum(buds, n_tok).sum() * 512)
     qo = heads * (256 + 512)
     return dict(packed=packed, selected_kv=kv, q_out=qo, total=packed + kv + qo)
@@ -77,6 +78,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=60)
     ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
     ap.add_argument("--budget", type=int, default=None, help="token budget (config4's sweep point)")
+    ap.add_argument("--group-size", type=int, default=32, choices=[32, 64, 128, 256],
+                    help="tokens per quantization group (32 is the paper's default; 128 / 256 are its ablation)")
     ap.add_argument("--loop-steps", type=int, default=0,
                     help="instead of the default measurement: this many consecutive token steps (append, growing "
                          "context) over all the workload's layer caches in one call per token, eager and as one graph")
@@ -103,12 +106,16 @@ def main():
         w["label"] += f"_budget{args.budget}"
     elif args.workload == "config4":
         w["label"] += f"_budget{w['budget']}"
+    w["group_size"] = args.group_size
+    if args.group_size != 32:
+        w["label"] += f"_g{args.group_size}"
     R, NL = w["rotate"], w.get("layers", 1)
     batch, Hq, Hkv, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["dtype"]
     lens, buds = shape_of(w, 5000)
     L, budget = int(lens.max()), int(buds.max())   # the largest context and budget (all of them when not ragged)
-    max_ctx = -(-(L + 1 + max(0, args.loop_steps)) // 64) * 64
-    cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype)
+    gran = max(64, args.group_size)
+    max_ctx = -(-(L + 1 + max(0, args.loop_steps)) // gran) * gran
+    cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype, group_size=args.group_size)
     units, n_rep = cfg.units, cfg.n_rep
     if NL > 1 and args.steps == 600:
         args.steps, args.warmup, args.stage_steps = 40, 4, 16   # a step is NL layers
@@ -305,7 +312,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w["label"], "batch": batch, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128,
                    "context": L if w["L"] != "ragged" else [int(x) for x in lens],
-                   "budget": budget if w["budget"] != "11%" else [int(x) for x in buds], "group_size": 32,
+                   "budget": budget if w["budget"] != "11%" else [int(x) for x in buds],
+                   "group_size": args.group_size,
                    "layers_per_step": NL, "rotating_caches": R * NL,
                    "algorithmic_bytes_per_layer": ab["total"]},
         "achieved_GBps": round(achieved, 1),
@@ -399,7 +407,7 @@ def decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, bud
         "dtype": "f16" if w["dtype"] == 0 else "bf16", "data": "synthetic",
         "config": {"workload": w["label"] + f"_decode_loop{N}", "batch": batch, "n_q_heads": Hq,
                    "n_kv_heads": w["n_kv_heads"], "head_dim": 128, "context_start": [int(x) for x in lens],
-                   "tokens_appended": N, "layers_per_token": NLt, "group_size": 32,
+                   "tokens_appended": N, "layers_per_token": NLt, "group_size": args.group_size,
                    "algorithmic_bytes_per_layer": ab["total"]},
         "achieved_GBps": round(ab["total"] / (us_layer * 1e-6) / 1e9, 1),
         "hbm_frac": round(ab["total"] / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -431,13 +439,14 @@ def cpu_baseline(d, w, lens, buds):
     L = np.repeat(lens, hkv)[:su].astype(np.int32)
     bud = np.repeat(buds, hkv)[:su].astype(np.int32)
     max_budget = int(buds.max())
-    bits, s, z = oracle.quantize(K, L, 32, w["dtype"], threads)        # prefill, not timed
+    g = w.get("group_size", 32)
+    bits, s, z = oracle.quantize(K, L, g, w["dtype"], threads)         # prefill, not timed
 
     def layer_step(nthreads):
         t0 = time.perf_counter()
-        oracle.append(K, V, L, kn, vn, bits, s, z, 32, w["dtype"])
+        oracle.append(K, V, L, kn, vn, bits, s, z, g, w["dtype"])
         L1 = (L + 1).astype(np.int32)
-        sc = oracle.score(bits, s, z, q, L1, 32, w["dtype"], nthreads)
+        sc = oracle.score(bits, s, z, q, L1, g, w["dtype"], nthreads)
         idx, cnt = oracle.topk(sc, L1, bud, max_budget)
         oracle.attention(K, V, q, L1, 1.0 / np.sqrt(128.0), w["dtype"], idx, cnt, nthreads)
         return time.perf_counter() - t0

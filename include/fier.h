@@ -23,17 +23,17 @@
  *   - Units are ordered batch-major: u = b * n_kv_heads + h.  The query heads that
  *     share kv head h are h * n_rep .. h * n_rep + n_rep - 1, n_rep = n_q_heads / n_kv_heads.
  *
- * Data layout in device memory (D = head_dim = 128, g = group_size = 32)
+ * Data layout in device memory (D = head_dim = 128, g = group_size: 32 by default, or 64, 128, 256)
  *   k, v     [batch][n_kv_heads][max_ctx][D]     16-bit floats (binary16 or bfloat16)
  *   kbits    [units][max_ctx][4] uint32            one 128-bit code word (16 bytes) per token:
  *              bit i of word d holds channel c = 64 (d & 1) + 2 i + (d >> 1), i.e. words 0 / 1 carry
  *              the even channels 0..62 / 64..126 and words 2 / 3 the odd channels 1..63 / 65..127.
  *              Bits of tokens not present are 0.  A wavefront reads the 64 tokens of a "pair block"
- *              (two quantization groups) as one coalesced 1 KiB request, lane = token.
- *   kmeta    [units][max_ctx / 32][D] uint32      low half = s, high half = z of group
- *              (u, G, c), both in the K dtype: dequant(k) = z + bit * s.
- *   Together 32 bytes per cached token and unit: 1/8 of a 16-bit key cache, the ratio
- *   (1 + 32/g)/16 of Eq. 8.
+ *              (two quantization groups when g = 32) as one coalesced 1 KiB request, lane = token.
+ *   kmeta    [units][max_ctx / g][D] uint32       low half = s, high half = z of group
+ *              (u, G, c), G = token / g, both in the K dtype: dequant(k) = z + bit * s.
+ *   Together 16 + 512/g bytes per cached token and unit (32 for g = 32: 1/8 of a 16-bit key cache), the
+ *   ratio (1 + 32/g)/16 of Eq. 8: 0.125, 0.078 and 0.070 for g = 32, 128 and 256 (Sec. 4.4 ablation).
  *   kabsmax  [units][D] float: max over the quantized tokens of max(|z|, |z + s|) per channel.  With
  *              it |score| <= R = sum_c |q_c| kabsmax_c is known before any score is computed, which
  *              lets the scoring kernel histogram its scores in the same pass (512 bytes per unit).
@@ -59,7 +59,7 @@ typedef enum {
   FIER_ESHAPE = -2,       /* head counts / context capacity not supported      */
   FIER_EALIGN = -3,       /* a device pointer is not 16-byte aligned            */
   FIER_EWORKSPACE = -4,   /* workspace missing                                  */
-  FIER_EUNSUPPORTED = -5, /* head_dim != 128, group_size != 32, n_rep > 8       */
+  FIER_EUNSUPPORTED = -5, /* head_dim != 128, group_size not 32/64/128/256, n_rep > 8 */
   FIER_EHIP = -6          /* a kernel launch failed                             */
 } fier_status;
 
@@ -69,7 +69,7 @@ typedef struct fier_config {
   int32_t n_q_heads;  /* multiple of n_kv_heads, n_rep = n_q_heads / n_kv_heads <= 8 */
   int32_t n_kv_heads;
   int32_t head_dim;   /* 128 */
-  int32_t group_size; /* 32 (tokens per quantization group, along each channel)      */
+  int32_t group_size; /* tokens per quantization group along each channel: 32, 64, 128 or 256; divides max_ctx */
   int32_t max_ctx;    /* row capacity of every unit's cache; multiple of 64, <= 2^20 */
   int32_t batch;
   int32_t kv_dtype;   /* fier_dtype of k, v, q, k_new, v_new and of (s, z)           */

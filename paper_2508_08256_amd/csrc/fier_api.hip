@@ -10,7 +10,6 @@
 namespace {
 
 constexpr int kD = 128;
-constexpr int kG = 32;
 constexpr int kPair = 64;
 constexpr size_t kAlign = 256;
 
@@ -22,10 +21,12 @@ int check_cfg(const fier_config* c) {
   if (c->batch <= 0 || c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->max_ctx <= 0) return FIER_EINVAL;
   if (c->kv_dtype != FIER_F16 && c->kv_dtype != FIER_BF16) return FIER_EINVAL;
   if (!(c->sm_scale == c->sm_scale)) return FIER_EINVAL;
-  if (c->head_dim != kD || c->group_size != kG) return FIER_EUNSUPPORTED;
+  if (c->head_dim != kD) return FIER_EUNSUPPORTED;
+  if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128 && c->group_size != 256)
+    return FIER_EUNSUPPORTED;
   if (c->n_q_heads % c->n_kv_heads != 0) return FIER_ESHAPE;
   if (c->n_q_heads / c->n_kv_heads > 8) return FIER_EUNSUPPORTED;
-  if (c->max_ctx % kPair != 0 || c->max_ctx > (1 << 20)) return FIER_ESHAPE;
+  if (c->max_ctx % kPair != 0 || c->max_ctx % c->group_size != 0 || c->max_ctx > (1 << 20)) return FIER_ESHAPE;
   if ((int64_t)c->batch * c->n_kv_heads > 65535) return FIER_ESHAPE;
   return FIER_OK;
 }
@@ -115,7 +116,7 @@ size_t fier_packed_bits_bytes(const fier_config* cfg) {
 
 size_t fier_packed_meta_bytes(const fier_config* cfg) {
   if (check_cfg(cfg) != FIER_OK) return 0;
-  return (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / kG) * kD * sizeof(uint32_t);
+  return (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / cfg->group_size) * kD * sizeof(uint32_t);
 }
 
 size_t fier_workspace_bytes(const fier_config* cfg, int32_t max_budget) {
@@ -131,7 +132,7 @@ int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* st
   if (st != FIER_OK) return st;
   return hip_status(fier::launch_quantize(cfg->kv_dtype, cache->k, cache->kbits, cache->kmeta, cache->kabsmax,
                                           cache->seq_lens, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
-                                          (hipStream_t)stream));
+                                          cfg->group_size, (hipStream_t)stream));
 }
 
 int fier_append_key(const fier_config* cfg, const fier_cache* cache, const void* k_new, const void* v_new,
@@ -144,7 +145,7 @@ int fier_append_key(const fier_config* cfg, const fier_cache* cache, const void*
   if (misaligned(k_new) || misaligned(v_new)) return FIER_EALIGN;
   return hip_status(fier::launch_append(cfg->kv_dtype, cache->k, cache->v, cache->kbits, cache->kmeta,
                                         cache->kabsmax, cache->seq_lens, k_new, v_new, units_of(cfg),
-                                        cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
+                                        cfg->n_kv_heads, cfg->max_ctx, cfg->group_size, (hipStream_t)stream));
 }
 
 int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, int32_t extra_tokens, float* scores,
@@ -158,7 +159,7 @@ int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, i
   return hip_status(fier::launch_score(cfg->kv_dtype, n_rep_of(cfg), cache->kbits, cache->kmeta, cache->kabsmax, q,
                                        cache->seq_lens, extra_tokens, scores, nullptr, nullptr, 0, nullptr, nullptr,
                                        nullptr, nullptr, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
-                                       (hipStream_t)stream));
+                                       cfg->group_size, (hipStream_t)stream));
 }
 
 int fier_topk(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
@@ -241,7 +242,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
       const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
       e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra,
                              w.sb.scores, &w.sb, budgets, max_budget, c->k, c->v, kn, vn, units, cfg->n_kv_heads,
-                             cfg->max_ctx, s);
+                             cfg->max_ctx, cfg->group_size, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
     if (phase == 0 || phase == 2) {
@@ -288,7 +289,7 @@ void fier_unpack_bits(const fier_config* cfg, const uint32_t* kbits_host, uint8_
 
 void fier_unpack_meta(const fier_config* cfg, const uint32_t* kmeta_host, uint16_t* s_host, uint16_t* z_host) {
   if (check_cfg(cfg) != FIER_OK || !kmeta_host || !s_host || !z_host) return;
-  const size_t n = (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / kG) * kD;
+  const size_t n = (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / cfg->group_size) * kD;
   for (size_t i = 0; i < n; ++i) {
     s_host[i] = (uint16_t)(kmeta_host[i] & 0xffffu);
     z_host[i] = (uint16_t)(kmeta_host[i] >> 16);

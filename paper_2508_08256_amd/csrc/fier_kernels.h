@@ -51,11 +51,12 @@ struct StepBuffers {    // carved from the caller's workspace
 };
 
 hipError_t launch_quantize(int dtype, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
-                           const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, hipStream_t st);
+                           const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, int group_size,
+                           hipStream_t st);
 
 hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
                          const int32_t* seq_lens, const void* k_new, const void* v_new, int units, int n_kv_heads,
-                         int max_ctx, hipStream_t st);
+                         int max_ctx, int group_size, hipStream_t st);
 
 // With sb != nullptr the kernel also builds the per-unit score histogram and its last workgroup per unit
 // finds the threshold bin for budgets[b] (first kernel of the fused step); with k_new != nullptr as well it
@@ -63,7 +64,7 @@ hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t*
 hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
-                        const void* v_new, int units, int n_kv_heads, int max_ctx, hipStream_t st);
+                        const void* v_new, int units, int n_kv_heads, int max_ctx, int group_size, hipStream_t st);
 
 hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, const int32_t* budgets,
                             int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,

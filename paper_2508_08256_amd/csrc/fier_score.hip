@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
                                                     int max_budget, uint32_t* __restrict__ K, uint32_t* __restrict__ V,
                                                     const uint32_t* __restrict__ k_new,
                                                     const uint32_t* __restrict__ v_new, float* __restrict__ newmax,
-                                                    int n_kv_heads, int max_ctx, int bpw) {
+                                                    int n_kv_heads, int max_ctx, int bpw, int gshift) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
   __shared__ __attribute__((aligned(16))) unsigned char a_lds[4 * kAWave];
 
@@ -103,7 +103,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const bool app = HIST && k_new != nullptr && Lold < max_ctx;  // this unit receives a new row in this step
   int L = HIST ? Lold + (app ? 1 : 0) : Lold + extra;
   L = L > max_ctx ? max_ctx : L;
-  const int tail_start = app ? (Lold / kG) * kG : L;  // tokens from here on are scored by the appending wave
+  const int gsize = kG << gshift;  // tokens per quantization group: 32, 64, 128 or 256
+  const int tail_start = app ? (Lold / gsize) * gsize : L;  // tokens from here on are scored by the appending wave
   // HIST: workgroup 0 is the appending one (dispatched first: its single wavefront has the longest chain of
   // dependent loads), workgroups 1.. score the ranges 0..
   const bool append_wg = HIST && blockIdx.x == 0;
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     // range 0 of a unit always runs so that an empty unit still gets its control block written
     if (range * (4 * kPair) * bpw >= L && !(HIST && range == 0)) return;
   }
-  const int n_groups = max_ctx / kG;
+  const int n_groups = max_ctx / gsize;
   const int row = lane >> 4, n = lane & 15;
   const int gsel = row >> 1;  // the group of the pair block whose (s, z) this row of lanes holds
   const int hsel = row & 1;   // the 64-channel half it holds
@@ -127,9 +128,11 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const uint32_t* __restrict__ bits_u = reinterpret_cast<const uint32_t*>(kbits) + (size_t)unit * max_ctx * 4;
   const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
   // lane l loads the whole 16-byte code word of token l of the block (one contiguous 1 KiB request per wavefront);
-  // the lane's (s, z) quad of block P is at meta_u[(2 P + gsel) * 32 + 16 hsel + n]
+  // the lane's (s, z) quad of block P is at meta_u[((2 P + gsel) >> gshift) * 32 + 16 hsel + n]: half-block
+  // 2 P + gsel (32 tokens) lies in group (2 P + gsel) >> gshift
   const uint4* const pb = reinterpret_cast<const uint4*>(bits_u) + ((size_t)P0 * kPair + lane);
-  const uint4* const pm = meta_u + ((size_t)(2 * P0 + gsel) * 32 + 16 * hsel + n);
+  const uint4* const pm = meta_u + ((size_t)((2 * P0 + gsel) >> gshift) * 32 + 16 * hsel + n);
+  const int pm_step = 256 >> gshift;  // uint4 per block step: a wave's next block is 4 blocks = 8 half-blocks on
   // blocks of this wave that hold tokens: P0, P0 + 4, ... below ceil(L / 64), at most bpw
   int nb = scoring ? ((L + kPair - 1) / kPair - P0 + 3) / 4 : 0;
   nb = nb > bpw ? bpw : nb;
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     w[1] = v.y;
     w[2] = v.z;
     w[3] = v.w;
-    m = pm[(size_t)i * 256];
+    m = pm[(size_t)i * pm_step];
   };
   uint32_t w_cur[4] = {0, 0, 0, 0};
   uint4 m_cur = make_uint4(0, 0, 0, 0);
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   FIER_PROF(1, HIST && unit == 0 && range == 3)
   if (append_wg) {
     if constexpr (HIST) {
-      if (wave == 0) {  // lane = channel pair (2 lane, 2 lane + 1)
+      if (wave == 0 && gshift == 0) {  // lane = channel pair (2 lane, 2 lane + 1)
         const uint32_t kn = k_new[(size_t)unit * (kD / 2) + lane];
         const uint32_t vn = v_new[(size_t)unit * (kD / 2) + lane];
         GroupCode gc;
@@ -212,6 +215,56 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
           scores[(size_t)unit * max_ctx + t0 + lane] = mine;
           atomicAdd(&lhist[sel_bin(mine, R, hscale, kSelBins)], 1u);
         }
+      } else if (wave == 0) {
+        // Groups of 64, 128 or 256 tokens: the tail group is re-derived 32 rows at a time; each of its pair blocks
+        // is scored as soon as its code words exist, lane = token, the 128 weights q_c s_c read from LDS in the
+        // order of the code word's bits (bit i of word d is channel 64 (d & 1) + 2 i + (d >> 1)).
+        float* wl = reinterpret_cast<float*>(a_lds);  // 128 floats; this workgroup scores nothing else
+        const uint32_t kn = k_new[(size_t)unit * (kD / 2) + lane];
+        const uint32_t vn = v_new[(size_t)unit * (kD / 2) + lane];
+        float q0 = 0.f, q1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+          q0 += w2f<DT>(qb[r * kD + 2 * lane]);
+          q1 += w2f<DT>(qb[r * kD + 2 * lane + 1]);
+        }
+        int t0, ntok;
+        float base = 0.f;
+        bool have_w = false;
+        const GroupScale gs = append_row_long<DT>(
+            K, V, const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
+            const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kmeta)), unit, Lold, max_ctx, 1 << gshift, kn, vn, lane,
+            t0, ntok, [&](int pb, const uint4& mine, const GroupScale& g) {
+              if (!have_w) {
+                have_w = true;
+                // channel 2 lane is bit (lane & 31) of word lane >> 5, channel 2 lane + 1 of word 2 + (lane >> 5)
+                wl[lane] = q0 * g.sf0;
+                wl[64 + lane] = q1 * g.sf1;
+                base = wave_allsum(q0 * g.zf0 + q1 * g.zf1);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+              }
+              const uint32_t wd[4] = {mine.x, mine.y, mine.z, mine.w};
+              float acc = 0.f;
+#pragma unroll
+              for (int d = 0; d < 4; ++d)
+#pragma unroll
+                for (int i = 0; i < 32; i += 4) {
+                  const float4 w4 = *reinterpret_cast<const float4*>(wl + 32 * d + i);
+                  acc += (wd[d] >> i & 1u) ? w4.x : 0.f;
+                  acc += (wd[d] >> (i + 1) & 1u) ? w4.y : 0.f;
+                  acc += (wd[d] >> (i + 2) & 1u) ? w4.z : 0.f;
+                  acc += (wd[d] >> (i + 3) & 1u) ? w4.w : 0.f;
+                }
+              const int tok = pb * kPair + lane;  // within the group
+              if (tok < ntok) {
+                const float sc = acc + base;
+                scores[(size_t)unit * max_ctx + t0 + tok] = sc;
+                atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
+              }
+            });
+        newmax[(size_t)unit * kD + 2 * lane] = fmaxf(fabsf(gs.zf0), fabsf(gs.zf0 + gs.sf0));
+        newmax[(size_t)unit * kD + 2 * lane + 1] = fmaxf(fabsf(gs.zf1), fabsf(gs.zf1 + gs.sf1));
       }
     }
   }
@@ -356,7 +409,8 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
                                   const void* q, const int32_t* seq_lens, int extra, float* scores,
                                   const StepBuffers* sb, const int32_t* budgets, int max_budget, void* K, void* V,
                                   const void* k_new, const void* v_new, int units, int n_kv_heads, int max_ctx,
-                                  hipStream_t st) {
+                                  int group_size, hipStream_t st) {
+  const int gshift = group_size == 256 ? 3 : group_size == 128 ? 2 : group_size == 64 ? 1 : 0;
   // blocks per wavefront: the smallest that lets every workgroup be resident at once (256 CUs; the registers
   // allow 4 workgroups per CU for the fused kernel, 8 for the score-only one), at least 4
   const int n_blocks = (max_ctx + kPair - 1) / kPair;
@@ -370,7 +424,8 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
     score_kernel<DT, R, HIST><<<grid, 256, 0, st>>>(                                                               \
         (const uint4*)kbits, (const uint4*)kmeta, kabsmax, (const uint16_t*)q, seq_lens, extra, scores,            \
         sb ? sb->ctl : nullptr, sb ? sb->hist : nullptr, budgets, max_budget, (uint32_t*)K, (uint32_t*)V,          \
-        (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx, bpw);      \
+        (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx, bpw,     \
+        gshift);                                                                                                  \
     break;
   switch (n_rep) {
     FIER_SCORE_CASE(1)
@@ -391,19 +446,19 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
 hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
-                        const void* v_new, int units, int n_kv_heads, int max_ctx, hipStream_t st) {
+                        const void* v_new, int units, int n_kv_heads, int max_ctx, int group_size, hipStream_t st) {
   if (sb) {
     if (dtype == DT_F16)
       return launch_score_dt<DT_F16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
-                                           max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, st);
+                                           max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, group_size, st);
     return launch_score_dt<DT_BF16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
-                                          max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, st);
+                                          max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, group_size, st);
   }
   if (dtype == DT_F16)
     return launch_score_dt<DT_F16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
-                                          0, nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, st);
+                                          0, nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, group_size, st);
   return launch_score_dt<DT_BF16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr, 0,
-                                         nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, st);
+                                         nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, group_size, st);
 }
 
 }  // namespace fier

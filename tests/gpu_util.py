@@ -23,9 +23,9 @@ def i32(a):
 
 
 class DeviceWorkload:
-    def __init__(self, wl):
+    def __init__(self, wl, group_size=32):
         self.wl = wl
-        self.cfg = B.make_config(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.max_ctx, wl.dtype)
+        self.cfg = B.make_config(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.max_ctx, wl.dtype, group_size=group_size)
         self.K = to_dev(wl.K, wl.dtype)
         self.V = to_dev(wl.V, wl.dtype)
         self.q = to_dev(wl.q, wl.dtype)

@@ -33,7 +33,10 @@ def test_config_validation():
     ok = B.make_config(2, 32, 8, 4096, B.BF16)
     assert B.check_config(ok) == B.OK
     assert B.check_config(B.make_config(2, 32, 8, 4096, head_dim=64)) == B.EUNSUPPORTED
-    assert B.check_config(B.make_config(2, 32, 8, 4096, group_size=128)) == B.EUNSUPPORTED
+    assert B.check_config(B.make_config(2, 32, 8, 4096, group_size=128)) == B.OK
+    assert B.check_config(B.make_config(2, 32, 8, 4096, group_size=48)) == B.EUNSUPPORTED
+    assert B.check_config(B.make_config(2, 32, 8, 4160, group_size=256)) == B.ESHAPE   # 256 does not divide it
+    assert B.packed_meta_bytes(B.make_config(2, 32, 8, 4096, group_size=256)) == 2 * 8 * 16 * 512
     assert B.check_config(B.make_config(2, 30, 8, 4096)) == B.ESHAPE
     assert B.check_config(B.make_config(2, 72, 8, 4096)) == B.EUNSUPPORTED      # n_rep = 9
     assert B.check_config(B.make_config(2, 32, 8, 4100)) == B.ESHAPE            # not a multiple of 64

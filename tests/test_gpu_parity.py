@@ -45,11 +45,11 @@ def case(request, gu, oracle):
     return wl, gu.DeviceWorkload(wl)
 
 
-def _compare_packed(dw, L, bits_o, s_o, z_o):
+def _compare_packed(dw, L, bits_o, s_o, z_o, g=G):
     bits, s, z = dw.cache.unpack()
     for u in range(dw.wl.units):
         n = int(L[u])
-        ng = -(-n // G)
+        ng = -(-n // g)
         npair_tok = -(-n // 64) * 64
         assert np.array_equal(bits[u, :n], bits_o[u, :n]), f"bits differ in unit {u}"
         assert np.all(bits[u, n:npair_tok] == 0), f"bits of absent tokens set in unit {u}"
@@ -594,3 +594,70 @@ def test_decode_loop_many_steps_eager_and_graph(gu, oracle):
         assert np.array_equal(cnts.cpu().numpy(), cnt_e), rep
         assert np.array_equal(outs.cpu().numpy(), out_e), rep
         assert int(dw.seq_lens[0]) == lens0[0] + steps
+
+
+@pytest.mark.parametrize("g", [64, 128, 256])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_larger_quantization_groups(gu, oracle, g, dtype):
+    """Group sizes of the ablation in Sec. 4.4 (g = 128, 256; 64 for completeness): bulk quantization, the
+    append invariant across group boundaries, scores, and the fused step with an append, all against the oracle
+    run with the same g."""
+    n_rep = 1 if dtype == F16 else 4
+    lens = [1000, 333, 64, 1]
+    wl = synth.make_workload(f"g{g}", 40 + g + dtype, 4, 2 * n_rep, 2, lens, [100, 50, 64, 2], dtype, max_ctx=1280,
+                             n_planted=4, chan="lognormal" if dtype == BF16 else "ones")
+    dw = gu.DeviceWorkload(wl, group_size=g)
+    L = wl.unit_lens.copy()
+    # ---- bulk quantization, bit-exact ---------------------------------------------------------------------------
+    B.quantize_keys(dw.cfg, dw.cache)
+    torch.cuda.synchronize()
+    K, V = wl.K.copy(), wl.V.copy()
+    bits, s, z = oracle.quantize(K, L, g, dtype, 4)
+    _compare_packed(dw, L, bits, s, z, g)
+    # ---- scores -----------------------------------------------------------------------------------------------------
+    sc_d = torch.zeros((wl.units, wl.max_ctx), dtype=torch.float32, device="cuda")
+    B.score(dw.cfg, dw.cache, dw.q, 0, sc_d)
+    torch.cuda.synchronize()
+    sc_o = oracle.score(bits, s, z, wl.q, L, g, dtype, 4)
+    deq = np.abs(oracle.dequantize(bits, s, z, L, g, dtype))
+    qa = np.abs(synth.words_to_f32(wl.q, dtype).astype(np.float64)).sum(axis=1)
+    absterm = np.einsum("utd,ud->ut", deq, qa)
+    sc_g = sc_d.cpu().numpy()
+    for u in range(wl.units):
+        n = int(L[u])
+        assert np.all(score_tolerance_ok(sc_g[u, :n], sc_o[u, :n], absterm[u, :n])), u
+    # ---- 70 appends through fier_append_key: the state equals a bulk quantization of the grown prefix ---------------
+    rng = np.random.default_rng(g)
+    steps = 70
+    kn_all = synth.f32_to_words(rng.standard_normal((steps, wl.units, 128)).astype(np.float32) * 1.5, dtype)
+    vn_all = synth.f32_to_words(rng.standard_normal((steps, wl.units, 128)).astype(np.float32), dtype)
+    kn_d, vn_d = gu.to_dev(kn_all, dtype), gu.to_dev(vn_all, dtype)
+    for t in range(steps):
+        B.append_key(dw.cfg, dw.cache, kn_d[t], vn_d[t])
+        dw.seq_lens.add_(1)
+        oracle.append(K, V, L, kn_all[t], vn_all[t], bits, s, z, g, dtype)
+        L = (L + 1).astype(np.int32)
+    torch.cuda.synchronize()
+    _compare_packed(dw, L, bits, s, z, g)
+    bits_b, s_b, z_b = oracle.quantize(K, L, g, dtype, 4)
+    _compare_packed(dw, L, bits_b, s_b, z_b, g)
+    # ---- the fused step with one more append --------------------------------------------------------------------------
+    mb = int(wl.unit_budgets.max())
+    kn1 = synth.f32_to_words(rng.standard_normal((wl.units, 128)).astype(np.float32), dtype)
+    vn1 = synth.f32_to_words(rng.standard_normal((wl.units, 128)).astype(np.float32), dtype)
+    out = torch.zeros((1, wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+    B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), gu.to_dev(kn1, dtype)[None].contiguous(),
+                  gu.to_dev(vn1, dtype)[None].contiguous(), dw.budgets, mb, out, idx, cnt, dw.workspace(mb))
+    torch.cuda.synchronize()
+    oracle.append(K, V, L, kn1, vn1, bits, s, z, g, dtype)
+    L = (L + 1).astype(np.int32)
+    sc_o = oracle.score(bits, s, z, wl.q, L, g, dtype, 4)
+    idx_o, cnt_o = oracle.topk(sc_o, L, wl.unit_budgets, mb)
+    ig, cg = idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
+    check_index_sets(ig, cg, idx_o, cnt_o, sc_o, L)
+    want = oracle.attention(K, V, wl.q, L, 1.0 / np.sqrt(128.0), dtype, np.ascontiguousarray(np.where(ig < 0, 0, ig)),
+                            cg, 4)
+    assert np.abs(out.cpu().numpy()[0] - want).max() <= 2e-3
+    _compare_packed(dw, L, bits, s, z, g)
