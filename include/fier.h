@@ -169,6 +169,18 @@ int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n
                      float *out, int32_t *idx_out, int32_t *count_out, void *workspace, void *stream);
 
 /*
+ * The deployment policy of Sec. 4.1 (the method is not applied to the first two layers): as fier_decode_step,
+ * except that every layer l with dense_layers[l] != 0 (HOST array of n_layers bytes; NULL = no such layer) runs
+ * full attention over all seq_len (+ 1) rows after its append; its packed cache is still kept up to date.  For
+ * those layers idx_out and count_out are not written.  If any layer is dense the workspace must have
+ * fier_workspace_bytes(cfg, max_ctx) bytes.
+ */
+int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int32_t n_layers,
+                           const uint8_t *dense_layers, const void *q, const void *k_new, const void *v_new,
+                           const int32_t *budgets, int32_t max_budget, float *out, int32_t *idx_out,
+                           int32_t *count_out, void *workspace, void *stream);
+
+/*
  * One of the three kernels of fier_decode_step alone, for measurement: phase 1 = append + score + score
  * histogram, 2 = exact threshold, 3 = selection + attention over the selected rows + merge.  Same arguments
  * as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and these

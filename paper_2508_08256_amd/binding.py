@@ -19,7 +19,7 @@ EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = -1, -2, -3, -4, -5, -6
 
 SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_status_string",
            "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk",
-           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_phase", "fier_unpack_bits",
+           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_unpack_bits",
            "fier_unpack_meta"]
 
 
@@ -91,6 +91,8 @@ def lib():
         L.fier_dense_attn.argtypes = [cfgp, cachep, vp, i32, vp, vp, vp]
         L.fier_decode_step.restype = C.c_int
         L.fier_decode_step.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.fier_decode_step_mixed.restype = C.c_int
+        L.fier_decode_step_mixed.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         L.fier_decode_step_phase.restype = C.c_int
         L.fier_decode_step_phase.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp]
         L.fier_unpack_bits.restype = None
@@ -212,6 +214,16 @@ def decode_step(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, 
     _check(lib().fier_decode_step(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(budgets),
                                   int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out), _ptr(workspace),
                                   _stream()), "fier_decode_step")
+
+
+def decode_step_mixed(cfg: Config, caches, dense_layers, q, k_new, v_new, budgets, max_budget: int, out, idx_out,
+                      count_out, workspace):
+    """fier_decode_step with full attention on the layers flagged in dense_layers (a sequence of bools)."""
+    arr = (Cache * len(caches))(*[c.c for c in caches])
+    flags = (C.c_uint8 * len(caches))(*[1 if d else 0 for d in dense_layers])
+    _check(lib().fier_decode_step_mixed(C.byref(cfg), arr, len(caches), flags, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                        _ptr(budgets), int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
+                                        _ptr(workspace), _stream()), "fier_decode_step_mixed")
 
 
 def decode_step_phase(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, out, idx_out, count_out,

@@ -207,10 +207,10 @@ int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void*
                                       cfg->max_ctx, (hipStream_t)stream));
 }
 
-static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
-                            const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget,
-                            float* out, int32_t* idx_out, int32_t* count_out, void* workspace, int32_t phase,
-                            void* stream) {
+static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, int32_t n_layers,
+                            const uint8_t* dense_layers, const void* q, const void* k_new, const void* v_new,
+                            const int32_t* budgets, int32_t max_budget, float* out, int32_t* idx_out,
+                            int32_t* count_out, void* workspace, int32_t phase, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
   if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
@@ -237,9 +237,24 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
     int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : nullptr;
     int32_t* cntl = count_out ? count_out + (size_t)l * units : nullptr;
     hipError_t e;
+    const char* kn = extra ? static_cast<const char*>(k_new) + (size_t)l * units * kD * esz : nullptr;
+    const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
+    if (dense_layers && dense_layers[l]) {
+      // full attention for this layer: append (the packed cache stays up to date), then attend over every row
+      if (extra) {
+        e = fier::launch_append(cfg->kv_dtype, c->k, c->v, c->kbits, c->kmeta, c->kabsmax, c->seq_lens, kn, vn, units,
+                                cfg->n_kv_heads, cfg->max_ctx, cfg->group_size, s);
+        if (e != hipSuccess) return FIER_EHIP;
+      }
+      Workspace wd = carve(cfg, cfg->max_ctx, workspace);
+      const int n_splits = (cfg->max_ctx + fier::kAttnRowsDense - 1) / fier::kAttnRowsDense;
+      e = fier::launch_attn(cfg->kv_dtype, n_rep, c->k, c->v, ql, nullptr, nullptr, c->seq_lens, extra, cfg->max_ctx,
+                            fier::kAttnRowsDense, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, outl, units,
+                            cfg->n_kv_heads, cfg->max_ctx, s);
+      if (e != hipSuccess) return FIER_EHIP;
+      continue;
+    }
     if (phase == 0 || phase == 1) {
-      const char* kn = extra ? static_cast<const char*>(k_new) + (size_t)l * units * kD * esz : nullptr;
-      const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
       e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra,
                              w.sb.scores, &w.sb, budgets, max_budget, c->k, c->v, kn, vn, units, cfg->n_kv_heads,
                              cfg->max_ctx, cfg->group_size, s);
@@ -261,8 +276,16 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
 int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
                      const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget, float* out,
                      int32_t* idx_out, int32_t* count_out, void* workspace, void* stream) {
-  return decode_step_impl(cfg, layers, n_layers, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
+  return decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
                           workspace, 0, stream);
+}
+
+int fier_decode_step_mixed(const fier_config* cfg, const fier_cache* layers, int32_t n_layers,
+                           const uint8_t* dense_layers, const void* q, const void* k_new, const void* v_new,
+                           const int32_t* budgets, int32_t max_budget, float* out, int32_t* idx_out,
+                           int32_t* count_out, void* workspace, void* stream) {
+  return decode_step_impl(cfg, layers, n_layers, dense_layers, q, k_new, v_new, budgets, max_budget, out, idx_out,
+                          count_out, workspace, 0, stream);
 }
 
 int fier_decode_step_phase(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
@@ -270,7 +293,7 @@ int fier_decode_step_phase(const fier_config* cfg, const fier_cache* layers, int
                            float* out, int32_t* idx_out, int32_t* count_out, void* workspace, int32_t phase,
                            void* stream) {
   if (phase < 1) return FIER_EINVAL;
-  return decode_step_impl(cfg, layers, n_layers, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
+  return decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
                           workspace, phase, stream);
 }
 

@@ -661,3 +661,37 @@ def test_larger_quantization_groups(gu, oracle, g, dtype):
                             cg, 4)
     assert np.abs(out.cpu().numpy()[0] - want).max() <= 2e-3
     _compare_packed(dw, L, bits, s, z, g)
+
+
+def test_mixed_step_dense_first_layers(gu, oracle):
+    """Sec. 4.1 policy: the first layers attend over the whole cache, the others through the selection; one call."""
+    import gpu_util
+
+    wls = [synth.make_workload(f"mixed{l}", 300 + l, 2, 8, 2, [1500, 700], [160, 80], BF16, max_ctx=1536,
+                               n_planted=4, chan="lognormal") for l in range(4)]
+    dws = [gpu_util.DeviceWorkload(w) for w in wls]
+    for dw in dws:
+        B.quantize_keys(dw.cfg, dw.cache)
+    cfg = dws[0].cfg
+    q = torch.stack([dw.q.reshape(2, 8, 128) for dw in dws]).contiguous()
+    kn = torch.stack([dw.k_new for dw in dws]).contiguous()
+    vn = torch.stack([dw.v_new for dw in dws]).contiguous()
+    out = torch.zeros((4, 4, 4, 128), dtype=torch.float32, device="cuda")
+    idx = torch.full((4, 4, 160), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((4, 4), -1, dtype=torch.int32, device="cuda")
+    dense = [True, True, False, False]
+    B.decode_step_mixed(cfg, [dw.cache for dw in dws], dense, q, kn, vn, dws[0].budgets, 160, out, idx, cnt,
+                        B.make_workspace(cfg, cfg.max_ctx))
+    torch.cuda.synchronize()
+    for l, wl in enumerate(wls):
+        r = oracle_step(oracle, wl, append=True)
+        if dense[l]:
+            want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype, None, None, 2)
+            assert int(cnt[l].max()) == -1 and int(idx[l].max()) == -1      # not written for dense layers
+        else:
+            ig, cg = idx.cpu().numpy()[l], cnt.cpu().numpy()[l]
+            check_index_sets(ig, cg, r["idx"], r["count"], r["scores"], r["L"])
+            want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                                    np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 2)
+        assert np.abs(out.cpu().numpy()[l] - want).max() <= 2e-3, l
+        _compare_packed(dws[l], r["L"], r["bits"], r["s"], r["z"])       # also the dense layers' packed cache
