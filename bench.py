@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--budget", type=int, default=None, help="token budget (config4's sweep point)")
     ap.add_argument("--group-size", type=int, default=32, choices=[32, 64, 128, 256],
                     help="tokens per quantization group (32 is the paper's default; 128 / 256 are its ablation)")
+    ap.add_argument("--dense-first", type=int, default=0,
+                    help="run full attention on the first N layers of every step (the paper's deployment leaves the "
+                         "first two layers dense); only the step time changes")
     ap.add_argument("--loop-steps", type=int, default=0,
                     help="instead of the default measurement: this many consecutive token steps (append, growing "
                          "context) over all the workload's layer caches in one call per token, eager and as one graph")
@@ -162,9 +165,18 @@ def main():
     cnt = torch.zeros((NL, units), dtype=torch.int32, device="cuda")
     scores = torch.zeros((units, max_ctx), dtype=torch.float32, device="cuda")
 
+    if args.dense_first > 0:
+        w["label"] += f"_dense{args.dense_first}"
+        ws_mixed = B.make_workspace(cfg, max_ctx)
+        dense_flags = [l < args.dense_first for l in range(NL)]
+
     def step(i):
         r = i % R
-        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0][0])
+        if args.dense_first > 0:
+            B.decode_step_mixed(cfg, caches[r], dense_flags, qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt,
+                                ws_mixed)
+        else:
+            B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0][0])
 
     def timed(fn, n, warm):
         for i in range(warm):
