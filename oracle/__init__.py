@@ -57,6 +57,14 @@ def lib():
         L.fier_oracle_score.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, i32]
         L.fier_oracle_topk.restype = None
         L.fier_oracle_topk.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp]
+        L.fier_oracle_page_minmax.restype = None
+        L.fier_oracle_page_minmax.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.fier_oracle_page_score.restype = None
+        L.fier_oracle_page_score.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, vp]
+        L.fier_oracle_page_mean.restype = None
+        L.fier_oracle_page_mean.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.fier_oracle_expand_pages.restype = None
+        L.fier_oracle_expand_pages.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp, vp]
         L.fier_oracle_attention.restype = None
         L.fier_oracle_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f64, vp, vp, vp,
                                             i32, vp, i32]
@@ -160,6 +168,54 @@ def topk(scores, L, budget, max_budget: int):
     count = np.zeros((U,), np.int32)
     lib().fier_oracle_topk(_p(scores), U, Lcap, _p(L), _p(budget), max_budget, _p(idx), _p(count))
     return idx, count
+
+
+def page_minmax(K, L, page: int, dtype: int):
+    """Channel-wise min / max key vectors of every page (raw 16-bit words): [U][Lcap/page][D] each."""
+    U, Lcap, D = K.shape
+    _chk(K, np.uint16)
+    _chk(L, np.int32, (U,))
+    assert Lcap % page == 0
+    kmin = np.zeros((U, Lcap // page, D), np.uint16)
+    kmax = np.zeros_like(kmin)
+    lib().fier_oracle_page_minmax(_p(K), U, Lcap, D, page, dtype, _p(L), _p(kmin), _p(kmax))
+    return kmin, kmax
+
+
+def page_score(kmin, kmax, q, L, page: int, dtype: int, mode: int) -> np.ndarray:
+    """Page importance of Eq. 1-3 (mode 0: max over channels as printed; mode 1: sum over channels)."""
+    U, NP, D = kmin.shape
+    _chk(kmin, np.uint16)
+    _chk(kmax, np.uint16, (U, NP, D))
+    _chk(q, np.uint16)
+    _chk(L, np.int32, (U,))
+    n_rep = q.shape[1]
+    assert q.shape == (U, n_rep, D)
+    out = np.zeros((U, NP), np.float64)
+    lib().fier_oracle_page_score(_p(kmin), _p(kmax), _p(q), U, n_rep, NP * page, D, page, dtype, _p(L), mode, _p(out))
+    return out
+
+
+def page_mean(scores, L, page: int) -> np.ndarray:
+    """Average token score per page over the tokens present."""
+    U, Lcap = scores.shape
+    _chk(scores, np.float64)
+    _chk(L, np.int32, (U,))
+    out = np.zeros((U, Lcap // page), np.float64)
+    lib().fier_oracle_page_mean(_p(scores), U, Lcap, page, _p(L), _p(out))
+    return out
+
+
+def expand_pages(page_idx, page_cnt, L, page: int, max_budget: int):
+    """Tokens of the selected pages, ascending, clipped to the lengths: (idx [U][max_budget], cnt [U])."""
+    U, max_pages = page_idx.shape
+    _chk(page_idx, np.int32)
+    _chk(page_cnt, np.int32, (U,))
+    _chk(L, np.int32, (U,))
+    idx = np.full((U, max_budget), -1, np.int32)
+    cnt = np.zeros(U, np.int32)
+    lib().fier_oracle_expand_pages(_p(page_idx), _p(page_cnt), U, max_pages, page, _p(L), max_budget, _p(idx), _p(cnt))
+    return idx, cnt
 
 
 def attention(K, V, q, L, sm_scale: float, dtype: int, idx=None, count=None, n_threads: int = 1):

@@ -27,6 +27,9 @@
  * for the score, brute-force top-k, scipy softmax for full-budget attention,
  * planted-token recall (Observation 2).  The paper prints no numeric example
  * of scores or outputs, so end-to-end values are pinned only through those.
+ * The page-level functions at the end (the comparison baseline of Sec. 3.2)
+ * are pinned by single-token pages (library max / dot), the upper-bound
+ * property, numpy means and brute force (tests/test_oracle_pages.py).
  *
  * Build: gcc -O2 -std=c99 -ffp-contract=off -fopenmp -shared -fPIC
  */
@@ -388,6 +391,121 @@ void fier_oracle_attention(const uint16_t *K, const uint16_t *V,
         free(logit);
     }
     (void)n_threads;
+}
+
+/* ------------------------------------------------------------------------
+ * Page-level importance (the page-retrieval baseline the paper compares with,
+ * Sec. 3.2 Eq. 1-3, and its "averaged quantized score" ablation, Sec. 4.4).
+ *
+ * A page = `page` consecutive tokens of one unit.  Its metadata are the
+ * channel-wise maximum and minimum key vectors over the tokens present
+ * (input values, hence exact 16-bit words).
+ * ---------------------------------------------------------------------- */
+void fier_oracle_page_minmax(const uint16_t *K, int n_units, int Lcap, int D,
+                             int page, int dtype, const int32_t *L,
+                             uint16_t *kmin, uint16_t *kmax)
+{
+    int n_pages = Lcap / page;
+    for (int u = 0; u < n_units; ++u)
+        for (int p = 0; p < n_pages; ++p)
+            for (int c = 0; c < D; ++c) {
+                size_t o = ((size_t)u * n_pages + p) * D + c;
+                int t0 = p * page;
+                kmin[o] = 0;
+                kmax[o] = 0;
+                if (t0 >= L[u])
+                    continue;
+                int t1 = t0 + page < L[u] ? t0 + page : L[u];
+                uint16_t wmin = K[((size_t)u * Lcap + t0) * D + c], wmax = wmin;
+                for (int t = t0 + 1; t < t1; ++t) {
+                    uint16_t w = K[((size_t)u * Lcap + t) * D + c];
+                    if (load16(w, dtype) < load16(wmin, dtype)) wmin = w;
+                    if (load16(w, dtype) > load16(wmax, dtype)) wmax = w;
+                }
+                kmin[o] = wmin;
+                kmax[o] = wmax;
+            }
+}
+
+/* Eq. 1-3: alpha_max = q (.) k_max, alpha_min = q (.) k_min, elementwise;
+ * mode 0: s_P = max over the channels of max(alpha_max_i, alpha_min_i), the
+ *         formula as the paper prints it (Eq. 3);
+ * mode 1: s_P = sum over the channels of max(alpha_max_i, alpha_min_i), the
+ *         channel-wise upper bound of q . k for every key of the page.
+ * With several query heads per kv head the per-head page scores are added
+ * (same convention as the token scores).  Pages without tokens get -inf.   */
+void fier_oracle_page_score(const uint16_t *kmin, const uint16_t *kmax,
+                            const uint16_t *q, int n_units, int n_rep,
+                            int Lcap, int D, int page, int dtype,
+                            const int32_t *L, int mode, double *out)
+{
+    int n_pages = Lcap / page;
+    for (int u = 0; u < n_units; ++u)
+        for (int p = 0; p < n_pages; ++p) {
+            double total = 0.0;
+            if (p * page >= L[u]) {
+                out[(size_t)u * n_pages + p] = -INFINITY;
+                continue;
+            }
+            for (int h = 0; h < n_rep; ++h) {
+                double acc = mode == 0 ? -INFINITY : 0.0;
+                for (int c = 0; c < D; ++c) {
+                    size_t o = ((size_t)u * n_pages + p) * D + c;
+                    double qc = load16(q[((size_t)u * n_rep + h) * D + c], dtype);
+                    double a_max = qc * (double)load16(kmax[o], dtype);
+                    double a_min = qc * (double)load16(kmin[o], dtype);
+                    double m = a_max > a_min ? a_max : a_min;
+                    if (mode == 0)
+                        acc = m > acc ? m : acc;
+                    else
+                        acc += m;
+                }
+                total += acc;
+            }
+            out[(size_t)u * n_pages + p] = total;
+        }
+}
+
+/* Sec. 4.4 ablation: the page metric is the average of the (1-bit) token
+ * scores over the tokens present in the page.  Empty pages get -inf.      */
+void fier_oracle_page_mean(const double *scores, int n_units, int Lcap,
+                           int page, const int32_t *L, double *out)
+{
+    int n_pages = Lcap / page;
+    for (int u = 0; u < n_units; ++u)
+        for (int p = 0; p < n_pages; ++p) {
+            int t0 = p * page;
+            if (t0 >= L[u]) {
+                out[(size_t)u * n_pages + p] = -INFINITY;
+                continue;
+            }
+            int t1 = t0 + page < L[u] ? t0 + page : L[u];
+            double acc = 0.0;
+            for (int t = t0; t < t1; ++t)
+                acc += scores[(size_t)u * Lcap + t];
+            out[(size_t)u * n_pages + p] = acc / (double)(t1 - t0);
+        }
+}
+
+/* All tokens of the selected pages (page_idx ascending, page_cnt of them), in
+ * ascending order, clipped to the unit's length.                           */
+void fier_oracle_expand_pages(const int32_t *page_idx, const int32_t *page_cnt,
+                              int n_units, int max_pages, int page,
+                              const int32_t *L, int max_budget, int32_t *idx,
+                              int32_t *cnt)
+{
+    for (int u = 0; u < n_units; ++u) {
+        int n = 0;
+        for (int k = 0; k < page_cnt[u]; ++k) {
+            int p = page_idx[(size_t)u * max_pages + k];
+            for (int j = 0; j < page; ++j) {
+                int t = p * page + j;
+                if (t < L[u] && n < max_budget)
+                    idx[(size_t)u * max_budget + n++] = t;
+            }
+        }
+        cnt[u] = n;
+    }
 }
 
 int fier_oracle_max_threads(void)
