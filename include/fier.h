@@ -193,6 +193,38 @@ int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int
                            float *out, int32_t *idx_out, int32_t *count_out, void *workspace, int32_t phase,
                            void *stream);
 
+/*
+ * Page-level importance, the page-retrieval baseline the paper compares with (Sec. 3.2, Eq. 1-3) and the
+ * "averaged quantized score per page" ablation of Sec. 4.4: a second workload for fier_topk and fier_sparse_attn.
+ * A page = page_tokens (8, 16 or 32) consecutive tokens of a unit.
+ *   page_meta [units][max_ctx / page_tokens][D] uint32, device: channel-wise minimum (low half) and maximum (high
+ *   half) key of the page over the tokens present, in the K dtype; fier_page_meta_bytes bytes (512 per page: the
+ *   load ratio 2 / page_tokens of the paper).
+ * fier_page_minmax builds it from the K rows [0, seq_len); fier_page_append folds the row k_new
+ * ([batch][n_kv_heads][D]) written at position seq_len into its page (call it next to fier_append_key).
+ * fier_page_score: page_scores [units][max_ctx / page_tokens] float.  mode 0: max over the channels of
+ * max(q_i kmax_i, q_i kmin_i), Eq. 3 as printed (exact); mode 1: the sum over the channels instead, an upper bound
+ * of q . k for every key of the page.  Per-head page scores of the query heads of a kv head are added.  Pages without
+ * tokens get -inf.
+ * fier_page_mean_score: page score = average of the token scores (fier_score's output) over the page's tokens.
+ * Selection: call fier_topk on page_scores with a fier_config whose max_ctx is max_ctx / page_tokens (a multiple of 64)
+ * and a device array of page counts ceil(seq_len / page_tokens) as its seq_lens.
+ * fier_expand_pages: idx [units][max_budget] = the tokens of the selected pages (page_idx [units][max_pages] ascending,
+ * page_count [units]) in ascending order, clipped to seq_len + extra_tokens; count [units] = how many.
+ */
+size_t fier_page_meta_bytes(const fier_config *cfg, int32_t page_tokens);
+int fier_page_minmax(const fier_config *cfg, const fier_cache *cache, int32_t page_tokens, uint32_t *page_meta,
+                     void *stream);
+int fier_page_append(const fier_config *cfg, const int32_t *seq_lens, int32_t page_tokens, const void *k_new,
+                     uint32_t *page_meta, void *stream);
+int fier_page_score(const fier_config *cfg, const uint32_t *page_meta, int32_t page_tokens, const int32_t *seq_lens,
+                    int32_t extra_tokens, const void *q, int32_t mode, float *page_scores, void *stream);
+int fier_page_mean_score(const fier_config *cfg, const float *scores, const int32_t *seq_lens, int32_t extra_tokens,
+                         int32_t page_tokens, float *page_scores, void *stream);
+int fier_expand_pages(const fier_config *cfg, const int32_t *page_idx, const int32_t *page_count, int32_t max_pages,
+                      const int32_t *seq_lens, int32_t extra_tokens, int32_t page_tokens, int32_t *idx, int32_t *count,
+                      int32_t max_budget, void *stream);
+
 /* Host helpers for inspection: physical packed layout -> logical arrays, all host memory.
  * bits [units][max_ctx][D] one byte (0/1) per element; s, z [units][max_ctx/32][D] raw 16-bit words. */
 void fier_unpack_bits(const fier_config *cfg, const uint32_t *kbits_host, uint8_t *bits_host);

@@ -19,7 +19,8 @@ EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = -1, -2, -3, -4, -5, -6
 
 SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_status_string",
            "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk",
-           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_unpack_bits",
+           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_page_meta_bytes",
+           "fier_page_minmax", "fier_page_append", "fier_page_score", "fier_page_mean_score", "fier_expand_pages", "fier_unpack_bits",
            "fier_unpack_meta"]
 
 
@@ -91,6 +92,18 @@ def lib():
         L.fier_dense_attn.argtypes = [cfgp, cachep, vp, i32, vp, vp, vp]
         L.fier_decode_step.restype = C.c_int
         L.fier_decode_step.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.fier_page_meta_bytes.restype = C.c_size_t
+        L.fier_page_meta_bytes.argtypes = [cfgp, i32]
+        L.fier_page_minmax.restype = C.c_int
+        L.fier_page_minmax.argtypes = [cfgp, cachep, i32, vp, vp]
+        L.fier_page_append.restype = C.c_int
+        L.fier_page_append.argtypes = [cfgp, vp, i32, vp, vp, vp]
+        L.fier_page_score.restype = C.c_int
+        L.fier_page_score.argtypes = [cfgp, vp, i32, vp, i32, vp, i32, vp, vp]
+        L.fier_page_mean_score.restype = C.c_int
+        L.fier_page_mean_score.argtypes = [cfgp, vp, vp, i32, i32, vp, vp]
+        L.fier_expand_pages.restype = C.c_int
+        L.fier_expand_pages.argtypes = [cfgp, vp, vp, i32, vp, i32, i32, vp, vp, i32, vp]
         L.fier_decode_step_mixed.restype = C.c_int
         L.fier_decode_step_mixed.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         L.fier_decode_step_phase.restype = C.c_int
@@ -214,6 +227,37 @@ def decode_step(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, 
     _check(lib().fier_decode_step(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(budgets),
                                   int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out), _ptr(workspace),
                                   _stream()), "fier_decode_step")
+
+
+def page_meta_bytes(cfg: Config, page_tokens: int) -> int:
+    return int(lib().fier_page_meta_bytes(C.byref(cfg), int(page_tokens)))
+
+
+def page_minmax(cfg: Config, cache: DeviceCache, page_tokens: int, page_meta):
+    _check(lib().fier_page_minmax(C.byref(cfg), C.byref(cache.c), int(page_tokens), _ptr(page_meta), _stream()),
+           "fier_page_minmax")
+
+
+def page_append(cfg: Config, seq_lens, page_tokens: int, k_new, page_meta):
+    _check(lib().fier_page_append(C.byref(cfg), _ptr(seq_lens), int(page_tokens), _ptr(k_new), _ptr(page_meta),
+                                  _stream()), "fier_page_append")
+
+
+def page_score(cfg: Config, page_meta, page_tokens: int, seq_lens, extra_tokens: int, q, mode: int, page_scores):
+    _check(lib().fier_page_score(C.byref(cfg), _ptr(page_meta), int(page_tokens), _ptr(seq_lens), int(extra_tokens),
+                                 _ptr(q), int(mode), _ptr(page_scores), _stream()), "fier_page_score")
+
+
+def page_mean_score(cfg: Config, scores, seq_lens, extra_tokens: int, page_tokens: int, page_scores):
+    _check(lib().fier_page_mean_score(C.byref(cfg), _ptr(scores), _ptr(seq_lens), int(extra_tokens), int(page_tokens),
+                                      _ptr(page_scores), _stream()), "fier_page_mean_score")
+
+
+def expand_pages(cfg: Config, page_idx, page_count, max_pages: int, seq_lens, extra_tokens: int, page_tokens: int,
+                 idx, count, max_budget: int):
+    _check(lib().fier_expand_pages(C.byref(cfg), _ptr(page_idx), _ptr(page_count), int(max_pages), _ptr(seq_lens),
+                                   int(extra_tokens), int(page_tokens), _ptr(idx), _ptr(count), int(max_budget),
+                                   _stream()), "fier_expand_pages")
 
 
 def decode_step_mixed(cfg: Config, caches, dense_layers, q, k_new, v_new, budgets, max_budget: int, out, idx_out,

@@ -297,6 +297,74 @@ int fier_decode_step_phase(const fier_config* cfg, const fier_cache* layers, int
                           workspace, phase, stream);
 }
 
+// ---- page-level importance ------------------------------------------------------------------------------------------
+static int check_page(const fier_config* cfg, int32_t page_tokens) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  if (page_tokens != 8 && page_tokens != 16 && page_tokens != 32) return FIER_EUNSUPPORTED;
+  return FIER_OK;  // max_ctx is a multiple of 64, hence of the page size
+}
+
+size_t fier_page_meta_bytes(const fier_config* cfg, int32_t page_tokens) {
+  if (check_page(cfg, page_tokens) != FIER_OK) return 0;
+  return (size_t)units_of(cfg) * (size_t)(cfg->max_ctx / page_tokens) * kD * sizeof(uint32_t);
+}
+
+int fier_page_minmax(const fier_config* cfg, const fier_cache* cache, int32_t page_tokens, uint32_t* page_meta,
+                     void* stream) {
+  int st = check_page(cfg, page_tokens);
+  if (st != FIER_OK) return st;
+  if (!cache || !cache->k || !cache->seq_lens || !page_meta) return FIER_EINVAL;
+  if (misaligned(cache->k) || misaligned(page_meta)) return FIER_EALIGN;
+  return hip_status(fier::launch_page_minmax(cfg->kv_dtype, cache->k, cache->seq_lens, page_meta, units_of(cfg),
+                                             cfg->n_kv_heads, cfg->max_ctx, page_tokens, (hipStream_t)stream));
+}
+
+int fier_page_append(const fier_config* cfg, const int32_t* seq_lens, int32_t page_tokens, const void* k_new,
+                     uint32_t* page_meta, void* stream) {
+  int st = check_page(cfg, page_tokens);
+  if (st != FIER_OK) return st;
+  if (!seq_lens || !k_new || !page_meta) return FIER_EINVAL;
+  if (misaligned(k_new) || misaligned(page_meta)) return FIER_EALIGN;
+  return hip_status(fier::launch_page_append(cfg->kv_dtype, k_new, seq_lens, page_meta, units_of(cfg),
+                                             cfg->n_kv_heads, cfg->max_ctx, page_tokens, (hipStream_t)stream));
+}
+
+int fier_page_score(const fier_config* cfg, const uint32_t* page_meta, int32_t page_tokens, const int32_t* seq_lens,
+                    int32_t extra_tokens, const void* q, int32_t mode, float* page_scores, void* stream) {
+  int st = check_page(cfg, page_tokens);
+  if (st != FIER_OK) return st;
+  if (!page_meta || !seq_lens || !q || !page_scores || extra_tokens < 0 || extra_tokens > 1 || mode < 0 || mode > 1)
+    return FIER_EINVAL;
+  if (misaligned(page_meta) || misaligned(q) || misaligned(page_scores)) return FIER_EALIGN;
+  return hip_status(fier::launch_page_score(cfg->kv_dtype, n_rep_of(cfg), page_meta, q, seq_lens, extra_tokens, mode,
+                                            page_scores, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx, page_tokens,
+                                            (hipStream_t)stream));
+}
+
+int fier_page_mean_score(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
+                         int32_t page_tokens, float* page_scores, void* stream) {
+  int st = check_page(cfg, page_tokens);
+  if (st != FIER_OK) return st;
+  if (!scores || !seq_lens || !page_scores || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
+  if (misaligned(scores) || misaligned(page_scores)) return FIER_EALIGN;
+  return hip_status(fier::launch_page_mean(scores, seq_lens, extra_tokens, page_scores, units_of(cfg),
+                                           cfg->n_kv_heads, cfg->max_ctx, page_tokens, (hipStream_t)stream));
+}
+
+int fier_expand_pages(const fier_config* cfg, const int32_t* page_idx, const int32_t* page_count, int32_t max_pages,
+                      const int32_t* seq_lens, int32_t extra_tokens, int32_t page_tokens, int32_t* idx,
+                      int32_t* count, int32_t max_budget, void* stream) {
+  int st = check_page(cfg, page_tokens);
+  if (st != FIER_OK) return st;
+  if (!page_idx || !page_count || !seq_lens || !idx || !count || max_pages <= 0 || max_budget <= 0 ||
+      extra_tokens < 0 || extra_tokens > 1)
+    return FIER_EINVAL;
+  return hip_status(fier::launch_expand_pages(page_idx, page_count, max_pages, seq_lens, extra_tokens, page_tokens,
+                                              idx, count, max_budget, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
+                                              (hipStream_t)stream));
+}
+
 void fier_unpack_bits(const fier_config* cfg, const uint32_t* kbits_host, uint8_t* bits_host) {
   if (check_cfg(cfg) != FIER_OK || !kbits_host || !bits_host) return;
   const size_t n_tok = (size_t)units_of(cfg) * (size_t)cfg->max_ctx;

@@ -86,4 +86,18 @@ hipError_t launch_attn(int dtype, int n_rep, const void* K, const void* V, const
                        int n_splits, float sm_scale, float* po, float* pm, float* pl, float* out, int units,
                        int n_kv_heads, int max_ctx, hipStream_t st);
 
+// ---- page-level importance (comparison workload) -------------------------------------------------------------------
+hipError_t launch_page_minmax(int dtype, const void* K, const int32_t* seq_lens, uint32_t* page_meta, int units,
+                              int n_kv_heads, int max_ctx, int P, hipStream_t st);
+hipError_t launch_page_append(int dtype, const void* k_new, const int32_t* seq_lens, uint32_t* page_meta, int units,
+                              int n_kv_heads, int max_ctx, int P, hipStream_t st);
+hipError_t launch_page_score(int dtype, int n_rep, const uint32_t* page_meta, const void* q, const int32_t* seq_lens,
+                             int extra, int mode, float* out, int units, int n_kv_heads, int max_ctx, int P,
+                             hipStream_t st);
+hipError_t launch_page_mean(const float* scores, const int32_t* seq_lens, int extra, float* out, int units,
+                            int n_kv_heads, int max_ctx, int P, hipStream_t st);
+hipError_t launch_expand_pages(const int32_t* page_idx, const int32_t* page_count, int max_pages,
+                               const int32_t* seq_lens, int extra, int P, int32_t* idx, int32_t* count,
+                               int max_budget, int units, int n_kv_heads, int max_ctx, hipStream_t st);
+
 }  // namespace fier
