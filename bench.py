@@ -80,6 +80,11 @@ def main():
     ap.add_argument("--budget", type=int, default=None, help="token budget (config4's sweep point)")
     ap.add_argument("--group-size", type=int, default=32, choices=[32, 64, 128, 256],
                     help="tokens per quantization group (32 is the paper's default; 128 / 256 are its ablation)")
+    ap.add_argument("--selector", default="fier", choices=["fier", "quest", "quant-page"],
+                    help="what picks the tokens: fier = the fused 1-bit token-level step (default); quest = page min/max "
+                         "scores (Eq. 1-3, pages of 16 tokens), top pages, their tokens; quant-page = the same with the "
+                         "averaged 1-bit score per page as the page metric (Sec. 4.4 ablation).  The page selectors run "
+                         "as separate calls: append, page score, fier_topk over pages, expansion, fier_sparse_attn")
     ap.add_argument("--dense-first", type=int, default=0,
                     help="run full attention on the first N layers of every step (the paper's deployment leaves the "
                          "first two layers dense); only the step time changes")
@@ -116,7 +121,7 @@ def main():
     batch, Hq, Hkv, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["dtype"]
     lens, buds = shape_of(w, 5000)
     L, budget = int(lens.max()), int(buds.max())   # the largest context and budget (all of them when not ragged)
-    gran = max(64, args.group_size)
+    gran = max(64, args.group_size) if args.selector == "fier" else 1024
     max_ctx = -(-(L + 1 + max(0, args.loop_steps)) // gran) * gran
     cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype, group_size=args.group_size)
     units, n_rep = cfg.units, cfg.n_rep
@@ -170,9 +175,46 @@ def main():
         ws_mixed = B.make_workspace(cfg, max_ctx)
         dense_flags = [l < args.dense_first for l in range(NL)]
 
+    if args.selector != "fier":
+        assert NL == 1 and w["L"] != "ragged", "the page selectors are benchmarked on single-layer, fixed-length workloads"
+        PG = 16
+        w["label"] += f"_{args.selector}_p{PG}"
+        n_pages = max_ctx // PG
+        assert n_pages % 64 == 0, "context capacity must be a multiple of 1024 for the page-level top-k"
+        pcfg = B.make_config(batch, Hq, Hkv, n_pages, dtype)
+        metas = []
+        for r in range(R):
+            m = torch.zeros(B.page_meta_bytes(cfg, PG) // 4, dtype=torch.int32, device="cuda")
+            B.page_minmax(cfg, caches[r][0], PG, m)
+            metas.append(m)
+        max_pages = max(1, budget // PG)
+        page_budgets = torch.full((batch,), max_pages, dtype=torch.int32, device="cuda")
+        page_lens = torch.full((batch,), -(-(L + 1) // PG), dtype=torch.int32, device="cuda")
+        pscores = torch.zeros((units, n_pages), dtype=torch.float32, device="cuda")
+        pidx = torch.zeros((units, max_pages), dtype=torch.int32, device="cuda")
+        pcnt = torch.zeros((units,), dtype=torch.int32, device="cuda")
+        tidx = torch.zeros((units, budget), dtype=torch.int32, device="cuda")
+        tcnt = torch.zeros((units,), dtype=torch.int32, device="cuda")
+
+    def page_step(i):
+        r = i % R
+        c = caches[r][0]
+        B.append_key(cfg, c, kns[r][0], vns[r][0])                  # K/V rows + 1-bit cache (quant-page needs it)
+        if args.selector == "quest":
+            B.page_append(cfg, seq_lens, PG, kns[r][0], metas[r])
+            B.page_score(cfg, metas[r], PG, seq_lens, 1, qs[r][0], 0, pscores)
+        else:
+            B.score(cfg, c, qs[r][0], 1, scores)
+            B.page_mean_score(cfg, scores, seq_lens, 1, PG, pscores)
+        B.topk(pcfg, pscores, page_lens, 0, page_budgets, max_pages, pidx, pcnt)
+        B.expand_pages(cfg, pidx, pcnt, max_pages, seq_lens, 1, PG, tidx, tcnt, budget)
+        B.sparse_attn(cfg, c, qs[r][0], tidx, tcnt, budget, out1, wss[0][0])
+
     def step(i):
         r = i % R
-        if args.dense_first > 0:
+        if args.selector != "fier":
+            page_step(i)
+        elif args.dense_first > 0:
             B.decode_step_mixed(cfg, caches[r], dense_flags, qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt,
                                 ws_mixed)
         else:
@@ -284,6 +326,29 @@ def main():
     us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
     us_attn, _ = timed(st_attn, max(24, ns // 4), 4)
 
+    stages = None
+    if args.selector != "fier":
+        def st_est(i):
+            r = i % R
+            if args.selector == "quest":
+                B.page_append(cfg, seq_lens, PG, kns[r][0], metas[r])
+                B.page_score(cfg, metas[r], PG, seq_lens, 1, qs[r][0], 0, pscores)
+            else:
+                B.score(cfg, caches[r][0], qs[r][0], 1, scores)
+                B.page_mean_score(cfg, scores, seq_lens, 1, PG, pscores)
+
+        def st_recall(i):
+            B.topk(pcfg, pscores, page_lens, 0, page_budgets, max_pages, pidx, pcnt)
+            B.expand_pages(cfg, pidx, pcnt, max_pages, seq_lens, 1, PG, tidx, tcnt, budget)
+
+        def st_pattn(i):
+            r = i % R
+            B.sparse_attn(cfg, caches[r][0], qs[r][0], tidx, tcnt, budget, out1, wss[0][0])
+
+        stages = {"importance_estimation": round(timed(st_est, ns, 4)[0], 3),
+                  "topk_recall": round(timed(st_recall, ns, 4)[0], 3),
+                  "topk_self_attention": round(timed(st_pattn, ns, 4)[0], 3)}
+
     if args.pmc_calibration:
         a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         bq = torch.empty_like(a)
@@ -348,6 +413,11 @@ def main():
                      "bytes_per_launch": k3_bytes, "us_per_launch": round(us_k3 / NL, 3)},
         "setup_s": round(t_setup, 1),
     }
+    if stages is not None:
+        res["selector"] = args.selector
+        res["selector_stages_us"] = stages      # the unfused page-level pipeline, stage by stage (cf. Tab. 6)
+        for k in ("kernels_us", "kernel_GBps", "roofline"):
+            res[k] = None                       # those describe the fused token-level step, not this pipeline
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(hosts, w, lens, buds)
