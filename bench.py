@@ -7,7 +7,8 @@ selected rows -- issued as ONE call of ``fier_decode_step`` on one layer's cache
 over R distinct layer caches (R x touched bytes >= 1 GB) so that the 256 MB Infinity Cache cannot hold the
 working set; all inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line (see the design doc for the byte model).
+Prints ONE JSON line.  Byte model: 16 + 512/g bytes of packed keys and (s, z) per cached token and unit, 512 bytes
+per selected token and unit (its K and V rows), 768 bytes per query head (q in, fp32 output out).
 """
 from __future__ import annotations
 
