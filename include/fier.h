@@ -77,13 +77,23 @@ typedef struct fier_config {
 } fier_config;
 
 typedef struct fier_cache { /* one layer; all pointers device, caller-owned */
-  void *k;
-  void *v;
+  void *k; /* block_table == NULL: [units][max_ctx][head_dim], unit = sequence * n_kv_heads + kv head.      */
+  void *v; /* block_table != NULL: a pool [pool blocks][n_kv_heads][block_tokens][head_dim]                 */
   uint32_t *kbits;         /* fier_packed_bits_bytes(cfg) bytes */
   uint32_t *kmeta;         /* fier_packed_meta_bytes(cfg) bytes */
   float *kabsmax;          /* [units][D]: per channel, an upper bound of |dequantized key| over the
                               tokens quantized so far; written by fier_quantize_keys, raised by appends */
   const int32_t *seq_lens; /* [batch] */
+  /* Paged K / V rows (optional).  block_table is [batch][max_ctx / block_tokens]: entry j of sequence b is
+   * the pool block that holds its tokens [j * block_tokens, (j + 1) * block_tokens), for all kv heads.
+   * Entries that cover tokens < seq_len (+ the appended one) must be valid pool block numbers: the kernels
+   * cannot check them; later entries are never read.  k and v share the table.  block_tokens is a power of
+   * two >= max(64, group_size) that divides max_ctx, else FIER_ESHAPE; NULL with block_tokens = 0 selects
+   * the contiguous layout (block_tokens != 0 with a NULL table: FIER_EINVAL).  The packed 1-bit cache
+   * (kbits, kmeta, kabsmax), the scores and every index are per unit and contiguous in both layouts, so
+   * results are bit-identical whichever layout holds the rows. */
+  const int32_t *block_table;
+  int32_t block_tokens;
 } fier_cache;
 
 /* Sizes (host only, no GPU needed).  0 if cfg is invalid. */

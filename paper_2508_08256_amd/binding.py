@@ -46,7 +46,8 @@ class Config(C.Structure):
 
 class Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("kbits", C.c_void_p), ("kmeta", C.c_void_p),
-                ("kabsmax", C.c_void_p), ("seq_lens", C.c_void_p)]
+                ("kabsmax", C.c_void_p), ("seq_lens", C.c_void_p), ("block_table", C.c_void_p),
+                ("block_tokens", C.c_int32)]
 
 
 def make_config(batch, n_q_heads, n_kv_heads, max_ctx, kv_dtype=F16, head_dim=128, group_size=32, sm_scale=None):
@@ -161,21 +162,32 @@ def check_config(cfg: Config) -> int:
 
 
 class DeviceCache:
-    """One layer's buffers on the GPU.  k, v: [units][max_ctx][128] 16-bit tensors; seq_lens [batch] int32."""
+    """One layer's buffers on the GPU.  k, v: [units][max_ctx][128] 16-bit tensors; seq_lens [batch] int32.
+    With block_table ([batch][max_ctx / block_tokens] int32), k and v are block pools
+    [pool blocks][n_kv_heads][block_tokens][128] instead."""
 
-    def __init__(self, cfg: Config, k, v, seq_lens):
+    def __init__(self, cfg: Config, k, v, seq_lens, block_table=None):
         import torch
 
         self.cfg = cfg
-        self.k, self.v, self.seq_lens = k, v, seq_lens
-        assert k.is_cuda and k.is_contiguous() and v.is_contiguous()
-        assert k.element_size() == 2 and tuple(k.shape) == (cfg.units, cfg.max_ctx, cfg.head_dim), k.shape
+        self.k, self.v, self.seq_lens, self.block_table = k, v, seq_lens, block_table
+        assert k.is_cuda and k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        assert k.element_size() == 2
+        block_tokens = 0
+        if block_table is None:
+            assert tuple(k.shape) == (cfg.units, cfg.max_ctx, cfg.head_dim), k.shape
+        else:
+            assert k.dim() == 4 and k.shape[1] == cfg.n_kv_heads and k.shape[3] == cfg.head_dim, k.shape
+            block_tokens = int(k.shape[2])
+            assert block_table.is_cuda and block_table.dtype == torch.int32 and block_table.is_contiguous()
+            assert tuple(block_table.shape) == (cfg.batch, cfg.max_ctx // block_tokens), block_table.shape
         assert seq_lens.dtype == torch.int32 and seq_lens.numel() == cfg.batch
         self.kbits = torch.zeros(packed_bits_bytes(cfg) // 4, dtype=torch.int32, device=k.device)
         self.kmeta = torch.zeros(packed_meta_bytes(cfg) // 4, dtype=torch.int32, device=k.device)
         self.kabsmax = torch.zeros(cfg.units * cfg.head_dim, dtype=torch.float32, device=k.device)
         self.c = Cache(k.data_ptr(), v.data_ptr(), self.kbits.data_ptr(), self.kmeta.data_ptr(),
-                       self.kabsmax.data_ptr(), seq_lens.data_ptr())
+                       self.kabsmax.data_ptr(), seq_lens.data_ptr(),
+                       block_table.data_ptr() if block_table is not None else None, block_tokens)
 
     def unpack(self):
         """Logical view of the packed state on the host: bits [units][max_ctx][D] u8, s, z [units][groups][D] u16."""

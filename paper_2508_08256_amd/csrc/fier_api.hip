@@ -31,12 +31,37 @@ int check_cfg(const fier_config* c) {
   return FIER_OK;
 }
 
-int check_cache(const fier_cache* k) {
+// Block-table fields of a cache: absent (contiguous rows), or a power-of-two block size that holds whole pair
+// blocks, quantization groups and pages and divides the row capacity.
+int check_blocks(const fier_config* c, const fier_cache* k) {
+  if (!k->block_table) return k->block_tokens == 0 ? FIER_OK : FIER_EINVAL;
+  const int32_t bt = k->block_tokens;
+  if (bt < kPair || (bt & (bt - 1)) != 0 || bt < c->group_size || c->max_ctx % bt != 0) return FIER_ESHAPE;
+  if ((reinterpret_cast<uintptr_t>(k->block_table) & 3u) != 0) return FIER_EALIGN;
+  return FIER_OK;
+}
+
+int check_cache(const fier_config* c, const fier_cache* k) {
   if (!k || !k->k || !k->v || !k->kbits || !k->kmeta || !k->kabsmax || !k->seq_lens) return FIER_EINVAL;
   if (misaligned(k->k) || misaligned(k->v) || misaligned(k->kbits) || misaligned(k->kmeta) ||
       misaligned(k->kabsmax))
     return FIER_EALIGN;
-  return FIER_OK;
+  return check_blocks(c, k);
+}
+
+// Where the K / V rows of the cache live (contiguous per unit, or in pool blocks through the block table).
+fier::KvLayout layout_of(const fier_config* c, const fier_cache* k) {
+  fier::KvLayout lay;
+  lay.table = k->block_table;
+  lay.n_kv_heads = c->n_kv_heads;
+  lay.max_ctx = c->max_ctx;
+  lay.shift = 0;
+  lay.blocks_per_seq = 0;
+  if (k->block_table) {
+    while ((1 << lay.shift) < k->block_tokens) ++lay.shift;
+    lay.blocks_per_seq = c->max_ctx / k->block_tokens;
+  }
+  return lay;
 }
 
 inline int units_of(const fier_config* c) { return c->batch * c->n_kv_heads; }
@@ -128,9 +153,9 @@ size_t fier_workspace_bytes(const fier_config* cfg, int32_t max_budget) {
 int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
-  st = check_cache(cache);
+  st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
-  return hip_status(fier::launch_quantize(cfg->kv_dtype, cache->k, cache->kbits, cache->kmeta, cache->kabsmax,
+  return hip_status(fier::launch_quantize(cfg->kv_dtype, layout_of(cfg, cache), cache->k, cache->kbits, cache->kmeta, cache->kabsmax,
                                           cache->seq_lens, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
                                           cfg->group_size, (hipStream_t)stream));
 }
@@ -139,11 +164,11 @@ int fier_append_key(const fier_config* cfg, const fier_cache* cache, const void*
                     void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
-  st = check_cache(cache);
+  st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
   if (!k_new || !v_new) return FIER_EINVAL;
   if (misaligned(k_new) || misaligned(v_new)) return FIER_EALIGN;
-  return hip_status(fier::launch_append(cfg->kv_dtype, cache->k, cache->v, cache->kbits, cache->kmeta,
+  return hip_status(fier::launch_append(cfg->kv_dtype, layout_of(cfg, cache), cache->k, cache->v, cache->kbits, cache->kmeta,
                                         cache->kabsmax, cache->seq_lens, k_new, v_new, units_of(cfg),
                                         cfg->n_kv_heads, cfg->max_ctx, cfg->group_size, (hipStream_t)stream));
 }
@@ -152,11 +177,11 @@ int fier_score(const fier_config* cfg, const fier_cache* cache, const void* q, i
                void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
-  st = check_cache(cache);
+  st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
   if (!q || !scores || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
   if (misaligned(q) || misaligned(scores)) return FIER_EALIGN;
-  return hip_status(fier::launch_score(cfg->kv_dtype, n_rep_of(cfg), cache->kbits, cache->kmeta, cache->kabsmax, q,
+  return hip_status(fier::launch_score(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->kbits, cache->kmeta, cache->kabsmax, q,
                                        cache->seq_lens, extra_tokens, scores, nullptr, nullptr, 0, nullptr, nullptr,
                                        nullptr, nullptr, units_of(cfg), cfg->n_kv_heads, cfg->max_ctx,
                                        cfg->group_size, (hipStream_t)stream));
@@ -177,14 +202,14 @@ int fier_sparse_attn(const fier_config* cfg, const fier_cache* cache, const void
                      const int32_t* count, int32_t max_budget, float* out, void* workspace, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
-  st = check_cache(cache);
+  st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
   if (!q || !idx || !count || !out || max_budget < 1) return FIER_EINVAL;
   if (!workspace) return FIER_EWORKSPACE;
   if (misaligned(q) || misaligned(idx) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
   if (max_budget > cfg->max_ctx) return FIER_EINVAL;
   Workspace w = carve(cfg, max_budget, workspace);
-  return hip_status(fier::launch_attn(cfg->kv_dtype, n_rep_of(cfg), cache->k, cache->v, q, idx, count,
+  return hip_status(fier::launch_attn(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->k, cache->v, q, idx, count,
                                       cache->seq_lens, 0, max_budget, fier::kAttnRowsSparse, splits_for(max_budget),
                                       cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
                                       cfg->max_ctx, (hipStream_t)stream));
@@ -194,14 +219,14 @@ int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void*
                     void* workspace, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
-  st = check_cache(cache);
+  st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
   if (!q || !out || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
   if (!workspace) return FIER_EWORKSPACE;
   if (misaligned(q) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
   Workspace w = carve(cfg, cfg->max_ctx, workspace);
   const int n_splits = (cfg->max_ctx + fier::kAttnRowsDense - 1) / fier::kAttnRowsDense;
-  return hip_status(fier::launch_attn(cfg->kv_dtype, n_rep_of(cfg), cache->k, cache->v, q, nullptr, nullptr,
+  return hip_status(fier::launch_attn(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->k, cache->v, q, nullptr, nullptr,
                                       cache->seq_lens, extra_tokens, cfg->max_ctx, fier::kAttnRowsDense, n_splits,
                                       cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
                                       cfg->max_ctx, (hipStream_t)stream));
@@ -222,7 +247,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
       misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
-    st = check_cache(&layers[l]);
+    st = check_cache(cfg, &layers[l]);
     if (st != FIER_OK) return st;
   }
   const int units = units_of(cfg), n_rep = n_rep_of(cfg);
@@ -237,25 +262,26 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
     int32_t* idxl = idx_out ? idx_out + (size_t)l * units * max_budget : nullptr;
     int32_t* cntl = count_out ? count_out + (size_t)l * units : nullptr;
     hipError_t e;
+    const fier::KvLayout lay = layout_of(cfg, c);
     const char* kn = extra ? static_cast<const char*>(k_new) + (size_t)l * units * kD * esz : nullptr;
     const char* vn = extra ? static_cast<const char*>(v_new) + (size_t)l * units * kD * esz : nullptr;
     if (dense_layers && dense_layers[l]) {
       // full attention for this layer: append (the packed cache stays up to date), then attend over every row
       if (extra) {
-        e = fier::launch_append(cfg->kv_dtype, c->k, c->v, c->kbits, c->kmeta, c->kabsmax, c->seq_lens, kn, vn, units,
+        e = fier::launch_append(cfg->kv_dtype, lay, c->k, c->v, c->kbits, c->kmeta, c->kabsmax, c->seq_lens, kn, vn, units,
                                 cfg->n_kv_heads, cfg->max_ctx, cfg->group_size, s);
         if (e != hipSuccess) return FIER_EHIP;
       }
       Workspace wd = carve(cfg, cfg->max_ctx, workspace);
       const int n_splits = (cfg->max_ctx + fier::kAttnRowsDense - 1) / fier::kAttnRowsDense;
-      e = fier::launch_attn(cfg->kv_dtype, n_rep, c->k, c->v, ql, nullptr, nullptr, c->seq_lens, extra, cfg->max_ctx,
+      e = fier::launch_attn(cfg->kv_dtype, lay, n_rep, c->k, c->v, ql, nullptr, nullptr, c->seq_lens, extra, cfg->max_ctx,
                             fier::kAttnRowsDense, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, outl, units,
                             cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
       continue;
     }
     if (phase == 0 || phase == 1) {
-      e = fier::launch_score(cfg->kv_dtype, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra,
+      e = fier::launch_score(cfg->kv_dtype, lay, n_rep, c->kbits, c->kmeta, c->kabsmax, ql, c->seq_lens, extra,
                              w.sb.scores, &w.sb, budgets, max_budget, c->k, c->v, kn, vn, units, cfg->n_kv_heads,
                              cfg->max_ctx, cfg->group_size, s);
       if (e != hipSuccess) return FIER_EHIP;
@@ -265,7 +291,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
       if (e != hipSuccess) return FIER_EHIP;
     }
     if (phase == 0 || phase == 3) {
-      e = fier::launch_select_attend(cfg->kv_dtype, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
+      e = fier::launch_select_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
                                      cfg->sm_scale, idxl, outl, c->kabsmax, units, cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
@@ -316,7 +342,9 @@ int fier_page_minmax(const fier_config* cfg, const fier_cache* cache, int32_t pa
   if (st != FIER_OK) return st;
   if (!cache || !cache->k || !cache->seq_lens || !page_meta) return FIER_EINVAL;
   if (misaligned(cache->k) || misaligned(page_meta)) return FIER_EALIGN;
-  return hip_status(fier::launch_page_minmax(cfg->kv_dtype, cache->k, cache->seq_lens, page_meta, units_of(cfg),
+  st = check_blocks(cfg, cache);
+  if (st != FIER_OK) return st;
+  return hip_status(fier::launch_page_minmax(cfg->kv_dtype, layout_of(cfg, cache), cache->k, cache->seq_lens, page_meta, units_of(cfg),
                                              cfg->n_kv_heads, cfg->max_ctx, page_tokens, (hipStream_t)stream));
 }
 

@@ -34,7 +34,7 @@ struct AttnState {
 // Attend over entries [start, end) of a row list; row_of(j) gives the cache row of entry j.  The workgroup's
 // 16 lane rows (4 waves x 4) take entries round-robin in batches of kAttnUnroll.
 template <int DT, int NREP, class RowOf>
-__device__ __forceinline__ void attend_rows(const uint4* __restrict__ Ku, const uint4* __restrict__ Vu,
+__device__ __forceinline__ void attend_rows(const uint4* __restrict__ K, const uint4* __restrict__ V, const KvRows kv,
                                             const uint4 (&qr)[NREP], RowOf row_of, int start, int end, int max_ctx,
                                             float scale_log2e, AttnState<NREP>& st) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -48,8 +48,9 @@ __device__ __forceinline__ void attend_rows(const uint4* __restrict__ Ku, const 
       valid[u] = j < end;
       int t = valid[u] ? row_of(j) : 0;
       t = (t < 0 || t >= max_ctx) ? 0 : t;
-      kk[u] = Ku[(size_t)t * (kD / 8) + cn];
-      vv[u] = Vu[(size_t)t * (kD / 8) + cn];
+      const size_t ro = kv.row(t) * (kD / 8) + cn;
+      kk[u] = K[ro];
+      vv[u] = V[ro];
     }
 #pragma unroll
     for (int r = 0; r < NREP; ++r) {
@@ -114,7 +115,8 @@ constexpr int kAttnMfmaLds = 4 * 144;  // LDS floats attend_rows_mfma needs: per
 // attend_rows) and the P.V product stays on the vector ALUs.  One running (m, l) per head and wavefront.
 // q_unit: the unit's NREP query rows; sh: kAttnMfmaLds floats of LDS.
 template <int DT, int NREP, class RowOf>
-__device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ Ku, const uint4* __restrict__ Vu,
+__device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ K, const uint4* __restrict__ V,
+                                                 const KvRows kv,
                                                  const uint4* __restrict__ q_unit, RowOf row_of, int start, int end,
                                                  int max_ctx, float scale_log2e, AttnState<NREP>& st, float* sh) {
   static_assert(NREP >= 1 && NREP <= 8, "heads per kv head");
@@ -140,14 +142,15 @@ __device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ Ku, c
     int tk = valid ? row_of(jk) : 0;
     tk = (tk < 0 || tk >= max_ctx) ? 0 : tk;
     uint4 kk[4], vv[4];
+    const size_t rk = kv.row(tk) * (kD / 8);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) kk[c] = Ku[(size_t)tk * (kD / 8) + 4 * c + kq];
+    for (int c = 0; c < 4; ++c) kk[c] = K[rk + 4 * c + kq];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int jv = j0 + 4 * u + kq;
       int tv = jv < end ? row_of(jv) : 0;
       tv = (tv < 0 || tv >= max_ctx) ? 0 : tv;
-      vv[u] = Vu[(size_t)tv * (kD / 8) + n];
+      vv[u] = V[kv.row(tv) * (kD / 8) + n];
     }
     floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
                                                          int max_budget, int rows_per_wg, int n_splits,
                                                          float scale_log2e, float* __restrict__ po,
                                                          float* __restrict__ pm, float* __restrict__ pl,
-                                                         int n_kv_heads, int max_ctx) {
+                                                         int n_kv_heads, int max_ctx, KvLayout lay) {
   __shared__ float sh_o[NREP * kPartialFloats];
 
   const int cn = threadIdx.x & 15;
@@ -329,8 +332,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   if (start >= n) return;
   const int end = n < start + rows_per_wg ? n : start + rows_per_wg;
   const int32_t* __restrict__ sel = idx ? idx + (size_t)unit * max_budget : nullptr;
-  const uint4* __restrict__ Ku = K + (size_t)unit * max_ctx * (kD / 8);
-  const uint4* __restrict__ Vu = V + (size_t)unit * max_ctx * (kD / 8);
+  const KvRows kv = lay.rows_of(unit);
 
   uint4 qr[NREP];
 #pragma unroll
@@ -341,15 +343,15 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   if constexpr (NREP >= 3) {
     const uint4* q_unit = q + (size_t)unit * NREP * (kD / 8);
     if (sel)
-      attend_rows_mfma<DT, NREP>(Ku, Vu, q_unit, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st,
+      attend_rows_mfma<DT, NREP>(K, V, kv, q_unit, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st,
                                  sh_o);
     else
-      attend_rows_mfma<DT, NREP>(Ku, Vu, q_unit, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st, sh_o);
+      attend_rows_mfma<DT, NREP>(K, V, kv, q_unit, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st, sh_o);
   } else {
     if (sel)
-      attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st);
+      attend_rows<DT, NREP>(K, V, kv, qr, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st);
     else
-      attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st);
+      attend_rows<DT, NREP>(K, V, kv, qr, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st);
   }
   store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
 }
@@ -457,7 +459,8 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ q,
     const int32_t* __restrict__ seq_lens, int extra, int max_budget, float scale_log2e, float* __restrict__ po,
     float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
-    float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx) {
+    float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx,
+    KvLayout lay) {
   __shared__ float sh_o[NREP * kPartialFloats > 4 * 130 ? NREP * kPartialFloats : 4 * 130];
   __shared__ uint16_t rows[kRangeTokens * RPW];  // selected tokens, relative to the workgroup's first token
   __shared__ uint32_t scan_tmp[4];
@@ -536,18 +539,17 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   FIER_PROF(21, unit == 0 && wg == 3)
 
   // ---- attention over the selected rows of these ranges --------------------------------------------------------
-  const uint4* __restrict__ Ku = K + (size_t)unit * max_ctx * (kD / 8);
-  const uint4* __restrict__ Vu = V + (size_t)unit * max_ctx * (kD / 8);
+  const KvRows kv = lay.rows_of(unit);
   uint4 qr[NREP];
 #pragma unroll
   for (int h = 0; h < NREP; ++h) qr[h] = q[((size_t)unit * NREP + h) * (kD / 8) + cn];
   AttnState<NREP> st;
   st.init();
   if constexpr (NREP >= 3)
-    attend_rows_mfma<DT, NREP>(Ku, Vu, q + (size_t)unit * NREP * (kD / 8), [&](int j) { return tok0 + (int)rows[j]; },
+    attend_rows_mfma<DT, NREP>(K, V, kv, q + (size_t)unit * NREP * (kD / 8), [&](int j) { return tok0 + (int)rows[j]; },
                                0, (int)n_sel_total, max_ctx, scale_log2e, st, sh_o);
   else
-    attend_rows<DT, NREP>(Ku, Vu, qr, [&](int j) { return tok0 + (int)rows[j]; }, 0, (int)n_sel_total, max_ctx,
+    attend_rows<DT, NREP>(K, V, kv, qr, [&](int j) { return tok0 + (int)rows[j]; }, 0, (int)n_sel_total, max_ctx,
                           scale_log2e, st);
   FIER_PROF(22, unit == 0 && wg == 3)
   store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, po, pm, pl);
@@ -605,7 +607,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
 }
 
 template <int DT>
-static hipError_t launch_attn_dt(int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
+static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
                                  const int32_t* count, const int32_t* seq_lens, int extra, int max_budget,
                                  int rows_per_wg, int n_splits, float sm_scale, float* po, float* pm, float* pl,
                                  int units, int n_kv_heads, int max_ctx, hipStream_t st) {
@@ -615,7 +617,7 @@ static hipError_t launch_attn_dt(int n_rep, const void* K, const void* V, const 
   case R:                                                                                                          \
     attn_split_kernel<DT, R><<<grid, 256, 0, st>>>((const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count,  \
                                                    seq_lens, extra, max_budget, rows_per_wg, n_splits, sl2, po, pm, \
-                                                   pl, n_kv_heads, max_ctx);                                       \
+                                                   pl, n_kv_heads, max_ctx, lay);                                  \
     break;
   switch (n_rep) {
     FIER_ATTN_CASE(1)
@@ -634,7 +636,7 @@ static hipError_t launch_attn_dt(int n_rep, const void* K, const void* V, const 
 }
 
 template <int DT, int RPW>
-static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, const void* K, const void* V,
+static hipError_t launch_select_attend_dt(KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                           const void* q, const int32_t* seq_lens, int extra, int max_budget,
                                           float sm_scale, int32_t* idx_out, float* out, float* kabsmax, int units,
                                           int n_kv_heads, int max_ctx, hipStream_t st) {
@@ -645,7 +647,8 @@ static hipError_t launch_select_attend_dt(int n_rep, const StepBuffers& sb, cons
   case R:                                                                                                          \
     select_attend_kernel<DT, R, RPW><<<grid, 256, 0, st>>>(                                                        \
         sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K, (const uint4*)V, (const uint4*)q, seq_lens, extra,       \
-        max_budget, sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax, n_ranges, n_kv_heads, max_ctx);    \
+        max_budget, sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax, n_ranges, n_kv_heads, max_ctx,     \
+        lay);                                                                                                      \
     break;
   switch (n_rep) {
     FIER_SA_CASE(1)
@@ -671,12 +674,12 @@ int select_attend_ranges_per_wg(int max_budget, int max_ctx) {
   return rpw;
 }
 
-hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+hipError_t launch_select_attend(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
                                 int32_t* idx_out, float* out, float* kabsmax, int units, int n_kv_heads, int max_ctx,
                                 hipStream_t st) {
 #define FIER_SA_RPW(DT, RPW)                                                                                        \
-  return launch_select_attend_dt<DT, RPW>(n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out, \
+  return launch_select_attend_dt<DT, RPW>(lay, n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out, \
                                           kabsmax, units, n_kv_heads, max_ctx, st)
   const int rpw = select_attend_ranges_per_wg(max_budget, max_ctx);
   if (dtype == DT_F16) {
@@ -692,16 +695,16 @@ hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, con
 #undef FIER_SA_RPW
 }
 
-hipError_t launch_attn(int dtype, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
+hipError_t launch_attn(int dtype, KvLayout lay, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
                        const int32_t* count, const int32_t* seq_lens, int extra, int max_budget, int rows_per_wg,
                        int n_splits, float sm_scale, float* po, float* pm, float* pl, float* out, int units,
                        int n_kv_heads, int max_ctx, hipStream_t st) {
   hipError_t e;
   if (dtype == DT_F16)
-    e = launch_attn_dt<DT_F16>(n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
+    e = launch_attn_dt<DT_F16>(lay, n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
                                sm_scale, po, pm, pl, units, n_kv_heads, max_ctx, st);
   else
-    e = launch_attn_dt<DT_BF16>(n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
+    e = launch_attn_dt<DT_BF16>(lay, n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
                                 sm_scale, po, pm, pl, units, n_kv_heads, max_ctx, st);
   if (e != hipSuccess) return e;
   attn_merge_kernel<<<units * n_rep, 128, 0, st>>>(po, pm, pl, idx ? count : nullptr, seq_lens, extra, max_budget,

@@ -6,6 +6,41 @@
 
 namespace fier {
 
+// ---- where the K / V rows live -----------------------------------------------------------------------------------------
+// Contiguous caches hold row t of unit u at row u * max_ctx + t.  Paged caches (a block table, as serving stacks keep
+// ragged batches) hold the rows in pools [n_blocks][n_kv_heads][block_tokens][D]; sequence b's logical block j is
+// pool block table[b * blocks_per_seq + j].  block_tokens is a power of two >= 64, so the 64 tokens of a pair block,
+// a quantization group and a page always lie inside one block.
+struct KvRows {  // the rows of one unit
+  const int32_t* blocks;  // the sequence's block list; nullptr: contiguous
+  size_t base;            // contiguous: u * max_ctx; paged: head * block_tokens
+  size_t block_stride;    // paged: rows per pool block = n_kv_heads * block_tokens
+  int shift, mask;        // log2(block_tokens), block_tokens - 1
+  __device__ __forceinline__ size_t row(int t) const {
+    return blocks ? (size_t)blocks[t >> shift] * block_stride + base + (size_t)(t & mask) : base + (size_t)t;
+  }
+};
+struct KvLayout {  // one cache; passed to the kernels by value
+  const int32_t* table;  // [batch][blocks_per_seq]; nullptr: contiguous
+  int blocks_per_seq, shift, n_kv_heads, max_ctx;
+  __device__ __forceinline__ KvRows rows_of(int unit) const {
+    KvRows r;
+    if (table) {
+      const int b = unit / n_kv_heads, h = unit - b * n_kv_heads;
+      r.blocks = table + (size_t)b * blocks_per_seq;
+      r.base = (size_t)h << shift;
+      r.block_stride = (size_t)n_kv_heads << shift;
+    } else {
+      r.blocks = nullptr;
+      r.base = (size_t)unit * max_ctx;
+      r.block_stride = 0;
+    }
+    r.shift = shift;
+    r.mask = (1 << shift) - 1;
+    return r;
+  }
+};
+
 constexpr int kAttnRowsSparse = 128;  // selected rows per workgroup of the split attention kernel
 constexpr int kAttnRowsDense = 512;   // rows per workgroup when attending over the whole cache
 
@@ -50,18 +85,18 @@ struct StepBuffers {    // carved from the caller's workspace
   float* pl;
 };
 
-hipError_t launch_quantize(int dtype, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
                            const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, int group_size,
                            hipStream_t st);
 
-hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+hipError_t launch_append(int dtype, KvLayout lay, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
                          const int32_t* seq_lens, const void* k_new, const void* v_new, int units, int n_kv_heads,
                          int max_ctx, int group_size, hipStream_t st);
 
 // With sb != nullptr the kernel also builds the per-unit score histogram and its last workgroup per unit
 // finds the threshold bin for budgets[b] (first kernel of the fused step); with k_new != nullptr as well it
 // appends the new K/V rows first (extra must then be 1).
-hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
+hipError_t launch_score(int dtype, KvLayout lay, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
                         const void* v_new, int units, int n_kv_heads, int max_ctx, int group_size, hipStream_t st);
@@ -70,7 +105,7 @@ hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int 
                             int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,
                             hipStream_t st);
 
-hipError_t launch_select_attend(int dtype, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+hipError_t launch_select_attend(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
                                 int32_t* idx_out, float* out, float* kabsmax, int units, int n_kv_heads, int max_ctx,
                                 hipStream_t st);
@@ -81,13 +116,13 @@ hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, 
 
 // idx == nullptr: attend over rows [0, seq_len + extra) (dense).  rows_per_wg rows of the selection per
 // workgroup; partials (po, pm, pl) hold n_splits entries per (unit, query head).
-hipError_t launch_attn(int dtype, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
+hipError_t launch_attn(int dtype, KvLayout lay, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
                        const int32_t* count, const int32_t* seq_lens, int extra, int max_budget, int rows_per_wg,
                        int n_splits, float sm_scale, float* po, float* pm, float* pl, float* out, int units,
                        int n_kv_heads, int max_ctx, hipStream_t st);
 
 // ---- page-level importance (comparison workload) -------------------------------------------------------------------
-hipError_t launch_page_minmax(int dtype, const void* K, const int32_t* seq_lens, uint32_t* page_meta, int units,
+hipError_t launch_page_minmax(int dtype, KvLayout lay, const void* K, const int32_t* seq_lens, uint32_t* page_meta, int units,
                               int n_kv_heads, int max_ctx, int P, hipStream_t st);
 hipError_t launch_page_append(int dtype, const void* k_new, const int32_t* seq_lens, uint32_t* page_meta, int units,
                               int n_kv_heads, int max_ctx, int P, hipStream_t st);

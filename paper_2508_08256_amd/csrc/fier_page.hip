@@ -17,7 +17,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void page_minmax_kernel(const uint32_t* __restrict__ K,
                                                           const int32_t* __restrict__ seq_lens,
                                                           uint32_t* __restrict__ page_meta, int n_kv_heads,
-                                                          int max_ctx, int P) {
+                                                          int max_ctx, int P, KvLayout lay) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int unit = blockIdx.y;
   const int n_pages = max_ctx / P;
@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void page_minmax_kernel(const uint32_t* __rest
   uint2 res = make_uint2(0, 0);
   if (t0 < L) {
     const int nt = L - t0 < P ? L - t0 : P;
-    const uint32_t* src = K + ((size_t)unit * max_ctx + t0) * (kD / 2) + lane;
+    const uint32_t* src = K + lay.rows_of(unit).row(t0) * (kD / 2) + lane;  // a page lies inside one block
     uint32_t w = src[0];
     uint32_t mn0 = w & 0xffffu, mx0 = mn0, mn1 = w >> 16, mx1 = mn1;
     for (int t = 1; t < nt; ++t) {
@@ -183,13 +183,15 @@ __global__ __launch_bounds__(256) void expand_pages_kernel(const int32_t* __rest
   }
 }
 
-hipError_t launch_page_minmax(int dtype, const void* K, const int32_t* seq_lens, uint32_t* page_meta, int units,
+hipError_t launch_page_minmax(int dtype, KvLayout lay, const void* K, const int32_t* seq_lens, uint32_t* page_meta, int units,
                               int n_kv_heads, int max_ctx, int P, hipStream_t st) {
   dim3 grid((max_ctx / P + 3) / 4, units);
   if (dtype == DT_F16)
-    page_minmax_kernel<DT_F16><<<grid, 256, 0, st>>>((const uint32_t*)K, seq_lens, page_meta, n_kv_heads, max_ctx, P);
+    page_minmax_kernel<DT_F16><<<grid, 256, 0, st>>>((const uint32_t*)K, seq_lens, page_meta, n_kv_heads, max_ctx, P,
+                                                     lay);
   else
-    page_minmax_kernel<DT_BF16><<<grid, 256, 0, st>>>((const uint32_t*)K, seq_lens, page_meta, n_kv_heads, max_ctx, P);
+    page_minmax_kernel<DT_BF16><<<grid, 256, 0, st>>>((const uint32_t*)K, seq_lens, page_meta, n_kv_heads, max_ctx, P,
+                                                     lay);
   return hipGetLastError();
 }
 

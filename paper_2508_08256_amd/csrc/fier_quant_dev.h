@@ -3,6 +3,7 @@
 #pragma once
 
 #include "fier_dev.h"
+#include "fier_kernels.h"
 
 namespace fier {
 
@@ -133,18 +134,18 @@ __device__ __forceinline__ void raise_absmax(float* __restrict__ slot, float a) 
 // falls in from the rows present (the new row comes from registers) and stores its code words and (s, z).
 // Returns the group's code in gc; t0 = first token of the group, ntok = tokens now present in it.
 template <int DT>
-__device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* __restrict__ V,
+__device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* __restrict__ V, const KvRows kv,
                                            uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta, int unit,
                                            int L, int max_ctx, uint32_t kn, uint32_t vn, int lane, GroupCode& gc,
                                            int& t0, int& ntok) {
   const int n_groups = max_ctx / kG;
-  K[((size_t)unit * max_ctx + L) * (kD / 2) + lane] = kn;
-  V[((size_t)unit * max_ctx + L) * (kD / 2) + lane] = vn;
+  K[kv.row(L) * (kD / 2) + lane] = kn;
+  V[kv.row(L) * (kD / 2) + lane] = vn;
   const int Gi = L / kG;
   t0 = Gi * kG;
   ntok = L - t0 + 1;
   uint32_t rows[kG];
-  const uint32_t* src = K + ((size_t)unit * max_ctx + t0) * (kD / 2) + lane;
+  const uint32_t* src = K + kv.row(t0) * (kD / 2) + lane;  // a group lies inside one block
 #pragma unroll
   for (int t = 0; t < kG; ++t) {
     // rows before the new one come from memory (t0 + t < L: never the row written above)
@@ -170,18 +171,19 @@ __device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* _
 // group's scale.
 template <int DT, class OnBlock>
 __device__ __forceinline__ GroupScale append_row_long(uint32_t* __restrict__ K, uint32_t* __restrict__ V,
-                                                      uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta,
+                                                      const KvRows kv, uint32_t* __restrict__ kbits,
+                                                      uint32_t* __restrict__ kmeta,
                                                       int unit, int L, int max_ctx, int ns, uint32_t kn, uint32_t vn,
                                                       int lane, int& t0, int& ntok, OnBlock on_block) {
   const int g = kG * ns;
   const int n_groups = max_ctx / g;
-  K[((size_t)unit * max_ctx + L) * (kD / 2) + lane] = kn;
-  V[((size_t)unit * max_ctx + L) * (kD / 2) + lane] = vn;
+  K[kv.row(L) * (kD / 2) + lane] = kn;
+  V[kv.row(L) * (kD / 2) + lane] = vn;
   const int Gi = L / g;
   t0 = Gi * g;
   ntok = L - t0 + 1;
   const int n_present = ntok;
-  const uint32_t* src = K + ((size_t)unit * max_ctx + t0) * (kD / 2) + lane;
+  const uint32_t* src = K + kv.row(t0) * (kD / 2) + lane;  // a group lies inside one block
   // rows before the new one come from memory (never the row written above), the new one from registers
   auto row_at = [&](int t) { return t == n_present - 1 ? kn : src[(size_t)t * (kD / 2)]; };
   const GroupScale gs = long_group_scale<DT>(row_at, ntok);

@@ -25,7 +25,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void quantize_kernel(const uint32_t* __restrict__ K, uint32_t* __restrict__ kbits,
                                                        uint32_t* __restrict__ kmeta, float* __restrict__ kabsmax,
                                                        const int32_t* __restrict__ seq_lens, int n_kv_heads,
-                                                       int max_ctx) {
+                                                       int max_ctx, KvLayout lay) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int unit = blockIdx.y;
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const uint32_t* __restric
     uint32_t meta0 = 0, meta1 = 0;
     if (ntok > 0) {
       uint32_t rows[kG];
-      const uint32_t* src = K + ((size_t)unit * max_ctx + t0) * (kD / 2) + lane;
+      const uint32_t* src = K + lay.rows_of(unit).row(t0) * (kD / 2) + lane;
 #pragma unroll
       for (int t = 0; t < kG; ++t) rows[t] = src[(size_t)(t < ntok ? t : 0) * (kD / 2)];
       GroupCode gc;
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void quantize_long_kernel(const uint32_t* __re
                                                             uint32_t* __restrict__ kbits,
                                                             uint32_t* __restrict__ kmeta, float* __restrict__ kabsmax,
                                                             const int32_t* __restrict__ seq_lens, int n_kv_heads,
-                                                            int max_ctx, int ns) {
+                                                            int max_ctx, int ns, KvLayout lay) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int unit = blockIdx.y;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void quantize_long_kernel(const uint32_t* __re
   if (t0 >= L) return;
   const int ntok = L - t0 > g ? g : L - t0;
   const int n_groups = max_ctx / g;
-  const uint32_t* src = K + ((size_t)unit * max_ctx + t0) * (kD / 2) + lane;
+  const uint32_t* src = K + lay.rows_of(unit).row(t0) * (kD / 2) + lane;
   auto row_at = [&](int t) { return src[(size_t)t * (kD / 2)]; };
   const GroupScale gs = long_group_scale<DT>(row_at, ntok);
   uint2* mdst = reinterpret_cast<uint2*>(kmeta + ((size_t)unit * n_groups + Gi) * kD) + lane;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(64) void append_kernel(uint32_t* __restrict__ K, ui
                                                     const int32_t* __restrict__ seq_lens,
                                                     const uint32_t* __restrict__ k_new,
                                                     const uint32_t* __restrict__ v_new, int n_kv_heads, int max_ctx,
-                                                    int ns) {
+                                                    int ns, KvLayout lay) {
   const int lane = threadIdx.x;
   const int unit = blockIdx.x;
   const int L = seq_lens[unit / n_kv_heads];
@@ -132,10 +132,11 @@ __global__ __launch_bounds__(64) void append_kernel(uint32_t* __restrict__ K, ui
   float amax_lo, amax_hi;
   if (ns == 1) {
     GroupCode gc;
-    append_row<DT>(K, V, kbits, kmeta, unit, L, max_ctx, kn, vn, lane, gc, t0, ntok);
+    append_row<DT>(K, V, lay.rows_of(unit), kbits, kmeta, unit, L, max_ctx, kn, vn, lane, gc, t0, ntok);
     amax_lo = gc.amax_lo, amax_hi = gc.amax_hi;
   } else {
-    const GroupScale gs = append_row_long<DT>(K, V, kbits, kmeta, unit, L, max_ctx, ns, kn, vn, lane, t0, ntok,
+    const GroupScale gs = append_row_long<DT>(K, V, lay.rows_of(unit), kbits, kmeta, unit, L, max_ctx, ns, kn, vn, lane,
+                                              t0, ntok,
                                               [](int, const uint4&, const GroupScale&) {});
     amax_lo = fmaxf(fabsf(gs.zf0), fabsf(gs.zf0 + gs.sf0));
     amax_hi = fmaxf(fabsf(gs.zf1), fabsf(gs.zf1 + gs.sf1));
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(64) void append_kernel(uint32_t* __restrict__ K, ui
   raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane + 1, amax_hi);
 }
 
-hipError_t launch_quantize(int dtype, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
                            const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, int group_size,
                            hipStream_t st) {
   zero_absmax_kernel<<<(units * kD + 255) / 256, 256, 0, st>>>(kabsmax, units * kD);
@@ -153,34 +154,34 @@ hipError_t launch_quantize(int dtype, const void* K, uint32_t* kbits, uint32_t* 
     dim3 grid_long((max_ctx / group_size + 3) / 4, units);
     if (dtype == DT_F16)
       quantize_long_kernel<DT_F16><<<grid_long, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens,
-                                                             n_kv_heads, max_ctx, ns);
+                                                             n_kv_heads, max_ctx, ns, lay);
     else
       quantize_long_kernel<DT_BF16><<<grid_long, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens,
-                                                              n_kv_heads, max_ctx, ns);
+                                                              n_kv_heads, max_ctx, ns, lay);
     return hipGetLastError();
   }
   dim3 grid((max_ctx / kPair + 3) / 4, units);
   if (dtype == DT_F16)
     quantize_kernel<DT_F16><<<grid, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                  max_ctx);
+                                                  max_ctx, lay);
   else
     quantize_kernel<DT_BF16><<<grid, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                   max_ctx);
+                                                   max_ctx, lay);
   return hipGetLastError();
 }
 
-hipError_t launch_append(int dtype, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+hipError_t launch_append(int dtype, KvLayout lay, void* K, void* V, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
                          const int32_t* seq_lens, const void* k_new, const void* v_new, int units, int n_kv_heads,
                          int max_ctx, int group_size, hipStream_t st) {
   const int ns = group_size / kG;
   if (dtype == DT_F16)
     append_kernel<DT_F16><<<units, 64, 0, st>>>((uint32_t*)K, (uint32_t*)V, kbits, kmeta, kabsmax, seq_lens,
                                                 (const uint32_t*)k_new, (const uint32_t*)v_new, n_kv_heads, max_ctx,
-                                                ns);
+                                                ns, lay);
   else
     append_kernel<DT_BF16><<<units, 64, 0, st>>>((uint32_t*)K, (uint32_t*)V, kbits, kmeta, kabsmax, seq_lens,
                                                  (const uint32_t*)k_new, (const uint32_t*)v_new, n_kv_heads, max_ctx,
-                                                 ns);
+                                                 ns, lay);
   return hipGetLastError();
 }
 

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
                                                     int max_budget, uint32_t* __restrict__ K, uint32_t* __restrict__ V,
                                                     const uint32_t* __restrict__ k_new,
                                                     const uint32_t* __restrict__ v_new, float* __restrict__ newmax,
-                                                    int n_kv_heads, int max_ctx, int bpw, int gshift) {
+                                                    int n_kv_heads, int max_ctx, int bpw, int gshift, KvLayout lay) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
   __shared__ __attribute__((aligned(16))) unsigned char a_lds[4 * kAWave];
 
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
         const uint32_t vn = v_new[(size_t)unit * (kD / 2) + lane];
         GroupCode gc;
         int t0, ntok;
-        append_row<DT>(K, V, const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
+        append_row<DT>(K, V, lay.rows_of(unit), const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
                        const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kmeta)), unit, Lold, max_ctx, kn, vn,
                        lane, gc, t0, ntok);
         newmax[(size_t)unit * kD + 2 * lane] = gc.amax_lo;
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
         float base = 0.f;
         bool have_w = false;
         const GroupScale gs = append_row_long<DT>(
-            K, V, const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
+            K, V, lay.rows_of(unit), const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
             const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kmeta)), unit, Lold, max_ctx, 1 << gshift, kn, vn, lane,
             t0, ntok, [&](int pb, const uint4& mine, const GroupScale& g) {
               if (!have_w) {
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
 }
 
 template <int DT, bool HIST>
-static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
+static hipError_t launch_score_dt(KvLayout lay, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                                   const void* q, const int32_t* seq_lens, int extra, float* scores,
                                   const StepBuffers* sb, const int32_t* budgets, int max_budget, void* K, void* V,
                                   const void* k_new, const void* v_new, int units, int n_kv_heads, int max_ctx,
@@ -425,7 +425,7 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
         (const uint4*)kbits, (const uint4*)kmeta, kabsmax, (const uint16_t*)q, seq_lens, extra, scores,            \
         sb ? sb->ctl : nullptr, sb ? sb->hist : nullptr, budgets, max_budget, (uint32_t*)K, (uint32_t*)V,          \
         (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx, bpw,     \
-        gshift);                                                                                                  \
+        gshift, lay);                                                                                             \
     break;
   switch (n_rep) {
     FIER_SCORE_CASE(1)
@@ -443,21 +443,21 @@ static hipError_t launch_score_dt(int n_rep, const uint32_t* kbits, const uint32
   return hipGetLastError();
 }
 
-hipError_t launch_score(int dtype, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
+hipError_t launch_score(int dtype, KvLayout lay, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
                         const void* v_new, int units, int n_kv_heads, int max_ctx, int group_size, hipStream_t st) {
   if (sb) {
     if (dtype == DT_F16)
-      return launch_score_dt<DT_F16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
+      return launch_score_dt<DT_F16, true>(lay, n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
                                            max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, group_size, st);
-    return launch_score_dt<DT_BF16, true>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
+    return launch_score_dt<DT_BF16, true>(lay, n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, sb, budgets,
                                           max_budget, K, V, k_new, v_new, units, n_kv_heads, max_ctx, group_size, st);
   }
   if (dtype == DT_F16)
-    return launch_score_dt<DT_F16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
+    return launch_score_dt<DT_F16, false>(lay, n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr,
                                           0, nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, group_size, st);
-  return launch_score_dt<DT_BF16, false>(n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr, 0,
+  return launch_score_dt<DT_BF16, false>(lay, n_rep, kbits, kmeta, kabsmax, q, seq_lens, extra, scores, nullptr, nullptr, 0,
                                          nullptr, nullptr, nullptr, nullptr, units, n_kv_heads, max_ctx, group_size, st);
 }
 

@@ -83,6 +83,28 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert lib.fier_quantize_keys(C.byref(bad), C.byref(good), None) == B.EUNSUPPORTED
 
 
+def test_block_table_fields_are_validated():
+    lib = B.lib()
+    cfg = B.make_config(1, 8, 8, 1024, group_size=128)
+    ptrs = (0x1000, 0x2000, 0x3000, 0x4000, 0x4800, 0x5000)
+
+    def status(table, block_tokens):
+        return lib.fier_quantize_keys(C.byref(cfg), C.byref(B.Cache(*ptrs, table, block_tokens)), None)
+
+    assert status(None, 64) == B.EINVAL          # a block size without a table
+    assert status(0x6000, 0) == B.ESHAPE
+    assert status(0x6000, 64) == B.ESHAPE        # smaller than a quantization group
+    assert status(0x6000, 192) == B.ESHAPE       # not a power of two
+    assert status(0x6000, 2048) == B.ESHAPE      # does not divide the row capacity
+    assert status(0x6002, 128) == B.EALIGN
+    cfg32 = B.make_config(1, 8, 8, 1024)
+    assert lib.fier_quantize_keys(C.byref(cfg32), C.byref(B.Cache(*ptrs, 0x6000, 32)), None) == B.ESHAPE
+    arr = (B.Cache * 1)(B.Cache(*ptrs, 0x6000, 96))
+    assert lib.fier_decode_step(C.byref(cfg32), arr, 1, 0x6000, None, None, 0x5100, 16, 0x9000, None, None,
+                                0xA000, None) == B.ESHAPE
+    assert lib.fier_page_minmax(C.byref(cfg32), C.byref(B.Cache(*ptrs, 0x6000, 96)), 16, 0x7000, None) == B.ESHAPE
+
+
 def test_unpack_helpers_follow_the_documented_layout():
     """bit i of word d of a token <-> channel 64 (d & 1) + 2 i + (d >> 1);  meta word = s | z << 16."""
     cfg = B.make_config(1, 2, 2, 128)
