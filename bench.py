@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--loop-steps", type=int, default=0,
                     help="instead of the default measurement: this many consecutive token steps (append, growing "
                          "context) over all the workload's layer caches in one call per token, eager and as one graph")
+    ap.add_argument("--block-tokens", type=int, default=0,
+                    help="hold the K / V rows in a block pool of this block size behind a shuffled block table "
+                         "(a paged serving cache); 0 = contiguous rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-steps", type=int, default=240, help="launches per stage for the per-stage timing")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -118,11 +121,14 @@ def main():
     w["group_size"] = args.group_size
     if args.group_size != 32:
         w["label"] += f"_g{args.group_size}"
+    if args.block_tokens:
+        w["label"] += f"_paged{args.block_tokens}"
     R, NL = w["rotate"], w.get("layers", 1)
     batch, Hq, Hkv, dtype = w["batch"], w["n_q_heads"], w["n_kv_heads"], w["dtype"]
     lens, buds = shape_of(w, 5000)
     L, budget = int(lens.max()), int(buds.max())   # the largest context and budget (all of them when not ragged)
     gran = max(64, args.group_size) if args.selector == "fier" else 1024
+    gran = max(gran, args.block_tokens)
     max_ctx = -(-(L + 1 + max(0, args.loop_steps)) // gran) * gran
     cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype, group_size=args.group_size)
     units, n_rep = cfg.units, cfg.n_rep
@@ -140,15 +146,28 @@ def main():
             d = synth.make_workload_device(f"{args.workload}_cache{r}_{layer}", 1000 * 2 + r * NL + layer, batch, Hq,
                                            Hkv, lens, buds, dtype, max_ctx=max_ctx, chan=w["chan"],
                                            n_planted=w["n_planted"])
-            c = B.DeviceCache(cfg, d["K"], d["V"], seq_lens)
+            if r == 0 and layer == 0:
+                hosts = {k: (v[:min(units, 32)].clone() if k in ("K", "V", "q", "k_new", "v_new") else v)
+                         for k, v in d.items()}
+            if args.block_tokens:
+                bt, per_seq = args.block_tokens, max_ctx // args.block_tokens
+                gen = torch.Generator(device="cpu").manual_seed(7 + r * NL + layer)
+                table = torch.randperm(batch * per_seq, generator=gen).to(torch.int32).cuda()
+                pools = []
+                for name in ("K", "V"):
+                    blocks = d[name].view(batch, Hkv, per_seq, bt, 128).permute(0, 2, 1, 3, 4).reshape(-1, Hkv, bt, 128).contiguous()
+                    pool = torch.empty_like(blocks)
+                    pool[table.long()] = blocks
+                    pools.append(pool)
+                    d[name] = None
+                c = B.DeviceCache(cfg, pools[0], pools[1], seq_lens, table.view(batch, per_seq).contiguous())
+            else:
+                c = B.DeviceCache(cfg, d["K"], d["V"], seq_lens)
             B.quantize_keys(cfg, c)
             cl.append(c)
             ql.append(d["q"].reshape(batch, Hq, 128))
             kl.append(d["k_new"].reshape(units, 128))
             vl.append(d["v_new"].reshape(units, 128))
-            if r == 0 and layer == 0:
-                hosts = {k: (v[:min(units, 32)].clone() if k in ("K", "V", "q", "k_new", "v_new") else v)
-                         for k, v in d.items()}
             del d
         caches.append(cl)
         qs.append(torch.stack(ql).contiguous())

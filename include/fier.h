@@ -87,7 +87,7 @@ typedef struct fier_cache { /* one layer; all pointers device, caller-owned */
   /* Paged K / V rows (optional).  block_table is [batch][max_ctx / block_tokens]: entry j of sequence b is
    * the pool block that holds its tokens [j * block_tokens, (j + 1) * block_tokens), for all kv heads.
    * Entries that cover tokens < seq_len (+ the appended one) must be valid pool block numbers: the kernels
-   * cannot check them; later entries are never read.  k and v share the table.  block_tokens is a power of
+   * cannot check them; later entries may be loaded but are never used.  k and v share the table.  block_tokens is a power of
    * two >= max(64, group_size) that divides max_ctx, else FIER_ESHAPE; NULL with block_tokens = 0 selects
    * the contiguous layout (block_tokens != 0 with a NULL table: FIER_EINVAL).  The packed 1-bit cache
    * (kbits, kmeta, kabsmax), the scores and every index are per unit and contiguous in both layouts, so

@@ -31,11 +31,12 @@ struct AttnState {
   }
 };
 
-// Attend over entries [start, end) of a row list; row_of(j) gives the cache row of entry j.  The workgroup's
+// Attend over entries [start, end) of a row list; row_of(j) gives the row of entry j in the K / V arrays (the
+// callers map a token to its row: contiguous, or through the block table).  The workgroup's
 // 16 lane rows (4 waves x 4) take entries round-robin in batches of kAttnUnroll.
 template <int DT, int NREP, class RowOf>
-__device__ __forceinline__ void attend_rows(const uint4* __restrict__ K, const uint4* __restrict__ V, const KvRows kv,
-                                            const uint4 (&qr)[NREP], RowOf row_of, int start, int end, int max_ctx,
+__device__ __forceinline__ void attend_rows(const uint4* __restrict__ K, const uint4* __restrict__ V,
+                                            const uint4 (&qr)[NREP], RowOf row_of, int start, int end,
                                             float scale_log2e, AttnState<NREP>& st) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rs = lane >> 4, cn = lane & 15;
@@ -46,9 +47,7 @@ __device__ __forceinline__ void attend_rows(const uint4* __restrict__ K, const u
     for (int u = 0; u < kAttnUnroll; ++u) {
       const int j = i0 + u * 4 + rs;
       valid[u] = j < end;
-      int t = valid[u] ? row_of(j) : 0;
-      t = (t < 0 || t >= max_ctx) ? 0 : t;
-      const size_t ro = kv.row(t) * (kD / 8) + cn;
+      const size_t ro = row_of(valid[u] ? j : start) * (kD / 8) + cn;
       kk[u] = K[ro];
       vv[u] = V[ro];
     }
@@ -116,9 +115,8 @@ constexpr int kAttnMfmaLds = 4 * 144;  // LDS floats attend_rows_mfma needs: per
 // q_unit: the unit's NREP query rows; sh: kAttnMfmaLds floats of LDS.
 template <int DT, int NREP, class RowOf>
 __device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ K, const uint4* __restrict__ V,
-                                                 const KvRows kv,
                                                  const uint4* __restrict__ q_unit, RowOf row_of, int start, int end,
-                                                 int max_ctx, float scale_log2e, AttnState<NREP>& st, float* sh) {
+                                                 float scale_log2e, AttnState<NREP>& st, float* sh) {
   static_assert(NREP >= 1 && NREP <= 8, "heads per kv head");
   static_assert(NREP * kPartialFloats >= kAttnMfmaLds || NREP < 3, "the callers lend the partials' LDS");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -139,18 +137,14 @@ __device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ K, co
     // K rows in the matrix view (token j0 + n), V rows in the row-owner view (tokens j0 + 4u + kq, channels 8n..8n+7)
     const int jk = j0 + n;
     const bool valid = jk < end;
-    int tk = valid ? row_of(jk) : 0;
-    tk = (tk < 0 || tk >= max_ctx) ? 0 : tk;
     uint4 kk[4], vv[4];
-    const size_t rk = kv.row(tk) * (kD / 8);
+    const size_t rk = row_of(valid ? jk : start) * (kD / 8);
 #pragma unroll
     for (int c = 0; c < 4; ++c) kk[c] = K[rk + 4 * c + kq];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int jv = j0 + 4 * u + kq;
-      int tv = jv < end ? row_of(jv) : 0;
-      tv = (tv < 0 || tv >= max_ctx) ? 0 : tv;
-      vv[u] = V[kv.row(tv) * (kD / 8) + n];
+      vv[u] = V[row_of(jv < end ? jv : start) * (kD / 8) + n];
     }
     floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -333,6 +327,24 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   const int end = n < start + rows_per_wg ? n : start + rows_per_wg;
   const int32_t* __restrict__ sel = idx ? idx + (size_t)unit * max_budget : nullptr;
   const KvRows kv = lay.rows_of(unit);
+  // whole-cache attention over paged rows: the block numbers of this workgroup's rows wait in LDS
+  __shared__ int32_t lblk[kAttnRowsDense / 64];
+  const bool window = !sel && kv.blocks != nullptr;
+  if (window) {
+    const int bi = (start >> kv.shift) + (int)threadIdx.x;
+    if (threadIdx.x < kAttnRowsDense / 64) lblk[threadIdx.x] = bi < lay.blocks_per_seq ? kv.blocks[bi] : 0;
+    __syncthreads();
+  }
+  const int first_block = start >> kv.shift;
+  auto row_sel = [&](int j) {
+    int t = sel[j];
+    t = (t < 0 || t >= max_ctx) ? 0 : t;
+    return kv.row(t);
+  };
+  auto row_all = [&](int j) {
+    return window ? (size_t)lblk[(j >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(j & kv.mask)
+                  : kv.base + (size_t)j;
+  };
 
   uint4 qr[NREP];
 #pragma unroll
@@ -343,15 +355,14 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   if constexpr (NREP >= 3) {
     const uint4* q_unit = q + (size_t)unit * NREP * (kD / 8);
     if (sel)
-      attend_rows_mfma<DT, NREP>(K, V, kv, q_unit, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st,
-                                 sh_o);
+      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_sel, start, end, scale_log2e, st, sh_o);
     else
-      attend_rows_mfma<DT, NREP>(K, V, kv, q_unit, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st, sh_o);
+      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_all, start, end, scale_log2e, st, sh_o);
   } else {
     if (sel)
-      attend_rows<DT, NREP>(K, V, kv, qr, [&](int j) { return sel[j]; }, start, end, max_ctx, scale_log2e, st);
+      attend_rows<DT, NREP>(K, V, qr, row_sel, start, end, scale_log2e, st);
     else
-      attend_rows<DT, NREP>(K, V, kv, qr, [&](int j) { return j; }, start, end, max_ctx, scale_log2e, st);
+      attend_rows<DT, NREP>(K, V, qr, row_all, start, end, scale_log2e, st);
   }
   store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
 }
@@ -465,6 +476,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   __shared__ uint16_t rows[kRangeTokens * RPW];  // selected tokens, relative to the workgroup's first token
   __shared__ uint32_t scan_tmp[4];
   __shared__ uint32_t flag;
+  __shared__ int32_t lblk[RPW * kRangeTokens / 64];  // paged rows: block numbers of this workgroup's tokens
 
   const int tid = threadIdx.x;
   const int cn = tid & 15;
@@ -475,6 +487,11 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   const int tok0 = wg * RPW * kRangeTokens;
   if (tok0 >= n && wg != 0) return;
   FIER_PROF(20, unit == 0 && wg == 3)
+  const KvRows kv = lay.rows_of(unit);
+  if (kv.blocks && tid < RPW * kRangeTokens / 64) {  // in flight during the selection; barriers follow
+    const int bi = (tok0 >> kv.shift) + tid;
+    lblk[tid] = bi < lay.blocks_per_seq ? kv.blocks[bi] : 0;
+  }
   UnitCtl* __restrict__ c = &ctl[unit];
   const int tbin = c->tbin;
   const float R = c->R, hscale = c->scale;
@@ -539,18 +556,22 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   FIER_PROF(21, unit == 0 && wg == 3)
 
   // ---- attention over the selected rows of these ranges --------------------------------------------------------
-  const KvRows kv = lay.rows_of(unit);
   uint4 qr[NREP];
 #pragma unroll
   for (int h = 0; h < NREP; ++h) qr[h] = q[((size_t)unit * NREP + h) * (kD / 8) + cn];
   AttnState<NREP> st;
   st.init();
+  const int first_block = tok0 >> kv.shift;
+  auto row_of = [&](int j) {
+    const int t = tok0 + (int)rows[j];
+    return kv.blocks ? (size_t)lblk[(t >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(t & kv.mask)
+                     : kv.base + (size_t)t;
+  };
   if constexpr (NREP >= 3)
-    attend_rows_mfma<DT, NREP>(K, V, kv, q + (size_t)unit * NREP * (kD / 8), [&](int j) { return tok0 + (int)rows[j]; },
-                               0, (int)n_sel_total, max_ctx, scale_log2e, st, sh_o);
+    attend_rows_mfma<DT, NREP>(K, V, q + (size_t)unit * NREP * (kD / 8), row_of, 0, (int)n_sel_total, scale_log2e, st,
+                               sh_o);
   else
-    attend_rows<DT, NREP>(K, V, kv, qr, [&](int j) { return tok0 + (int)rows[j]; }, 0, (int)n_sel_total, max_ctx,
-                          scale_log2e, st);
+    attend_rows<DT, NREP>(K, V, qr, row_of, 0, (int)n_sel_total, scale_log2e, st);
   FIER_PROF(22, unit == 0 && wg == 3)
   store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, po, pm, pl);
   FIER_PROF(23, unit == 0 && wg == 3)
@@ -613,6 +634,7 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
                                  int units, int n_kv_heads, int max_ctx, hipStream_t st) {
   dim3 grid(n_splits, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
+  if (!idx && rows_per_wg > kAttnRowsDense) return hipErrorInvalidValue;  // the kernel's block-number window
 #define FIER_ATTN_CASE(R)                                                                                          \
   case R:                                                                                                          \
     attn_split_kernel<DT, R><<<grid, 256, 0, st>>>((const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count,  \
