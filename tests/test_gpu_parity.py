@@ -399,21 +399,39 @@ def test_fused_step_multi_layer(gu, oracle):
         assert np.abs(out.cpu().numpy()[l] - want).max() <= 2e-3
 
 
-def _full_size_case(gu, oracle, shape, seed, sample_units):
+def _full_size_case(gu, oracle, shape, seed, sample_units, block_tokens=0):
     """A full-size workload generated on the GPU exactly as bench.py does, run through fier_decode_step in the
-    launch configuration bench.py times, and checked against the oracle on a sample of units."""
-    d = synth.make_workload_device("full", seed, shape["batch"], shape["n_q_heads"], shape["n_kv_heads"],
-                                   [shape["L"]] * shape["batch"], [shape["budget"]] * shape["batch"], shape["dtype"],
-                                   max_ctx=-(-(shape["L"] + 1) // 64) * 64, chan=shape["chan"],
+    launch configuration bench.py times, and checked against the oracle on a sample of units.  shape["L"] and
+    shape["budget"] are one number or one per sequence; block_tokens != 0 moves the rows into a shuffled block
+    pool first."""
+    batch, Hq, Hkv, dtype = (shape[k] for k in ("batch", "n_q_heads", "n_kv_heads", "dtype"))
+    lens = np.broadcast_to(np.asarray(shape["L"], np.int64), (batch,)).copy()
+    buds = np.broadcast_to(np.asarray(shape["budget"], np.int64), (batch,)).copy()
+    gran = max(64, block_tokens)
+    d = synth.make_workload_device("full", seed, batch, Hq, Hkv, lens, buds, dtype,
+                                   max_ctx=-(-(int(lens.max()) + 1) // gran) * gran, chan=shape["chan"],
                                    n_planted=shape["n_planted"])
-    batch, Hq, Hkv, L, budget, dtype = (shape[k] for k in ("batch", "n_q_heads", "n_kv_heads", "L", "budget", "dtype"))
+    budget = int(buds.max())
     max_ctx = d["max_ctx"]
     cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype)
     n_rep = cfg.n_rep
     # host copies of the sampled units BEFORE the step (the step appends in place)
     K0 = {u: synth.words_of(d["K"][u]) for u in sample_units}
     V0 = {u: synth.words_of(d["V"][u]) for u in sample_units}
-    cache = B.DeviceCache(cfg, d["K"], d["V"], d["seq_lens"])
+    if block_tokens:
+        per_seq = max_ctx // block_tokens
+        table = torch.randperm(batch * per_seq, generator=torch.Generator().manual_seed(seed)).to(torch.int32).cuda()
+        pools = []
+        for name in ("K", "V"):
+            blocks = d[name].view(batch, Hkv, per_seq, block_tokens, 128).permute(0, 2, 1, 3, 4)
+            blocks = blocks.reshape(-1, Hkv, block_tokens, 128).contiguous()
+            pool = torch.empty_like(blocks)
+            pool[table.long()] = blocks
+            pools.append(pool)
+            d[name] = None
+        cache = B.DeviceCache(cfg, pools[0], pools[1], d["seq_lens"], table.view(batch, per_seq).contiguous())
+    else:
+        cache = B.DeviceCache(cfg, d["K"], d["V"], d["seq_lens"])
     B.quantize_keys(cfg, cache)
     out = torch.zeros((1, batch, Hq, 128), dtype=torch.float32, device="cuda")
     idx = torch.full((1, cfg.units, budget), -1, dtype=torch.int32, device="cuda")
@@ -430,13 +448,15 @@ def _full_size_case(gu, oracle, shape, seed, sample_units):
     kb = cache.kbits.view(cfg.units, max_ctx, 4)
     km = cache.kmeta.view(cfg.units, max_ctx // 32, 128)
     for u in sample_units:
+        L, bud_u = int(lens[u // Hkv]), int(min(buds[u // Hkv], lens[u // Hkv] + 1))
         wl = synth.Workload("unit", 1, n_rep, 1, 128, max_ctx, dtype, np.array([L], np.int32),
-                            np.array([budget], np.int32), K0[u][None].copy(), V0[u][None].copy(), q_all[u][None].copy(),
+                            np.array([bud_u], np.int32), K0[u][None].copy(), V0[u][None].copy(), q_all[u][None].copy(),
                             kn_all[u][None].copy(), vn_all[u][None].copy(), [d["planted"][u]])
         r = oracle_step(oracle, wl, append=True, n_threads=8)
-        swapped = check_index_sets(idx_g[u:u + 1], cnt_g[u:u + 1], r["idx"], r["count"], r["scores"], r["L"])
+        ig = np.ascontiguousarray(idx_g[u:u + 1, :bud_u])
+        swapped = check_index_sets(ig, cnt_g[u:u + 1], r["idx"], r["count"], r["scores"], r["L"])
         want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], dtype,
-                                np.ascontiguousarray(np.where(idx_g[u:u + 1] < 0, 0, idx_g[u:u + 1])), cnt_g[u:u + 1], 8)
+                                np.ascontiguousarray(np.where(ig < 0, 0, ig)), cnt_g[u:u + 1], 8)
         err = np.abs(out_g[u] - want[0]).max()
         assert err <= 2e-3, (u, err)
         # packed state of the unit after the append, bit for bit
@@ -457,9 +477,14 @@ def _full_size_case(gu, oracle, shape, seed, sample_units):
         assert set(d["planted"][u].tolist()) <= set(idx_g[u, :cnt_g[u]].tolist())
         print(f"[full-size] unit {u}: swapped near-ties {swapped}, attention max err {err:.2e}", flush=True)
     # properties that hold for every unit at any size
-    assert np.all(cnt_g == budget)
-    assert np.all(np.diff(idx_g, axis=1) > 0) and idx_g.min() >= 0 and idx_g.max() <= L
+    unit_len = np.repeat(lens, Hkv)
+    unit_bud = np.minimum(np.repeat(buds, Hkv), unit_len + 1)
+    assert np.array_equal(cnt_g, unit_bud)
+    for u in range(cfg.units):
+        sel = idx_g[u, :unit_bud[u]]
+        assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] <= unit_len[u], u
     assert np.all(np.isfinite(out_g))
+    return out_g, idx_g
 
 
 def test_full_size_config2_sampled_units(gu, oracle):
@@ -472,6 +497,34 @@ def test_full_size_config3_sampled_units(gu, oracle):
     """Llama-3-8B-shaped GQA layer: batch 4, 32 q / 8 kv heads, 131072 tokens, bf16, budget 4096."""
     _full_size_case(gu, oracle, dict(batch=4, n_q_heads=32, n_kv_heads=8, L=131072, budget=4096, dtype=BF16,
                                      chan="lognormal", n_planted=64), 3000, [5, 30])
+
+
+@pytest.mark.parametrize("budget", [256, 16384])
+def test_full_size_config4_sampled_units(gu, oracle, budget):
+    """The budget sweep's shape (32 MHA heads, 65536 tokens) at its two ends: 8 ranges per workgroup of the last
+    kernel at B = 256, a quarter of the cache gathered at B = 16384."""
+    _full_size_case(gu, oracle, dict(batch=1, n_q_heads=32, n_kv_heads=32, L=65536, budget=budget, dtype=F16,
+                                     chan="ones", n_planted=64), 4000 + budget, [7, 22])
+
+
+def test_full_size_config5_layer_sampled_units(gu, oracle):
+    """One layer of the ragged serving batch: 16 sequences of 8192..65536 tokens, 32 q / 8 kv heads, bf16, budget
+    11 % of each context; the shortest and the longest sequence are among the sampled units."""
+    rng = np.random.default_rng(5000)
+    lens = rng.integers(8192, 65537, size=16)
+    buds = np.array([int(round(0.11 * int(l))) for l in lens])
+    lo, hi = int(np.argmin(lens)), int(np.argmax(lens))
+    _full_size_case(gu, oracle, dict(batch=16, n_q_heads=32, n_kv_heads=8, L=lens, budget=buds, dtype=BF16,
+                                     chan="lognormal", n_planted=64), 5000, [8 * lo + 3, 8 * hi + 6, 77])
+
+
+def test_full_size_config2_paged_equals_contiguous(gu, oracle):
+    """The bench configuration with its rows in 64-token blocks behind a shuffled block table: the same outputs and
+    the same index lists as the contiguous layout, bit for bit (one unit also against the oracle)."""
+    shape = dict(batch=1, n_q_heads=32, n_kv_heads=32, L=32768, budget=3604, dtype=F16, chan="ones", n_planted=64)
+    out_c, idx_c = _full_size_case(gu, oracle, shape, 2000, [])
+    out_p, idx_p = _full_size_case(gu, oracle, shape, 2000, [13], block_tokens=64)
+    assert np.array_equal(out_c, out_p) and np.array_equal(idx_c, idx_p)
 
 
 def test_decode_step_phases_equal_the_fused_call(gu):
