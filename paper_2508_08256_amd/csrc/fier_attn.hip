@@ -487,6 +487,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   const int tok0 = wg * RPW * kRangeTokens;
   if (tok0 >= n && wg != 0) return;
   FIER_PROF(20, unit == 0 && wg == 3)
+  FIER_PROF_WG(5)
   const KvRows kv = lay.rows_of(unit);
   if (kv.blocks && tid < RPW * kRangeTokens / 64) {  // in flight during the selection; barriers follow
     const int bi = (tok0 >> kv.shift) + tid;
@@ -575,6 +576,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   FIER_PROF(22, unit == 0 && wg == 3)
   store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, po, pm, pl);
   FIER_PROF(23, unit == 0 && wg == 3)
+  FIER_PROF_WG(6)
 
   const int n_wgs = (n + RPW * kRangeTokens - 1) / (RPW * kRangeTokens);  // workgroups of this unit in use
   if (!last_arriver(&c->arrive[2], n_wgs > 0 ? (uint32_t)n_wgs : 1u, &flag)) return;
@@ -583,6 +585,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   merge_heads<NREP>(po, pm, pl, unit, n_slots, n_wgs, sh_o, out + (size_t)unit * NREP * kD);
   if (tid == 0) c->arrive[2] = 0;
   FIER_PROF(25, unit == 0)
+  FIER_PROF_WG(7)
   // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
   if (extra && seq_lens[b] < max_ctx && tid < kD) {
     float* slot = kabsmax + (size_t)unit * kD + tid;

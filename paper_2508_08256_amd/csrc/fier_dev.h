@@ -9,8 +9,14 @@
 extern __device__ unsigned long long fier_prof_slots[64];
 #define FIER_PROF(slot, cond) \
   if ((cond) && threadIdx.x == 0) fier_prof_slots[slot] = wall_clock64();
+// one time stamp per workgroup and point (the host reduces them)
+extern __device__ unsigned long long fier_prof_wg[8][4096];
+#define FIER_PROF_WG(point)                                                                  \
+  if (threadIdx.x == 0 && blockIdx.y * gridDim.x + blockIdx.x < 4096)                        \
+    fier_prof_wg[point][blockIdx.y * gridDim.x + blockIdx.x] = wall_clock64();
 #else
 #define FIER_PROF(slot, cond)
+#define FIER_PROF_WG(point)
 #endif
 
 namespace fier {

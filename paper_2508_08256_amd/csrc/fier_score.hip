@@ -66,8 +66,8 @@ __device__ __forceinline__ uint32_t row_allmax_u32(uint32_t x) {
   return x;
 }
 
-// grid (ceil(max_ctx / (256 bpw)) [+ 1 if HIST], units), block 256: workgroup x owns 4 bpw consecutive pair blocks
-// of its unit, wave w the blocks 4 bpw x + w, + 4, + 8, ...  The launcher picks bpw so that the whole grid is
+// grid (units * (n_x [+ 1 if HIST])), n_x = ceil(max_ctx / (256 bpw)), block 256: scoring workgroup x of a unit
+// owns 4 bpw consecutive pair blocks, wave w the blocks 4 bpw x + w, + 4, + 8, ...  The launcher picks bpw so that the whole grid is
 // resident at once: the per-workgroup prologue (q, R) and epilogue (histogram flush, arrival) are then paid once.
 //
 // HIST (first kernel of the fused step): every score is also counted in an equal-width histogram of kSelBins
@@ -89,14 +89,21 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
                                                     int max_budget, uint32_t* __restrict__ K, uint32_t* __restrict__ V,
                                                     const uint32_t* __restrict__ k_new,
                                                     const uint32_t* __restrict__ v_new, float* __restrict__ newmax,
-                                                    int n_kv_heads, int max_ctx, int bpw, int gshift, KvLayout lay) {
+                                                    int n_kv_heads, int max_ctx, int bpw, int gshift, int n_x, KvLayout lay) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
   __shared__ __attribute__((aligned(16))) unsigned char a_lds[4 * kAWave];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int unit = blockIdx.y;
+  // Workgroups are dispatched in the order of their index.  HIST: the first `units` workgroups are the appending
+  // ones (their single wavefront has the longest chain of dependent loads: started last, it would end the kernel
+  // late), then n_x scoring workgroups per unit, a unit's ranges next to each other.
+  const int n_units = (int)gridDim.x / (n_x + (HIST ? 1 : 0));
+  const bool append_wg = HIST && (int)blockIdx.x < n_units;
+  const int wid = (int)blockIdx.x - (HIST ? n_units : 0);
+  const int unit = append_wg ? (int)blockIdx.x : wid / n_x;
+  const int range = append_wg ? -1 : wid - unit * n_x;
   const int b = unit / n_kv_heads;
   int Lold = seq_lens[b];
   Lold = Lold < 0 ? 0 : (Lold > max_ctx ? max_ctx : Lold);
@@ -105,10 +112,6 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   L = L > max_ctx ? max_ctx : L;
   const int gsize = kG << gshift;  // tokens per quantization group: 32, 64, 128 or 256
   const int tail_start = app ? (Lold / gsize) * gsize : L;  // tokens from here on are scored by the appending wave
-  // HIST: workgroup 0 is the appending one (dispatched first: its single wavefront has the longest chain of
-  // dependent loads), workgroups 1.. score the ranges 0..
-  const bool append_wg = HIST && blockIdx.x == 0;
-  const int range = (int)blockIdx.x - (HIST ? 1 : 0);
   if (append_wg) {
     if (!app) return;
   } else {
@@ -120,6 +123,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const int gsel = row >> 1;  // the group of the pair block whose (s, z) this row of lanes holds
   const int hsel = row & 1;   // the 64-channel half it holds
   FIER_PROF(0, HIST && unit == 0 && range == 3)
+  if (HIST) { FIER_PROF_WG(0) }
   FIER_PROF(7, HIST && unit == 0 && append_wg)
 
   // ---- first block's loads go out before anything else (their addresses do not depend on q) ----------------
@@ -401,6 +405,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       c->scale = hscale;
     }
     FIER_PROF(3, unit == 0 && range == 3)
+    FIER_PROF_WG(1)
   }
 }
 
@@ -418,14 +423,15 @@ static hipError_t launch_score_dt(KvLayout lay, int n_rep, const uint32_t* kbits
   const int per_unit = wg_slots / units > 0 ? wg_slots / units : 1;
   int bpw = (n_blocks + 4 * per_unit - 1) / (4 * per_unit);
   bpw = bpw < 4 ? 4 : bpw;
-  dim3 grid((n_blocks + 4 * bpw - 1) / (4 * bpw) + (HIST ? 1 : 0), units);
+  const int n_x = (n_blocks + 4 * bpw - 1) / (4 * bpw);  // scoring workgroups per unit
+  dim3 grid((unsigned)units * (unsigned)(n_x + (HIST ? 1 : 0)));
 #define FIER_SCORE_CASE(R)                                                                                         \
   case R:                                                                                                          \
     score_kernel<DT, R, HIST><<<grid, 256, 0, st>>>(                                                               \
         (const uint4*)kbits, (const uint4*)kmeta, kabsmax, (const uint16_t*)q, seq_lens, extra, scores,            \
         sb ? sb->ctl : nullptr, sb ? sb->hist : nullptr, budgets, max_budget, (uint32_t*)K, (uint32_t*)V,          \
         (const uint32_t*)k_new, (const uint32_t*)v_new, sb ? sb->newmax : nullptr, n_kv_heads, max_ctx, bpw,     \
-        gshift, lay);                                                                                             \
+        gshift, n_x, lay);                                                                                        \
     break;
   switch (n_rep) {
     FIER_SCORE_CASE(1)

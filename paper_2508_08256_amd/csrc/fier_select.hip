@@ -61,6 +61,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   constexpr int kChunkTokens = kClassifyTokens * NV;
   if (chunk * kChunkTokens >= n && chunk != 0) return;
   FIER_PROF(10, unit == 0 && chunk == 1)
+  FIER_PROF_WG(2)
   UnitCtl* __restrict__ c = &ctl[unit];
   const float R = c->R, scale = c->scale;
   const float* __restrict__ s = scores + (size_t)unit * max_ctx;
@@ -147,6 +148,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
   if (tid == 4 * NV) store_coherent(&useg[chunk], n_local);
   const int nc = n > 0 ? (n + kChunkTokens - 1) / kChunkTokens : 1;  // workgroups of this unit
   FIER_PROF(12, unit == 0 && chunk == 1)
+  FIER_PROF_WG(3)
   if (!last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) return;
   FIER_PROF(13, unit == 0)
 
@@ -230,6 +232,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     if (count_out) count_out[unit] = B;
   }
   FIER_PROF(16, unit == 0)
+  FIER_PROF_WG(4)
 }
 
 hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, const int32_t* budgets,

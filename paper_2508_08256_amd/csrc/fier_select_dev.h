@@ -1,5 +1,5 @@
-// Exact threshold selection among the candidates of the threshold bin, as device functions shared by the
-// threshold kernel (long contexts) and by the tail of the score kernel (contexts up to 64k tokens).
+// Exact threshold selection among the candidates of the threshold bin: device functions of the threshold kernel
+// (second kernel of the fused step).
 #pragma once
 
 #include "fier_dev.h"
