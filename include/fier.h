@@ -172,7 +172,8 @@ int fier_dense_attn(const fier_config *cfg, const fier_cache *cache, const void 
  *   idx_out / count_out   optional (NULL): [n_layers][units][max_budget] / [n_layers][units], the
  *            selection of every layer, for inspection
  *   workspace  fier_workspace_bytes(cfg, max_budget) bytes, reused by every layer
- * seq_lens are not modified.
+ * seq_lens are not modified.  A sequence whose cache is full (seq_len >= max_ctx) is not appended
+ * to: the step works on its max_ctx rows as if k_new were NULL for it.
  */
 int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
                      const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,

@@ -527,6 +527,46 @@ def test_full_size_config2_paged_equals_contiguous(gu, oracle):
     assert np.array_equal(out_c, out_p) and np.array_equal(idx_c, idx_p)
 
 
+def test_maximum_context_capacity(gu, oracle):
+    """max_ctx = 2^20, the largest the library accepts: 2^20 - 1 cached tokens, the step appends the last row
+    (1024 ranges, 256 classification stretches, 16384 pair blocks per unit); two query heads on one kv head."""
+    _full_size_case(gu, oracle, dict(batch=1, n_q_heads=2, n_kv_heads=1, L=(1 << 20) - 1, budget=50000, dtype=BF16,
+                                     chan="lognormal", n_planted=64), 6000, [0])
+
+
+def test_full_cache_is_not_appended_to(gu):
+    """A unit with seq_len == max_ctx keeps its rows: the step with k_new equals the step without, over max_ctx
+    rows, and the cache (rows, packed codes, metadata) is untouched; the other sequence of the batch still appends."""
+    import gpu_util
+
+    wl = synth.make_workload("fullcache", 77, 2, 4, 2, [1024, 700], [96, 64], F16, max_ctx=1024, n_planted=4)
+    runs = []
+    for append in (True, False):
+        dw = gpu_util.DeviceWorkload(wl)
+        B.quantize_keys(dw.cfg, dw.cache)
+        torch.cuda.synchronize()
+        before = (dw.K[:2].clone(), dw.V[:2].clone(), dw.cache.kbits.clone(), dw.cache.kmeta.clone())
+        out = torch.zeros((1, wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+        idx = torch.full((1, wl.units, 96), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+        kn = dw.k_new[None].contiguous() if append else None
+        vn = dw.v_new[None].contiguous() if append else None
+        B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, 96, out, idx, cnt,
+                      dw.workspace(96))
+        torch.cuda.synchronize()
+        if append:   # units 0, 1 belong to the full sequence
+            assert torch.equal(dw.K[:2], before[0]) and torch.equal(dw.V[:2], before[1])
+            per_unit_bits = dw.cache.kbits.numel() // wl.units
+            per_unit_meta = dw.cache.kmeta.numel() // wl.units
+            assert torch.equal(dw.cache.kbits[:2 * per_unit_bits], before[2][:2 * per_unit_bits])
+            assert torch.equal(dw.cache.kmeta[:2 * per_unit_meta], before[3][:2 * per_unit_meta])
+            assert torch.equal(gu.to_dev(wl.k_new, F16)[2:], dw.K[2:, 700])       # the other sequence did append
+        runs.append((out.cpu().numpy()[0], idx.cpu().numpy()[0], cnt.cpu().numpy()[0]))
+    for a, b in zip(*runs):
+        assert np.array_equal(a[:2], b[:2])
+    assert runs[0][2].tolist() == [96, 96, 64, 64]
+
+
 def test_decode_step_phases_equal_the_fused_call(gu):
     wl = synth.config1()
     import gpu_util
