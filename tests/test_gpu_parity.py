@@ -527,6 +527,24 @@ def test_full_size_config2_paged_equals_contiguous(gu, oracle):
     assert np.array_equal(out_c, out_p) and np.array_equal(idx_c, idx_p)
 
 
+def test_fused_step_empty_sequence_and_zero_budget(gu, oracle):
+    """An empty sequence that receives its first row attends to that row alone (output = v_new); without the
+    append it yields zeros; a budget of 0 selects nothing and yields zeros."""
+    wl = synth.make_workload("empty", 91, 3, 6, 3, [0, 500, 0], [5, 0, 0], BF16, max_ctx=512, n_planted=0, plant=False)
+    dw, out, idx, cnt = _fused(gu, wl, append=True)
+    assert cnt.tolist() == [1, 1, 1, 0, 0, 0, 0, 0, 0]
+    assert np.array_equal(idx[:3, 0], [0, 0, 0])
+    v_new = synth.words_to_f32(wl.v_new, BF16)
+    for u in range(3):
+        for r in range(wl.n_rep):
+            assert np.array_equal(out[u, r], v_new[u])
+    assert not out[3:].any()
+    r = oracle_step(oracle, wl, append=True)
+    assert np.array_equal(cnt, r["count"]) and np.abs(out - r["out"]).max() <= 2e-3
+    dw, out, idx, cnt = _fused(gu, wl, append=False)
+    assert not cnt.any() and not out.any()
+
+
 def test_maximum_context_capacity(gu, oracle):
     """max_ctx = 2^20, the largest the library accepts: 2^20 - 1 cached tokens, the step appends the last row
     (1024 ranges, 256 classification stretches, 16384 pair blocks per unit); two query heads on one kv head."""
