@@ -55,18 +55,20 @@ __device__ __forceinline__ GroupScale group_scale(MinMax m) {
   g.zf0 = w2f<DT>(g.z0), g.zf1 = w2f<DT>(g.z1);
   return g;
 }
-// Codes of up to 32 rows (tokens 0..ntok-1 present) under scale g.  Lane lane_base + t receives the 128-bit code
-// word of token t in `mine`; b0 / b1 collect the lane's own two channels (bit t = token t).
-template <int DT>
+// Codes of up to 32 rows (tokens 0..ntok-1 present; FULL: all 32, ntok is not looked at) under scale g.  Lane
+// lane_base + t receives the 128-bit code word of token t in `mine`; b0 / b1 collect the lane's own two channels
+// (bit t = token t).
+template <int DT, bool FULL = false>
 __device__ __forceinline__ void code_rows(const uint32_t (&rows)[kG], int ntok, const GroupScale& g, int lane,
                                           int lane_base, uint4& mine, uint32_t& b0, uint32_t& b1) {
 #pragma clang fp contract(off)
   b0 = 0, b1 = 0;
+  uint32_t r = rows[0];
 #pragma unroll
   for (int t = 0; t < kG; ++t) {
-    const float a = lo16f<DT>(rows[t]) - g.zf0;
-    const float b = hi16f<DT>(rows[t]) - g.zf1;
-    const bool present = t < ntok;
+    const float a = lo16f<DT>(r) - g.zf0;
+    const float b = hi16f<DT>(r) - g.zf1;
+    const bool present = FULL || t < ntok;
     const bool c0 = present && (a + a >= g.sf0), c1 = present && (b + b >= g.sf1);
     const uint64_t even = __ballot(c0);
     const uint64_t odd = __ballot(c1);
@@ -74,6 +76,13 @@ __device__ __forceinline__ void code_rows(const uint32_t (&rows)[kG], int ntok, 
     b1 |= c1 ? (1u << t) : 0u;
     if (lane == lane_base + t)
       mine = make_uint4((uint32_t)even, (uint32_t)(even >> 32), (uint32_t)odd, (uint32_t)(odd >> 32));
+    if (t + 1 < kG) {
+      // An empty statement that "produces" the next row and `mine`: the next row's compares cannot start before
+      // this row's ballots have been used up.  Left to itself the compiler makes the ballots of all 32 rows first,
+      // and 64 of them do not fit the scalar registers (they were spilled to vector lanes and read back).
+      r = rows[t + 1];
+      asm volatile("" : "+v"(r), "+v"(mine.x), "+v"(mine.y), "+v"(mine.z), "+v"(mine.w));
+    }
   }
 }
 template <int DT>

@@ -20,18 +20,97 @@
 
 namespace fier {
 
-// grid (ceil(n_pairs / 4), units), block 256: wave w of block x owns pair block 4x + w.
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+// Both 16-bit floats of a word as signed integers that order like the floats (sign-magnitude -> two's
+// complement; the map is its own inverse).  Minimum and maximum of finite values can then be taken two channels
+// at a time with packed integer instructions, for fp16 and bf16 alike; -0 sorts below +0, which the
+// canonicalisation of zeros in group_scale makes immaterial.
+__device__ __forceinline__ short2_t order_keys(uint32_t pair) {
+  const short2_t v = __builtin_bit_cast(short2_t, pair);
+  return v ^ ((v >> 15) & (short)0x7fff);
+}
+
+// Whole pair blocks (64 tokens present).  grid (ceil(n_pairs / (4 bpw)), units), block 256: wave w of workgroup x
+// owns the pair blocks 4 bpw x + w, + 4, + 8, ...  The 32 rows of a group sit in registers (one dword per row and
+// lane).  As soon as a group of a pair block has been coded, its registers receive the same group of the wave's
+// next block, so that one group (8 KiB per wavefront) is in flight while the other is worked on.  A unit's last,
+// partial pair block is left to quantize_tail_kernel.
 template <int DT>
 __global__ __launch_bounds__(256) void quantize_kernel(const uint32_t* __restrict__ K, uint32_t* __restrict__ kbits,
                                                        uint32_t* __restrict__ kmeta, float* __restrict__ kabsmax,
                                                        const int32_t* __restrict__ seq_lens, int n_kv_heads,
-                                                       int max_ctx, KvLayout lay) {
+                                                       int max_ctx, int bpw, KvLayout lay) {
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  // the wavefront's number as a scalar: everything derived from it (addresses, branches) is then uniform for the
+  // compiler too
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int unit = blockIdx.y;
-  const int P = blockIdx.x * 4 + wave;
+  const int P0 = blockIdx.x * (4 * bpw) + wave;
   int L = seq_lens[unit / n_kv_heads];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
+  const int n_full = L / kPair;
+  if (P0 >= n_full) return;
+  const int n_groups = max_ctx / kG;
+  const KvRows kv = lay.rows_of(unit);
+  auto load_group = [&](uint32_t (&rows)[kG], int P, int h) {
+    const uint32_t* src = K + kv.row(P * kPair + h * kG) * (kD / 2) + lane;
+#pragma unroll
+    for (int t = 0; t < kG; ++t) rows[t] = src[t * (kD / 2)];
+  };
+  float amax0 = 0.f, amax1 = 0.f;
+  uint4 mine;
+  auto quantize = [&](const uint32_t (&rows)[kG], int P, int h) {
+    short2_t mn = order_keys(rows[0]), mx = mn;
+#pragma unroll
+    for (int t = 1; t < kG; ++t) {
+      const short2_t k = order_keys(rows[t]);
+      mn = __builtin_elementwise_min(mn, k);
+      mx = __builtin_elementwise_max(mx, k);
+    }
+    const uint32_t mnw = __builtin_bit_cast(uint32_t, order_keys(__builtin_bit_cast(uint32_t, mn)));
+    const uint32_t mxw = __builtin_bit_cast(uint32_t, order_keys(__builtin_bit_cast(uint32_t, mx)));
+    MinMax m;
+    m.mn0 = lo16f<DT>(mnw), m.mn1 = hi16f<DT>(mnw);
+    m.mx0 = lo16f<DT>(mxw), m.mx1 = hi16f<DT>(mxw);
+    const GroupScale g = group_scale<DT>(m);
+    uint32_t b0, b1;
+    code_rows<DT, true>(rows, kG, g, lane, h * kG, mine, b0, b1);
+    uint2* mdst = reinterpret_cast<uint2*>(kmeta + ((size_t)unit * n_groups + 2 * P + h) * kD) + lane;
+    *mdst = make_uint2(g.s0 | (g.z0 << 16), g.s1 | (g.z1 << 16));
+    amax0 = fmaxf(amax0, fmaxf(fabsf(g.zf0), fabsf(g.zf0 + g.sf0)));
+    amax1 = fmaxf(amax1, fmaxf(fabsf(g.zf1), fabsf(g.zf1 + g.sf1)));
+  };
+  uint32_t ra[kG], rb[kG];
+  load_group(ra, P0, 0);
+  load_group(rb, P0, 1);
+  for (int i = 0; i < bpw; ++i) {
+    const int P = P0 + 4 * i;
+    if (P >= n_full) break;
+    const bool more = i + 1 < bpw && P + 4 < n_full;
+    mine = make_uint4(0, 0, 0, 0);
+    quantize(ra, P, 0);
+    if (more) load_group(ra, P + 4, 0);
+    quantize(rb, P, 1);
+    if (more) load_group(rb, P + 4, 1);
+    reinterpret_cast<uint4*>(kbits)[(size_t)unit * max_ctx + P * kPair + lane] = mine;
+  }
+  raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane, amax0);
+  raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane + 1, amax1);
+}
+
+// grid (units), block 64: the unit's last pair block when it is partial (1 to 63 tokens present).
+template <int DT>
+__global__ __launch_bounds__(64) void quantize_tail_kernel(const uint32_t* __restrict__ K,
+                                                           uint32_t* __restrict__ kbits,
+                                                           uint32_t* __restrict__ kmeta, float* __restrict__ kabsmax,
+                                                           const int32_t* __restrict__ seq_lens, int n_kv_heads,
+                                                           int max_ctx, KvLayout lay) {
+  const int lane = threadIdx.x;
+  const int unit = blockIdx.x;
+  int L = seq_lens[unit / n_kv_heads];
+  L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
+  const int P = L / kPair;
   if (P * kPair >= L) return;
   const int n_groups = max_ctx / kG;
   uint4 mine = make_uint4(0, 0, 0, 0);
@@ -160,13 +239,28 @@ hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbi
                                                               n_kv_heads, max_ctx, ns, lay);
     return hipGetLastError();
   }
-  dim3 grid((max_ctx / kPair + 3) / 4, units);
-  if (dtype == DT_F16)
+  // Pair blocks per wavefront: as many as make the grid about one resident round (256 CUs x 4 workgroups), at
+  // most 12 (longer grids run in several rounds, see the score kernel's launcher for the reasons), and no power of
+  // two from 4 on: such strides between the concurrently streaming workgroups collide in the memory channels
+  // (config-2 shape: 93 / 82 / 105 / 86 us at 4 / 6 / 8 / 12).  One block per wavefront is 3 x slower: launch and
+  // the per-wavefront update of the unit's absmax dominate.
+  const int n_pairs = max_ctx / kPair;
+  int bpw = (int)(((long)n_pairs * units + 4L * 1024 - 1) / (4L * 1024));
+  const int rounds = (bpw + 11) / 12;
+  bpw = (bpw + rounds - 1) / rounds;
+  if (bpw >= 4 && (bpw & (bpw - 1)) == 0) ++bpw;
+  dim3 grid((n_pairs + 4 * bpw - 1) / (4 * bpw), units);
+  if (dtype == DT_F16) {
     quantize_kernel<DT_F16><<<grid, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                  max_ctx, lay);
-  else
+                                                  max_ctx, bpw, lay);
+    quantize_tail_kernel<DT_F16><<<units, 64, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
+                                                       max_ctx, lay);
+  } else {
     quantize_kernel<DT_BF16><<<grid, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                   max_ctx, lay);
+                                                   max_ctx, bpw, lay);
+    quantize_tail_kernel<DT_BF16><<<units, 64, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens,
+                                                        n_kv_heads, max_ctx, lay);
+  }
   return hipGetLastError();
 }
 
