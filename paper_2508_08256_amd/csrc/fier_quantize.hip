@@ -1,7 +1,7 @@
 // 1-bit group quantizer of the key cache (Alg. 1 step 1; Eq. 5 read as round-to-nearest, Sec. 3.3)
 // and the decode-stage append of Sec. 3.1.
 //
-// Group size 32 (the default; larger groups, g = 64 / 128 / 256, take quantize_long_kernel below):
+// Group size 32 (the default; the larger groups g = 64 / 128 / 256 differ in how min / max are combined):
 // one wavefront owns one pair block (64 tokens = two groups of 32).  Lane l owns channels 2l and 2l+1:
 // every row read is one fully coalesced 256-byte request and the min/max over the 32 tokens of a group
 // never leaves the lane's registers.  The packed layout is token-major (16 bytes per token), so the
@@ -31,75 +31,118 @@ __device__ __forceinline__ short2_t order_keys(uint32_t pair) {
   return v ^ ((v >> 15) & (short)0x7fff);
 }
 
-// Whole pair blocks (64 tokens present).  grid (ceil(n_pairs / (4 bpw)), units), block 256: wave w of workgroup x
-// owns the pair blocks 4 bpw x + w, + 4, + 8, ...  The 32 rows of a group sit in registers (one dword per row and
-// lane).  As soon as a group of a pair block has been coded, its registers receive the same group of the wave's
-// next block, so that one group (8 KiB per wavefront) is in flight while the other is worked on.  A unit's last,
-// partial pair block is left to quantize_tail_kernel.
-template <int DT>
+// Whole groups.  grid (ceil(n_pairs / (4 bpw)), units), block 256: wave w of workgroup x owns the pair blocks
+// 4 bpw x + w, + 4, + 8, ...; NS = group size / 32.  The 64 rows of a pair block sit in registers (one dword per
+// row and lane, two halves of 32).  As soon as a half has been coded, its registers receive the same half of the
+// wave's next block, so that 8 KiB per wavefront are in flight while the other half is worked on.
+//   NS = 1: the two halves are two groups.   NS = 2: the pair block is one group.
+//   NS = 4, 8: a group spans the pair blocks of 2 / 4 neighbouring wavefronts, which exchange their minima and
+//   maxima through LDS (one barrier per block): every row is still read exactly once.
+// A unit's last, partial group is left to the tail kernels.
+template <int DT, int NS>
 __global__ __launch_bounds__(256) void quantize_kernel(const uint32_t* __restrict__ K, uint32_t* __restrict__ kbits,
                                                        uint32_t* __restrict__ kmeta, float* __restrict__ kabsmax,
                                                        const int32_t* __restrict__ seq_lens, int n_kv_heads,
                                                        int max_ctx, int bpw, KvLayout lay) {
+  constexpr int kWavesPerGroup = NS >= 4 ? NS / 2 : 1;
+  __shared__ uint2 xch[2][4][64];  // [iteration parity][wavefront][lane]: packed (min, max) keys, NS >= 4 only
   const int lane = threadIdx.x & 63;
   // the wavefront's number as a scalar: everything derived from it (addresses, branches) is then uniform for the
   // compiler too
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int unit = blockIdx.y;
-  const int P0 = blockIdx.x * (4 * bpw) + wave;
+  const int base = blockIdx.x * (4 * bpw);
   int L = seq_lens[unit / n_kv_heads];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
-  const int n_full = L / kPair;
-  if (P0 >= n_full) return;
-  const int n_groups = max_ctx / kG;
+  // pair blocks that consist of whole groups
+  const int n_full = NS == 1 ? L / kPair : (L / (kG * NS)) * (NS / 2);
+  if (base >= n_full) return;
+  const int n_groups = max_ctx / (kG * NS);
   const KvRows kv = lay.rows_of(unit);
-  auto load_group = [&](uint32_t (&rows)[kG], int P, int h) {
+  auto load_half = [&](uint32_t (&rows)[kG], int P, int h) {
     const uint32_t* src = K + kv.row(P * kPair + h * kG) * (kD / 2) + lane;
 #pragma unroll
     for (int t = 0; t < kG; ++t) rows[t] = src[t * (kD / 2)];
   };
-  float amax0 = 0.f, amax1 = 0.f;
-  uint4 mine;
-  auto quantize = [&](const uint32_t (&rows)[kG], int P, int h) {
-    short2_t mn = order_keys(rows[0]), mx = mn;
+  auto minmax_keys = [&](const uint32_t (&rows)[kG], short2_t& mn, short2_t& mx) {
+    mn = mx = order_keys(rows[0]);
 #pragma unroll
     for (int t = 1; t < kG; ++t) {
       const short2_t k = order_keys(rows[t]);
       mn = __builtin_elementwise_min(mn, k);
       mx = __builtin_elementwise_max(mx, k);
     }
+  };
+  auto scale_of = [&](short2_t mn, short2_t mx) {
     const uint32_t mnw = __builtin_bit_cast(uint32_t, order_keys(__builtin_bit_cast(uint32_t, mn)));
     const uint32_t mxw = __builtin_bit_cast(uint32_t, order_keys(__builtin_bit_cast(uint32_t, mx)));
     MinMax m;
     m.mn0 = lo16f<DT>(mnw), m.mn1 = hi16f<DT>(mnw);
     m.mx0 = lo16f<DT>(mxw), m.mx1 = hi16f<DT>(mxw);
-    const GroupScale g = group_scale<DT>(m);
-    uint32_t b0, b1;
-    code_rows<DT, true>(rows, kG, g, lane, h * kG, mine, b0, b1);
-    uint2* mdst = reinterpret_cast<uint2*>(kmeta + ((size_t)unit * n_groups + 2 * P + h) * kD) + lane;
+    return group_scale<DT>(m);
+  };
+  float amax0 = 0.f, amax1 = 0.f;
+  auto store_meta = [&](int group, const GroupScale& g) {
+    uint2* mdst = reinterpret_cast<uint2*>(kmeta + ((size_t)unit * n_groups + group) * kD) + lane;
     *mdst = make_uint2(g.s0 | (g.z0 << 16), g.s1 | (g.z1 << 16));
     amax0 = fmaxf(amax0, fmaxf(fabsf(g.zf0), fabsf(g.zf0 + g.sf0)));
     amax1 = fmaxf(amax1, fmaxf(fabsf(g.zf1), fabsf(g.zf1 + g.sf1)));
   };
   uint32_t ra[kG], rb[kG];
-  load_group(ra, P0, 0);
-  load_group(rb, P0, 1);
+  if (base + wave < n_full) {
+    load_half(ra, base + wave, 0);
+    load_half(rb, base + wave, 1);
+  }
   for (int i = 0; i < bpw; ++i) {
-    const int P = P0 + 4 * i;
-    if (P >= n_full) break;
+    if (base + 4 * i >= n_full) break;  // the same for the whole workgroup
+    const int P = base + 4 * i + wave;
+    const bool active = P < n_full;  // the wavefronts of one group are active together
     const bool more = i + 1 < bpw && P + 4 < n_full;
-    mine = make_uint4(0, 0, 0, 0);
-    quantize(ra, P, 0);
-    if (more) load_group(ra, P + 4, 0);
-    quantize(rb, P, 1);
-    if (more) load_group(rb, P + 4, 1);
+    short2_t mn_a, mx_a, mn_b, mx_b;
+    if (active) {
+      minmax_keys(ra, mn_a, mx_a);
+      minmax_keys(rb, mn_b, mx_b);
+      if constexpr (NS >= 2) {
+        mn_a = __builtin_elementwise_min(mn_a, mn_b);
+        mx_a = __builtin_elementwise_max(mx_a, mx_b);
+      }
+    }
+    if constexpr (NS >= 4) {
+      if (active)
+        xch[i & 1][wave][lane] = make_uint2(__builtin_bit_cast(uint32_t, mn_a), __builtin_bit_cast(uint32_t, mx_a));
+      __syncthreads();  // the buffer of the other parity is rewritten only after the next barrier
+      if (active) {
+        const int first = wave & ~(kWavesPerGroup - 1);
+#pragma unroll
+        for (int k = 1; k < kWavesPerGroup; ++k) {
+          const uint2 o = xch[i & 1][first + ((wave + k) & (kWavesPerGroup - 1))][lane];
+          mn_a = __builtin_elementwise_min(mn_a, __builtin_bit_cast(short2_t, o.x));
+          mx_a = __builtin_elementwise_max(mx_a, __builtin_bit_cast(short2_t, o.y));
+        }
+      }
+    }
+    if (!active) continue;
+    const GroupScale ga = scale_of(mn_a, mx_a);
+    const GroupScale gb = NS == 1 ? scale_of(mn_b, mx_b) : ga;
+    uint4 mine = make_uint4(0, 0, 0, 0);
+    uint32_t b0, b1;
+    code_rows<DT, true>(ra, kG, ga, lane, 0, mine, b0, b1);
+    if (more) load_half(ra, P + 4, 0);
+    code_rows<DT, true>(rb, kG, gb, lane, kG, mine, b0, b1);
+    if (more) load_half(rb, P + 4, 1);
     reinterpret_cast<uint4*>(kbits)[(size_t)unit * max_ctx + P * kPair + lane] = mine;
+    if constexpr (NS == 1) {
+      store_meta(2 * P, ga);
+      store_meta(2 * P + 1, gb);
+    } else if ((P & (kWavesPerGroup - 1)) == 0) {  // the group's first wavefront
+      store_meta(P / (NS / 2), ga);
+    }
   }
   raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane, amax0);
   raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane + 1, amax1);
 }
 
-// grid (units), block 64: the unit's last pair block when it is partial (1 to 63 tokens present).
+// grid (units), block 64, g = 32: the unit's last pair block when it is partial (1 to 63 tokens present).
 template <int DT>
 __global__ __launch_bounds__(64) void quantize_tail_kernel(const uint32_t* __restrict__ K,
                                                            uint32_t* __restrict__ kbits,
@@ -141,24 +184,24 @@ __global__ __launch_bounds__(64) void quantize_tail_kernel(const uint32_t* __res
   raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane + 1, amax1);
 }
 
-// Groups of g = 32 ns tokens, ns in {2, 4, 8}.  grid (ceil(n_groups / 4), units), block 256: wave w of block x owns
-// group 4x + w.  The group's rows are read twice (min / max, then codes), 32 at a time; the second read hits L2.
+// grid (units), block 64, g = 32 ns with ns in {2, 4, 8}: the unit's last group when it is partial.  Its rows are
+// read twice (min / max, then codes), 32 at a time.
 template <int DT>
-__global__ __launch_bounds__(256) void quantize_long_kernel(const uint32_t* __restrict__ K,
-                                                            uint32_t* __restrict__ kbits,
-                                                            uint32_t* __restrict__ kmeta, float* __restrict__ kabsmax,
-                                                            const int32_t* __restrict__ seq_lens, int n_kv_heads,
-                                                            int max_ctx, int ns, KvLayout lay) {
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int unit = blockIdx.y;
+__global__ __launch_bounds__(64) void quantize_long_tail_kernel(const uint32_t* __restrict__ K,
+                                                                uint32_t* __restrict__ kbits,
+                                                                uint32_t* __restrict__ kmeta,
+                                                                float* __restrict__ kabsmax,
+                                                                const int32_t* __restrict__ seq_lens, int n_kv_heads,
+                                                                int max_ctx, int ns, KvLayout lay) {
+  const int lane = threadIdx.x;
+  const int unit = blockIdx.x;
   const int g = kG * ns;
-  const int Gi = blockIdx.x * 4 + wave;
   int L = seq_lens[unit / n_kv_heads];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
+  const int Gi = L / g;
   const int t0 = Gi * g;
   if (t0 >= L) return;
-  const int ntok = L - t0 > g ? g : L - t0;
+  const int ntok = L - t0;
   const int n_groups = max_ctx / g;
   const uint32_t* src = K + lay.rows_of(unit).row(t0) * (kD / 2) + lane;
   auto row_at = [&](int t) { return src[(size_t)t * (kD / 2)]; };
@@ -224,21 +267,29 @@ __global__ __launch_bounds__(64) void append_kernel(uint32_t* __restrict__ K, ui
   raise_absmax(kabsmax + (size_t)unit * kD + 2 * lane + 1, amax_hi);
 }
 
+template <int DT>
+static void launch_quantize_dt(KvLayout lay, const uint32_t* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
+                               const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, int ns, int bpw,
+                               dim3 grid, hipStream_t st) {
+#define FIER_Q_ARGS K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads, max_ctx
+  switch (ns) {
+    case 1:
+      quantize_kernel<DT, 1><<<grid, 256, 0, st>>>(FIER_Q_ARGS, bpw, lay);
+      quantize_tail_kernel<DT><<<units, 64, 0, st>>>(FIER_Q_ARGS, lay);
+      return;
+    case 2: quantize_kernel<DT, 2><<<grid, 256, 0, st>>>(FIER_Q_ARGS, bpw, lay); break;
+    case 4: quantize_kernel<DT, 4><<<grid, 256, 0, st>>>(FIER_Q_ARGS, bpw, lay); break;
+    default: quantize_kernel<DT, 8><<<grid, 256, 0, st>>>(FIER_Q_ARGS, bpw, lay); break;
+  }
+  quantize_long_tail_kernel<DT><<<units, 64, 0, st>>>(FIER_Q_ARGS, ns, lay);
+#undef FIER_Q_ARGS
+}
+
 hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
                            const int32_t* seq_lens, int units, int n_kv_heads, int max_ctx, int group_size,
                            hipStream_t st) {
   zero_absmax_kernel<<<(units * kD + 255) / 256, 256, 0, st>>>(kabsmax, units * kD);
   const int ns = group_size / kG;
-  if (ns > 1) {
-    dim3 grid_long((max_ctx / group_size + 3) / 4, units);
-    if (dtype == DT_F16)
-      quantize_long_kernel<DT_F16><<<grid_long, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens,
-                                                             n_kv_heads, max_ctx, ns, lay);
-    else
-      quantize_long_kernel<DT_BF16><<<grid_long, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens,
-                                                              n_kv_heads, max_ctx, ns, lay);
-    return hipGetLastError();
-  }
   // Pair blocks per wavefront: as many as make the grid about one resident round (256 CUs x 4 workgroups), at
   // most 12 (longer grids run in several rounds, see the score kernel's launcher for the reasons), and no power of
   // two from 4 on: such strides between the concurrently streaming workgroups collide in the memory channels
@@ -250,17 +301,12 @@ hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbi
   bpw = (bpw + rounds - 1) / rounds;
   if (bpw >= 4 && (bpw & (bpw - 1)) == 0) ++bpw;
   dim3 grid((n_pairs + 4 * bpw - 1) / (4 * bpw), units);
-  if (dtype == DT_F16) {
-    quantize_kernel<DT_F16><<<grid, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                  max_ctx, bpw, lay);
-    quantize_tail_kernel<DT_F16><<<units, 64, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                       max_ctx, lay);
-  } else {
-    quantize_kernel<DT_BF16><<<grid, 256, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, n_kv_heads,
-                                                   max_ctx, bpw, lay);
-    quantize_tail_kernel<DT_BF16><<<units, 64, 0, st>>>((const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens,
-                                                        n_kv_heads, max_ctx, lay);
-  }
+  if (dtype == DT_F16)
+    launch_quantize_dt<DT_F16>(lay, (const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, units, n_kv_heads, max_ctx, ns,
+                               bpw, grid, st);
+  else
+    launch_quantize_dt<DT_BF16>(lay, (const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, units, n_kv_heads, max_ctx,
+                                ns, bpw, grid, st);
   return hipGetLastError();
 }
 

@@ -774,6 +774,25 @@ def test_larger_quantization_groups(gu, oracle, g, dtype):
     _compare_packed(dw, L, bits, s, z, g)
 
 
+@pytest.mark.parametrize("g", [32, 64, 128, 256])
+def test_bulk_quantizer_several_blocks_per_wavefront(gu, oracle, g):
+    """Large enough (4160 pair blocks) that the bulk quantizer gives every wavefront two pair blocks, the second
+    one loaded while the first is coded; one sequence ends in the middle of a group, the other on a group boundary.
+    Bits, (s, z) and the absmax bound against the oracle, bit for bit."""
+    dtype = BF16 if g in (64, 256) else F16
+    lens = [16384 + 37, 9 * 1024]
+    wl = synth.make_workload(f"bulk{g}", 500 + g, 2, 8, 8, lens, [64, 64], dtype, max_ctx=16640, n_planted=2,
+                             chan="lognormal")
+    dw = gu.DeviceWorkload(wl, group_size=g)
+    B.quantize_keys(dw.cfg, dw.cache)
+    torch.cuda.synchronize()
+    bits, s, z = oracle.quantize(wl.K, wl.unit_lens, g, dtype, 8)
+    _compare_packed(dw, wl.unit_lens, bits, s, z, g)
+    deq = np.abs(oracle.dequantize(bits, s, z, wl.unit_lens, g, dtype))
+    want = np.stack([deq[u, :wl.unit_lens[u]].max(axis=0) for u in range(wl.units)]).astype(np.float32)
+    assert np.array_equal(dw.cache.kabsmax.cpu().numpy().reshape(wl.units, 128), want)
+
+
 def test_mixed_step_dense_first_layers(gu, oracle):
     """Sec. 4.1 policy: the first layers attend over the whole cache, the others through the selection; one call."""
     import gpu_util
