@@ -346,6 +346,20 @@ def main():
     us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
     us_attn, _ = timed(st_attn, max(24, ns // 4), 4)
 
+    # ---- the bulk quantizer (once per sequence, after prefill) and the stand-alone append ------------------
+    # (after everything else: fier_append_key rewrites row L of the caches with the same k_new the steps used)
+    def st_quant(i):
+        r, l = flat[i % len(flat)]
+        B.quantize_keys(cfg, caches[r][l])
+
+    def st_append(i):
+        r, l = flat[i % len(flat)]
+        B.append_key(cfg, caches[r][l], kns[r][l], vns[r][l])
+
+    us_quant, _ = timed(st_quant, max(6, min(24, len(flat))), 2)
+    us_append, _ = timed(st_append, max(24, ns // 4), 4)
+    quant_bytes = int(Hkv * lens.sum() * (256 + 16 + 512 // args.group_size))   # K rows in, codes and (s, z) out
+
     stages = None
     if args.selector != "fier":
         def st_est(i):
@@ -423,7 +437,9 @@ def main():
                        "select_attend_merge": round(us_k3 / NL, 3), "sum": round((us_k1 + us_k2 + us_k3) / NL, 3)},
         "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "select_attend_merge": round(k3_gbps, 1)},
         "standalone_calls_us": {"fier_score": round(us_score, 3), "fier_topk": round(us_topk, 3),
-                                "fier_sparse_attn": round(us_attn, 3)},
+                                "fier_sparse_attn": round(us_attn, 3), "fier_append_key": round(us_append, 3),
+                                "fier_quantize_keys": round(us_quant, 3)},
+        "quantize_GBps": round(quant_bytes / (us_quant * 1e-6) / 1e9, 1),
         "dense_attn_us": round(us_dense, 3),
         "dense_attn_GBps": round(dense_bytes / (us_dense * 1e-6) / 1e9, 1),
         "speedup_vs_dense_attn": round(us_dense / us_layer, 3),
