@@ -68,6 +68,18 @@ inline int units_of(const fier_config* c) { return c->batch * c->n_kv_heads; }
 inline int n_rep_of(const fier_config* c) { return c->n_q_heads / c->n_kv_heads; }
 inline int splits_for(int max_budget) { return (max_budget + fier::kAttnRowsSparse - 1) / fier::kAttnRowsSparse; }
 
+// Rows per workgroup of whole-cache attention: about 640 workgroups in all (measured: the fewer and longer the
+// workgroups the better, down to two or three per CU; config 2: 117 us at 512 rows, 99 us at 2304), a multiple of
+// 128 that is not a power of two (such strides between the workgroups' streams collide in the memory channels).
+inline int dense_rows_per_wg(const fier_config* c) {
+  const long total = (long)units_of(c) * c->max_ctx;
+  long rows = (total / 640 + 127) / 128 * 128;
+  rows = rows < fier::kAttnRowsDenseMin ? fier::kAttnRowsDenseMin : rows;
+  rows = rows > fier::kAttnRowsDenseMax - 128 ? fier::kAttnRowsDenseMax - 128 : rows;
+  if ((rows & (rows - 1)) == 0) rows += 128;
+  return (int)rows;
+}
+
 inline int ranges_of(const fier_config* c) { return (c->max_ctx + fier::kRangeTokens - 1) / fier::kRangeTokens; }
 
 struct Workspace {
@@ -225,9 +237,10 @@ int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void*
   if (!workspace) return FIER_EWORKSPACE;
   if (misaligned(q) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
   Workspace w = carve(cfg, cfg->max_ctx, workspace);
-  const int n_splits = (cfg->max_ctx + fier::kAttnRowsDense - 1) / fier::kAttnRowsDense;
+  const int rows_per_wg = dense_rows_per_wg(cfg);
+  const int n_splits = (cfg->max_ctx + rows_per_wg - 1) / rows_per_wg;
   return hip_status(fier::launch_attn(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->k, cache->v, q, nullptr, nullptr,
-                                      cache->seq_lens, extra_tokens, cfg->max_ctx, fier::kAttnRowsDense, n_splits,
+                                      cache->seq_lens, extra_tokens, cfg->max_ctx, rows_per_wg, n_splits,
                                       cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
                                       cfg->max_ctx, (hipStream_t)stream));
 }
@@ -273,9 +286,10 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
         if (e != hipSuccess) return FIER_EHIP;
       }
       Workspace wd = carve(cfg, cfg->max_ctx, workspace);
-      const int n_splits = (cfg->max_ctx + fier::kAttnRowsDense - 1) / fier::kAttnRowsDense;
+      const int rows_per_wg = dense_rows_per_wg(cfg);
+      const int n_splits = (cfg->max_ctx + rows_per_wg - 1) / rows_per_wg;
       e = fier::launch_attn(cfg->kv_dtype, lay, n_rep, c->k, c->v, ql, nullptr, nullptr, c->seq_lens, extra, cfg->max_ctx,
-                            fier::kAttnRowsDense, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, outl, units,
+                            rows_per_wg, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, outl, units,
                             cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
       continue;

@@ -328,11 +328,11 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   const int32_t* __restrict__ sel = idx ? idx + (size_t)unit * max_budget : nullptr;
   const KvRows kv = lay.rows_of(unit);
   // whole-cache attention over paged rows: the block numbers of this workgroup's rows wait in LDS
-  __shared__ int32_t lblk[kAttnRowsDense / 64];
+  __shared__ int32_t lblk[kAttnRowsDenseMax / 64];
   const bool window = !sel && kv.blocks != nullptr;
   if (window) {
     const int bi = (start >> kv.shift) + (int)threadIdx.x;
-    if (threadIdx.x < kAttnRowsDense / 64) lblk[threadIdx.x] = bi < lay.blocks_per_seq ? kv.blocks[bi] : 0;
+    if (threadIdx.x < kAttnRowsDenseMax / 64) lblk[threadIdx.x] = bi < lay.blocks_per_seq ? kv.blocks[bi] : 0;
     __syncthreads();
   }
   const int first_block = start >> kv.shift;
@@ -637,7 +637,7 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
                                  int units, int n_kv_heads, int max_ctx, hipStream_t st) {
   dim3 grid(n_splits, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
-  if (!idx && rows_per_wg > kAttnRowsDense) return hipErrorInvalidValue;  // the kernel's block-number window
+  if (!idx && rows_per_wg > kAttnRowsDenseMax) return hipErrorInvalidValue;  // the kernel's block-number window
 #define FIER_ATTN_CASE(R)                                                                                          \
   case R:                                                                                                          \
     attn_split_kernel<DT, R><<<grid, 256, 0, st>>>((const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count,  \

@@ -42,7 +42,8 @@ struct KvLayout {  // one cache; passed to the kernels by value
 };
 
 constexpr int kAttnRowsSparse = 128;  // selected rows per workgroup of the split attention kernel
-constexpr int kAttnRowsDense = 512;   // rows per workgroup when attending over the whole cache
+constexpr int kAttnRowsDenseMin = 512;   // rows per workgroup when attending over the whole cache: the launcher
+constexpr int kAttnRowsDenseMax = 3200;  // picks a multiple of 128 in this range (see dense_rows_per_wg)
 
 // ---- fused decode step -------------------------------------------------------------------------------
 // Three kernels per layer.  Each unit's tokens are spread over many workgroups; the few serial steps
