@@ -1,0 +1,97 @@
+"""Seeded random small configurations (heads, GQA ratio, ragged lengths around block / group / range boundaries,
+budgets, dtype, group size, contiguous or paged rows, with or without an append) through the fused step, each
+compared with the oracle run on the same inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2508_08256_amd import binding as B
+from paper_2508_08256_amd import synth
+from helpers import check_index_sets
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+
+    return gpu_util
+
+
+def _random_case(rng):
+    g = int(rng.choice([32, 32, 64, 128, 256]))
+    dtype = int(rng.integers(0, 2))
+    n_kv = int(rng.integers(1, 4))
+    n_rep = int(rng.integers(1, 9))
+    batch = int(rng.integers(1, 4))
+    cap_blocks = int(rng.integers(1, 12))                      # capacity in units of 256 tokens
+    max_ctx = 256 * cap_blocks
+    # lengths: uniform, or hugging a boundary (0, 1, multiples of 32 / 64 / 256 / 1024 +- 1, capacity - 1)
+    lens = []
+    for _ in range(batch):
+        if rng.random() < 0.5:
+            lens.append(int(rng.integers(0, max_ctx)))
+        else:
+            base = int(rng.choice([0, 32, 64, 256, 1024, 2048, max_ctx]))
+            lens.append(int(np.clip(base + rng.integers(-1, 2), 0, max_ctx - 1)))
+    budgets = [int(rng.choice([0, 1, 2, 17, 64, 200, 1000, max_ctx])) for _ in range(batch)]
+    budgets = [min(b, max_ctx) for b in budgets]
+    if max(budgets) == 0:
+        budgets[0] = 5
+    paged = bool(rng.random() < 0.4)
+    block_tokens = int(rng.choice([64, 128, 256])) if paged else 0
+    if paged and block_tokens < g:
+        block_tokens = 256
+    append = bool(rng.random() < 0.7)
+    return dict(g=g, dtype=dtype, n_kv=n_kv, n_rep=n_rep, batch=batch, max_ctx=max_ctx, lens=lens, budgets=budgets,
+                block_tokens=block_tokens, append=append)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_configuration(gu, oracle, seed):
+    rng = np.random.default_rng(9000 + seed)
+    c = _random_case(rng)
+    print(f"[random] seed {seed}: {c}", flush=True)
+    g, dtype = c["g"], c["dtype"]
+    wl = synth.make_workload(f"rnd{seed}", 9100 + seed, c["batch"], c["n_kv"] * c["n_rep"], c["n_kv"], c["lens"],
+                             c["budgets"], dtype, max_ctx=c["max_ctx"], n_planted=2, plant=min(c["lens"]) > 8,
+                             chan="lognormal" if seed % 2 else "ones")
+    dw = (gu.PagedWorkload(wl, c["block_tokens"], group_size=g, seed=seed) if c["block_tokens"]
+          else gu.DeviceWorkload(wl, group_size=g))
+    B.quantize_keys(dw.cfg, dw.cache)
+    mb = int(max(c["budgets"]))
+    out = torch.full((1, wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1, wl.units), -1, dtype=torch.int32, device="cuda")
+    kn = dw.k_new[None].contiguous() if c["append"] else None
+    vn = dw.v_new[None].contiguous() if c["append"] else None
+    B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt,
+                  dw.workspace(mb))
+    torch.cuda.synchronize()
+    # the oracle, step by step, with the same group size
+    K, V, L = wl.K.copy(), wl.V.copy(), wl.unit_lens.copy()
+    bits, s, z = oracle.quantize(K, L, g, dtype, 4)
+    if c["append"]:
+        oracle.append(K, V, L, wl.k_new, wl.v_new, bits, s, z, g, dtype)
+        L = (L + 1).astype(np.int32)
+    sc = oracle.score(bits, s, z, wl.q, L, g, dtype, 4)
+    idx_o, cnt_o = oracle.topk(sc, L, wl.unit_budgets, mb)
+    ig, cg, og = idx.cpu().numpy()[0], cnt.cpu().numpy()[0], out.cpu().numpy()[0]
+    check_index_sets(ig, cg, idx_o, cnt_o, sc, L)
+    want = oracle.attention(K, V, wl.q, L, 1.0 / np.sqrt(128.0), dtype, np.ascontiguousarray(np.where(ig < 0, 0, ig)),
+                            cg, 4)
+    assert np.isfinite(og).all() and np.abs(og - want).max() <= 2e-3
+    got = dw.cache.unpack()
+    for u in range(wl.units):
+        n = int(L[u])
+        ng = -(-n // g)
+        assert np.array_equal(got[0][u, :n], bits[u, :n]), u
+        assert np.array_equal(got[1][u, :ng], s[u, :ng]) and np.array_equal(got[2][u, :ng], z[u, :ng]), u
+    if c["block_tokens"]:
+        assert dw.poison_intact()
+        Kl = dw.logical(dw.K)
+        for u in range(wl.units):
+            assert np.array_equal(Kl[u, :int(L[u])], K[u, :int(L[u])]), u
