@@ -223,7 +223,7 @@ int fier_sparse_attn(const fier_config* cfg, const fier_cache* cache, const void
   Workspace w = carve(cfg, max_budget, workspace);
   return hip_status(fier::launch_attn(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->k, cache->v, q, idx, count,
                                       cache->seq_lens, 0, max_budget, fier::kAttnRowsSparse, splits_for(max_budget),
-                                      cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
+                                      cfg->sm_scale, w.po, w.pm, w.pl, w.sb.ctl, out, units_of(cfg), cfg->n_kv_heads,
                                       cfg->max_ctx, (hipStream_t)stream));
 }
 
@@ -241,7 +241,7 @@ int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void*
   const int n_splits = (cfg->max_ctx + rows_per_wg - 1) / rows_per_wg;
   return hip_status(fier::launch_attn(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->k, cache->v, q, nullptr, nullptr,
                                       cache->seq_lens, extra_tokens, cfg->max_ctx, rows_per_wg, n_splits,
-                                      cfg->sm_scale, w.po, w.pm, w.pl, out, units_of(cfg), cfg->n_kv_heads,
+                                      cfg->sm_scale, w.po, w.pm, w.pl, w.sb.ctl, out, units_of(cfg), cfg->n_kv_heads,
                                       cfg->max_ctx, (hipStream_t)stream));
 }
 
@@ -289,7 +289,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
       const int rows_per_wg = dense_rows_per_wg(cfg);
       const int n_splits = (cfg->max_ctx + rows_per_wg - 1) / rows_per_wg;
       e = fier::launch_attn(cfg->kv_dtype, lay, n_rep, c->k, c->v, ql, nullptr, nullptr, c->seq_lens, extra, cfg->max_ctx,
-                            rows_per_wg, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, outl, units,
+                            rows_per_wg, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, wd.sb.ctl, outl, units,
                             cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
       continue;

@@ -300,73 +300,6 @@ __device__ __forceinline__ void store_partials(const AttnState<NREP>& st, float*
   }
 }
 
-template <int DT, int NREP>
-__global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
-                                                         const uint4* __restrict__ q, const int32_t* __restrict__ idx,
-                                                         const int32_t* __restrict__ count,
-                                                         const int32_t* __restrict__ seq_lens, int extra,
-                                                         int max_budget, int rows_per_wg, int n_splits,
-                                                         float scale_log2e, float* __restrict__ po,
-                                                         float* __restrict__ pm, float* __restrict__ pl,
-                                                         int n_kv_heads, int max_ctx, KvLayout lay) {
-  __shared__ float sh_o[NREP * kPartialFloats];
-
-  const int cn = threadIdx.x & 15;
-  const int unit = blockIdx.y, split = blockIdx.x;
-  const int b = unit / n_kv_heads;
-  int n;
-  if (idx) {
-    n = count[unit];
-    n = n > max_budget ? max_budget : n;
-  } else {
-    n = seq_lens[b] + extra;
-    n = n > max_ctx ? max_ctx : n;
-  }
-  const int start = split * rows_per_wg;
-  if (start >= n) return;
-  const int end = n < start + rows_per_wg ? n : start + rows_per_wg;
-  const int32_t* __restrict__ sel = idx ? idx + (size_t)unit * max_budget : nullptr;
-  const KvRows kv = lay.rows_of(unit);
-  // whole-cache attention over paged rows: the block numbers of this workgroup's rows wait in LDS
-  __shared__ int32_t lblk[kAttnRowsDenseMax / 64];
-  const bool window = !sel && kv.blocks != nullptr;
-  if (window) {
-    const int bi = (start >> kv.shift) + (int)threadIdx.x;
-    if (threadIdx.x < kAttnRowsDenseMax / 64) lblk[threadIdx.x] = bi < lay.blocks_per_seq ? kv.blocks[bi] : 0;
-    __syncthreads();
-  }
-  const int first_block = start >> kv.shift;
-  auto row_sel = [&](int j) {
-    int t = sel[j];
-    t = (t < 0 || t >= max_ctx) ? 0 : t;
-    return kv.row(t);
-  };
-  auto row_all = [&](int j) {
-    return window ? (size_t)lblk[(j >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(j & kv.mask)
-                  : kv.base + (size_t)j;
-  };
-
-  uint4 qr[NREP];
-#pragma unroll
-  for (int r = 0; r < NREP; ++r) qr[r] = q[((size_t)unit * NREP + r) * (kD / 8) + cn];
-
-  AttnState<NREP> st;
-  st.init();
-  if constexpr (NREP >= 3) {
-    const uint4* q_unit = q + (size_t)unit * NREP * (kD / 8);
-    if (sel)
-      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_sel, start, end, scale_log2e, st, sh_o);
-    else
-      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_all, start, end, scale_log2e, st, sh_o);
-  } else {
-    if (sel)
-      attend_rows<DT, NREP>(K, V, qr, row_sel, start, end, scale_log2e, st);
-    else
-      attend_rows<DT, NREP>(K, V, qr, row_all, start, end, scale_log2e, st);
-  }
-  store_partials<NREP, false>(st, sh_o, unit, n_splits, split, po, pm, pl);
-}
-
 __device__ __forceinline__ float wave_allsum_f(float x) {
   x = row_allsum(x);
   x += xor16(x);
@@ -457,6 +390,87 @@ __device__ __forceinline__ void merge_heads(const float* __restrict__ po, const 
       }
     }
   }
+}
+
+// Stand-alone attention (fier_sparse_attn: rows from an index list; fier_dense_attn: all rows).  grid (n_splits,
+// units), block 256: a workgroup attends over rows_per_wg entries and stores one partial per query head; the unit's
+// last workgroup merges the partials of the splits in use (arrival counter in the unit's control block).
+template <int DT, int NREP>
+__global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
+                                                         const uint4* __restrict__ q, const int32_t* __restrict__ idx,
+                                                         const int32_t* __restrict__ count,
+                                                         const int32_t* __restrict__ seq_lens, int extra,
+                                                         int max_budget, int rows_per_wg, int n_splits,
+                                                         float scale_log2e, float* __restrict__ po,
+                                                         float* __restrict__ pm, float* __restrict__ pl,
+                                                         UnitCtl* __restrict__ ctl, float* __restrict__ out,
+                                                         int n_kv_heads, int max_ctx, KvLayout lay) {
+  __shared__ float sh_o[NREP * kPartialFloats];
+  __shared__ uint32_t flag;
+
+  const int cn = threadIdx.x & 15;
+  const int unit = blockIdx.y, split = blockIdx.x;
+  const int b = unit / n_kv_heads;
+  int n;
+  if (idx) {
+    n = count[unit];
+    n = n > max_budget ? max_budget : n;
+  } else {
+    n = seq_lens[b] + extra;
+    n = n > max_ctx ? max_ctx : n;
+  }
+  const int start = split * rows_per_wg;
+  if (n <= 0 && split == 0) {  // nothing to attend over: zeros
+    for (int o = threadIdx.x; o < NREP * kD; o += 256) out[(size_t)unit * NREP * kD + o] = 0.f;
+    return;
+  }
+  if (start >= n) return;
+  const int end = n < start + rows_per_wg ? n : start + rows_per_wg;
+  const int32_t* __restrict__ sel = idx ? idx + (size_t)unit * max_budget : nullptr;
+  const KvRows kv = lay.rows_of(unit);
+  // whole-cache attention over paged rows: the block numbers of this workgroup's rows wait in LDS
+  __shared__ int32_t lblk[kAttnRowsDenseMax / 64];
+  const bool window = !sel && kv.blocks != nullptr;
+  if (window) {
+    const int bi = (start >> kv.shift) + (int)threadIdx.x;
+    if (threadIdx.x < kAttnRowsDenseMax / 64) lblk[threadIdx.x] = bi < lay.blocks_per_seq ? kv.blocks[bi] : 0;
+    __syncthreads();
+  }
+  const int first_block = start >> kv.shift;
+  auto row_sel = [&](int j) {
+    int t = sel[j];
+    t = (t < 0 || t >= max_ctx) ? 0 : t;
+    return kv.row(t);
+  };
+  auto row_all = [&](int j) {
+    return window ? (size_t)lblk[(j >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(j & kv.mask)
+                  : kv.base + (size_t)j;
+  };
+
+  uint4 qr[NREP];
+#pragma unroll
+  for (int r = 0; r < NREP; ++r) qr[r] = q[((size_t)unit * NREP + r) * (kD / 8) + cn];
+
+  AttnState<NREP> st;
+  st.init();
+  if constexpr (NREP >= 3) {
+    const uint4* q_unit = q + (size_t)unit * NREP * (kD / 8);
+    if (sel)
+      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_sel, start, end, scale_log2e, st, sh_o);
+    else
+      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_all, start, end, scale_log2e, st, sh_o);
+  } else {
+    if (sel)
+      attend_rows<DT, NREP>(K, V, qr, row_sel, start, end, scale_log2e, st);
+    else
+      attend_rows<DT, NREP>(K, V, qr, row_all, start, end, scale_log2e, st);
+  }
+  store_partials<NREP, true>(st, sh_o, unit, n_splits, split, po, pm, pl);
+  // the unit's last workgroup merges the partials of the splits in use
+  const int used = (n + rows_per_wg - 1) / rows_per_wg;
+  if (!last_arriver(&ctl[unit].arrive[0], (uint32_t)used, &flag)) return;
+  merge_heads<NREP>(po, pm, pl, unit, n_splits, used, sh_o, out + (size_t)unit * NREP * kD);
+  if (threadIdx.x == 0) ctl[unit].arrive[0] = 0;
 }
 
 // Third kernel of the fused decode step.  grid (ceil(n_ranges / RPW), units), block 256: the workgroup owns RPW
@@ -594,47 +608,11 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   }
 }
 
-// grid (units * n_rep), block 128: thread c merges channel c of one query head over the splits in use.
-__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ po, const float* __restrict__ pm,
-                                                         const float* __restrict__ pl,
-                                                         const int32_t* __restrict__ count,
-                                                         const int32_t* __restrict__ seq_lens, int extra,
-                                                         int max_budget, int rows_per_wg, int n_splits, int n_rep,
-                                                         float* __restrict__ out, int n_kv_heads, int max_ctx) {
-  const int head = blockIdx.x;  // unit * n_rep + r
-  const int unit = head / n_rep;
-  const int b = unit / n_kv_heads;
-  int n;
-  if (count) {
-    n = count[unit];
-    n = n > max_budget ? max_budget : n;
-  } else {
-    n = seq_lens[b] + extra;
-    n = n > max_ctx ? max_ctx : n;
-  }
-  const int c = threadIdx.x;
-  if (n <= 0) {
-    out[(size_t)head * kD + c] = 0.f;
-    return;
-  }
-  const int used = (n + rows_per_wg - 1) / rows_per_wg;
-  const size_t base = (size_t)head * n_splits;
-  float M = -INFINITY;
-  for (int s = 0; s < used; ++s) M = fmaxf(M, pm[base + s]);
-  float acc = 0.f, lsum = 0.f;
-  for (int s = 0; s < used; ++s) {
-    const float w = __builtin_amdgcn_exp2f(pm[base + s] - M);
-    acc += w * po[(base + s) * kD + c];
-    lsum += w * pl[base + s];
-  }
-  out[(size_t)head * kD + c] = acc / lsum;
-}
-
 template <int DT>
 static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
                                  const int32_t* count, const int32_t* seq_lens, int extra, int max_budget,
                                  int rows_per_wg, int n_splits, float sm_scale, float* po, float* pm, float* pl,
-                                 int units, int n_kv_heads, int max_ctx, hipStream_t st) {
+                                 UnitCtl* ctl, float* out, int units, int n_kv_heads, int max_ctx, hipStream_t st) {
   dim3 grid(n_splits, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
   if (!idx && rows_per_wg > kAttnRowsDenseMax) return hipErrorInvalidValue;  // the kernel's block-number window
@@ -642,7 +620,7 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
   case R:                                                                                                          \
     attn_split_kernel<DT, R><<<grid, 256, 0, st>>>((const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count,  \
                                                    seq_lens, extra, max_budget, rows_per_wg, n_splits, sl2, po, pm, \
-                                                   pl, n_kv_heads, max_ctx, lay);                                  \
+                                                   pl, ctl, out, n_kv_heads, max_ctx, lay);                        \
     break;
   switch (n_rep) {
     FIER_ATTN_CASE(1)
@@ -722,19 +700,13 @@ hipError_t launch_select_attend(int dtype, KvLayout lay, int n_rep, const StepBu
 
 hipError_t launch_attn(int dtype, KvLayout lay, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
                        const int32_t* count, const int32_t* seq_lens, int extra, int max_budget, int rows_per_wg,
-                       int n_splits, float sm_scale, float* po, float* pm, float* pl, float* out, int units,
-                       int n_kv_heads, int max_ctx, hipStream_t st) {
-  hipError_t e;
+                       int n_splits, float sm_scale, float* po, float* pm, float* pl, UnitCtl* ctl, float* out,
+                       int units, int n_kv_heads, int max_ctx, hipStream_t st) {
   if (dtype == DT_F16)
-    e = launch_attn_dt<DT_F16>(lay, n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
-                               sm_scale, po, pm, pl, units, n_kv_heads, max_ctx, st);
-  else
-    e = launch_attn_dt<DT_BF16>(lay, n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
-                                sm_scale, po, pm, pl, units, n_kv_heads, max_ctx, st);
-  if (e != hipSuccess) return e;
-  attn_merge_kernel<<<units * n_rep, 128, 0, st>>>(po, pm, pl, idx ? count : nullptr, seq_lens, extra, max_budget,
-                                                   rows_per_wg, n_splits, n_rep, out, n_kv_heads, max_ctx);
-  return hipGetLastError();
+    return launch_attn_dt<DT_F16>(lay, n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
+                                  sm_scale, po, pm, pl, ctl, out, units, n_kv_heads, max_ctx, st);
+  return launch_attn_dt<DT_BF16>(lay, n_rep, K, V, q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits,
+                                 sm_scale, po, pm, pl, ctl, out, units, n_kv_heads, max_ctx, st);
 }
 
 }  // namespace fier

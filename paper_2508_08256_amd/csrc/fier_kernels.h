@@ -119,7 +119,7 @@ hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, 
 // workgroup; partials (po, pm, pl) hold n_splits entries per (unit, query head).
 hipError_t launch_attn(int dtype, KvLayout lay, int n_rep, const void* K, const void* V, const void* q, const int32_t* idx,
                        const int32_t* count, const int32_t* seq_lens, int extra, int max_budget, int rows_per_wg,
-                       int n_splits, float sm_scale, float* po, float* pm, float* pl, float* out, int units,
+                       int n_splits, float sm_scale, float* po, float* pm, float* pl, UnitCtl* ctl, float* out, int units,
                        int n_kv_heads, int max_ctx, hipStream_t st);
 
 // ---- page-level importance (comparison workload) -------------------------------------------------------------------
