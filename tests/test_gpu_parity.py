@@ -585,6 +585,51 @@ def test_full_cache_is_not_appended_to(gu):
     assert runs[0][2].tolist() == [96, 96, 64, 64]
 
 
+def test_calls_follow_the_stream_they_are_given(gu, oracle):
+    """Everything is enqueued on the caller's stream (here a side stream of default priority) and nothing
+    synchronises: the whole path on that stream, an event, then the results are read on the default stream; the
+    stand-alone attention calls are also replayed from a graph captured on the side stream."""
+    import gpu_util
+
+    wl = synth.make_workload("stream", 808, 2, 8, 4, [3000, 1200], [300, 120], BF16, max_ctx=3072, n_planted=4,
+                             chan="lognormal")
+    dw = gpu_util.DeviceWorkload(wl)
+    mb = 300
+    out = torch.zeros((1, wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+    dense = torch.zeros((wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+    sparse = torch.zeros_like(dense)
+    ws, ws_dense = dw.workspace(mb), B.make_workspace(dw.cfg, dw.cfg.max_ctx)
+    q1, kn, vn = dw.q[None].contiguous(), dw.k_new[None].contiguous(), dw.v_new[None].contiguous()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        B.quantize_keys(dw.cfg, dw.cache)
+        B.decode_step(dw.cfg, [dw.cache], q1, kn, vn, dw.budgets, mb, out, idx, cnt, ws)
+        idx_clamped = idx[0].clamp(min=0).contiguous()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            B.dense_attn(dw.cfg, dw.cache, dw.q, 1, dense, ws_dense)
+            B.sparse_attn(dw.cfg, dw.cache, dw.q, idx_clamped, cnt[0], mb, sparse, ws)
+        for _ in range(3):
+            dense.zero_()
+            sparse.zero_()
+            graph.replay()
+        done = torch.cuda.Event()
+        done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    r = oracle_step(oracle, wl, append=True)
+    ig, cg = idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
+    check_index_sets(ig, cg, r["idx"], r["count"], r["scores"], r["L"])
+    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                            np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 2)
+    assert np.abs(out.cpu().numpy()[0] - want).max() <= 2e-3
+    assert np.abs(sparse.cpu().numpy() - want).max() <= 2e-3
+    want_dense = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype, None, None, 2)
+    assert np.abs(dense.cpu().numpy() - want_dense).max() <= 2e-3
+
+
 def test_decode_step_phases_equal_the_fused_call(gu):
     wl = synth.config1()
     import gpu_util
