@@ -338,12 +338,16 @@ def main():
     def st_topk(i):
         B.topk(cfg, scores, seq_lens, 1, budgets, budget, idx[0:1], cnt[0:1])
 
+    def st_topk_ws(i):
+        B.topk_ws(cfg, scores, seq_lens, 1, budgets, budget, idx[0:1], cnt[0:1], wss[0][0])
+
     def st_attn(i):
         r, l = flat[i % len(flat)]
         B.sparse_attn(cfg, caches[r][l], qs[r][l:l + 1], idx[0:1], cnt[0:1], budget, out1, wss[0][0])
 
     us_score, _ = timed(st_score, max(24, ns // 4), 4)
     us_topk, _ = timed(st_topk, max(24, ns // 4), 4)
+    us_topk_ws, _ = timed(st_topk_ws, max(24, ns // 4), 4)
     us_attn, _ = timed(st_attn, max(24, ns // 4), 4)
 
     # ---- the bulk quantizer (once per sequence, after prefill) and the stand-alone append ------------------
@@ -437,6 +441,7 @@ def main():
                        "select_attend_merge": round(us_k3 / NL, 3), "sum": round((us_k1 + us_k2 + us_k3) / NL, 3)},
         "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "select_attend_merge": round(k3_gbps, 1)},
         "standalone_calls_us": {"fier_score": round(us_score, 3), "fier_topk": round(us_topk, 3),
+                                "fier_topk_ws": round(us_topk_ws, 3),
                                 "fier_sparse_attn": round(us_attn, 3), "fier_append_key": round(us_append, 3),
                                 "fier_quantize_keys": round(us_quant, 3)},
         "quantize_GBps": round(quant_bytes / (us_quant * 1e-6) / 1e9, 1),

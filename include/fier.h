@@ -147,6 +147,17 @@ int fier_topk(const fier_config *cfg, const float *scores, const int32_t *seq_le
               int32_t *count, void *stream);
 
 /*
+ * The same selection as fier_topk, bit for bit, computed by many workgroups per unit where a unit's scores do
+ * not fit the registers of one (contexts beyond 36864 tokens: four small kernels instead of one workgroup per
+ * unit streaming its scores four times; shorter contexts take fier_topk's kernel).  workspace:
+ * fier_workspace_bytes(cfg, max_budget) bytes, the same one the other calls use.  max_budget is the row pitch
+ * of idx as in fier_topk.
+ */
+int fier_topk_ws(const fier_config *cfg, const float *scores, const int32_t *seq_lens,
+                 int32_t extra_tokens, const int32_t *budgets, int32_t max_budget, int32_t *idx,
+                 int32_t *count, void *workspace, void *stream);
+
+/*
  * Alg. 1 step 4.  For every query head: p = softmax(sm_scale * q . K[S]^T), out = p V[S], with
  * S = idx[u][0 .. count[u]) (rows of this unit's cache, any order, each < max_ctx).  Inputs are
  * read in the K dtype, logits, softmax and the output are binary32.  out is

@@ -18,7 +18,7 @@ OK = 0
 EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = -1, -2, -3, -4, -5, -6
 
 SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_status_string",
-           "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk",
+           "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk", "fier_topk_ws",
            "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_page_meta_bytes",
            "fier_page_minmax", "fier_page_append", "fier_page_score", "fier_page_mean_score", "fier_expand_pages", "fier_unpack_bits",
            "fier_unpack_meta"]
@@ -221,6 +221,11 @@ def score(cfg: Config, cache: DeviceCache, q, extra_tokens: int, scores):
 def topk(cfg: Config, scores, seq_lens, extra_tokens: int, budgets, max_budget: int, idx, count):
     _check(lib().fier_topk(C.byref(cfg), _ptr(scores), _ptr(seq_lens), int(extra_tokens), _ptr(budgets),
                            int(max_budget), _ptr(idx), _ptr(count), _stream()), "fier_topk")
+
+
+def topk_ws(cfg: Config, scores, seq_lens, extra_tokens: int, budgets, max_budget: int, idx, count, workspace):
+    _check(lib().fier_topk_ws(C.byref(cfg), _ptr(scores), _ptr(seq_lens), int(extra_tokens), _ptr(budgets),
+                              int(max_budget), _ptr(idx), _ptr(count), _ptr(workspace), _stream()), "fier_topk_ws")
 
 
 def sparse_attn(cfg: Config, cache: DeviceCache, q, idx, count, max_budget: int, out, workspace):

@@ -210,6 +210,21 @@ int fier_topk(const fier_config* cfg, const float* scores, const int32_t* seq_le
                                       cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
 }
 
+int fier_topk_ws(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
+                 const int32_t* budgets, int32_t max_budget, int32_t* idx, int32_t* count, void* workspace,
+                 void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  if (!scores || !seq_lens || !budgets || !idx || !count) return FIER_EINVAL;
+  if (extra_tokens < 0 || extra_tokens > 1 || max_budget < 1) return FIER_EINVAL;
+  if (!workspace) return FIER_EWORKSPACE;
+  if (misaligned(scores) || misaligned(idx) || misaligned(workspace)) return FIER_EALIGN;
+  if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
+  Workspace w = carve(cfg, max_budget, workspace);
+  return hip_status(fier::launch_topk_ws(w.sb, scores, seq_lens, extra_tokens, budgets, max_budget, idx, count,
+                                         units_of(cfg), cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
+}
+
 int fier_sparse_attn(const fier_config* cfg, const fier_cache* cache, const void* q, const int32_t* idx,
                      const int32_t* count, int32_t max_budget, float* out, void* workspace, void* stream) {
   int st = check_cfg(cfg);

@@ -60,8 +60,9 @@ constexpr int kSubBins = 1024;         // second-level bins inside the threshold
 constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 
 struct UnitCtl {        // one per unit at the head of the workspace
-  uint32_t arrive[3];   // arrival counters of the kernels (the first one is unused); zero between calls
-  uint32_t unused0;
+  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention, [1] threshold kernel, [2] select + attend
+                        // kernel; zero between calls
+  uint32_t topk_max;    // fier_topk_ws: bit pattern of the largest |score| of the unit; zero between calls
   int32_t tbin;         // bins above are selected, bins below are not (-1: everything, kSelBins: nothing)
   uint32_t above;       // tokens in bins above tbin
   int32_t budget;       // tokens to select = min(budget, length, max_budget), >= 0
@@ -101,6 +102,11 @@ hipError_t launch_score(int dtype, KvLayout lay, int n_rep, const uint32_t* kbit
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
                         const void* v_new, int units, int n_kv_heads, int max_ctx, int group_size, hipStream_t st);
+
+// The same selection by many workgroups per unit where a unit's scores do not fit one workgroup's registers.
+hipError_t launch_topk_ws(const StepBuffers& sb, const float* scores, const int32_t* seq_lens, int extra,
+                          const int32_t* budgets, int max_budget, int32_t* idx, int32_t* count, int units,
+                          int n_kv_heads, int max_ctx, hipStream_t st);
 
 hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int extra, const int32_t* budgets,
                             int max_budget, int32_t* count_out, int units, int n_kv_heads, int max_ctx,

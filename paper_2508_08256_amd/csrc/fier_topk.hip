@@ -382,4 +382,125 @@ hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, 
   return hipGetLastError();
 }
 
+// ---- the same selection by many workgroups per unit (long contexts) ----------------------------------------------------
+// Four small kernels on the fused step's machinery: (1) largest |score| per unit = the histogram range R,
+// (2) 512-bin histogram of the scores over [-R, R], (3) the fused step's threshold kernel (exact threshold among the
+// candidates of the threshold bin, offsets of the 1024-token ranges in the ascending index list), (4) emission of the
+// indices range by range.  All decisions are the same integer comparisons as above: the result is identical.
+
+// grid (ceil(max_ctx / 4096), units), block 1024: thread t looks at tokens 4t..4t+3 of the workgroup's stretch.
+__global__ __launch_bounds__(1024) void topk_absmax_kernel(const float* __restrict__ scores,
+                                                           const int32_t* __restrict__ seq_lens, int extra,
+                                                           UnitCtl* __restrict__ ctl, int n_kv_heads, int max_ctx) {
+  __shared__ float tmp[kTkWaves];
+  const int unit = blockIdx.y;
+  int n = seq_lens[unit / n_kv_heads] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  const int i = blockIdx.x * kClassifyTokens + 4 * (int)threadIdx.x;
+  if (blockIdx.x * kClassifyTokens >= n) return;
+  float m = 0.f;
+  if (i < n) {
+    const float4 v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
+    m = fabsf(v.x);
+    if (i + 1 < n) m = fmaxf(m, fabsf(v.y));
+    if (i + 2 < n) m = fmaxf(m, fabsf(v.z));
+    if (i + 3 < n) m = fmaxf(m, fabsf(v.w));
+  }
+  m = block_minmax<true>(m, tmp);
+  // non-negative floats order like their bit patterns; the slot is zero between calls
+  if (threadIdx.x == 0 && m > 0.f) atomicMax(&ctl[unit].topk_max, __float_as_uint(m));
+}
+
+// Same grid.  Bins its stretch into an LDS histogram and adds it to the unit's; the unit's first workgroup also
+// publishes the range the scores are binned with, where the threshold kernel expects it.
+__global__ __launch_bounds__(1024) void topk_hist_kernel(const float* __restrict__ scores,
+                                                         const int32_t* __restrict__ seq_lens, int extra,
+                                                         UnitCtl* __restrict__ ctl, uint32_t* __restrict__ ghist,
+                                                         int n_kv_heads, int max_ctx) {
+  __shared__ uint32_t lhist[kSelBins];
+  const int unit = blockIdx.y, tid = threadIdx.x;
+  int n = seq_lens[unit / n_kv_heads] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  float R = __uint_as_float(ctl[unit].topk_max);
+  R = R > 0.f ? R : 1.0f;  // all scores zero: any range will do
+  const float scale = (float)kSelBins / (R + R);
+  if (blockIdx.x == 0 && tid == 0) {
+    ctl[unit].R = R;
+    ctl[unit].scale = scale;
+  }
+  if (blockIdx.x * kClassifyTokens >= n) return;
+  if (tid < kSelBins) lhist[tid] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * kClassifyTokens + 4 * tid;
+  if (i < n) {
+    const float4 v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (i + j < n) atomicAdd(&lhist[sel_bin(vv[j], R, scale, kSelBins)], 1u);
+  }
+  __syncthreads();
+  if (tid < kSelBins && lhist[tid]) atomicAdd(&ghist[(size_t)unit * kSelBins + tid], lhist[tid]);
+}
+
+// grid (n_ranges, units), block 256: the selected tokens of one 1024-token range, in token order, at the offset the
+// threshold kernel computed for the range.
+__global__ __launch_bounds__(256) void topk_emit_kernel(const float* __restrict__ scores,
+                                                        const int32_t* __restrict__ seq_lens, int extra,
+                                                        UnitCtl* __restrict__ ctl,
+                                                        const uint32_t* __restrict__ range_off, int max_budget,
+                                                        int32_t* __restrict__ idx, int n_ranges, int n_kv_heads,
+                                                        int max_ctx) {
+  __shared__ uint32_t scan_tmp[4];
+  const int unit = blockIdx.y, r = blockIdx.x, tid = threadIdx.x;
+  int n = seq_lens[unit / n_kv_heads] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  UnitCtl* __restrict__ c = &ctl[unit];
+  if (r == 0 && tid == 0) c->topk_max = 0;  // every reader of it has finished (earlier kernels)
+  const int i = r * kRangeTokens + 4 * tid;
+  if (r * kRangeTokens >= n) return;
+  const int tbin = c->tbin;
+  const float R = c->R, scale = c->scale;
+  const uint32_t T = c->T;
+  const int32_t idxT = c->idxT;
+  const uint32_t off = range_off[(size_t)unit * n_ranges + r];
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n) v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
+  const float vv[4] = {v.x, v.y, v.z, v.w};
+  uint32_t selm = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int bin = sel_bin(vv[j], R, scale, kSelBins);
+    const uint32_t key = score_key(vv[j]);
+    const bool sel = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
+    selm |= sel ? 1u << j : 0u;
+  }
+  uint32_t total;
+  uint32_t pos = off + block_excl_scan_u32<4>((uint32_t)__builtin_popcount(selm), scan_tmp, total);
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (selm >> j & 1u) {
+      if (pos < (uint32_t)max_budget) idx[(size_t)unit * max_budget + pos] = i + j;
+      ++pos;
+    }
+}
+
+hipError_t launch_topk_ws(const StepBuffers& sb_in, const float* scores, const int32_t* seq_lens, int extra,
+                          const int32_t* budgets, int max_budget, int32_t* idx, int32_t* count, int units,
+                          int n_kv_heads, int max_ctx, hipStream_t st) {
+  if (max_ctx <= 9 * 4 * kTkThreads)  // the scores of a unit fit one workgroup's registers: one kernel is faster
+    return launch_topk(scores, seq_lens, extra, budgets, max_budget, idx, count, units, n_kv_heads, max_ctx, st);
+  StepBuffers sb = sb_in;
+  sb.scores = const_cast<float*>(scores);  // the threshold kernel only reads them
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  dim3 grid4k((max_ctx + kClassifyTokens - 1) / kClassifyTokens, units);
+  topk_absmax_kernel<<<grid4k, 1024, 0, st>>>(scores, seq_lens, extra, sb.ctl, n_kv_heads, max_ctx);
+  topk_hist_kernel<<<grid4k, 1024, 0, st>>>(scores, seq_lens, extra, sb.ctl, sb.hist, n_kv_heads, max_ctx);
+  hipError_t e = launch_threshold(sb, seq_lens, extra, budgets, max_budget, count, units, n_kv_heads, max_ctx, st);
+  if (e != hipSuccess) return e;
+  topk_emit_kernel<<<dim3(n_ranges, units), 256, 0, st>>>(scores, seq_lens, extra, sb.ctl, sb.range_cnt, max_budget,
+                                                          idx, n_ranges, n_kv_heads, max_ctx);
+  return hipGetLastError();
+}
+
 }  // namespace fier

@@ -144,18 +144,27 @@ def test_score_within_tolerance(case, oracle, gu):
         assert np.all(np.isnan(got[u, n:])), "entries past the scored length must not be written"
 
 
-def _run_topk(gu, cfg, scores_np, lens, budgets, max_budget, extra=0):
+def _run_topk(gu, cfg, scores_np, lens, budgets, max_budget, extra=0, call="topk"):
     sc = torch.from_numpy(scores_np.astype(np.float32)).cuda()
     idx = torch.full((cfg.units, max_budget), -7, dtype=torch.int32, device="cuda")
     cnt = torch.full((cfg.units,), -7, dtype=torch.int32, device="cuda")
-    B.topk(cfg, sc, gu.i32(lens), extra, gu.i32(budgets), max_budget, idx, cnt)
+    if call == "topk":
+        B.topk(cfg, sc, gu.i32(lens), extra, gu.i32(budgets), max_budget, idx, cnt)
+    else:       # the many-workgroup form; twice on one workspace: it must leave the workspace as it found it
+        ws = B.make_workspace(cfg, max_budget)
+        for _ in range(2):
+            idx.fill_(-7)
+            B.topk_ws(cfg, sc, gu.i32(lens), extra, gu.i32(budgets), max_budget, idx, cnt, ws)
     torch.cuda.synchronize()
     return idx.cpu().numpy(), cnt.cpu().numpy()
 
 
-@pytest.mark.parametrize("kind", ["gauss", "equal", "ties", "two_values", "clustered", "signed_zero", "tiny_range"])
-def test_topk_exact_on_identical_scores(gu, oracle, kind):
-    """Same binary32 scores on both sides: the selected sets must be identical, ties to the lower index."""
+@pytest.mark.parametrize("call", ["topk", "topk_ws"])
+@pytest.mark.parametrize("kind", ["gauss", "equal", "ties", "two_values", "clustered", "signed_zero", "tiny_range",
+                                  "all_zero"])
+def test_topk_exact_on_identical_scores(gu, oracle, kind, call):
+    """Same binary32 scores on both sides: the selected sets must be identical, ties to the lower index.  The
+    capacity is beyond what one workgroup holds in registers, so fier_topk_ws takes its many-workgroup form."""
     rng = np.random.default_rng(sum(kind.encode()))   # a fixed seed per kind (hash() differs between processes)
     batch, H, Lcap = 3, 2, 40960
     lens = np.array([40960, 12345, 70], np.int32)
@@ -177,8 +186,10 @@ def test_topk_exact_on_identical_scores(gu, oracle, kind):
         sc[:, ::11] = -3.0
     elif kind == "tiny_range":
         sc = (1.0 + rng.integers(0, 3, sc.shape) * 2.0 ** -23).astype(np.float32)
+    elif kind == "all_zero":
+        sc[:] = 0.0
     max_budget = 4608
-    idx, cnt = _run_topk(gu, cfg, sc, lens, budgets, max_budget)
+    idx, cnt = _run_topk(gu, cfg, sc, lens, budgets, max_budget, call=call)
     ul = np.repeat(lens, H)
     ub = np.repeat(budgets, H)
     idx_o, cnt_o = oracle.topk(sc.astype(np.float64), ul, ub, max_budget)
@@ -195,6 +206,8 @@ def test_topk_budget_edges(gu, oracle):
     budgets = np.array([1, 999, 5000, 10, 1, 0], np.int32)
     sc = rng.standard_normal((6, 1024)).astype(np.float32)
     idx, cnt = _run_topk(gu, cfg, sc, lens, budgets, 1024)
+    idx2, cnt2 = _run_topk(gu, cfg, sc, lens, budgets, 1024, call="topk_ws")
+    assert np.array_equal(idx, idx2) and np.array_equal(cnt, cnt2)
     idx_o, cnt_o = oracle.topk(sc.astype(np.float64), lens, budgets, 1024)
     assert np.array_equal(cnt, cnt_o) and list(cnt) == [1, 999, 1000, 0, 1, 0]
     for u in range(6):
