@@ -404,12 +404,12 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
                                                          float scale_log2e, float* __restrict__ po,
                                                          float* __restrict__ pm, float* __restrict__ pl,
                                                          UnitCtl* __restrict__ ctl, float* __restrict__ out,
-                                                         int n_kv_heads, int max_ctx, KvLayout lay) {
+                                                         int n_kv_heads, int max_ctx, int unit_major, KvLayout lay) {
   __shared__ float sh_o[NREP * kPartialFloats];
   __shared__ uint32_t flag;
 
   const int cn = threadIdx.x & 15;
-  const int unit = blockIdx.y, split = blockIdx.x;
+  const int unit = unit_major ? blockIdx.x : blockIdx.y, split = unit_major ? blockIdx.y : blockIdx.x;
   const int b = unit / n_kv_heads;
   int n;
   if (idx) {
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const int32_t* __restrict__ seq_lens, int extra, int max_budget, float scale_log2e, float* __restrict__ po,
     float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
     float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx,
-    KvLayout lay) {
+    int unit_major, KvLayout lay) {
   __shared__ float sh_o[NREP * kPartialFloats > 4 * 130 ? NREP * kPartialFloats : 4 * 130];
   __shared__ uint16_t rows[kRangeTokens * RPW];  // selected tokens, relative to the workgroup's first token
   __shared__ uint32_t scan_tmp[4];
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
 
   const int tid = threadIdx.x;
   const int cn = tid & 15;
-  const int unit = blockIdx.y, wg = blockIdx.x;
+  const int unit = unit_major ? blockIdx.x : blockIdx.y, wg = unit_major ? blockIdx.y : blockIdx.x;
   const int b = unit / n_kv_heads;
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
@@ -512,7 +512,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   const float R = c->R, hscale = c->scale;
   const uint32_t T = c->T;
   const int32_t idxT = c->idxT;
-  const int n_slots = (int)gridDim.x;
+  const int n_slots = (int)(unit_major ? gridDim.y : gridDim.x);
 
   // ---- exact selection inside this workgroup's ranges, in token order ---------------------------------------
   float4 v[RPW];
@@ -613,14 +613,16 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
                                  const int32_t* count, const int32_t* seq_lens, int extra, int max_budget,
                                  int rows_per_wg, int n_splits, float sm_scale, float* po, float* pm, float* pl,
                                  UnitCtl* ctl, float* out, int units, int n_kv_heads, int max_ctx, hipStream_t st) {
-  dim3 grid(n_splits, units);
+  // dispatch order as in the select + attend kernel, for gathers; whole-cache attention streams and gains nothing
+  const int unit_major = idx != nullptr && (long)units * n_splits <= 2 * 256L * (n_rep >= 3 ? 4 : 7) ? 1 : 0;
+  dim3 grid = unit_major ? dim3(units, n_splits) : dim3(n_splits, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
   if (!idx && rows_per_wg > kAttnRowsDenseMax) return hipErrorInvalidValue;  // the kernel's block-number window
 #define FIER_ATTN_CASE(R)                                                                                          \
   case R:                                                                                                          \
     attn_split_kernel<DT, R><<<grid, 256, 0, st>>>((const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count,  \
                                                    seq_lens, extra, max_budget, rows_per_wg, n_splits, sl2, po, pm, \
-                                                   pl, ctl, out, n_kv_heads, max_ctx, lay);                        \
+                                                   pl, ctl, out, n_kv_heads, max_ctx, unit_major, lay);            \
     break;
   switch (n_rep) {
     FIER_ATTN_CASE(1)
@@ -644,14 +646,22 @@ static hipError_t launch_select_attend_dt(KvLayout lay, int n_rep, const StepBuf
                                           float sm_scale, int32_t* idx_out, float* out, float* kabsmax, int units,
                                           int n_kv_heads, int max_ctx, hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  dim3 grid((n_ranges + RPW - 1) / RPW, units);
+  const int n_wgs = (n_ranges + RPW - 1) / RPW;
+  // Dispatch order.  Workgroups go round-robin to the 8 XCDs; with the units varying fastest (and a multiple of 8
+  // of them) a unit's workgroups all run on one XCD, and its scores, offsets, partials and arrival counter stay in
+  // that XCD's L2: 20.8 -> 19.6 us at config 2, 29.4 -> 26.5 us at config 3.  That holds while the grid is at most
+  // about two resident rounds (256 CUs x 4 workgroups of this kernel for 3+ query heads per kv head, x 7
+  // otherwise); a longer grid of unequal sequences runs better with a unit's workgroups spread over the XCDs (69.7 against 75.5 us for
+  // the ragged 128-unit batch).
+  const int unit_major = (long)units * n_wgs <= 2 * 256L * (n_rep >= 3 ? 4 : 7) ? 1 : 0;
+  dim3 grid = unit_major ? dim3(units, n_wgs) : dim3(n_wgs, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
 #define FIER_SA_CASE(R)                                                                                            \
   case R:                                                                                                          \
     select_attend_kernel<DT, R, RPW><<<grid, 256, 0, st>>>(                                                        \
         sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K, (const uint4*)V, (const uint4*)q, seq_lens, extra,       \
         max_budget, sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax, n_ranges, n_kv_heads, max_ctx,     \
-        lay);                                                                                                      \
+        unit_major, lay);                                                                                          \
     break;
   switch (n_rep) {
     FIER_SA_CASE(1)

@@ -25,8 +25,11 @@ constexpr int kMaxRanges = (1 << 20) / kRangeTokens;  // max_ctx <= 2^20
 constexpr int kMaxChunks = (1 << 20) / kClassifyTokens;
 constexpr int kSpecCand = 64;                          // candidates per segment fetched before its count is known
 
-// grid (ceil(max_ctx / (4096 NV)), units), block 1024: a workgroup classifies NV stretches of 4096 tokens (thread t
+// grid (units, ceil(max_ctx / (4096 NV))), block 1024: a workgroup classifies NV stretches of 4096 tokens (thread t
 // the tokens 4t..4t+3 of each).  The launcher picks NV so that all workgroups are resident at once if possible.
+// Units vary fastest in the dispatch order: workgroups go round-robin to the 8 XCDs, so with a multiple of 8 units
+// all workgroups of a unit run on one XCD and its histogram, candidate segments and counters stay in that XCD's L2
+// (measured against chunks-fastest: 9.9 -> 8.4 us at config 2, 21.1 -> 16.5 us for the ragged 128-unit batch).
 template <int NV>
 __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __restrict__ scores,
                                                                 const int32_t* __restrict__ seq_lens, int extra,
@@ -54,7 +57,7 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int unit = blockIdx.x, chunk = blockIdx.y;
   const int b = unit / n_kv_heads;
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
@@ -247,7 +250,7 @@ hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int 
   if (wgs(1) > 512) nv = 2;
   if (wgs(2) > 2048) nv = 4;
   const int n_chunks = (max_ctx + kClassifyTokens * nv - 1) / (kClassifyTokens * nv);
-  dim3 grid(n_chunks, units);
+  dim3 grid(units, n_chunks);
 #define FIER_THR_CASE(NV)                                                                                            \
   threshold_kernel<NV><<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.hist, budgets,         \
                                                      max_budget, sb.range_cnt, sb.cand, sb.seg_cnt, count_out,      \
