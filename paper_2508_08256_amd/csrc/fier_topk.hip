@@ -388,16 +388,17 @@ hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, 
 // candidates of the threshold bin, offsets of the 1024-token ranges in the ascending index list), (4) emission of the
 // indices range by range.  All decisions are the same integer comparisons as above: the result is identical.
 
-// grid (ceil(max_ctx / 4096), units), block 1024: thread t looks at tokens 4t..4t+3 of the workgroup's stretch.
+// grid (units, ceil(max_ctx / 4096)), block 1024: thread t looks at tokens 4t..4t+3 of the workgroup's stretch.
+// (Units vary fastest in the dispatch order of all four kernels: a unit's workgroups share an XCD and its L2.)
 __global__ __launch_bounds__(1024) void topk_absmax_kernel(const float* __restrict__ scores,
                                                            const int32_t* __restrict__ seq_lens, int extra,
                                                            UnitCtl* __restrict__ ctl, int n_kv_heads, int max_ctx) {
   __shared__ float tmp[kTkWaves];
-  const int unit = blockIdx.y;
+  const int unit = blockIdx.x, chunk = blockIdx.y;
   int n = seq_lens[unit / n_kv_heads] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
-  const int i = blockIdx.x * kClassifyTokens + 4 * (int)threadIdx.x;
-  if (blockIdx.x * kClassifyTokens >= n) return;
+  const int i = chunk * kClassifyTokens + 4 * (int)threadIdx.x;
+  if (chunk * kClassifyTokens >= n) return;
   float m = 0.f;
   if (i < n) {
     const float4 v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
@@ -418,20 +419,20 @@ __global__ __launch_bounds__(1024) void topk_hist_kernel(const float* __restrict
                                                          UnitCtl* __restrict__ ctl, uint32_t* __restrict__ ghist,
                                                          int n_kv_heads, int max_ctx) {
   __shared__ uint32_t lhist[kSelBins];
-  const int unit = blockIdx.y, tid = threadIdx.x;
+  const int unit = blockIdx.x, chunk = blockIdx.y, tid = threadIdx.x;
   int n = seq_lens[unit / n_kv_heads] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
   float R = __uint_as_float(ctl[unit].topk_max);
   R = R > 0.f ? R : 1.0f;  // all scores zero: any range will do
   const float scale = (float)kSelBins / (R + R);
-  if (blockIdx.x == 0 && tid == 0) {
+  if (chunk == 0 && tid == 0) {
     ctl[unit].R = R;
     ctl[unit].scale = scale;
   }
-  if (blockIdx.x * kClassifyTokens >= n) return;
+  if (chunk * kClassifyTokens >= n) return;
   if (tid < kSelBins) lhist[tid] = 0;
   __syncthreads();
-  const int i = blockIdx.x * kClassifyTokens + 4 * tid;
+  const int i = chunk * kClassifyTokens + 4 * tid;
   if (i < n) {
     const float4 v = *reinterpret_cast<const float4*>(scores + (size_t)unit * max_ctx + i);
     const float vv[4] = {v.x, v.y, v.z, v.w};
@@ -443,7 +444,7 @@ __global__ __launch_bounds__(1024) void topk_hist_kernel(const float* __restrict
   if (tid < kSelBins && lhist[tid]) atomicAdd(&ghist[(size_t)unit * kSelBins + tid], lhist[tid]);
 }
 
-// grid (n_ranges, units), block 256: the selected tokens of one 1024-token range, in token order, at the offset the
+// grid (units, n_ranges), block 256: the selected tokens of one 1024-token range, in token order, at the offset the
 // threshold kernel computed for the range.
 __global__ __launch_bounds__(256) void topk_emit_kernel(const float* __restrict__ scores,
                                                         const int32_t* __restrict__ seq_lens, int extra,
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(256) void topk_emit_kernel(const float* __restrict_
                                                         int32_t* __restrict__ idx, int n_ranges, int n_kv_heads,
                                                         int max_ctx) {
   __shared__ uint32_t scan_tmp[4];
-  const int unit = blockIdx.y, r = blockIdx.x, tid = threadIdx.x;
+  const int unit = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
   int n = seq_lens[unit / n_kv_heads] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
   UnitCtl* __restrict__ c = &ctl[unit];
@@ -493,12 +494,12 @@ hipError_t launch_topk_ws(const StepBuffers& sb_in, const float* scores, const i
   StepBuffers sb = sb_in;
   sb.scores = const_cast<float*>(scores);  // the threshold kernel only reads them
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  dim3 grid4k((max_ctx + kClassifyTokens - 1) / kClassifyTokens, units);
+  dim3 grid4k(units, (max_ctx + kClassifyTokens - 1) / kClassifyTokens);
   topk_absmax_kernel<<<grid4k, 1024, 0, st>>>(scores, seq_lens, extra, sb.ctl, n_kv_heads, max_ctx);
   topk_hist_kernel<<<grid4k, 1024, 0, st>>>(scores, seq_lens, extra, sb.ctl, sb.hist, n_kv_heads, max_ctx);
   hipError_t e = launch_threshold(sb, seq_lens, extra, budgets, max_budget, count, units, n_kv_heads, max_ctx, st);
   if (e != hipSuccess) return e;
-  topk_emit_kernel<<<dim3(n_ranges, units), 256, 0, st>>>(scores, seq_lens, extra, sb.ctl, sb.range_cnt, max_budget,
+  topk_emit_kernel<<<dim3(units, n_ranges), 256, 0, st>>>(scores, seq_lens, extra, sb.ctl, sb.range_cnt, max_budget,
                                                           idx, n_ranges, n_kv_heads, max_ctx);
   return hipGetLastError();
 }
