@@ -485,7 +485,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const int32_t* __restrict__ seq_lens, int extra, int max_budget, float scale_log2e, float* __restrict__ po,
     float* __restrict__ pm, float* __restrict__ pl, int32_t* __restrict__ idx_out, float* __restrict__ out,
     float* __restrict__ kabsmax, const float* __restrict__ newmax, int n_ranges, int n_kv_heads, int max_ctx,
-    int unit_major, KvLayout lay) {
+    int order, int wgs_per_unit, KvLayout lay) {
   __shared__ float sh_o[NREP * kPartialFloats > 4 * 130 ? NREP * kPartialFloats : 4 * 130];
   __shared__ uint16_t rows[kRangeTokens * RPW];  // selected tokens, relative to the workgroup's first token
   __shared__ uint32_t scan_tmp[4];
@@ -494,7 +494,19 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
 
   const int tid = threadIdx.x;
   const int cn = tid & 15;
-  const int unit = unit_major ? blockIdx.x : blockIdx.y, wg = unit_major ? blockIdx.y : blockIdx.x;
+  // order: 0 = grid (workgroups, units); 1 = grid (units, workgroups); 2 = one-dimensional, groups of 8 units, a
+  // group's workgroups together and unit % 8 fastest (see the launcher)
+  int unit, wg;
+  if (order == 2) {
+    const int id = blockIdx.x;
+    const int g = id / (8 * wgs_per_unit);
+    const int rem = id - g * 8 * wgs_per_unit;
+    wg = rem >> 3;
+    unit = 8 * g + (rem & 7);
+  } else {
+    unit = order ? blockIdx.x : blockIdx.y;
+    wg = order ? blockIdx.y : blockIdx.x;
+  }
   const int b = unit / n_kv_heads;
   int n = seq_lens[b] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
@@ -512,7 +524,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   const float R = c->R, hscale = c->scale;
   const uint32_t T = c->T;
   const int32_t idxT = c->idxT;
-  const int n_slots = (int)(unit_major ? gridDim.y : gridDim.x);
+  const int n_slots = wgs_per_unit;
 
   // ---- exact selection inside this workgroup's ranges, in token order ---------------------------------------
   float4 v[RPW];
@@ -647,21 +659,24 @@ static hipError_t launch_select_attend_dt(KvLayout lay, int n_rep, const StepBuf
                                           int n_kv_heads, int max_ctx, hipStream_t st) {
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   const int n_wgs = (n_ranges + RPW - 1) / RPW;
-  // Dispatch order.  Workgroups go round-robin to the 8 XCDs; with the units varying fastest (and a multiple of 8
-  // of them) a unit's workgroups all run on one XCD, and its scores, offsets, partials and arrival counter stay in
-  // that XCD's L2: 20.8 -> 19.6 us at config 2, 29.4 -> 26.5 us at config 3.  That holds while the grid is at most
-  // about two resident rounds (256 CUs x 4 workgroups of this kernel for 3+ query heads per kv head, x 7
-  // otherwise); a longer grid of unequal sequences runs better with a unit's workgroups spread over the XCDs (69.7 against 75.5 us for
-  // the ragged 128-unit batch).
-  const int unit_major = (long)units * n_wgs <= 2 * 256L * (n_rep >= 3 ? 4 : 7) ? 1 : 0;
-  dim3 grid = unit_major ? dim3(units, n_wgs) : dim3(n_wgs, units);
+  // Dispatch order.  Workgroups go round-robin to the 8 XCDs in the order of their linear index; when a unit's
+  // workgroups all run on one XCD, its scores, offsets, partials and arrival counter stay in that XCD's L2.
+  //   1: units fastest (a multiple of 8 units puts unit u on XCD u % 8), for grids of at most about two resident
+  //      rounds (256 CUs x 4 workgroups of this kernel for 3+ query heads per kv head, x 7 otherwise):
+  //      20.8 -> 19.6 us at config 2, 29.4 -> 26.5 us at config 3 against order 0;
+  //   2: longer grids with a multiple of 8 units: groups of 8 units one after the other, inside a group the
+  //      workgroups in range order and unit % 8 fastest -- the same XCD assignment, but a sequence's ranges stay
+  //      together in time (the ragged 128-unit batch: 69.9 -> 62.9 us against order 0; order 1 there: 75.5 us);
+  //   0: ranges fastest, otherwise.
+  const int order = (long)units * n_wgs <= 2 * 256L * (n_rep >= 3 ? 4 : 7) ? 1 : (units % 8 == 0 ? 2 : 0);
+  dim3 grid = order == 2 ? dim3((unsigned)units * (unsigned)n_wgs) : (order ? dim3(units, n_wgs) : dim3(n_wgs, units));
   const float sl2 = sm_scale * 1.4426950408889634f;
 #define FIER_SA_CASE(R)                                                                                            \
   case R:                                                                                                          \
     select_attend_kernel<DT, R, RPW><<<grid, 256, 0, st>>>(                                                        \
         sb.scores, sb.ctl, sb.range_cnt, (const uint4*)K, (const uint4*)V, (const uint4*)q, seq_lens, extra,       \
         max_budget, sl2, sb.po, sb.pm, sb.pl, idx_out, out, kabsmax, sb.newmax, n_ranges, n_kv_heads, max_ctx,     \
-        unit_major, lay);                                                                                          \
+        order, n_wgs, lay);                                                                                        \
     break;
   switch (n_rep) {
     FIER_SA_CASE(1)
