@@ -1,6 +1,8 @@
 """Seeded random small configurations (heads, GQA ratio, ragged lengths around block / group / range boundaries,
 budgets, dtype, group size, contiguous or paged rows, with or without an append) through the fused step, each
 compared with the oracle run on the same inputs."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -21,13 +23,15 @@ def gu():
     return gpu_util
 
 
-def _random_case(rng):
+def _random_case(rng, big=False):
     g = int(rng.choice([32, 32, 64, 128, 256]))
     dtype = int(rng.integers(0, 2))
-    n_kv = int(rng.integers(1, 4))
+    n_kv = int(rng.integers(1, 3 if big else 4))
     n_rep = int(rng.integers(1, 9))
-    batch = int(rng.integers(1, 4))
-    cap_blocks = int(rng.integers(1, 12))                      # capacity in units of 256 tokens
+    batch = int(rng.integers(1, 3 if big else 4))
+    # capacity in units of 256 tokens; the big cases span several threshold chunks, score rounds and both top-k
+    # regimes of the stand-alone call (up to 51200 tokens)
+    cap_blocks = int(rng.integers(12, 201)) if big else int(rng.integers(1, 12))
     max_ctx = 256 * cap_blocks
     # lengths: uniform, or hugging a boundary (0, 1, multiples of 32 / 64 / 256 / 1024 +- 1, capacity - 1)
     lens = []
@@ -35,9 +39,11 @@ def _random_case(rng):
         if rng.random() < 0.5:
             lens.append(int(rng.integers(0, max_ctx)))
         else:
-            base = int(rng.choice([0, 32, 64, 256, 1024, 2048, max_ctx]))
+            base = int(rng.choice([0, 32, 64, 256, 1024, 2048, 4096, 8192, 36864, max_ctx] if big
+                                  else [0, 32, 64, 256, 1024, 2048, max_ctx]))
             lens.append(int(np.clip(base + rng.integers(-1, 2), 0, max_ctx - 1)))
-    budgets = [int(rng.choice([0, 1, 2, 17, 64, 200, 1000, max_ctx])) for _ in range(batch)]
+    budgets = [int(rng.choice([1, 17, 200, 1000, 3604, 10000, max_ctx] if big
+                              else [0, 1, 2, 17, 64, 200, 1000, max_ctx])) for _ in range(batch)]
     budgets = [min(b, max_ctx) for b in budgets]
     if max(budgets) == 0:
         budgets[0] = 5
@@ -50,10 +56,19 @@ def _random_case(rng):
                 block_tokens=block_tokens, append=append)
 
 
-@pytest.mark.parametrize("seed", range(40))
+# FIER_RANDOM_SEEDS=N runs the first N seeds (default 40)
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FIER_RANDOM_SEEDS", "40"))))
 def test_random_configuration(gu, oracle, seed):
-    rng = np.random.default_rng(9000 + seed)
-    c = _random_case(rng)
+    _run_case(gu, oracle, seed, np.random.default_rng(9000 + seed), big=False)
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FIER_RANDOM_BIG_SEEDS", "10"))))
+def test_random_long_configuration(gu, oracle, seed):
+    _run_case(gu, oracle, 100000 + seed, np.random.default_rng(19000 + seed), big=True)
+
+
+def _run_case(gu, oracle, seed, rng, big):
+    c = _random_case(rng, big)
     print(f"[random] seed {seed}: {c}", flush=True)
     g, dtype = c["g"], c["dtype"]
     wl = synth.make_workload(f"rnd{seed}", 9100 + seed, c["batch"], c["n_kv"] * c["n_rep"], c["n_kv"], c["lens"],
