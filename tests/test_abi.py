@@ -133,3 +133,21 @@ def test_no_cpu_fallback_when_library_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libfier.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.lib()
+
+
+def test_binding_refuses_a_workspace_that_is_too_small():
+    """The C ABI takes the workspace pointer alone; the binding knows the tensor's size and checks it against
+    fier_workspace_bytes before the call (whole-cache attention needs the size for max_budget = max_ctx)."""
+    import types
+
+    import torch
+
+    cfg = B.make_config(1, 8, 8, 4096)
+    small = torch.zeros(B.workspace_bytes(cfg, 64), dtype=torch.uint8)
+    cache = types.SimpleNamespace(c=B.Cache())
+    with pytest.raises(ValueError, match="fier_dense_attn: workspace"):
+        B.dense_attn(cfg, cache, None, 0, None, small)
+    with pytest.raises(ValueError, match="fier_sparse_attn: workspace"):
+        B.sparse_attn(cfg, cache, None, None, None, 65, None, small)
+    with pytest.raises(ValueError, match="fier_decode_step_mixed: workspace"):
+        B.decode_step_mixed(cfg, [cache], [True], None, None, None, None, 64, None, None, None, small)

@@ -9,7 +9,7 @@ import torch
 
 from paper_2508_08256_amd import binding as B
 from paper_2508_08256_amd import synth
-from helpers import check_index_sets
+from helpers import check_index_sets, score_tolerance_ok
 
 pytestmark = pytest.mark.gpu
 
@@ -110,3 +110,89 @@ def _run_case(gu, oracle, seed, rng, big):
         Kl = dw.logical(dw.K)
         for u in range(wl.units):
             assert np.array_equal(Kl[u, :int(L[u])], K[u, :int(L[u])]), u
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FIER_RANDOM_CALL_SEEDS", "24"))))
+def test_random_configuration_call_by_call(gu, oracle, seed):
+    """The same kind of random configuration through the stand-alone calls: bulk quantization, up to three
+    fier_append_key calls, fier_score, fier_topk and fier_topk_ws (on the device's own scores: identical sets),
+    fier_sparse_attn on the selection and fier_dense_attn, each against the oracle.  Every fourth seed is a long
+    one."""
+    big = seed % 4 == 3
+    rng = np.random.default_rng(29000 + seed)
+    c = _random_case(rng, big)
+    n_app = int(rng.integers(0, 4)) if c["append"] else 0
+    print(f"[random calls] seed {seed}: {c} appends {n_app}", flush=True)
+    g, dtype = c["g"], c["dtype"]
+    lens = [min(n, c["max_ctx"] - n_app) for n in c["lens"]]
+    wl = synth.make_workload(f"rndc{seed}", 29100 + seed, c["batch"], c["n_kv"] * c["n_rep"], c["n_kv"], lens,
+                             c["budgets"], dtype, max_ctx=c["max_ctx"], n_planted=2, plant=min(lens) > 8,
+                             chan="lognormal" if seed % 2 else "ones")
+    dw = (gu.PagedWorkload(wl, c["block_tokens"], group_size=g, seed=seed) if c["block_tokens"]
+          else gu.DeviceWorkload(wl, group_size=g))
+    cfg = dw.cfg
+    B.quantize_keys(cfg, dw.cache)
+    K, V, L = wl.K.copy(), wl.V.copy(), wl.unit_lens.copy()
+    bits, s, z = oracle.quantize(K, L, g, dtype, 4)
+    for a in range(n_app):                     # distinct new rows per append: the seeded rows, bit-rotated
+        kn = np.roll(wl.k_new, a, axis=-1)
+        vn = np.roll(wl.v_new, 2 * a, axis=-1)
+        B.append_key(cfg, dw.cache, gu.to_dev(kn, dtype), gu.to_dev(vn, dtype))
+        dw.seq_lens += 1                      # the caller advances the lengths after each append
+        oracle.append(K, V, L, kn, vn, bits, s, z, g, dtype)
+        L = (L + 1).astype(np.int32)
+    torch.cuda.synchronize()
+    got = dw.cache.unpack()
+    for u in range(wl.units):
+        n = int(L[u])
+        ng = -(-n // g)
+        assert np.array_equal(got[0][u, :n], bits[u, :n]), u
+        assert np.array_equal(got[1][u, :ng], s[u, :ng]) and np.array_equal(got[2][u, :ng], z[u, :ng]), u
+
+    # scores
+    scores = torch.full((wl.units, wl.max_ctx), float("nan"), dtype=torch.float32, device="cuda")
+    B.score(cfg, dw.cache, dw.q, 0, scores)
+    torch.cuda.synchronize()
+    sc_o = oracle.score(bits, s, z, wl.q, L, g, dtype, 4)
+    Kt = np.abs(oracle.dequantize(bits, s, z, L, g, dtype))
+    qa = np.abs(synth.words_to_f32(wl.q, dtype).astype(np.float64)).sum(axis=1)
+    absterm = np.einsum("utd,ud->ut", Kt, qa)
+    sc_g = scores.cpu().numpy()
+    for u in range(wl.units):
+        n = int(L[u])
+        assert np.all(score_tolerance_ok(sc_g[u, :n], sc_o[u, :n], absterm[u, :n])), u
+        assert np.all(np.isnan(sc_g[u, n:])), u
+
+    # selection: both calls on the device's scores give the oracle's set for those same binary32 scores
+    mb = int(max(c["budgets"]))
+    idx = torch.full((wl.units, mb), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((wl.units,), -7, dtype=torch.int32, device="cuda")
+    idx2, cnt2 = idx.clone(), cnt.clone()
+    ws = dw.workspace(mb)
+    B.topk(cfg, scores, dw.seq_lens, 0, dw.budgets, mb, idx, cnt)
+    B.topk_ws(cfg, scores, dw.seq_lens, 0, dw.budgets, mb, idx2, cnt2, ws)
+    torch.cuda.synchronize()
+    exact = np.where(np.isnan(sc_g), 0.0, sc_g).astype(np.float64)
+    idx_o, cnt_o = oracle.topk(exact, L, wl.unit_budgets, mb)
+    ig, cg = idx.cpu().numpy(), cnt.cpu().numpy()
+    assert np.array_equal(cg, cnt_o) and np.array_equal(cnt2.cpu().numpy(), cnt_o)
+    for u in range(wl.units):
+        assert np.array_equal(ig[u, :cg[u]], idx_o[u, :cg[u]]), u
+        assert np.array_equal(idx2.cpu().numpy()[u, :cg[u]], idx_o[u, :cg[u]]), u
+
+    # attention over that selection, and over the whole cache
+    out = torch.full((wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
+    out_d = torch.full_like(out, float("nan"))
+    B.sparse_attn(cfg, dw.cache, dw.q, idx, cnt, mb, out, ws)
+    B.dense_attn(cfg, dw.cache, dw.q, 0, out_d, dw.workspace(wl.max_ctx))   # sized for whole-cache attention
+    torch.cuda.synchronize()
+    sel = np.ascontiguousarray(np.where(ig < 0, 0, ig))
+    want = oracle.attention(K, V, wl.q, L, 1.0 / np.sqrt(128.0), dtype, sel, cg, 4)
+    want_d = oracle.attention(K, V, wl.q, L, 1.0 / np.sqrt(128.0), dtype, None, None, 4)
+    og, od = out.cpu().numpy(), out_d.cpu().numpy()
+    err_s = np.abs(og - want).reshape(wl.units, -1).max(axis=1)
+    err_d = np.abs(od - want_d).reshape(wl.units, -1).max(axis=1)
+    assert np.isfinite(og).all() and err_s.max() <= 2e-3, (err_s, err_d, cg)
+    assert np.isfinite(od).all() and err_d.max() <= 2e-3, (err_s, err_d)
+    if c["block_tokens"]:
+        assert dw.poison_intact()
