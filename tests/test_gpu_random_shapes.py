@@ -1,5 +1,5 @@
 """Seeded random small configurations (heads, GQA ratio, ragged lengths around block / group / range boundaries,
-budgets, dtype, group size, contiguous or paged rows, with or without an append) through the fused step, each
+budgets, dtype, group size, contiguous or paged rows, with or without an append) through one to three fused steps, each
 compared with the oracle run on the same inputs."""
 import os
 
@@ -78,33 +78,40 @@ def _run_case(gu, oracle, seed, rng, big):
           else gu.DeviceWorkload(wl, group_size=g))
     B.quantize_keys(dw.cfg, dw.cache)
     mb = int(max(c["budgets"]))
-    out = torch.full((1, wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
-    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
-    cnt = torch.full((1, wl.units), -1, dtype=torch.int32, device="cuda")
-    kn = dw.k_new[None].contiguous() if c["append"] else None
-    vn = dw.v_new[None].contiguous() if c["append"] else None
-    B.decode_step(dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt,
-                  dw.workspace(mb))
-    torch.cuda.synchronize()
-    # the oracle, step by step, with the same group size
+    ws = dw.workspace(mb)                      # one workspace for all steps: each call must leave it clean
     K, V, L = wl.K.copy(), wl.V.copy(), wl.unit_lens.copy()
     bits, s, z = oracle.quantize(K, L, g, dtype, 4)
-    if c["append"]:
-        oracle.append(K, V, L, wl.k_new, wl.v_new, bits, s, z, g, dtype)
-        L = (L + 1).astype(np.int32)
-    sc = oracle.score(bits, s, z, wl.q, L, g, dtype, 4)
-    idx_o, cnt_o = oracle.topk(sc, L, wl.unit_budgets, mb)
-    ig, cg, og = idx.cpu().numpy()[0], cnt.cpu().numpy()[0], out.cpu().numpy()[0]
-    check_index_sets(ig, cg, idx_o, cnt_o, sc, L)
-    want = oracle.attention(K, V, wl.q, L, 1.0 / np.sqrt(128.0), dtype, np.ascontiguousarray(np.where(ig < 0, 0, ig)),
-                            cg, 4)
-    assert np.isfinite(og).all() and np.abs(og - want).max() <= 2e-3
-    got = dw.cache.unpack()
-    for u in range(wl.units):
-        n = int(L[u])
-        ng = -(-n // g)
-        assert np.array_equal(got[0][u, :n], bits[u, :n]), u
-        assert np.array_equal(got[1][u, :ng], s[u, :ng]) and np.array_equal(got[2][u, :ng], z[u, :ng]), u
+    # one to three consecutive steps (fresh query and new rows each), the caller advancing the lengths in between
+    n_steps = int(rng.integers(1, 4)) if c["append"] and max(c["lens"]) + 3 <= c["max_ctx"] else 1
+    for t in range(n_steps):
+        q_w = np.roll(wl.q, 3 * t, axis=-1)
+        kn_w, vn_w = np.roll(wl.k_new, t, axis=-1), np.roll(wl.v_new, 2 * t, axis=-1)
+        out = torch.full((1, wl.units, wl.n_rep, 128), float("nan"), dtype=torch.float32, device="cuda")
+        idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.full((1, wl.units), -1, dtype=torch.int32, device="cuda")
+        kn = gu.to_dev(kn_w, dtype)[None].contiguous() if c["append"] else None
+        vn = gu.to_dev(vn_w, dtype)[None].contiguous() if c["append"] else None
+        B.decode_step(dw.cfg, [dw.cache], gu.to_dev(q_w, dtype)[None].contiguous(), kn, vn, dw.budgets, mb, out, idx,
+                      cnt, ws)
+        torch.cuda.synchronize()
+        # the oracle, step by step, with the same group size
+        if c["append"]:
+            oracle.append(K, V, L, kn_w, vn_w, bits, s, z, g, dtype)
+            L = (L + 1).astype(np.int32)
+            dw.seq_lens += 1
+        sc = oracle.score(bits, s, z, q_w, L, g, dtype, 4)
+        idx_o, cnt_o = oracle.topk(sc, L, wl.unit_budgets, mb)
+        ig, cg, og = idx.cpu().numpy()[0], cnt.cpu().numpy()[0], out.cpu().numpy()[0]
+        check_index_sets(ig, cg, idx_o, cnt_o, sc, L)
+        want = oracle.attention(K, V, q_w, L, 1.0 / np.sqrt(128.0), dtype,
+                                np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 4)
+        assert np.isfinite(og).all() and np.abs(og - want).max() <= 2e-3, t
+        got = dw.cache.unpack()
+        for u in range(wl.units):
+            n = int(L[u])
+            ng = -(-n // g)
+            assert np.array_equal(got[0][u, :n], bits[u, :n]), (t, u)
+            assert np.array_equal(got[1][u, :ng], s[u, :ng]) and np.array_equal(got[2][u, :ng], z[u, :ng]), (t, u)
     if c["block_tokens"]:
         assert dw.poison_intact()
         Kl = dw.logical(dw.K)
