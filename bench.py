@@ -330,6 +330,16 @@ def main():
 
     us_dense, _ = timed(st_dense, max(24, ns // 10), 4)
 
+    # what this machine's memory system gives a plain streaming copy (torch's own, 1 GiB operands, far beyond the
+    # 256 MB Infinity Cache): context for the roofline figures, which are quoted against the nominal 8 TB/s
+    big_a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    big_b = torch.empty_like(big_a)
+    us_copy, _ = timed(lambda i: big_b.copy_(big_a), 10, 2)
+    ceiling = {"copy_GBps": round(2 * big_a.numel() * 4 / (us_copy * 1e-6) / 1e9, 1),
+               "how": "torch copy_ of 1 GiB of float32, bytes read + bytes written; the read-only counterpart is "
+                      "dense_attn_GBps (this build's whole-cache attention)"}
+    del big_a, big_b
+
     # ---- stand-alone entry points (separate kernels, index list through memory) --------------------------
     def st_score(i):
         r, l = flat[i % len(flat)]
@@ -448,6 +458,7 @@ def main():
         "dense_attn_us": round(us_dense, 3),
         "dense_attn_GBps": round(dense_bytes / (us_dense * 1e-6) / 1e9, 1),
         "speedup_vs_dense_attn": round(us_dense / us_layer, 3),
+        "measured_ceiling": ceiling,
         "roofline": {"bound": "hbm", "kernel": "select_attend_kernel (selection, gather attention, merge)",
                      "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
