@@ -143,25 +143,32 @@ __device__ __forceinline__ void raise_absmax(float* __restrict__ slot, float a) 
 // falls in from the rows present (the new row comes from registers) and stores its code words and (s, z).
 // Returns the group's code in gc; t0 = first token of the group, ntok = tokens now present in it.
 template <int DT>
-__device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* __restrict__ V, const KvRows kv,
-                                           uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta, int unit,
-                                           int L, int max_ctx, uint32_t kn, uint32_t vn, int lane, GroupCode& gc,
-                                           int& t0, int& ntok) {
+__device__ __forceinline__ void append_load_rows(const uint32_t* __restrict__ K, const KvRows kv, int L, uint32_t kn,
+                                                 int lane, uint32_t (&rows)[kG], int& t0, int& ntok) {
+  const int Gi = L / kG;
+  t0 = Gi * kG;
+  ntok = L - t0 + 1;
+  const uint32_t* src = K + kv.row(t0) * (kD / 2) + lane;  // a group lies inside one block
+#pragma unroll
+  for (int t = 0; t < kG; ++t) {
+    // rows before the new one come from memory (t0 + t < L: never the row the append writes)
+    uint32_t r = t < ntok - 1 ? src[(size_t)t * (kD / 2)] : 0u;
+    rows[t] = (t == ntok - 1) ? kn : r;
+  }
+}
+
+// rows, t0, ntok: from append_load_rows (which may run well before: the loads are the long part of the chain)
+template <int DT>
+__device__ __forceinline__ void append_finish(uint32_t* __restrict__ K, uint32_t* __restrict__ V, const KvRows kv,
+                                              uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta, int unit,
+                                              int L, int max_ctx, uint32_t kn, uint32_t vn, int lane,
+                                              const uint32_t (&rows)[kG], int t0, int ntok, GroupCode& gc,
+                                              uint4& mine) {
   const int n_groups = max_ctx / kG;
   K[kv.row(L) * (kD / 2) + lane] = kn;
   V[kv.row(L) * (kD / 2) + lane] = vn;
   const int Gi = L / kG;
-  t0 = Gi * kG;
-  ntok = L - t0 + 1;
-  uint32_t rows[kG];
-  const uint32_t* src = K + kv.row(t0) * (kD / 2) + lane;  // a group lies inside one block
-#pragma unroll
-  for (int t = 0; t < kG; ++t) {
-    // rows before the new one come from memory (t0 + t < L: never the row written above)
-    uint32_t r = t < ntok - 1 ? src[(size_t)t * (kD / 2)] : 0u;
-    rows[t] = (t == ntok - 1) ? kn : r;
-  }
-  uint4 mine = make_uint4(0, 0, 0, 0);
+  mine = make_uint4(0, 0, 0, 0);
   quantize_group<DT>(rows, ntok, lane, 0, mine, gc);
   uint4* bdst = reinterpret_cast<uint4*>(kbits) + (size_t)unit * max_ctx + t0;
   uint2* mdst = reinterpret_cast<uint2*>(kmeta + ((size_t)unit * n_groups + Gi) * kD) + lane;
@@ -172,6 +179,16 @@ __device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* _
     uint2* mdst1 = reinterpret_cast<uint2*>(kmeta + ((size_t)unit * n_groups + Gi + 1) * kD) + lane;
     *mdst1 = make_uint2(0, 0);
   }
+}
+
+template <int DT>
+__device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* __restrict__ V, const KvRows kv,
+                                           uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta, int unit,
+                                           int L, int max_ctx, uint32_t kn, uint32_t vn, int lane, GroupCode& gc,
+                                           int& t0, int& ntok, uint4& mine) {
+  uint32_t rows[kG];
+  append_load_rows<DT>(K, kv, L, kn, lane, rows, t0, ntok);
+  append_finish<DT>(K, V, kv, kbits, kmeta, unit, L, max_ctx, kn, vn, lane, rows, t0, ntok, gc, mine);
 }
 
 // The same for groups of g = 32 ns tokens (ns in {2, 4, 8}): the tail group (up to g rows) is read twice, 32 rows at a

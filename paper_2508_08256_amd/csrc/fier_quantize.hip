@@ -254,7 +254,8 @@ __global__ __launch_bounds__(64) void append_kernel(uint32_t* __restrict__ K, ui
   float amax_lo, amax_hi;
   if (ns == 1) {
     GroupCode gc;
-    append_row<DT>(K, V, lay.rows_of(unit), kbits, kmeta, unit, L, max_ctx, kn, vn, lane, gc, t0, ntok);
+    uint4 mine;
+    append_row<DT>(K, V, lay.rows_of(unit), kbits, kmeta, unit, L, max_ctx, kn, vn, lane, gc, t0, ntok, mine);
     amax_lo = gc.amax_lo, amax_hi = gc.amax_hi;
   } else {
     const GroupScale gs = append_row_long<DT>(K, V, lay.rows_of(unit), kbits, kmeta, unit, L, max_ctx, ns, kn, vn, lane,

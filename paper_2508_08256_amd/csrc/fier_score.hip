@@ -105,6 +105,18 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const int unit = append_wg ? (int)blockIdx.x : wid / n_x;
   const int range = append_wg ? -1 : wid - unit * n_x;
   const int b = unit / n_kv_heads;
+  const uint16_t* qb = q + (size_t)unit * NREP * kD;
+  // The appending wavefront's chain of dependent loads is the longest in the kernel: what it needs and what does
+  // not depend on the sequence length (the new rows, its lanes' query values) leaves before anything else.
+  uint32_t kn = 0, vn = 0, qpair[NREP];
+#pragma unroll
+  for (int r = 0; r < NREP; ++r) qpair[r] = 0;
+  if (append_wg && wave == 0 && k_new != nullptr) {
+    kn = k_new[(size_t)unit * (kD / 2) + lane];
+    vn = v_new[(size_t)unit * (kD / 2) + lane];
+#pragma unroll
+    for (int r = 0; r < NREP; ++r) qpair[r] = reinterpret_cast<const uint32_t*>(qb + r * kD)[lane];
+  }
   int Lold = seq_lens[b];
   Lold = Lold < 0 ? 0 : (Lold > max_ctx ? max_ctx : Lold);
   const bool app = HIST && k_new != nullptr && Lold < max_ctx;  // this unit receives a new row in this step
@@ -118,6 +130,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     // range 0 of a unit always runs so that an empty unit still gets its control block written
     if (range * (4 * kPair) * bpw >= L && !(HIST && range == 0)) return;
   }
+  // ... and the rows of the group the new token falls in as soon as the length is known (g = 32; the longer groups
+  // read theirs in two passes inside append_row_long)
+  uint32_t tail_rows[kG];
+  int tail_t0 = 0, tail_ntok = 0;
+  if (HIST && append_wg && wave == 0 && gshift == 0)
+    append_load_rows<DT>(K, lay.rows_of(unit), Lold, kn, lane, tail_rows, tail_t0, tail_ntok);
   const int n_groups = max_ctx / gsize;
   const int row = lane >> 4, n = lane & 15;
   const int gsel = row >> 1;  // the group of the pair block whose (s, z) this row of lanes holds
@@ -158,7 +176,6 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   // ---- the lane's 4 query channels c = 64 hsel + 4 n + e, summed over the query heads of this kv head ------
   float qs[4];
   float R = 0.f, hscale = 0.f;
-  const uint16_t* qb = q + (size_t)unit * NREP * kD;
   {
 #pragma unroll
     for (int e = 0; e < 4; ++e) qs[e] = 0.f;
@@ -191,46 +208,56 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   if (append_wg) {
     if constexpr (HIST) {
       if (wave == 0 && gshift == 0) {  // lane = channel pair (2 lane, 2 lane + 1)
-        const uint32_t kn = k_new[(size_t)unit * (kD / 2) + lane];
-        const uint32_t vn = v_new[(size_t)unit * (kD / 2) + lane];
         GroupCode gc;
-        int t0, ntok;
-        append_row<DT>(K, V, lay.rows_of(unit), const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
-                       const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kmeta)), unit, Lold, max_ctx, kn, vn,
-                       lane, gc, t0, ntok);
+        const int t0 = tail_t0, ntok = tail_ntok;
+        uint4 mine;  // lane t < 32: the code word of token t0 + t
+        append_finish<DT>(K, V, lay.rows_of(unit), const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kbits)),
+                          const_cast<uint32_t*>(reinterpret_cast<const uint32_t*>(kmeta)), unit, Lold, max_ctx, kn, vn,
+                          lane, tail_rows, t0, ntok, gc, mine);
         newmax[(size_t)unit * kD + 2 * lane] = gc.amax_lo;
         newmax[(size_t)unit * kD + 2 * lane + 1] = gc.amax_hi;
         float q0 = 0.f, q1 = 0.f;
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
-          q0 += w2f<DT>(qb[r * kD + 2 * lane]);
-          q1 += w2f<DT>(qb[r * kD + 2 * lane + 1]);
+          q0 += lo16f<DT>(qpair[r]);
+          q1 += hi16f<DT>(qpair[r]);
         }
-        const float w0 = q0 * gc.s_lo, w1 = q1 * gc.s_hi;
+        // lane = token: the 128 weights q_c s_c go through LDS in the order of the code word's bits (channel 2 lane
+        // is bit lane & 31 of word lane >> 5, channel 2 lane + 1 of word 2 + (lane >> 5)); every lane then adds up
+        // the weights of its own token's set bits -- one wavefront-wide sum (the base) instead of one per token
+        float* wl = reinterpret_cast<float*>(a_lds);  // 128 floats; this workgroup scores nothing else
+        wl[lane] = q0 * gc.s_lo;
+        wl[64 + lane] = q1 * gc.s_hi;
         const float base = wave_allsum(q0 * gc.z_lo + q1 * gc.z_hi);
-        float mine = 0.f;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint32_t wd[4] = {mine.x, mine.y, mine.z, mine.w};
+        float acc = 0.f;
 #pragma unroll
-        for (int t = 0; t < kG; ++t) {
-          float v = ((gc.bits_lo >> t) & 1u ? w0 : 0.f) + ((gc.bits_hi >> t) & 1u ? w1 : 0.f);
-          v = wave_allsum(v);
-          if (lane == t) mine = v + base;
-        }
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+          for (int i = 0; i < 32; i += 4) {
+            const float4 w4 = *reinterpret_cast<const float4*>(wl + 32 * d + i);
+            acc += (wd[d] >> i & 1u) ? w4.x : 0.f;
+            acc += (wd[d] >> (i + 1) & 1u) ? w4.y : 0.f;
+            acc += (wd[d] >> (i + 2) & 1u) ? w4.z : 0.f;
+            acc += (wd[d] >> (i + 3) & 1u) ? w4.w : 0.f;
+          }
         if (lane < ntok) {
-          scores[(size_t)unit * max_ctx + t0 + lane] = mine;
-          atomicAdd(&lhist[sel_bin(mine, R, hscale, kSelBins)], 1u);
+          const float sc = acc + base;
+          scores[(size_t)unit * max_ctx + t0 + lane] = sc;
+          atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
         }
       } else if (wave == 0) {
         // Groups of 64, 128 or 256 tokens: the tail group is re-derived 32 rows at a time; each of its pair blocks
         // is scored as soon as its code words exist, lane = token, the 128 weights q_c s_c read from LDS in the
         // order of the code word's bits (bit i of word d is channel 64 (d & 1) + 2 i + (d >> 1)).
         float* wl = reinterpret_cast<float*>(a_lds);  // 128 floats; this workgroup scores nothing else
-        const uint32_t kn = k_new[(size_t)unit * (kD / 2) + lane];
-        const uint32_t vn = v_new[(size_t)unit * (kD / 2) + lane];
         float q0 = 0.f, q1 = 0.f;
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
-          q0 += w2f<DT>(qb[r * kD + 2 * lane]);
-          q1 += w2f<DT>(qb[r * kD + 2 * lane + 1]);
+          q0 += lo16f<DT>(qpair[r]);
+          q1 += hi16f<DT>(qpair[r]);
         }
         int t0, ntok;
         float base = 0.f;
