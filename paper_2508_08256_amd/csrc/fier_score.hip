@@ -444,15 +444,15 @@ static hipError_t launch_score_dt(KvLayout lay, int n_rep, const uint32_t* kbits
                                   int group_size, hipStream_t st) {
   const int gshift = group_size == 256 ? 3 : group_size == 128 ? 2 : group_size == 64 ? 1 : 0;
   // Blocks per wavefront.  The smallest that lets every workgroup be resident at once (256 CUs; the registers
-  // allow 4 workgroups per CU for the fused kernel, 8 for the score-only one), at least 4: prologue (q, R) and
-  // epilogue (histogram flush) are then paid once.  Beyond 12 the grid is cut into several rounds of shorter
+  // allow 5 workgroups per CU for the fused kernel -- 4 with 8 query heads per kv head --, 8 for the score-only
+  // one), at least 4: prologue (q, R) and epilogue (histogram flush) are then paid once.  Beyond 12 the grid is cut into several rounds of shorter
   // workgroups instead: a workgroup's lifetime bounds the ragged end of the kernel, and in a batch of unequal
   // contexts (the host cannot see the lengths) the short units' workgroups exit at once and the dispatcher
   // backfills the machine with the long units' -- with one round, a few long units would stream alone at one
   // block in flight per wavefront.  Strides of a power of two between the workgroups' streams are avoided (they
   // collide in the memory channels: measured 8 vs 7 or 9, 16 vs 13).
   const int n_blocks = (max_ctx + kPair - 1) / kPair;
-  const int wg_slots = HIST ? 256 * 4 - units : 256 * 8;
+  const int wg_slots = HIST ? 256 * 5 - units : 256 * 8;
   const int per_unit = wg_slots / units > 0 ? wg_slots / units : 1;
   int bpw = (n_blocks + 4 * per_unit - 1) / (4 * per_unit);
   bpw = bpw < 4 ? 4 : bpw;
