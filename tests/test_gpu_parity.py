@@ -643,6 +643,52 @@ def test_calls_follow_the_stream_they_are_given(gu, oracle):
     assert np.abs(dense.cpu().numpy() - want_dense).max() <= 2e-3
 
 
+def test_two_streams_run_independent_decode_loops(gu):
+    """The library keeps no state of its own: two sequences, each with its own cache and workspace, decoded
+    concurrently on two streams (default priority) give bit for bit what the same two loops give one after the
+    other on one stream."""
+    import gpu_util
+
+    def make(seed, dtype):
+        wl = synth.make_workload(f"two{seed}", seed, 2, 8, 4, [2900, 700], [256, 90], dtype, max_ctx=3072,
+                                 n_planted=4, chan="lognormal")
+        return wl, gpu_util.DeviceWorkload(wl)
+
+    def run(streams):
+        res = []
+        jobs = [make(911, F16), make(912, BF16)]
+        state = []
+        for (wl, dw), st in zip(jobs, streams):
+            with torch.cuda.stream(st):
+                B.quantize_keys(dw.cfg, dw.cache)
+                out = torch.zeros((12, wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+                idx = torch.full((12, wl.units, 256), -1, dtype=torch.int32, device="cuda")
+                state.append((wl, dw, out, idx, dw.workspace(256)))
+        torch.cuda.synchronize()
+        for t in range(12):                                # the two loops interleaved token by token
+            for (wl, dw, out, idx, ws), st in zip(state, streams):
+                with torch.cuda.stream(st):
+                    q = torch.roll(dw.q, t, dims=-1)[None].contiguous()
+                    kn = torch.roll(dw.k_new, t, dims=-1)[None].contiguous()
+                    cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+                    B.decode_step(dw.cfg, [dw.cache], q, kn, dw.v_new[None].contiguous(), dw.budgets, 256,
+                                  out[t:t + 1], idx[t:t + 1], cnt, ws)
+                    dw.seq_lens += 1
+        torch.cuda.synchronize()
+        for wl, dw, out, idx, ws in state:
+            res.append((out.cpu().numpy(), idx.cpu().numpy(), dw.cache.unpack()))
+        return res
+
+    one = torch.cuda.current_stream()
+    serial = run([one, one])
+    both = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    for a, b in zip(serial, both):
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        for x, y in zip(a[2], b[2]):
+            assert np.array_equal(x, y)
+    assert np.isfinite(serial[0][0]).all() and (serial[0][1][:, :, 0] >= 0).all()
+
+
 def test_decode_step_phases_equal_the_fused_call(gu):
     wl = synth.config1()
     import gpu_util
