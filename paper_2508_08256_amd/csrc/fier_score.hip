@@ -24,6 +24,8 @@
 // loads (s, z) of channels c = 64h + 4n + e, e = 0..3, as one 16-byte request.  Channel c sits in code word
 // kq = h + 2(e & 1) at bit i = 2n + (e >> 1), i.e. byte y = i / 8, bit k = i % 8: MFMA j = k / 4, B register
 // r = k % 4, contraction index K = 16 kq + 4r + y.
+#include <type_traits>
+
 #include "fier_dev.h"
 #include "fier_kernels.h"
 #include "fier_quant_dev.h"
@@ -146,7 +148,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
 
   // ---- first block's loads go out before anything else (their addresses do not depend on q) ----------------
   const int P0 = range * (4 * bpw) + wave;  // this wave's blocks: P0, P0 + 4, ...
-  const bool scoring = !append_wg && P0 * kPair < L;
+  const int lim = L < tail_start ? L : tail_start;  // tokens below this are scored by the scoring workgroups
+  const bool scoring = !append_wg && P0 * kPair < lim;
   const uint32_t* __restrict__ bits_u = reinterpret_cast<const uint32_t*>(kbits) + (size_t)unit * max_ctx * 4;
   const uint4* __restrict__ meta_u = kmeta + (size_t)unit * n_groups * (kD / 4);
   // lane l loads the whole 16-byte code word of token l of the block (one contiguous 1 KiB request per wavefront);
@@ -155,8 +158,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
   const uint4* const pb = reinterpret_cast<const uint4*>(bits_u) + ((size_t)P0 * kPair + lane);
   const uint4* const pm = meta_u + ((size_t)((2 * P0 + gsel) >> gshift) * 32 + 16 * hsel + n);
   const int pm_step = 256 >> gshift;  // uint4 per block step: a wave's next block is 4 blocks = 8 half-blocks on
-  // blocks of this wave that hold tokens: P0, P0 + 4, ... below ceil(L / 64), at most bpw
-  int nb = scoring ? ((L + kPair - 1) / kPair - P0 + 3) / 4 : 0;
+  // blocks of this wave that hold tokens to score: P0, P0 + 4, ... below ceil(lim / 64), at most bpw; only the
+  // last of them can be a partial one
+  int nb = scoring ? ((lim + kPair - 1) / kPair - P0 + 3) / 4 : 0;
   nb = nb > bpw ? bpw : nb;
   // block P0 + 4 i of this wave; past the wave's last block the last one is fetched again (unconditional loads
   // keep the count of outstanding requests the same on every path)
@@ -323,11 +327,13 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     const int a_even = wave * kAWave + ((n & 4) ? kAZeroRow : a_real) + 16 * row;
     const int a_odd = wave * kAWave + ((n & 4) ? a_real : kAZeroRow) + 16 * row;
 
-    for (int it = 0; it < nb; ++it) {
+    // full_tag: every token of the block is below `lim`.  The store and the count are then unmasked, so the number
+    // of memory operations in flight is the same on every path and the wait for the next block's loads can leave
+    // this block's store outstanding -- with a masked store the compiler has to wait for everything, and the
+    // store's acknowledgement (it is the last operation issued) lands on the critical path of every iteration.
+    auto score_block = [&](auto full_tag, int it) {
+      constexpr bool FULL = decltype(full_tag)::value;
       const int P = P0 + 4 * it;
-      uint32_t w_nxt[4];
-      uint4 m_nxt;
-      fetch(w_nxt, m_nxt, it + 1);  // the next block is on its way while this one is scored
       // The B layout wants, in lane (row r, n), word r of the tokens 16 t + n, t = 0..3; the load left word d of
       // token 16 r + n in register d: a 4x4 transpose between register index and lane row, two swap stages.
       {
@@ -406,14 +412,21 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       f = fmaf((float)dg[3], 16777216.0f, f);
       const float sc = fmaf(f, inv_scale, base);
       const int tok = P * kPair + lane;
-      if (tok < L && tok < tail_start) {
+      if (FULL || tok < lim) {
         scores[(size_t)unit * max_ctx + tok] = sc;
         if (HIST) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
       }
+    };
+    for (int it = 0; it + 1 < nb; ++it) {
+      uint32_t w_nxt[4];
+      uint4 m_nxt;
+      fetch(w_nxt, m_nxt, it + 1);  // the next block is on its way while this one is scored
+      score_block(std::true_type(), it);
 #pragma unroll
       for (int t = 0; t < 4; ++t) w_cur[t] = w_nxt[t];
       m_cur = m_nxt;
     }
+    score_block(std::false_type(), nb - 1);  // the wave's last block may be a partial one
   }
 
   FIER_PROF(2, HIST && unit == 0 && range == 3)
