@@ -150,8 +150,9 @@ __device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t* tm
 // writes back / invalidates a whole L2 and costs tens of microseconds when a thousand workgroups do it, so
 // the few words one workgroup hands to another are instead written with device-scope atomic stores (write
 // through to memory) and read with device-scope atomic loads; the arrival counter is a device-scope atomic.
-// The workgroup-scope fences inside __syncthreads make every wave wait for the completion of its own stores
-// before the barrier, hence before the arrival is counted.
+// Before the arrival is counted every wave waits for the acknowledgement of its own stores (an explicit
+// s_waitcnt: the workgroup-scope fence of __syncthreads does not wait for global stores, since the waves of a
+// workgroup share one L1), and the barrier then orders all of them before the counting wave's atomic.
 __device__ __forceinline__ void store_coherent(uint32_t* p, uint32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -175,7 +176,8 @@ __device__ __forceinline__ unsigned long long load_coherent(const unsigned long 
 // brings it to `expected`.  Everything the other workgroups published with store_coherent / atomics before
 // arriving can then be read with load_coherent.  Nobody waits for anybody.  flag: one word of LDS.
 __device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expected, uint32_t* flag) {
-  __syncthreads();  // all of this workgroup's stores and atomics have completed
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's stores and atomics have been acknowledged
+  __syncthreads();                                  // ... and so have those of the other waves
   if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   return *flag == expected - 1;
