@@ -17,9 +17,12 @@
  *     enqueue work and never synchronise; results are valid once the stream has been
  *     synchronised by the caller.  Calls that touch the same buffers must be ordered by
  *     the caller (same stream, or events).
- *   - Every device pointer must be 16-byte aligned (FIER_EALIGN otherwise).
+ *   - Every device pointer must be 16-byte aligned, a workspace 256-byte aligned (FIER_EALIGN otherwise).
  *   - Arguments are validated on the host before anything is launched; on any error
- *     nothing has been enqueued.  FIER_EHIP reports a failed launch.
+ *     nothing has been enqueued.  FIER_EHIP reports a failed launch: kernels launched before the failing
+ *     one may already have run, and the workspace must then be zero-filled again before it is reused.
+ *   - K, V, q, k_new and v_new must be finite (no infinities, no NaNs): the quantizer's minimum / maximum,
+ *     the score bound and the selection are defined on finite values only.
  *   - Units are ordered batch-major: u = b * n_kv_heads + h.  The query heads that
  *     share kv head h are h * n_rep .. h * n_rep + n_rep - 1, n_rep = n_q_heads / n_kv_heads.
  *
@@ -39,9 +42,11 @@
  *              lets the scoring kernel histogram its scores in the same pass (512 bytes per unit).
  *   seq_lens [batch] int32, device: tokens currently valid in each sequence.
  *
- * Workspace: fier_workspace_bytes(cfg, max_budget) bytes of device memory, 256-byte aligned.  The
- * caller zero-fills it ONCE after allocating it; every call leaves the counters inside it zero again,
- * so it can be reused by any later call with the same cfg and max_budget (one call at a time).
+ * Workspace: device memory, 256-byte aligned, passed to every call that needs scratch as a pointer and its
+ * size in bytes.  A call returns FIER_EWORKSPACE, before anything is launched, when the pointer is NULL or the
+ * size is below fier_workspace_bytes(cfg, max_budget) for the max_budget the call works with (whole-cache
+ * attention: max_ctx).  The caller zero-fills it ONCE after allocating it; every call leaves the counters
+ * inside it zero again, so it can be reused by any later call with the same cfg (one call at a time).
  */
 #ifndef FIER_H
 #define FIER_H
@@ -58,7 +63,7 @@ typedef enum {
   FIER_EINVAL = -1,       /* null pointer, negative size, bad enum            */
   FIER_ESHAPE = -2,       /* head counts / context capacity not supported      */
   FIER_EALIGN = -3,       /* a device pointer is not 16-byte aligned            */
-  FIER_EWORKSPACE = -4,   /* workspace missing                                  */
+  FIER_EWORKSPACE = -4,   /* workspace missing or smaller than the call needs  */
   FIER_EUNSUPPORTED = -5, /* head_dim != 128, group_size not 32/64/128/256, n_rep > 8 */
   FIER_EHIP = -6          /* a kernel launch failed                             */
 } fier_status;
@@ -82,7 +87,9 @@ typedef struct fier_cache { /* one layer; all pointers device, caller-owned */
   uint32_t *kbits;         /* fier_packed_bits_bytes(cfg) bytes */
   uint32_t *kmeta;         /* fier_packed_meta_bytes(cfg) bytes */
   float *kabsmax;          /* [units][D]: per channel, an upper bound of |dequantized key| over the
-                              tokens quantized so far; written by fier_quantize_keys, raised by appends */
+                              tokens quantized so far; written by fier_quantize_keys, raised by appends.  A cache
+                              that is filled by appends alone (no fier_quantize_keys call) must start with it
+                              zero-filled */
   const int32_t *seq_lens; /* [batch] */
   /* Paged K / V rows (optional).  block_table is [batch][max_ctx / block_tokens]: entry j of sequence b is
    * the pool block that holds its tokens [j * block_tokens, (j + 1) * block_tokens), for all kv heads.
@@ -155,7 +162,7 @@ int fier_topk(const fier_config *cfg, const float *scores, const int32_t *seq_le
  */
 int fier_topk_ws(const fier_config *cfg, const float *scores, const int32_t *seq_lens,
                  int32_t extra_tokens, const int32_t *budgets, int32_t max_budget, int32_t *idx,
-                 int32_t *count, void *workspace, void *stream);
+                 int32_t *count, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Alg. 1 step 4.  For every query head: p = softmax(sm_scale * q . K[S]^T), out = p V[S], with
@@ -165,13 +172,13 @@ int fier_topk_ws(const fier_config *cfg, const float *scores, const int32_t *seq
  */
 int fier_sparse_attn(const fier_config *cfg, const fier_cache *cache, const void *q,
                      const int32_t *idx, const int32_t *count, int32_t max_budget, float *out,
-                     void *workspace, void *stream);
+                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* Sec. 3.1 full-cache decode attention softmax(sm_scale * q K^T) V over rows [0, seq_len +
  * extra_tokens): the "Full KV" comparison of Sec. 4.5, same kernels as step 4 without the gather.
  * workspace: fier_workspace_bytes(cfg, max_ctx). */
 int fier_dense_attn(const fier_config *cfg, const fier_cache *cache, const void *q,
-                    int32_t extra_tokens, float *out, void *workspace, void *stream);
+                    int32_t extra_tokens, float *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * One whole decode step (Alg. 1 with the append of Sec. 3.1) for n_layers layers, one enqueue:
@@ -188,7 +195,8 @@ int fier_dense_attn(const fier_config *cfg, const fier_cache *cache, const void 
  */
 int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
                      const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
-                     float *out, int32_t *idx_out, int32_t *count_out, void *workspace, void *stream);
+                     float *out, int32_t *idx_out, int32_t *count_out, void *workspace, size_t workspace_bytes,
+                     void *stream);
 
 /*
  * The deployment policy of Sec. 4.1 (the method is not applied to the first two layers): as fier_decode_step,
@@ -200,7 +208,7 @@ int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n
 int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int32_t n_layers,
                            const uint8_t *dense_layers, const void *q, const void *k_new, const void *v_new,
                            const int32_t *budgets, int32_t max_budget, float *out, int32_t *idx_out,
-                           int32_t *count_out, void *workspace, void *stream);
+                           int32_t *count_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * One of the three kernels of fier_decode_step alone, for measurement: phase 1 = append + score + score
@@ -212,8 +220,8 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
  */
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
                            const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
-                           float *out, int32_t *idx_out, int32_t *count_out, void *workspace, int32_t phase,
-                           void *stream);
+                           float *out, int32_t *idx_out, int32_t *count_out, void *workspace,
+                           size_t workspace_bytes, int32_t phase, void *stream);
 
 /*
  * Page-level importance, the page-retrieval baseline the paper compares with (Sec. 3.2, Eq. 1-3) and the

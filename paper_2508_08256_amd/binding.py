@@ -87,12 +87,14 @@ def lib():
         L.fier_score.argtypes = [cfgp, cachep, vp, i32, vp, vp]
         L.fier_topk.restype = C.c_int
         L.fier_topk.argtypes = [cfgp, vp, vp, i32, vp, i32, vp, vp, vp]
+        L.fier_topk_ws.restype = C.c_int
+        L.fier_topk_ws.argtypes = [cfgp, vp, vp, i32, vp, i32, vp, vp, vp, C.c_size_t, vp]
         L.fier_sparse_attn.restype = C.c_int
-        L.fier_sparse_attn.argtypes = [cfgp, cachep, vp, vp, vp, i32, vp, vp, vp]
+        L.fier_sparse_attn.argtypes = [cfgp, cachep, vp, vp, vp, i32, vp, vp, C.c_size_t, vp]
         L.fier_dense_attn.restype = C.c_int
-        L.fier_dense_attn.argtypes = [cfgp, cachep, vp, i32, vp, vp, vp]
+        L.fier_dense_attn.argtypes = [cfgp, cachep, vp, i32, vp, vp, C.c_size_t, vp]
         L.fier_decode_step.restype = C.c_int
-        L.fier_decode_step.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.fier_decode_step.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, vp]
         L.fier_page_meta_bytes.restype = C.c_size_t
         L.fier_page_meta_bytes.argtypes = [cfgp, i32]
         L.fier_page_minmax.restype = C.c_int
@@ -106,9 +108,9 @@ def lib():
         L.fier_expand_pages.restype = C.c_int
         L.fier_expand_pages.argtypes = [cfgp, vp, vp, i32, vp, i32, i32, vp, vp, i32, vp]
         L.fier_decode_step_mixed.restype = C.c_int
-        L.fier_decode_step_mixed.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.fier_decode_step_mixed.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, vp]
         L.fier_decode_step_phase.restype = C.c_int
-        L.fier_decode_step_phase.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp]
+        L.fier_decode_step_phase.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, i32, vp]
         L.fier_unpack_bits.restype = None
         L.fier_unpack_bits.argtypes = [cfgp, vp, vp]
         L.fier_unpack_meta.restype = None
@@ -157,14 +159,11 @@ def make_workspace(cfg: Config, max_budget: int):
     return torch.zeros(n, dtype=torch.uint8, device="cuda")
 
 
-def _ws(workspace, cfg: Config, max_budget: int, what: str):
-    """Pointer of a workspace tensor after checking its size: the C ABI takes the pointer alone and cannot."""
-    if workspace is not None:
-        need = workspace_bytes(cfg, max_budget)
-        have = workspace.numel() * workspace.element_size()
-        if have < need:
-            raise ValueError(f"{what}: workspace of {have} bytes, fier_workspace_bytes(cfg, {int(max_budget)}) = {need}")
-    return _ptr(workspace)
+def _ws(workspace):
+    """(pointer, size in bytes) of a workspace tensor, as the C entry points take it; they check the size."""
+    if workspace is None:
+        return None, 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
 
 
 def check_config(cfg: Config) -> int:
@@ -235,19 +234,18 @@ def topk(cfg: Config, scores, seq_lens, extra_tokens: int, budgets, max_budget: 
 
 def topk_ws(cfg: Config, scores, seq_lens, extra_tokens: int, budgets, max_budget: int, idx, count, workspace):
     _check(lib().fier_topk_ws(C.byref(cfg), _ptr(scores), _ptr(seq_lens), int(extra_tokens), _ptr(budgets),
-                              int(max_budget), _ptr(idx), _ptr(count), _ws(workspace, cfg, max_budget, "fier_topk_ws"),
-                              _stream()), "fier_topk_ws")
+                              int(max_budget), _ptr(idx), _ptr(count), *_ws(workspace), _stream()), "fier_topk_ws")
 
 
 def sparse_attn(cfg: Config, cache: DeviceCache, q, idx, count, max_budget: int, out, workspace):
     _check(lib().fier_sparse_attn(C.byref(cfg), C.byref(cache.c), _ptr(q), _ptr(idx), _ptr(count), int(max_budget),
-                                  _ptr(out), _ws(workspace, cfg, max_budget, "fier_sparse_attn"), _stream()),
+                                  _ptr(out), *_ws(workspace), _stream()),
            "fier_sparse_attn")
 
 
 def dense_attn(cfg: Config, cache: DeviceCache, q, extra_tokens: int, out, workspace):
     _check(lib().fier_dense_attn(C.byref(cfg), C.byref(cache.c), _ptr(q), int(extra_tokens), _ptr(out),
-                                 _ws(workspace, cfg, cfg.max_ctx, "fier_dense_attn"), _stream()), "fier_dense_attn")
+                                 *_ws(workspace), _stream()), "fier_dense_attn")
 
 
 def decode_step(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, out, idx_out, count_out, workspace):
@@ -255,7 +253,7 @@ def decode_step(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, 
     arr = (Cache * len(caches))(*[c.c for c in caches])
     _check(lib().fier_decode_step(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(budgets),
                                   int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
-                                  _ws(workspace, cfg, max_budget, "fier_decode_step"), _stream()), "fier_decode_step")
+                                  *_ws(workspace), _stream()), "fier_decode_step")
 
 
 def page_meta_bytes(cfg: Config, page_tokens: int) -> int:
@@ -296,8 +294,7 @@ def decode_step_mixed(cfg: Config, caches, dense_layers, q, k_new, v_new, budget
     flags = (C.c_uint8 * len(caches))(*[1 if d else 0 for d in dense_layers])
     _check(lib().fier_decode_step_mixed(C.byref(cfg), arr, len(caches), flags, _ptr(q), _ptr(k_new), _ptr(v_new),
                                         _ptr(budgets), int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
-                                        _ws(workspace, cfg, cfg.max_ctx if any(dense_layers) else max_budget,
-                                            "fier_decode_step_mixed"), _stream()), "fier_decode_step_mixed")
+                                        *_ws(workspace), _stream()), "fier_decode_step_mixed")
 
 
 def decode_step_phase(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, out, idx_out, count_out,
@@ -306,5 +303,4 @@ def decode_step_phase(cfg: Config, caches, q, k_new, v_new, budgets, max_budget:
     arr = (Cache * len(caches))(*[c.c for c in caches])
     _check(lib().fier_decode_step_phase(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new),
                                         _ptr(budgets), int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
-                                        _ws(workspace, cfg, max_budget, "fier_decode_step_phase"), int(phase),
-                                        _stream()), "fier_decode_step_phase")
+                                        *_ws(workspace), int(phase), _stream()), "fier_decode_step_phase")

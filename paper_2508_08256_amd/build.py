@@ -35,22 +35,29 @@ def _run(cmd):
         sys.stderr.write(err + "\n")
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every kernel file for gfx950 and link libfier.so next to this file.  Always recompiles."""
-    objdir = os.path.join(HERE, "_build")
+def build(verbose: bool = False, prof: bool = False) -> str:
+    """Compile every kernel file for gfx950 and link libfier.so next to this file.  Always recompiles.
+
+    prof=True builds the tuning variant libfier_prof.so instead: the same sources with -DFIER_PROF_ENABLE (per-phase
+    and per-workgroup time stamps inside the kernels) plus fier_prof.hip, which holds the stamps and exports
+    fier_prof_read / fier_prof_read_wg / fier_prof_reset.  Nothing in the product loads it."""
+    objdir = os.path.join(HERE, "_build_prof" if prof else "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
+    flags = FLAGS + (["-DFIER_PROF_ENABLE", "-fgpu-rdc"] if prof else [])
+    lib = os.path.join(HERE, "libfier_prof.so") if prof else LIB
     jobs = []
-    for src in SOURCES:
+    for src in SOURCES + (["fier_prof.hip"] if prof else []):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        jobs.append(([hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj], obj))
+        jobs.append(([hipcc] + flags + ["-c", os.path.join(CSRC, src), "-o", obj], obj))
     with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
         list(ex.map(lambda j: _run(j[0]), jobs))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [j[1] for j in jobs])
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + (["-fgpu-rdc"] if prof else []) + ["-o", lib] +
+         [j[1] for j in jobs])
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    build(verbose=True, prof="--prof" in sys.argv[1:])

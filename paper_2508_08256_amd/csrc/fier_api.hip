@@ -127,6 +127,13 @@ Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? FIER_OK : FIER_EHIP; }
 
+// The caller's workspace against what the call is going to carve from it.
+inline int check_workspace(const void* ws, size_t have, size_t need) {
+  if (!ws || have < need) return FIER_EWORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(ws) & (kAlign - 1)) != 0) return FIER_EALIGN;
+  return FIER_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -137,7 +144,7 @@ const char* fier_status_string(int status) {
     case FIER_EINVAL: return "invalid argument";
     case FIER_ESHAPE: return "unsupported shape";
     case FIER_EALIGN: return "device pointer not 16-byte aligned";
-    case FIER_EWORKSPACE: return "workspace missing";
+    case FIER_EWORKSPACE: return "workspace missing or too small";
     case FIER_EUNSUPPORTED: return "unsupported configuration";
     case FIER_EHIP: return "kernel launch failed";
     default: return "unknown status";
@@ -212,29 +219,32 @@ int fier_topk(const fier_config* cfg, const float* scores, const int32_t* seq_le
 
 int fier_topk_ws(const fier_config* cfg, const float* scores, const int32_t* seq_lens, int32_t extra_tokens,
                  const int32_t* budgets, int32_t max_budget, int32_t* idx, int32_t* count, void* workspace,
-                 void* stream) {
+                 size_t workspace_bytes, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
   if (!scores || !seq_lens || !budgets || !idx || !count) return FIER_EINVAL;
   if (extra_tokens < 0 || extra_tokens > 1 || max_budget < 1) return FIER_EINVAL;
-  if (!workspace) return FIER_EWORKSPACE;
-  if (misaligned(scores) || misaligned(idx) || misaligned(workspace)) return FIER_EALIGN;
+  if (misaligned(scores) || misaligned(idx)) return FIER_EALIGN;
   if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
+  st = check_workspace(workspace, workspace_bytes, carve(cfg, max_budget, nullptr).bytes);
+  if (st != FIER_OK) return st;
   Workspace w = carve(cfg, max_budget, workspace);
   return hip_status(fier::launch_topk_ws(w.sb, scores, seq_lens, extra_tokens, budgets, max_budget, idx, count,
                                          units_of(cfg), cfg->n_kv_heads, cfg->max_ctx, (hipStream_t)stream));
 }
 
 int fier_sparse_attn(const fier_config* cfg, const fier_cache* cache, const void* q, const int32_t* idx,
-                     const int32_t* count, int32_t max_budget, float* out, void* workspace, void* stream) {
+                     const int32_t* count, int32_t max_budget, float* out, void* workspace, size_t workspace_bytes,
+                     void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
   st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
   if (!q || !idx || !count || !out || max_budget < 1) return FIER_EINVAL;
-  if (!workspace) return FIER_EWORKSPACE;
-  if (misaligned(q) || misaligned(idx) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
+  if (misaligned(q) || misaligned(idx) || misaligned(out)) return FIER_EALIGN;
   if (max_budget > cfg->max_ctx) return FIER_EINVAL;
+  st = check_workspace(workspace, workspace_bytes, carve(cfg, max_budget, nullptr).bytes);
+  if (st != FIER_OK) return st;
   Workspace w = carve(cfg, max_budget, workspace);
   return hip_status(fier::launch_attn(cfg->kv_dtype, layout_of(cfg, cache), n_rep_of(cfg), cache->k, cache->v, q, idx, count,
                                       cache->seq_lens, 0, max_budget, fier::kAttnRowsSparse, splits_for(max_budget),
@@ -243,14 +253,15 @@ int fier_sparse_attn(const fier_config* cfg, const fier_cache* cache, const void
 }
 
 int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void* q, int32_t extra_tokens, float* out,
-                    void* workspace, void* stream) {
+                    void* workspace, size_t workspace_bytes, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
   st = check_cache(cfg, cache);
   if (st != FIER_OK) return st;
   if (!q || !out || extra_tokens < 0 || extra_tokens > 1) return FIER_EINVAL;
-  if (!workspace) return FIER_EWORKSPACE;
-  if (misaligned(q) || misaligned(out) || misaligned(workspace)) return FIER_EALIGN;
+  if (misaligned(q) || misaligned(out)) return FIER_EALIGN;
+  st = check_workspace(workspace, workspace_bytes, carve(cfg, cfg->max_ctx, nullptr).bytes);
+  if (st != FIER_OK) return st;
   Workspace w = carve(cfg, cfg->max_ctx, workspace);
   const int rows_per_wg = dense_rows_per_wg(cfg);
   const int n_splits = (cfg->max_ctx + rows_per_wg - 1) / rows_per_wg;
@@ -263,21 +274,25 @@ int fier_dense_attn(const fier_config* cfg, const fier_cache* cache, const void*
 static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, int32_t n_layers,
                             const uint8_t* dense_layers, const void* q, const void* k_new, const void* v_new,
                             const int32_t* budgets, int32_t max_budget, float* out, int32_t* idx_out,
-                            int32_t* count_out, void* workspace, int32_t phase, void* stream) {
+                            int32_t* count_out, void* workspace, size_t workspace_bytes, int32_t phase,
+                            void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
   if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
   if (max_budget > cfg->max_ctx || phase < 0 || phase > 3) return FIER_EINVAL;
-  if (!workspace) return FIER_EWORKSPACE;
-  if (misaligned(q) || misaligned(out) || misaligned(workspace) || misaligned(k_new) || misaligned(v_new) ||
-      misaligned(idx_out))
+  if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
     st = check_cache(cfg, &layers[l]);
     if (st != FIER_OK) return st;
   }
+  // a layer that runs whole-cache attention carves the workspace for selections of max_ctx rows
+  bool any_dense = false;
+  for (int l = 0; dense_layers && l < n_layers; ++l) any_dense = any_dense || dense_layers[l] != 0;
+  st = check_workspace(workspace, workspace_bytes, carve(cfg, any_dense ? cfg->max_ctx : max_budget, nullptr).bytes);
+  if (st != FIER_OK) return st;
   const int units = units_of(cfg), n_rep = n_rep_of(cfg);
   const int extra = k_new ? 1 : 0;
   const size_t esz = 2;
@@ -330,26 +345,26 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
 
 int fier_decode_step(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
                      const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget, float* out,
-                     int32_t* idx_out, int32_t* count_out, void* workspace, void* stream) {
+                     int32_t* idx_out, int32_t* count_out, void* workspace, size_t workspace_bytes, void* stream) {
   return decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
-                          workspace, 0, stream);
+                          workspace, workspace_bytes, 0, stream);
 }
 
 int fier_decode_step_mixed(const fier_config* cfg, const fier_cache* layers, int32_t n_layers,
                            const uint8_t* dense_layers, const void* q, const void* k_new, const void* v_new,
                            const int32_t* budgets, int32_t max_budget, float* out, int32_t* idx_out,
-                           int32_t* count_out, void* workspace, void* stream) {
+                           int32_t* count_out, void* workspace, size_t workspace_bytes, void* stream) {
   return decode_step_impl(cfg, layers, n_layers, dense_layers, q, k_new, v_new, budgets, max_budget, out, idx_out,
-                          count_out, workspace, 0, stream);
+                          count_out, workspace, workspace_bytes, 0, stream);
 }
 
 int fier_decode_step_phase(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
                            const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget,
-                           float* out, int32_t* idx_out, int32_t* count_out, void* workspace, int32_t phase,
-                           void* stream) {
+                           float* out, int32_t* idx_out, int32_t* count_out, void* workspace,
+                           size_t workspace_bytes, int32_t phase, void* stream) {
   if (phase < 1) return FIER_EINVAL;
   return decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
-                          workspace, phase, stream);
+                          workspace, workspace_bytes, phase, stream);
 }
 
 // ---- page-level importance ------------------------------------------------------------------------------------------

@@ -4,7 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-// Optional time stamps for kernel tuning (a tuning build defines FIER_PROF_ENABLE); compiled out of the library.
+// Optional time stamps for kernel tuning: `python -m paper_2508_08256_amd.build --prof` compiles the same sources
+// with -DFIER_PROF_ENABLE plus fier_prof.hip (which defines the two arrays and the calls that read them) into
+// libfier_prof.so.  The library proper is compiled without the flag and contains none of this.
 #ifdef FIER_PROF_ENABLE
 extern __device__ unsigned long long fier_prof_slots[64];
 #define FIER_PROF(slot, cond) \
@@ -101,11 +103,16 @@ __device__ __forceinline__ uint32_t score_key(float v) {
   return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
-// bin of the equal-width histogram over [-R, R]; monotone non-decreasing in v, the same in every kernel
+// bin of the equal-width histogram over [-R, R]; monotone non-decreasing in v, the same in every kernel.  The
+// clamp is done in floating point (the maximum and minimum of a NaN and a number are the number), so the
+// conversion to an integer always sees a value in [0, n_bins - 1]: with scale = 0 (R = 0: every score is zero)
+// everything lands in bin 0.
 __device__ __forceinline__ int sel_bin(float v, float R, float scale, int n_bins) {
-  int bin = (int)((v + R) * scale);
-  return bin > n_bins - 1 ? n_bins - 1 : (bin < 0 ? 0 : bin);
+  const float x = fminf(fmaxf((v + R) * scale, 0.0f), (float)(n_bins - 1));
+  return (int)x;
 }
+// bins per unit of score for scores in [-R, R]; 0 when the range is empty
+__device__ __forceinline__ float sel_scale(float R, int n_bins) { return R > 0.0f ? (float)n_bins / (R + R) : 0.0f; }
 
 // Inclusive prefix sum over the 64 lanes with DPP (row shifts inside each row of 16 lanes, then the last lane of
 // a row broadcast into the following rows): six dependent ALU ops instead of six LDS-crossbar shuffles.
@@ -180,7 +187,12 @@ __device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expecte
   __syncthreads();                                  // ... and so have those of the other waves
   if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
-  return *flag == expected - 1;
+  const bool last = *flag == expected - 1;
+  // reader side: nothing the last arriver loads afterwards may be moved above the counter's return by the compiler
+  // (the hardware issues a wave's memory operations in program order, and load_coherent never hits a stale line)
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  asm volatile("" ::: "memory");
+  return last;
 }
 
 }  // namespace fier

@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       // lane 0's sum is taken so that R is bit-identical in every lane, wave and workgroup (the binning must be
       // the same function everywhere)
       R = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(rpart)));
-      hscale = (float)kSelBins / (R + R);
+      hscale = sel_scale(R, kSelBins);
       for (int i = tid; i < kSelBins; i += 256) lhist[i] = 0;
       __syncthreads();
     }

@@ -30,7 +30,7 @@ __device__ __forceinline__ bool exact_select_lds(const unsigned long long* lcand
   for (int k = tid; k < SUBBINS; k += NT) hist[k] = 0;
   if (tid == 0) *n_sub = 0;
   __syncthreads();
-  const float lo_b = (float)tbin / scale - R;  // lower edge of the threshold bin
+  const float lo_b = scale > 0.0f ? (float)tbin / scale - R : 0.0f;  // lower edge of the threshold bin
   const float scale2 = scale * (float)SUBBINS;
   for (uint32_t k = tid; k < n_cand; k += NT) {
     const float x = key_score((uint32_t)(lcand[k] >> 32));

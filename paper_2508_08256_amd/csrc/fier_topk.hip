@@ -72,8 +72,7 @@ __device__ __forceinline__ void find_bin_from_top(const uint32_t* hist, int nb, 
 
 // bin of the equal-width histogram; monotone non-decreasing in v
 __device__ __forceinline__ int value_bin(float v, float lo, float scale) {
-  int bin = (int)((v - lo) * scale);
-  return bin > kTkBins - 1 ? kTkBins - 1 : (bin < 0 ? 0 : bin);
+  return (int)fminf(fmaxf((v - lo) * scale, 0.0f), (float)(kTkBins - 1));  // clamped before the conversion
 }
 
 // Visit the unit's scores as 16-byte chunks: chunk c of thread tid covers tokens (c * 1024 + tid) * 4 .. + 3.

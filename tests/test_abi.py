@@ -69,16 +69,17 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert lib.fier_score(C.byref(cfg), C.byref(good), 0x6000, 2, 0x7000, None) == B.EINVAL
     assert lib.fier_score(C.byref(cfg), C.byref(good), 0x6004, 0, 0x7000, None) == B.EALIGN
     assert lib.fier_topk(C.byref(cfg), 0x6000, 0x5000, 0, 0x5100, 0, 0x7000, 0x8000, None) == B.EINVAL
-    assert lib.fier_sparse_attn(C.byref(cfg), C.byref(good), 0x6000, 0x7000, 0x8000, 16, 0x9000, None,
+    big = 1 << 30
+    assert lib.fier_sparse_attn(C.byref(cfg), C.byref(good), 0x6000, 0x7000, 0x8000, 16, 0x9000, None, big,
                                 None) == B.EWORKSPACE
-    assert lib.fier_sparse_attn(C.byref(cfg), C.byref(good), 0x6000, 0x7000, 0x8000, 512, 0x9000, 0xA000,
+    assert lib.fier_sparse_attn(C.byref(cfg), C.byref(good), 0x6000, 0x7000, 0x8000, 512, 0x9000, 0xA000, big,
                                 None) == B.EINVAL                                 # budget above capacity
-    assert lib.fier_dense_attn(C.byref(cfg), C.byref(good), 0x6000, 0, 0x9000, None, None) == B.EWORKSPACE
+    assert lib.fier_dense_attn(C.byref(cfg), C.byref(good), 0x6000, 0, 0x9000, None, big, None) == B.EWORKSPACE
     arr = (B.Cache * 1)(good)
     assert lib.fier_decode_step(C.byref(cfg), arr, 1, 0x6000, 0x7000, None, 0x5100, 16, 0x9000, None, None,
-                                0xA000, None) == B.EINVAL                         # k_new without v_new
+                                0xA000, big, None) == B.EINVAL                    # k_new without v_new
     assert lib.fier_decode_step(C.byref(cfg), arr, 0, 0x6000, None, None, 0x5100, 16, 0x9000, None, None,
-                                0xA000, None) == B.EINVAL
+                                0xA000, big, None) == B.EINVAL
     bad = B.make_config(1, 8, 8, 256, head_dim=96)
     assert lib.fier_quantize_keys(C.byref(bad), C.byref(good), None) == B.EUNSUPPORTED
 
@@ -101,7 +102,7 @@ def test_block_table_fields_are_validated():
     assert lib.fier_quantize_keys(C.byref(cfg32), C.byref(B.Cache(*ptrs, 0x6000, 32)), None) == B.ESHAPE
     arr = (B.Cache * 1)(B.Cache(*ptrs, 0x6000, 96))
     assert lib.fier_decode_step(C.byref(cfg32), arr, 1, 0x6000, None, None, 0x5100, 16, 0x9000, None, None,
-                                0xA000, None) == B.ESHAPE
+                                0xA000, 1 << 30, None) == B.ESHAPE
     assert lib.fier_page_minmax(C.byref(cfg32), C.byref(B.Cache(*ptrs, 0x6000, 96)), 16, 0x7000, None) == B.ESHAPE
 
 
@@ -135,19 +136,56 @@ def test_no_cpu_fallback_when_library_missing(monkeypatch, tmp_path):
         B.lib()
 
 
-def test_binding_refuses_a_workspace_that_is_too_small():
-    """The C ABI takes the workspace pointer alone; the binding knows the tensor's size and checks it against
-    fier_workspace_bytes before the call (whole-cache attention needs the size for max_budget = max_ctx)."""
+def test_every_call_checks_the_workspace_size_before_any_launch():
+    """Every entry point that carves a workspace takes its size and returns FIER_EWORKSPACE, on the host and before
+    any launch, when it is smaller than fier_workspace_bytes for the selection size the call works with: the
+    budget for the sparse calls, the row capacity for whole-cache attention (also inside the mixed step).  Dummy
+    pointers: nothing may be launched (a launch on them would fault; on this machine there is not even a GPU)."""
+    lib = B.lib()
+    cfg = B.make_config(1, 8, 8, 4096)
+    good = B.Cache(0x1000, 0x2000, 0x3000, 0x4000, 0x4800, 0x5000)
+    arr = (B.Cache * 1)(good)
+    ws = 0x100000
+    need64, need_all = B.workspace_bytes(cfg, 64), B.workspace_bytes(cfg, 4096)
+    assert 0 < need64 < need_all
+    cfgp, cachep = C.byref(cfg), C.byref(good)
+    assert lib.fier_sparse_attn(cfgp, cachep, 0x6000, 0x7000, 0x8000, 64, 0x9000, ws, need64 - 1, None) == B.EWORKSPACE
+    assert lib.fier_sparse_attn(cfgp, cachep, 0x6000, 0x7000, 0x8000, 65, 0x9000, ws, need64, None) == B.EWORKSPACE
+    assert lib.fier_dense_attn(cfgp, cachep, 0x6000, 0, 0x9000, ws, need64, None) == B.EWORKSPACE
+    assert lib.fier_dense_attn(cfgp, cachep, 0x6000, 0, 0x9000, ws, need_all - 1, None) == B.EWORKSPACE
+    assert lib.fier_topk_ws(cfgp, 0x6000, 0x5000, 0, 0x5100, 64, 0x7000, 0x8000, ws, need64 - 1, None) == B.EWORKSPACE
+    step = (cfgp, arr, 1, 0x6000, None, None, 0x5100, 64, 0x9000, None, None)
+    assert lib.fier_decode_step(*step, ws, need64 - 1, None) == B.EWORKSPACE
+    assert lib.fier_decode_step(*step, ws, 0, None) == B.EWORKSPACE
+    assert lib.fier_decode_step(*step, None, need64, None) == B.EWORKSPACE
+    assert lib.fier_decode_step_phase(*step, ws, need64 - 1, 1, None) == B.EWORKSPACE
+    dense = (C.c_uint8 * 1)(1)
+    mixed = (cfgp, arr, 1, dense, 0x6000, None, None, 0x5100, 64, 0x9000, None, None)
+    assert lib.fier_decode_step_mixed(*mixed, ws, need64, None) == B.EWORKSPACE      # a dense layer needs max_ctx
+    assert lib.fier_decode_step_mixed(*mixed, ws, need_all - 1, None) == B.EWORKSPACE
+    none_dense = (C.c_uint8 * 1)(0)
+    mixed0 = (cfgp, arr, 1, none_dense, 0x6000, None, None, 0x5100, 64, 0x9000, None, None)
+    assert lib.fier_decode_step_mixed(*mixed0, ws, need64 - 1, None) == B.EWORKSPACE
+    # the workspace must be 256-byte aligned, as the header says
+    assert lib.fier_decode_step(*step, ws + 16, need64, None) == B.EALIGN
+    assert lib.fier_sparse_attn(cfgp, cachep, 0x6000, 0x7000, 0x8000, 64, 0x9000, ws + 128, need64, None) == B.EALIGN
+
+
+def test_binding_passes_the_workspace_size(monkeypatch):
+    """The binding hands the tensor's size to the C entry point, which refuses a short one."""
     import types
 
     import torch
 
+    monkeypatch.setattr(B, "_stream", lambda: None)   # no GPU here; the check comes before any launch
+
     cfg = B.make_config(1, 8, 8, 4096)
     small = torch.zeros(B.workspace_bytes(cfg, 64), dtype=torch.uint8)
-    cache = types.SimpleNamespace(c=B.Cache())
-    with pytest.raises(ValueError, match="fier_dense_attn: workspace"):
-        B.dense_attn(cfg, cache, None, 0, None, small)
-    with pytest.raises(ValueError, match="fier_sparse_attn: workspace"):
-        B.sparse_attn(cfg, cache, None, None, None, 65, None, small)
-    with pytest.raises(ValueError, match="fier_decode_step_mixed: workspace"):
-        B.decode_step_mixed(cfg, [cache], [True], None, None, None, None, 64, None, None, None, small)
+    cache = types.SimpleNamespace(c=B.Cache(0x1000, 0x2000, 0x3000, 0x4000, 0x4800, 0x5000))
+    t = types.SimpleNamespace(data_ptr=lambda: 0x6000)
+    for call in (lambda: B.dense_attn(cfg, cache, t, 0, t, small),
+                 lambda: B.sparse_attn(cfg, cache, t, t, t, 65, t, small),
+                 lambda: B.decode_step_mixed(cfg, [cache], [True], t, None, None, t, 64, t, None, None, small)):
+        with pytest.raises(B.FierError) as e:
+            call()
+        assert e.value.status == B.EWORKSPACE
