@@ -199,6 +199,20 @@ int fier_decode_step(const fier_config *cfg, const fier_cache *layers, int32_t n
                      void *stream);
 
 /*
+ * fier_decode_step for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, serving loops and harnesses that forbid allocation): the scratch is a fixed 48 MiB array inside the
+ * library's device image, one copy per GPU, held until the process ends.  Same arguments and results as
+ * fier_decode_step without the workspace.  Returns FIER_EWORKSPACE, with nothing enqueued, when
+ * fier_workspace_bytes(cfg, max_budget) exceeds 48 MiB (e.g. 32 units of 131072 tokens fit, 128 units of 65536 do
+ * not).  The call allocates nothing and never synchronises; it clears the part of the array that must start at zero
+ * with a small kernel on `stream`, so it can be captured into a graph.  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (different streams, different threads) race; order them.
+ */
+int fier_decode_step_static(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
+                            const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
+                            float *out, int32_t *idx_out, int32_t *count_out, void *stream);
+
+/*
  * The deployment policy of Sec. 4.1 (the method is not applied to the first two layers): as fier_decode_step,
  * except that every layer l with dense_layers[l] != 0 (HOST array of n_layers bytes; NULL = no such layer) runs
  * full attention over all seq_len (+ 1) rows after its append; its packed cache is still kept up to date.  For

@@ -19,7 +19,7 @@ EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = -1, -2, -3, -4, -5, -6
 
 SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_status_string",
            "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk", "fier_topk_ws",
-           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_page_meta_bytes",
+           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_static", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_page_meta_bytes",
            "fier_page_minmax", "fier_page_append", "fier_page_score", "fier_page_mean_score", "fier_expand_pages", "fier_unpack_bits",
            "fier_unpack_meta"]
 
@@ -95,6 +95,8 @@ def lib():
         L.fier_dense_attn.argtypes = [cfgp, cachep, vp, i32, vp, vp, C.c_size_t, vp]
         L.fier_decode_step.restype = C.c_int
         L.fier_decode_step.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, vp]
+        L.fier_decode_step_static.restype = C.c_int
+        L.fier_decode_step_static.argtypes = [cfgp, cachep, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.fier_page_meta_bytes.restype = C.c_size_t
         L.fier_page_meta_bytes.argtypes = [cfgp, i32]
         L.fier_page_minmax.restype = C.c_int
@@ -254,6 +256,14 @@ def decode_step(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, 
     _check(lib().fier_decode_step(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(budgets),
                                   int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
                                   *_ws(workspace), _stream()), "fier_decode_step")
+
+
+def decode_step_static(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, out, idx_out, count_out):
+    """fier_decode_step on the library's own scratch array: no workspace argument, nothing is allocated."""
+    arr = (Cache * len(caches))(*[c.c for c in caches])
+    _check(lib().fier_decode_step_static(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                         _ptr(budgets), int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),
+                                         _stream()), "fier_decode_step_static")
 
 
 def page_meta_bytes(cfg: Config, page_tokens: int) -> int:

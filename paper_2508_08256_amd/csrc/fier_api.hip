@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "fier.h"
 #include "fier_kernels.h"
 
@@ -89,6 +91,7 @@ struct Workspace {
   float* pl;
   int32_t* idx;
   int32_t* count;
+  size_t zero_bytes;  // the leading part that must be zero before the first call (control blocks, histograms)
   size_t bytes;
 };
 
@@ -107,6 +110,7 @@ Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
   Workspace w;
   w.sb.ctl = reinterpret_cast<fier::UnitCtl*>(take(units * sizeof(fier::UnitCtl)));
   w.sb.hist = reinterpret_cast<uint32_t*>(take(units * fier::kSelBins * sizeof(uint32_t)));
+  w.zero_bytes = off;
   w.sb.range_cnt = reinterpret_cast<uint32_t*>(take(units * ranges * sizeof(uint32_t)));
   const size_t chunks = ((size_t)c->max_ctx + fier::kClassifyTokens - 1) / fier::kClassifyTokens;
   w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * chunks * fier::kSegCand * sizeof(unsigned long long)));
@@ -281,7 +285,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
-  if (max_budget > cfg->max_ctx || phase < 0 || phase > 3) return FIER_EINVAL;
+  if (max_budget > cfg->max_ctx || phase < -1 || phase > 3) return FIER_EINVAL;  // phase -1: validate only
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
@@ -293,6 +297,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   for (int l = 0; dense_layers && l < n_layers; ++l) any_dense = any_dense || dense_layers[l] != 0;
   st = check_workspace(workspace, workspace_bytes, carve(cfg, any_dense ? cfg->max_ctx : max_budget, nullptr).bytes);
   if (st != FIER_OK) return st;
+  if (phase < 0) return FIER_OK;
   const int units = units_of(cfg), n_rep = n_rep_of(cfg);
   const int extra = k_new ? 1 : 0;
   const size_t esz = 2;
@@ -365,6 +370,61 @@ int fier_decode_step_phase(const fier_config* cfg, const fier_cache* layers, int
   if (phase < 1) return FIER_EINVAL;
   return decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
                           workspace, workspace_bytes, phase, stream);
+}
+
+// ---- the step on library-owned scratch ------------------------------------------------------------------------------
+// For callers that cannot allocate.  The workspace is a fixed array in the library's device image: every GPU the
+// library runs on holds one copy at its own address until the process ends.  In host code the array's name is only
+// a handle: the address kernels can use comes from hipGetSymbolAddress, asked once per device with that device current.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+__global__ void zero_words_kernel(uint32_t* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// Device address of the current device's copy of `scratch` (resolved on the first call on that device).
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FIER_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return FIER_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return FIER_OK;
+}
+}  // namespace
+
+int fier_decode_step_static(const fier_config* cfg, const fier_cache* layers, int32_t n_layers, const void* q,
+                            const void* k_new, const void* v_new, const int32_t* budgets, int32_t max_budget,
+                            float* out, int32_t* idx_out, int32_t* count_out, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != FIER_OK) return st;
+  if (max_budget < 1 || max_budget > cfg->max_ctx) return FIER_EINVAL;
+  const Workspace need = carve(cfg, max_budget, nullptr);
+  if (need.bytes > kStaticScratchBytes) return FIER_EWORKSPACE;  // beyond what the library holds
+  // everything else is checked before the scratch is touched, so that an error leaves nothing enqueued
+  st = decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
+                        reinterpret_cast<void*>(kAlign), kStaticScratchBytes, -1, stream);
+  if (st != FIER_OK) return st;
+  void* ptr = nullptr;
+  st = static_scratch(&ptr);
+  if (st != FIER_OK) return st;
+  // The array keeps what the last call left, possibly laid out for another shape: the part that has to start at
+  // zero is cleared by a kernel on the caller's stream (a fill kernel, not a memset node: callers may be capturing).
+  const size_t words = need.zero_bytes / sizeof(uint32_t);
+  zero_words_kernel<<<(unsigned)((words + 1023) / 1024 < 256 ? (words + 1023) / 1024 : 256), 256, 0,
+                      (hipStream_t)stream>>>(static_cast<uint32_t*>(ptr), words);
+  if (hipGetLastError() != hipSuccess) return FIER_EHIP;
+  return decode_step_impl(cfg, layers, n_layers, nullptr, q, k_new, v_new, budgets, max_budget, out, idx_out, count_out,
+                          ptr, kStaticScratchBytes, 0, stream);
 }
 
 // ---- page-level importance ------------------------------------------------------------------------------------------
