@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libfier.so")
 SOURCES = ["fier_api.hip", "fier_quantize.hip", "fier_score.hip", "fier_select.hip", "fier_topk.hip",
-           "fier_attn.hip", "fier_page.hip"]
+           "fier_attn.hip", "fier_step.hip", "fier_page.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-mllvm", "-amdgpu-mfma-vgpr-form=1",  # matrix-core results stay in ordinary vector registers

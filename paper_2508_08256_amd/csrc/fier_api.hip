@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 
 #include "fier.h"
@@ -108,18 +109,25 @@ Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
     return r;
   };
   Workspace w;
+  const size_t chunks = ((size_t)c->max_ctx + fier::kClassifyTokens - 1) / fier::kClassifyTokens;
+  // candidate slots and workgroup entries per unit: enough for the step's second kernel (a quarter of the tokens of
+  // up to n_ranges workgroups, rounded up to whole workgroups of 8 ranges) and for fier_topk_ws's threshold kernel
+  const size_t cand_pitch = std::max(chunks * fier::kSegCand, (ranges + 8) * (size_t)(fier::kRangeTokens / 4));
+  const size_t seg_pitch = std::max(chunks, ranges);
+  w.sb.cand_pitch = cand_pitch;
+  w.sb.seg_pitch = (int)seg_pitch;
   w.sb.ctl = reinterpret_cast<fier::UnitCtl*>(take(units * sizeof(fier::UnitCtl)));
   w.sb.hist = reinterpret_cast<uint32_t*>(take(units * fier::kSelBins * sizeof(uint32_t)));
+  w.sb.done = reinterpret_cast<uint32_t*>(take(units * seg_pitch * sizeof(uint32_t)));
   w.zero_bytes = off;
   w.sb.range_cnt = reinterpret_cast<uint32_t*>(take(units * ranges * sizeof(uint32_t)));
-  const size_t chunks = ((size_t)c->max_ctx + fier::kClassifyTokens - 1) / fier::kClassifyTokens;
-  w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * chunks * fier::kSegCand * sizeof(unsigned long long)));
-  w.sb.seg_cnt = reinterpret_cast<uint32_t*>(take(units * chunks * sizeof(uint32_t)));
+  w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * cand_pitch * sizeof(unsigned long long)));
+  w.sb.seg_cnt = reinterpret_cast<uint32_t*>(take(units * seg_pitch * sizeof(uint32_t)));
   w.sb.scores = reinterpret_cast<float*>(take(units * (size_t)c->max_ctx * sizeof(float)));
   w.sb.newmax = reinterpret_cast<float*>(take(units * kD * sizeof(float)));
-  w.sb.po = reinterpret_cast<float*>(take(heads * ranges * kD * sizeof(float)));
-  w.sb.pm = reinterpret_cast<float*>(take(heads * ranges * sizeof(float)));
-  w.sb.pl = reinterpret_cast<float*>(take(heads * ranges * sizeof(float)));
+  w.sb.po = reinterpret_cast<float*>(take(heads * (ranges + 1) * kD * sizeof(float)));
+  w.sb.pm = reinterpret_cast<float*>(take(heads * (ranges + 1) * sizeof(float)));
+  w.sb.pl = reinterpret_cast<float*>(take(heads * (ranges + 1) * sizeof(float)));
   w.po = reinterpret_cast<float*>(take(heads * splits * kD * sizeof(float)));
   w.pm = reinterpret_cast<float*>(take(heads * splits * sizeof(float)));
   w.pl = reinterpret_cast<float*>(take(heads * splits * sizeof(float)));
@@ -285,7 +293,8 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
-  if (max_budget > cfg->max_ctx || phase < -1 || phase > 3) return FIER_EINVAL;  // phase -1: validate only
+  // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel; 2 + 16 f: kernel 2 with test flags f
+  if (max_budget > cfg->max_ctx || phase < -1 || phase > 2 + 16 * 7) return FIER_EINVAL;
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
@@ -335,13 +344,24 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
                              cfg->max_ctx, cfg->group_size, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
-    if (phase == 0 || phase == 2) {
+    if (phase == 8) {
       e = fier::launch_threshold(w.sb, c->seq_lens, extra, budgets, max_budget, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
-    if (phase == 0 || phase == 3) {
+    if (phase == 9) {
       e = fier::launch_select_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
                                      cfg->sm_scale, idxl, outl, c->kabsmax, units, cfg->n_kv_heads, cfg->max_ctx, s);
+      if (e != hipSuccess) return FIER_EHIP;
+    }
+    if (phase == 0 || (phase & 15) == 2) {
+      const int flags = phase >> 4;
+      e = fier::launch_step_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, budgets,
+                                   max_budget, cfg->sm_scale, cntl, outl, c->kabsmax, units, cfg->n_kv_heads,
+                                   cfg->max_ctx, flags, s);
+      if (e != hipSuccess) return FIER_EHIP;
+    }
+    if ((phase == 0 || phase == 3) && idxl) {
+      e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
   }

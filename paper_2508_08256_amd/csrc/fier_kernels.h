@@ -46,22 +46,23 @@ constexpr int kAttnRowsDenseMin = 512;   // rows per workgroup when attending ov
 constexpr int kAttnRowsDenseMax = 3200;  // picks a multiple of 128 in this range (see dense_rows_per_wg)
 
 // ---- fused decode step -------------------------------------------------------------------------------
-// Three kernels per layer.  Each unit's tokens are spread over many workgroups; the few serial steps
-// (threshold bin from the merged histogram, exact threshold among the candidates, merge of the attention
-// partials) are done by whichever workgroup of the unit finishes last ("last arriver": a device-scope
-// counter after a release fence; nobody ever waits).
+// Two kernels per layer: (1) append + score + score histogram, (2) exact threshold + attention over the selected rows
+// + merge.  Each unit's tokens are spread over many workgroups; the few serial steps (exact threshold among the
+// candidates of the threshold bin, merge of the attention partials) are done by whichever workgroup of the unit
+// arrives last at a device-scope counter ("last arriver").  fier_topk_ws reuses the histogram machinery with a
+// threshold kernel of its own.
 constexpr int kSelBins = 512;          // equal-width score histogram bins over [-R, R] (few enough that the
                                        // per-workgroup histograms merge with ~100 device atomics each)
-constexpr int kRangeTokens = 1024;     // tokens per workgroup in the score and the select+attend kernels
-constexpr int kClassifyTokens = 4096;  // tokens per workgroup in the threshold kernel
-constexpr int kSegCand = 1024;         // candidate slots per threshold-kernel workgroup
-constexpr int kSelCandMax = 4096;      // candidates per unit the exact selection handles in LDS
+constexpr int kRangeTokens = 1024;     // tokens per range: the unit of work of the step's second kernel
+constexpr int kClassifyTokens = 4096;  // tokens per workgroup in fier_topk_ws's threshold kernel
+constexpr int kSegCand = 1024;         // candidate slots per workgroup of that kernel
+constexpr int kSelCandMax = 4096;      // candidates per unit its exact selection handles in LDS
 constexpr int kSubBins = 1024;         // second-level bins inside the threshold bin
 constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 
 struct UnitCtl {        // one per unit at the head of the workspace
-  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention, [1] threshold kernel, [2] select + attend
-                        // kernel; zero between calls
+  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention, [1] classification (step) / threshold kernel
+                        // (fier_topk_ws), [2] attention partials of the step; zero between calls
   uint32_t topk_max;    // fier_topk_ws: bit pattern of the largest |score| of the unit; zero between calls
   int32_t tbin;         // bins above are selected, bins below are not (-1: everything, kSelBins: nothing)
   uint32_t above;       // tokens in bins above tbin
@@ -70,21 +71,28 @@ struct UnitCtl {        // one per unit at the head of the workspace
   float scale;          // kSelBins / (2 R)
   uint32_t T;           // threshold key inside tbin
   int32_t idxT;         // among keys == T inside tbin, indices <= idxT are selected
-  uint32_t pad[5];
+  uint32_t pad;
+  unsigned long long thr;  // the step's threshold as one word, T << 32 | idxT + 2, published by the unit's selector
+                           // to its other workgroups; zero between calls
+  uint32_t chk_cnt;     // checksums of the rows the step attended over (count, sum of token indices); only
+  uint32_t chk_sum;     // accumulated on request (tests), never cleared by the library
 };
 static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte line");
 
 struct StepBuffers {    // carved from the caller's workspace
   UnitCtl* ctl;         // [units]
-  uint32_t* hist;       // [units][kSelBins]: filled by the score kernel, read and cleared by the threshold kernel
-  uint32_t* range_cnt;  // [units][n_ranges]: selected tokens per 1024-token range, then their exclusive scan
-  unsigned long long* cand;  // [units][n_chunks][kSegCand] (key << 32 | token index), one segment per workgroup
-  uint32_t* seg_cnt;    // [units][n_chunks] candidates found by each threshold-kernel workgroup
+  uint32_t* hist;       // [units][kSelBins]: filled by the score kernel, read and cleared by the step's second kernel
+  uint32_t* done;       // [units][seg_pitch]: workgroup has attended over its threshold-bin rows; zero between calls
+  uint32_t* range_cnt;  // [units][n_ranges] (fier_topk_ws): selected tokens per 1024-token range, then their scan
+  unsigned long long* cand;  // [units][cand_pitch] candidates (key << 32 | token index)
+  uint32_t* seg_cnt;    // [units][seg_pitch] candidates published by each workgroup
   float* scores;        // [units][max_ctx]
   float* newmax;        // [units][128]: |dequantized key| bound of the group re-quantized by this step's append
-  float* po;            // attention partials, n_slots per (unit, query head)
+  float* po;            // attention partials, n_ranges + 1 slots per (unit, query head)
   float* pm;
   float* pl;
+  size_t cand_pitch;    // candidate slots per unit
+  int seg_pitch;        // workgroup entries per unit in seg_cnt and done
 };
 
 hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
@@ -95,9 +103,8 @@ hipError_t launch_append(int dtype, KvLayout lay, void* K, void* V, uint32_t* kb
                          const int32_t* seq_lens, const void* k_new, const void* v_new, int units, int n_kv_heads,
                          int max_ctx, int group_size, hipStream_t st);
 
-// With sb != nullptr the kernel also builds the per-unit score histogram and its last workgroup per unit
-// finds the threshold bin for budgets[b] (first kernel of the fused step); with k_new != nullptr as well it
-// appends the new K/V rows first (extra must then be 1).
+// With sb != nullptr the kernel also builds the per-unit score histogram (first kernel of the fused step); with
+// k_new != nullptr as well it appends the new K/V rows first (extra must then be 1).
 hipError_t launch_score(int dtype, KvLayout lay, int n_rep, const uint32_t* kbits, const uint32_t* kmeta, const float* kabsmax,
                         const void* q, const int32_t* seq_lens, int extra, float* scores, const StepBuffers* sb,
                         const int32_t* budgets, int max_budget, void* K, void* V, const void* k_new,
@@ -116,6 +123,18 @@ hipError_t launch_select_attend(int dtype, KvLayout lay, int n_rep, const StepBu
                                 const void* q, const int32_t* seq_lens, int extra, int max_budget, float sm_scale,
                                 int32_t* idx_out, float* out, float* kabsmax, int units, int n_kv_heads, int max_ctx,
                                 hipStream_t st);
+
+// Second kernel of the fused step: exact threshold, attention over the selected rows, merge.  count_out may be null.
+// flags (tests): bit 0 = no workgroup picks up the threshold itself (the merger's fallback does all threshold-bin rows),
+// bit 1 = accumulate the checksums of the attended rows in the control blocks, bit 2 = the selector gives up.
+hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+                              const void* q, const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
+                              float sm_scale, int32_t* count_out, float* out, float* kabsmax, int units, int n_kv_heads,
+                              int max_ctx, int flags, hipStream_t st);
+// The ascending index list of the selection that kernel made (an optional output of the step).
+hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
+                                int units, int n_kv_heads, int max_ctx, hipStream_t st);
+int step_ranges_per_wg(int max_budget, int max_ctx);
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
                        int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,

@@ -95,7 +95,7 @@ __device__ __forceinline__ bool exact_select_lds(const unsigned long long* lcand
 // The same selection streamed over all n scores of the unit (load(k) returns score k), restricted to the threshold
 // bin: four 8-bit radix passes over the keys give T, an ordered pass gives idxT and the per-range counts of the
 // selected candidates.  Slow (five passes by one workgroup) but independent of how the scores cluster.
-// hist: 256 words.  Every thread of the NT-thread workgroup must call it.
+// hist: 256 words; rsel may be null (no per-range counts wanted).  Every thread of the NT-thread workgroup must call it.
 template <int NT, class Load>
 __device__ __forceinline__ void stream_select(Load load, int n, int tbin, float R, float scale, uint32_t r_want,
                                               uint32_t* hist, uint32_t* scan_tmp, uint32_t* res, uint32_t* rsel,
@@ -142,7 +142,7 @@ __device__ __forceinline__ void stream_select(Load load, int n, int tbin, float 
     }
     uint32_t total;
     const uint32_t before = run_eq + block_excl_scan_u32<NT / 64>(eq ? 1u : 0u, scan_tmp, total);
-    if (gt || (eq && before < r)) atomicAdd(&rsel[k / kRangeTokens], 1u);
+    if (rsel && (gt || (eq && before < r))) atomicAdd(&rsel[k / kRangeTokens], 1u);
     if (eq && before == r - 1) res[1] = (uint32_t)k;
     run_eq += total;
   }

@@ -1,0 +1,758 @@
+// Second kernel of the fused decode step: exact top-B threshold (Alg. 1 step 3) and attention over the selected
+// rows (Alg. 1 step 4) in ONE launch, with no workgroup ever depending on the progress of a workgroup that may not
+// be running.
+//
+// The score kernel has left, per unit, its scores and their 512-bin histogram over [-R, R].  Here a workgroup owns
+// RPW consecutive 1024-token ranges of a unit and
+//   1. finds, from the unit's histogram, the bin `tbin` that holds the B-th largest score (the same few hundred
+//      integer additions in every workgroup of the unit: cheaper than a serial step somewhere plus the wait for it);
+//   2. classifies its own scores: tokens in bins above tbin are selected for certain ("sure" rows), tokens inside
+//      tbin are the candidates for the threshold (about 1 % of the tokens).  The sure rows go to an LDS list, the
+//      candidates to an LDS list and, as (key, index) pairs, to the unit's candidate slots in memory;
+//   3. counts its arrival.  The unit's LAST arriver ("selector") reads all candidates of the unit, histograms them
+//      once more inside the threshold bin (1024 sub-bins), ranks the members of the decisive sub-bin pairwise
+//      (larger key first, equal keys by lower index) and publishes the exact threshold (T, idxT) as one 64-bit word;
+//   4. meanwhile every workgroup, the selector after it has published, gathers its sure rows and attends over
+//      them -- the bulk of the work runs while the serial selection of step 3 is under way;
+//   5. then picks up the threshold word (it has long been there; if not, it polls for a bounded time), applies
+//      `key > T or (key == T and index <= idxT)` to its own few candidates, attends over the selected ones, marks
+//      itself done, stores its partial (m, l, o) per query head and counts its second arrival;
+//   6. the unit's last arriver of that second counter merges the partials.  Should a workgroup have given up at 5
+//      (its flag is missing), the merger redoes that workgroup's candidate rows itself first: the result never
+//      depends on the poll succeeding, so a workgroup only ever waits for a bounded time and every wavefront exits.
+// All selection decisions are integer comparisons of order-preserving keys: exact and deterministic.
+//
+// The ascending index list of the selection (idx_out of the step, an optional output) is written by a small
+// separate kernel from the scores and the threshold this kernel leaves in the unit's control block.
+#include "fier_attn_dev.h"
+#include "fier_dev.h"
+#include "fier_kernels.h"
+#include "fier_select_dev.h"
+
+namespace fier {
+
+namespace {
+
+constexpr int kStepThreads = 256;
+constexpr int kCandRegs = 8;        // candidate slots a selector thread holds in registers per sweep
+constexpr int kLateRows = 256;      // rows per batch of the late (threshold-bin) gather
+constexpr int kMaxStepWgs = (1 << 20) / kRangeTokens;  // workgroups of one unit at most (max_ctx <= 2^20, RPW >= 1)
+constexpr int kPollMax = 4096;      // polls of the threshold word before a workgroup gives up (each ~0.3 us)
+
+// selector scratch in LDS (dead before the partials use the same bytes)
+struct SelScratch {
+  uint32_t hist[kSubBins];                    // sub-bin histogram; the radix fallback uses its first 256 words
+  unsigned long long sub_list[kSubCandMax];   // members of the decisive sub-bin
+  uint16_t seg_size[kMaxStepWgs];             // candidates published by each workgroup of the unit
+  uint32_t res[2];
+  uint32_t n_sub;
+  uint32_t max_seg;
+};
+
+// The unit's threshold word: 0 = not there yet; T << 32 | idxT + 2 (never zero: idxT >= -1, never one of the marks:
+// idxT < 2^20); kThrGaveUp = the selector gave up waiting for the range workgroups; kThrClosed = the merging
+// workgroup has been here.
+constexpr unsigned long long kThrGaveUp = ~0ull;
+constexpr unsigned long long kThrClosed = ~0ull - 1;
+__device__ __forceinline__ unsigned long long pack_threshold(uint32_t T, int32_t idxT) {
+  return ((unsigned long long)T << 32) | (uint32_t)(idxT + 2);
+}
+__device__ __forceinline__ bool is_threshold(unsigned long long w) { return w != 0ull && w < kThrClosed; }
+
+}  // namespace
+
+// What the kernel needs besides the template parameters; passed by value.
+struct StepArgs {
+  const float* scores;
+  UnitCtl* ctl;
+  uint32_t* ghist;
+  const int32_t* budgets;
+  int max_budget;
+  unsigned long long* cand;  // [units][cand_pitch]: slot k * nc + w = k-th candidate of workgroup w of the unit
+  uint32_t* seg_cnt;         // [units][wgs_per_unit]
+  uint32_t* done;            // [units][wgs_per_unit]: 1 once the workgroup has attended over its candidate rows
+  const uint4* K;
+  const uint4* V;
+  const uint4* q;
+  const int32_t* seq_lens;
+  int extra;
+  float scale_log2e;
+  float* po;
+  float* pm;
+  float* pl;
+  float* out;
+  int32_t* count_out;
+  float* kabsmax;
+  const float* newmax;
+  int n_kv_heads, max_ctx, order, wgs_per_unit;
+  size_t cand_pitch;
+  int flags;  // tests: bit 0 = no workgroup picks up the threshold itself (the merger attends over all threshold-bin
+              // rows); bit 1 = checksums of the attended rows; bit 2 = the selector gives up (the merger selects)
+  KvLayout lay;
+};
+
+// grid: wgs_per_unit workgroups per unit (dispatch order given by `order`, see the launcher), block 256.
+// (the second launch bound asks the compiler for the registers-per-thread that let 5 / 4 / 3 / 2 workgroups share a
+// CU: the gather wants many rows in flight per CU more than it wants registers)
+template <int DT, int NREP, int RPW>
+__global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NREP <= 6 ? 3 : 2))) void step_attend_kernel(
+    const StepArgs a) {
+  constexpr int CAP = kRangeTokens * RPW;  // tokens the workgroup owns
+  constexpr int SEGCAP = CAP / 4;          // candidates it can publish (a quarter of its tokens)
+  constexpr size_t kScratchBytes =
+      sizeof(SelScratch) > sizeof(float) * NREP * kPartialFloats ? sizeof(SelScratch) : sizeof(float) * NREP * kPartialFloats;
+  static_assert(kScratchBytes >= sizeof(float) * 4 * 130, "merge_heads needs 4 x 130 floats");
+  __shared__ __attribute__((aligned(16))) unsigned char scratch[kScratchBytes];
+  __shared__ uint16_t rows[CAP];         // sure rows from the front, candidates from the back (offsets from tok0)
+  __shared__ uint16_t xrows[kLateRows];  // one batch of late rows (offsets from a base token)
+  __shared__ uint32_t ckey[kLateRows];   // keys of the workgroup's first candidates (the rest are read back from memory)
+  __shared__ uint32_t scan_tmp[4];
+  __shared__ int found[2];
+  __shared__ uint32_t flag;
+  __shared__ unsigned long long thr_sh;
+  __shared__ int32_t lblk[RPW * kRangeTokens / 64];  // paged rows: block numbers of this workgroup's tokens
+
+  float* const sh_o = reinterpret_cast<float*>(scratch);
+  SelScratch* const ss = reinterpret_cast<SelScratch*>(scratch);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int cn = tid & 15;
+  // order: 0 = grid (workgroups, units); 1 = grid (units, workgroups); 2 = one-dimensional, groups of 8 units, a
+  // group's workgroups together and unit % 8 fastest (see the launcher)
+  // Per unit wgs_per_unit + 1 workgroups: number 0 is the unit's selector (no tokens of its own), numbers 1.. own the
+  // ranges.  Every order puts a unit's selector ahead of its range workgroups.
+  int unit, wg_raw;
+  const int wpu1 = a.wgs_per_unit + 1;
+  if (a.order == 2) {
+    const int id = blockIdx.x;
+    const int g = id / (8 * wpu1);
+    const int rem = id - g * 8 * wpu1;
+    wg_raw = rem >> 3;
+    unit = 8 * g + (rem & 7);
+  } else {
+    unit = a.order ? blockIdx.x : blockIdx.y;
+    wg_raw = a.order ? blockIdx.y : blockIdx.x;
+  }
+  const bool is_selector = wg_raw == 0;
+  const int wg = wg_raw - 1;
+  const int max_ctx = a.max_ctx;
+  const int b = unit / a.n_kv_heads;
+  UnitCtl* __restrict__ c = &a.ctl[unit];
+  uint32_t* __restrict__ gh = a.ghist + (size_t)unit * kSelBins;
+  // what does not depend on the sequence length leaves with it: the unit's histogram (thread t owns bins 511 - 2t
+  // and 510 - 2t: descending score order), the range of the binning, the budget
+  const uint2 hpair = *reinterpret_cast<const uint2*>(gh + (kSelBins - 2 - 2 * tid));
+  const float R = c->R, hscale = c->scale;
+  int B = a.budgets[b];
+  int n = a.seq_lens[b] + a.extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  const int tok0 = is_selector ? 0 : wg * CAP;
+  if (!is_selector && tok0 >= n && wg != 0) return;
+  const int nc = n > 0 ? (n + CAP - 1) / CAP : 1;  // workgroups of this unit that run
+  FIER_PROF_WG(2)
+  const int n_slots = a.wgs_per_unit + 1;          // partial slots per (unit, head): one spare for the merger
+
+  const KvRows kv = a.lay.rows_of(unit);
+  if (!is_selector && kv.blocks && tid < RPW * kRangeTokens / 64) {  // in flight during the selection; barriers follow
+    const int bi = (tok0 >> kv.shift) + tid;
+    lblk[tid] = bi < a.lay.blocks_per_seq ? kv.blocks[bi] : 0;
+  }
+  const float* __restrict__ s_unit = a.scores + (size_t)unit * max_ctx;
+  unsigned long long* __restrict__ ucand = a.cand + (size_t)unit * a.cand_pitch;
+  uint32_t* __restrict__ useg = a.seg_cnt + (size_t)unit * a.wgs_per_unit;
+  uint32_t* __restrict__ udone = a.done + (size_t)unit * a.wgs_per_unit;
+
+  // ---- 1. the workgroup's scores; meanwhile the threshold bin from the histogram ---------------------------------
+  float4 v[RPW];
+#pragma unroll
+  for (int rr = 0; rr < RPW; ++rr) {
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
+    v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!is_selector && i < n) v[rr] = *reinterpret_cast<const float4*>(s_unit + i);  // i + 3 < max_ctx; masked below
+  }
+  B = B > a.max_budget ? a.max_budget : B;
+  B = B > n ? n : B;
+  B = B < 0 ? 0 : B;
+  if (is_selector && !(B > 0 && B < n)) return;  // everything or nothing is selected: there is no threshold to find
+  if (tid == 0) {
+    found[0] = B >= n ? -1 : kSelBins;  // everything / nothing selected by bin alone
+    found[1] = 0;
+  }
+  {
+    uint32_t total;
+    const uint32_t c0 = hpair.y, c1 = hpair.x;
+    const uint32_t before = block_excl_scan_u32<4>(c0 + c1, scan_tmp, total);  // has barriers
+    if (B > 0 && B < n) {
+      if (before < (uint32_t)B && (uint32_t)B <= before + c0) {
+        found[0] = kSelBins - 1 - 2 * tid;
+        found[1] = (int)before;
+      } else if (before + c0 < (uint32_t)B && (uint32_t)B <= before + c0 + c1) {
+        found[0] = kSelBins - 2 - 2 * tid;
+        found[1] = (int)(before + c0);
+      }
+    }
+    __syncthreads();
+  }
+  const int tbin = found[0];
+  const uint32_t above = (uint32_t)found[1];
+  const bool need_threshold = tbin >= 0 && tbin < kSelBins && B > 0;
+
+  // ---- the unit's selector: the exact threshold, as soon as every range workgroup has published its candidates -----
+  if (is_selector) {
+    // the rest of the unit will wait for what follows: ahead of the other workgroups' gather loops on this CU
+    __builtin_amdgcn_s_setprio(3);
+    if (tid == 0) {
+      uint32_t arrived = 0;
+      for (int spin = 0; spin < kPollMax; ++spin) {
+        arrived = load_coherent(&c->arrive[1]);
+        if (arrived >= (uint32_t)nc) break;
+        __builtin_amdgcn_s_sleep(8);
+      }
+      flag = (arrived >= (uint32_t)nc && !(a.flags & 4)) ? 1u : 0u;
+    }
+    __syncthreads();
+    FIER_PROF(13, unit == 0)
+    unsigned long long word = kThrGaveUp;  // the range workgroups did not all arrive in time: the merger selects
+    if (flag) {
+      uint32_t T = 0;
+      int32_t idxT = -1;
+    const uint32_t r_want = (uint32_t)B - above;  // candidates to take, >= 1
+    const uint32_t n_slot_rows = (uint32_t)SEGCAP;
+    // segment sizes and the first sweep of candidate slots leave together
+    uint32_t my_max = 0;
+    bool over = false;
+    if (tid == 0) {
+      ss->max_seg = 0;
+      ss->res[0] = 0;
+      ss->res[1] = 0;
+    }
+    uint32_t segc[(kMaxStepWgs + kStepThreads - 1) / kStepThreads];
+#pragma unroll
+    for (int k = 0; k < (kMaxStepWgs + kStepThreads - 1) / kStepThreads; ++k) {
+      const int w = k * kStepThreads + tid;
+      segc[k] = w < nc ? load_coherent(&useg[w]) : 0u;
+    }
+    unsigned long long e[kCandRegs];
+    const uint32_t slots_all = n_slot_rows * (uint32_t)nc;  // slots that exist for this unit's workgroups
+#pragma unroll
+    for (int k = 0; k < kCandRegs; ++k) {
+      const uint32_t sidx = (uint32_t)(k * kStepThreads + tid);
+      e[k] = sidx < slots_all ? load_coherent(&ucand[sidx]) : 0ull;
+    }
+#pragma unroll
+    for (int k = 0; k < (kMaxStepWgs + kStepThreads - 1) / kStepThreads; ++k) {
+      const int w = k * kStepThreads + tid;
+      if (w < nc) {
+        over = over || segc[k] > n_slot_rows;
+        const uint32_t sz = segc[k] > n_slot_rows ? n_slot_rows : segc[k];
+        ss->seg_size[w] = (uint16_t)sz;
+        my_max = my_max > sz ? my_max : sz;
+      }
+    }
+    for (int k = tid; k < kSubBins; k += kStepThreads) ss->hist[k] = 0;
+    __syncthreads();
+    FIER_PROF(16, unit == 0)
+    if (my_max) atomicMax(&ss->max_seg, my_max);
+    const bool overflow = __syncthreads_or(over);
+    bool done = false;
+    if (!overflow) {
+      // slots k * nc + w with k < max_seg may hold candidates: swept 8 x 256 at a time
+      const uint32_t n_scan = ss->max_seg * (uint32_t)nc;
+      const uint32_t sweep = (uint32_t)(kCandRegs * kStepThreads);
+      const uint32_t n_sweeps = (n_scan + sweep - 1) / sweep;
+      const float lo_b = hscale > 0.0f ? (float)tbin / hscale - R : 0.0f;  // lower edge of the threshold bin
+      const float scale2 = hscale * (float)kSubBins;
+      auto sub_of = [&](unsigned long long ent) {
+        return sel_bin(key_score((uint32_t)(ent >> 32)), -lo_b, scale2, kSubBins);
+      };
+      // slot sidx = k * nc + w holds candidate k of workgroup w if k < seg_size[w]; a thread's slots are 256 apart,
+      // so (k, w) advance by (256 / nc, 256 % nc) with a carry: no division per slot
+      const uint32_t unc = (uint32_t)nc;
+      const uint32_t step_k = (uint32_t)kStepThreads / unc, step_w = (uint32_t)kStepThreads % unc;
+      uint32_t vmask = 0;  // first sweep: which of the thread's slots hold a candidate
+      {
+        uint32_t k_s = (uint32_t)tid / unc, w_s = (uint32_t)tid % unc;
+        for (uint32_t sw = 0; sw < n_sweeps; ++sw) {
+#pragma unroll
+          for (int k = 0; k < kCandRegs; ++k) {
+            const uint32_t sidx = sw * sweep + (uint32_t)(k * kStepThreads + tid);
+            if (sw > 0) e[k] = sidx < n_scan ? load_coherent(&ucand[sidx]) : 0ull;
+            const bool valid = sidx < n_scan && k_s < (uint32_t)ss->seg_size[w_s];
+            if (valid) atomicAdd(&ss->hist[sub_of(e[k])], 1u);
+            if (sw == 0 && valid) vmask |= 1u << k;
+            k_s += step_k;
+            w_s += step_w;
+            if (w_s >= unc) {
+              w_s -= unc;
+              ++k_s;
+            }
+          }
+        }
+      }
+      if (tid == 0) ss->n_sub = 0;
+      __syncthreads();
+      FIER_PROF(17, unit == 0)
+      // sub-bin t with (count in sub-bins > t) < r_want <= (count in sub-bins >= t); descending ownership
+      {
+        constexpr int PER = kSubBins / kStepThreads;
+        uint32_t cntb[PER], sum = 0;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          cntb[k] = ss->hist[kSubBins - 1 - (PER * tid + k)];
+          sum += cntb[k];
+        }
+        uint32_t total;
+        uint32_t before = block_excl_scan_u32<4>(sum, scan_tmp, total);
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          if (before < r_want && r_want <= before + cntb[k]) {
+            ss->res[0] = (uint32_t)(kSubBins - 1 - (PER * tid + k));
+            ss->res[1] = before;
+          }
+          before += cntb[k];
+        }
+        __syncthreads();
+      }
+      const int tsub = (int)ss->res[0];
+      const uint32_t r2 = r_want - ss->res[1];  // rank wanted inside the sub-bin, 1-based
+      const uint32_t n_in_sub = ss->hist[tsub];
+      __syncthreads();
+      FIER_PROF(18, unit == 0)
+      if (n_in_sub <= (uint32_t)kSubCandMax) {
+        if (n_sweeps == 1) {  // the candidates are still in the registers
+#pragma unroll
+          for (int k = 0; k < kCandRegs; ++k)
+            if ((vmask >> k & 1u) && sub_of(e[k]) == tsub) ss->sub_list[atomicAdd(&ss->n_sub, 1u)] = e[k];
+        } else {
+          uint32_t k_s = (uint32_t)tid / unc, w_s = (uint32_t)tid % unc;
+          for (uint32_t sw = 0; sw < n_sweeps; ++sw) {
+#pragma unroll
+            for (int k = 0; k < kCandRegs; ++k) {
+              const uint32_t sidx = sw * sweep + (uint32_t)(k * kStepThreads + tid);
+              const bool valid = sidx < n_scan && k_s < (uint32_t)ss->seg_size[w_s];
+              if (valid) {
+                const unsigned long long ent = load_coherent(&ucand[sidx]);
+                if (sub_of(ent) == tsub) ss->sub_list[atomicAdd(&ss->n_sub, 1u)] = ent;
+              }
+              k_s += step_k;
+              w_s += step_w;
+              if (w_s >= unc) {
+                w_s -= unc;
+                ++k_s;
+              }
+            }
+          }
+        }
+        __syncthreads();
+        // rank the members of the decisive sub-bin: larger key first, equal keys by lower index
+        for (uint32_t m = tid; m < n_in_sub; m += kStepThreads) {
+          const unsigned long long me = ss->sub_list[m];
+          const uint32_t mk = (uint32_t)(me >> 32), mi = (uint32_t)me;
+          uint32_t rank = 0;
+          for (uint32_t j = 0; j < n_in_sub; ++j) {
+            const unsigned long long o = ss->sub_list[j];
+            const uint32_t ok = (uint32_t)(o >> 32), oi = (uint32_t)o;
+            rank += (ok > mk) || (ok == mk && oi < mi);
+          }
+          if (rank == r2 - 1) {
+            ss->res[0] = mk;
+            ss->res[1] = mi;
+          }
+        }
+        __syncthreads();
+        T = ss->res[0];
+        idxT = (int32_t)ss->res[1];
+        done = true;
+      }
+    }
+    if (!done) {
+      // candidates that do not fit (scores clustered far more tightly than the a-priori range resolves): radix
+      // selection streamed over the unit's scores
+      __syncthreads();
+      stream_select<kStepThreads>([&](int k) { return s_unit[k]; }, n, tbin, R, hscale, r_want, ss->hist, scan_tmp,
+                                  ss->res, nullptr, T, idxT);
+    }
+      word = pack_threshold(T, idxT);
+    }
+    __builtin_amdgcn_s_setprio(0);
+    // Publish.  The merging workgroup closes the word with an exchange of its own when it needs the threshold; of the
+    // two, whoever finds the other's mark is the last to touch the word and the arrival counter and clears them.
+    if (tid == 0) {
+      const unsigned long long old = __hip_atomic_exchange(&c->thr, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old != 0ull) {
+        store_coherent(&c->thr, 0ull);
+        store_coherent(&c->arrive[1], 0u);
+      }
+    }
+    FIER_PROF(15, unit == 0)
+    return;
+  }
+
+  // ---- 2. classify the workgroup's tokens: sure rows and candidates ------------------------------------------------
+  uint32_t dmask = 0, cmask = 0;  // bit 4 rr + j = token j of the thread in range rr
+#pragma unroll
+  for (int rr = 0; rr < RPW; ++rr) {
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
+    const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool ok = i + j < n;
+      const int bin = sel_bin(vv[j], R, hscale, kSelBins);
+      dmask |= (ok && bin > tbin) ? 1u << (4 * rr + j) : 0u;
+      cmask |= (ok && bin == tbin) ? 1u << (4 * rr + j) : 0u;
+    }
+  }
+  uint32_t listed;  // sure rows (low half) and candidates (high half) of the whole workgroup
+  {
+    // list positions in thread order (one workgroup scan for both lists), so that the lists, and with them the order
+    // in which the rows are summed, are the same in every run
+    const uint32_t packed = (uint32_t)__builtin_popcount(dmask) | ((uint32_t)__builtin_popcount(cmask) << 16);
+    const uint32_t at = block_excl_scan_u32<4>(packed, scan_tmp, listed);
+    uint32_t pd = at & 0xffffu, pc = at >> 16;
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+      const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t off = (uint32_t)(rr * kRangeTokens + 4 * tid + j);
+        if (dmask >> (4 * rr + j) & 1u) rows[pd++] = (uint16_t)off;
+        if (cmask >> (4 * rr + j) & 1u) {
+          rows[CAP - 1 - pc] = (uint16_t)off;
+          if (pc < (uint32_t)kLateRows) ckey[pc] = score_key(vv[j]);
+          if (pc < (uint32_t)SEGCAP)
+            store_coherent(&ucand[(size_t)pc * nc + wg],
+                           ((unsigned long long)score_key(vv[j]) << 32) | (uint32_t)(tok0 + (int)off));
+          ++pc;
+        }
+      }
+    }
+  }
+  const int n_sure = (int)(listed & 0xffffu);
+  const int n_cand = (int)(listed >> 16);
+  if (tid == 0) store_coherent(&useg[wg], (uint32_t)n_cand);
+  // ---- 3. arrival: the candidates are acknowledged, the unit's selector may read them.  Nothing is waited for.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();  // (also: the row lists are complete)
+  if (tid == 0) __hip_atomic_fetch_add(&c->arrive[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // ---- 4. attention over the sure rows ----------------------------------------------------------------------------
+  FIER_PROF_WG(3)
+  uint4 qr[NREP];
+#pragma unroll
+  for (int h = 0; h < NREP; ++h) qr[h] = a.q[((size_t)unit * NREP + h) * (kD / 8) + cn];
+  const uint4* q_unit = a.q + (size_t)unit * NREP * (kD / 8);
+  AttnState<NREP> st;
+  st.init();
+  const int first_block = tok0 >> kv.shift;
+  auto row_sure = [&](int j) {
+    const int t = tok0 + (int)rows[j];
+    return kv.blocks ? (size_t)lblk[(t >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(t & kv.mask)
+                     : kv.base + (size_t)t;
+  };
+  if constexpr (NREP >= 3)
+    attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_sure, 0, n_sure, a.scale_log2e, st, sh_o);
+  else
+    attend_rows<DT, NREP>(a.K, a.V, qr, row_sure, 0, n_sure, a.scale_log2e, st);
+  FIER_PROF_WG(4)
+  uint32_t chk_cnt = (uint32_t)n_sure, chk_sum = 0;
+  if (a.flags & 2)
+    for (int j = tid; j < n_sure; j += kStepThreads) chk_sum += (uint32_t)(tok0 + (int)rows[j]);
+
+  // Attention over the candidates of tokens [base, base + span) of this unit that the threshold selects, in batches
+  // through xrows; list(k) gives the k-th candidate's offset from base, or -1.  Every thread of the workgroup calls it.
+  bool resumed = false;
+  // key_of(k, t) the key of that candidate.
+  auto attend_late = [&](uint32_t T, int32_t idxT, int base, int count, auto&& list, auto&& key_of,
+                         AttnState<NREP>& state) {
+    for (int k0 = 0; k0 < count; k0 += kLateRows) {
+      const int k = k0 + tid;
+      int off = -1;
+      if (k < count) {
+        off = list(k);
+        if (off >= 0) {
+          const int t = base + off;
+          const uint32_t key = key_of(k, t);
+          if (!(key > T || (key == T && t <= idxT))) off = -1;
+        }
+      }
+      uint32_t n_x_u;
+      const uint32_t at = block_excl_scan_u32<4>(off >= 0 ? 1u : 0u, scan_tmp, n_x_u);  // its first barrier frees xrows
+      if (off >= 0) {
+        xrows[at] = (uint16_t)off;
+        if (a.flags & 2) chk_sum += (uint32_t)(base + off);
+      }
+      __syncthreads();
+      const int n_x = (int)n_x_u;
+      auto row_late = [&](int j) { return kv.row(base + (int)xrows[j]); };
+      if constexpr (NREP >= 3)
+        attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_late, 0, n_x, a.scale_log2e, state, sh_o, resumed);
+      else
+        attend_rows<DT, NREP>(a.K, a.V, qr, row_late, 0, n_x, a.scale_log2e, state);
+      resumed = true;
+      if (tid == 0) chk_cnt += (uint32_t)n_x;
+    }
+  };
+
+  // ---- 5. the workgroup's own candidates, once the threshold is known ---------------------------------------------
+  resumed = true;  // the state continues from the sure rows
+  if (need_threshold && n_cand > 0) {
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long w = 0;
+      if (!(a.flags & 1))
+        for (int spin = 0; spin < kPollMax; ++spin) {
+          w = load_coherent(&c->thr);
+          if (w) break;
+          __builtin_amdgcn_s_sleep(16);
+        }
+      thr_sh = w;
+    }
+    __syncthreads();
+    const unsigned long long w = thr_sh;
+    if (is_threshold(w)) {
+      attend_late((uint32_t)(w >> 32), (int32_t)(uint32_t)w - 2, tok0, n_cand,
+                  [&](int k) { return (int)rows[CAP - 1 - k]; },
+                  [&](int k, int t) { return k < kLateRows ? ckey[k] : score_key(s_unit[t]); }, st);
+      if (tid == 0) store_coherent(&udone[wg], 1u);
+    }
+  } else if (tid == 0) {
+    store_coherent(&udone[wg], 1u);  // nothing to pick up
+  }
+
+  if (a.flags & 2) {
+    chk_sum = wave_sum_u32(chk_sum);
+    if (lane == 0 && chk_sum) atomicAdd(&c->chk_sum, chk_sum);
+    if (tid == 0 && chk_cnt) atomicAdd(&c->chk_cnt, chk_cnt);
+    chk_sum = 0;
+    chk_cnt = 0;
+  }
+  FIER_PROF_WG(5)
+  store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, a.po, a.pm, a.pl);
+  FIER_PROF_WG(6)
+
+  if (!last_arriver(&c->arrive[2], (uint32_t)nc, &flag)) return;
+  // ---- 6. the unit's last workgroup: anything left over, then the merge ---------------------------------------------
+  int n_used = nc;
+  uint32_t T = 0;
+  int32_t idxT = -1;
+  if (need_threshold) {
+    // Close the threshold word.  Normally it holds the selector's result; if the selector gave up, or is still at
+    // work, the threshold is found here by the radix selection streamed over the unit's scores.  Whoever of the two
+    // finds the other's mark clears the word and the arrival counter (the selector polls that counter).
+    if (tid == 0) thr_sh = __hip_atomic_exchange(&c->thr, kThrClosed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const unsigned long long wthr = thr_sh;
+    if (wthr != 0ull && tid == 0) {
+      c->thr = 0ull;
+      c->arrive[1] = 0;
+    }
+    if (is_threshold(wthr)) {
+      T = (uint32_t)(wthr >> 32);
+      idxT = (int32_t)(uint32_t)wthr - 2;
+    } else {
+      __syncthreads();
+      stream_select<kStepThreads>([&](int k) { return s_unit[k]; }, n, tbin, R, hscale, (uint32_t)B - above, ss->hist,
+                                  scan_tmp, ss->res, nullptr, T, idxT);
+      __syncthreads();
+    }
+    bool missing = false;
+    for (int w = tid; w < nc; w += kStepThreads) missing = missing || load_coherent(&udone[w]) == 0u;
+    if (__syncthreads_or(missing)) {
+      // some workgroup did not pick up the threshold: its candidate rows are attended over here, into the spare slot
+      st.init();
+      resumed = false;
+      for (int w = 0; w < nc; ++w) {
+        if (load_coherent(&udone[w]) != 0u) continue;  // the same value in every thread
+        const int base = w * CAP;
+        const int span = n - base < CAP ? n - base : CAP;
+        attend_late(T, idxT, base, span,
+                    [&](int k) { return sel_bin(s_unit[base + k], R, hscale, kSelBins) == tbin ? k : -1; },
+                    [&](int, int t) { return score_key(s_unit[t]); }, st);
+      }
+      if (a.flags & 2) {
+        chk_sum = wave_sum_u32(chk_sum);
+        if (lane == 0 && chk_sum) atomicAdd(&c->chk_sum, chk_sum);
+        if (tid == 0 && chk_cnt) atomicAdd(&c->chk_cnt, chk_cnt);
+      }
+      store_partials<NREP, true>(st, sh_o, unit, n_slots, nc, a.po, a.pm, a.pl);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the spare slot is read back below by other wavefronts
+      __syncthreads();
+      n_used = nc + 1;
+    }
+  }
+  merge_heads<NREP>(a.po, a.pm, a.pl, unit, n_slots, n_used, sh_o, a.out + (size_t)unit * NREP * kD);
+  FIER_PROF_WG(7)
+  // counters and flags back to zero for the next call, the unit's histogram too (all its readers have arrived); the
+  // selection for the index-list kernel
+  for (int w = tid; w < nc; w += kStepThreads) udone[w] = 0u;
+  for (int k = tid; k < kSelBins; k += kStepThreads) gh[k] = 0;
+  if (tid == 0) {
+    c->arrive[2] = 0;
+    if (!need_threshold) c->arrive[1] = 0;  // no selector ran
+    c->tbin = tbin;
+    c->above = above;
+    c->budget = B;
+    c->T = T;
+    c->idxT = idxT;
+    if (a.count_out) a.count_out[unit] = B;
+  }
+  // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
+  if (a.extra && a.seq_lens[b] < max_ctx && tid < kD) {
+    float* slot = a.kabsmax + (size_t)unit * kD + tid;
+    const float nm = a.newmax[(size_t)unit * kD + tid];
+    if (nm > *slot) *slot = nm;
+  }
+}
+
+// The ascending index list of the step's selection: idx[unit][0 .. budget) from the scores and the threshold the
+// step left in the control block.  grid (units), block 1024: the workgroup walks its unit 4096 tokens at a time and
+// keeps a running offset, so the list comes out in token order.  An optional output of the step, off its fast path.
+__global__ __launch_bounds__(1024) void step_emit_idx_kernel(const float* __restrict__ scores,
+                                                             const int32_t* __restrict__ seq_lens, int extra,
+                                                             const UnitCtl* __restrict__ ctl, int max_budget,
+                                                             int32_t* __restrict__ idx, int n_kv_heads, int max_ctx) {
+  __shared__ uint32_t scan_tmp[16];
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  int n = seq_lens[unit / n_kv_heads] + extra;
+  n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  const UnitCtl* __restrict__ c = &ctl[unit];
+  const int tbin = c->tbin;
+  const float R = c->R, scale = c->scale;
+  const uint32_t T = c->T;
+  const int32_t idxT = c->idxT;
+  const float* __restrict__ s = scores + (size_t)unit * max_ctx;
+  int32_t* __restrict__ out = idx + (size_t)unit * max_budget;
+  uint32_t run = 0;
+  for (int i0 = 0; i0 < n; i0 += 4096) {
+    const int i = i0 + 4 * tid;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n) v = *reinterpret_cast<const float4*>(s + i);
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    uint32_t selm = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int bin = sel_bin(vv[j], R, scale, kSelBins);
+      const uint32_t key = score_key(vv[j]);
+      const bool sel = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
+      selm |= sel ? 1u << j : 0u;
+    }
+    uint32_t total;
+    uint32_t pos = run + block_excl_scan_u32<16>((uint32_t)__builtin_popcount(selm), scan_tmp, total);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (selm >> j & 1u) {
+        if (pos < (uint32_t)max_budget) out[pos] = i + j;
+        ++pos;
+      }
+    run += total;
+  }
+}
+
+int step_ranges_per_wg(int max_budget, int max_ctx) {
+  // about a hundred selected rows per workgroup: rows per 1024-token range = 1024 * budget / context
+  const double per_range = 1024.0 * (double)max_budget / (double)max_ctx;
+  int rpw = 1;
+  while (rpw < 8 && per_range * rpw < 96.0) rpw *= 2;
+  return rpw;
+}
+
+template <int DT, int RPW>
+static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+                                        const void* q, const int32_t* seq_lens, int extra, const int32_t* budgets,
+                                        int max_budget, float sm_scale, int32_t* count_out, float* out, float* kabsmax,
+                                        int units, int n_kv_heads, int max_ctx, int flags, hipStream_t st) {
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  const int n_wgs = (n_ranges + RPW - 1) / RPW;
+  // Dispatch order.  Workgroups go round-robin to the 8 XCDs in the order of their linear index; when a unit's
+  // workgroups all run on one XCD, its scores, candidates, partials and arrival counters stay in that XCD's L2.
+  //   1: units fastest (a multiple of 8 units puts unit u on XCD u % 8), for grids that are resident at once;
+  //   2: longer grids with a multiple of 8 units: groups of 8 units one after the other, inside a group the
+  //      workgroups in range order and unit % 8 fastest -- the same XCD assignment, but a unit's workgroups stay
+  //      together in time, which also keeps the wait for the unit's threshold short;
+  //   0: ranges fastest, otherwise.
+  // Order 1 only while every workgroup is resident at once (the second launch bound of the kernel: 5 / 4 / 3 / 2
+  // workgroups per CU, 256 CUs): its workgroups poll for their unit's threshold, and a unit spread over two rounds
+  // of workgroups would have the first round waiting for the second.
+  const long resident = 256L * (n_rep <= 2 ? 5 : (n_rep <= 4 ? 4 : (n_rep <= 6 ? 3 : 2)));
+  const int gw = n_wgs + 1;  // a unit's selector and its range workgroups
+  const int order = (long)units * gw <= resident ? 1 : (units % 8 == 0 ? 2 : 0);
+  dim3 grid = order == 2 ? dim3((unsigned)units * (unsigned)gw) : (order ? dim3(units, gw) : dim3(gw, units));
+  StepArgs a;
+  a.scores = sb.scores;
+  a.ctl = sb.ctl;
+  a.ghist = sb.hist;
+  a.budgets = budgets;
+  a.max_budget = max_budget;
+  a.cand = sb.cand;
+  a.seg_cnt = sb.seg_cnt;
+  a.done = sb.done;
+  a.K = (const uint4*)K;
+  a.V = (const uint4*)V;
+  a.q = (const uint4*)q;
+  a.seq_lens = seq_lens;
+  a.extra = extra;
+  a.scale_log2e = sm_scale * 1.4426950408889634f;
+  a.po = sb.po;
+  a.pm = sb.pm;
+  a.pl = sb.pl;
+  a.out = out;
+  a.count_out = count_out;
+  a.kabsmax = kabsmax;
+  a.newmax = sb.newmax;
+  a.n_kv_heads = n_kv_heads;
+  a.max_ctx = max_ctx;
+  a.order = order;
+  a.wgs_per_unit = n_wgs;
+  a.cand_pitch = sb.cand_pitch;
+  a.flags = flags;
+  a.lay = lay;
+  if ((size_t)n_wgs * (RPW * kRangeTokens / 4) > sb.cand_pitch || n_wgs > sb.seg_pitch) return hipErrorInvalidValue;
+#define FIER_STEP_CASE(R)                                                   \
+  case R:                                                                   \
+    step_attend_kernel<DT, R, RPW><<<grid, kStepThreads, 0, st>>>(a);       \
+    break;
+  switch (n_rep) {
+    FIER_STEP_CASE(1)
+    FIER_STEP_CASE(2)
+    FIER_STEP_CASE(3)
+    FIER_STEP_CASE(4)
+    FIER_STEP_CASE(5)
+    FIER_STEP_CASE(6)
+    FIER_STEP_CASE(7)
+    FIER_STEP_CASE(8)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef FIER_STEP_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
+                              const void* q, const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
+                              float sm_scale, int32_t* count_out, float* out, float* kabsmax, int units, int n_kv_heads,
+                              int max_ctx, int flags, hipStream_t st) {
+#define FIER_STEP_RPW(DT, RPW)                                                                                        \
+  return launch_step_attend_dt<DT, RPW>(lay, n_rep, sb, K, V, q, seq_lens, extra, budgets, max_budget, sm_scale,      \
+                                        count_out, out, kabsmax, units, n_kv_heads, max_ctx, flags, st)
+  const int rpw = step_ranges_per_wg(max_budget, max_ctx);
+  if (dtype == DT_F16) {
+    if (rpw == 1) FIER_STEP_RPW(DT_F16, 1);
+    if (rpw == 2) FIER_STEP_RPW(DT_F16, 2);
+    if (rpw == 4) FIER_STEP_RPW(DT_F16, 4);
+    FIER_STEP_RPW(DT_F16, 8);
+  }
+  if (rpw == 1) FIER_STEP_RPW(DT_BF16, 1);
+  if (rpw == 2) FIER_STEP_RPW(DT_BF16, 2);
+  if (rpw == 4) FIER_STEP_RPW(DT_BF16, 4);
+  FIER_STEP_RPW(DT_BF16, 8);
+#undef FIER_STEP_RPW
+}
+
+hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
+                                int units, int n_kv_heads, int max_ctx, hipStream_t st) {
+  step_emit_idx_kernel<<<units, 1024, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, max_budget, idx, n_kv_heads, max_ctx);
+  return hipGetLastError();
+}
+
+}  // namespace fier

@@ -705,7 +705,7 @@ def test_decode_step_phases_equal_the_fused_call(gu):
         if mode == "fused":
             B.decode_step(*args)
         else:
-            for p in (1, 2, 3, 3):      # the last phase may be repeated on what the earlier ones left behind
+            for p in (1, 2, 3, 3):      # the index list may be written again from what the step left behind
                 B.decode_step_phase(*args, p)
         torch.cuda.synchronize()
         outs.append((out.clone(), idx.clone(), cnt.clone(), dw.cache.kbits.clone()))
