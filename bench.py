@@ -97,6 +97,9 @@ def main():
                          "(a paged serving cache); 0 = contiguous rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-steps", type=int, default=240, help="launches per stage for the per-stage timing")
+    ap.add_argument("--other-workloads", default="config3,config4:256,config4:16384",
+                    help="comma-separated workloads (name or name:budget) measured after the headline one and reported, "
+                         "in short form, under other_workloads of the same JSON line ('' = none; 'all' adds config5)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain element-wise copy of 256 MiB (read 256 MiB, write 256 MiB) three times, "
                          "so that a rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
@@ -104,7 +107,31 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    res = measure(args, args.workload, args.budget, detail=True)
+    if res is None:
+        return
+    plain = (args.selector == "fier" and args.dense_first == 0 and args.group_size == 32 and not args.block_tokens
+             and args.workload == "config2" and args.budget is None)
+    others = args.other_workloads
+    if others == "all":
+        others = "config3,config4:256,config4:16384,config5"
+    if plain and others:
+        import gc
 
+        import torch
+        res["other_workloads"] = {}
+        for item in others.split(","):
+            name, _, b = item.partition(":")
+            gc.collect()
+            torch.cuda.empty_cache()
+            short = measure(args, name, int(b) if b else None, detail=False)
+            res["other_workloads"][short.pop("label")] = short
+    print(json.dumps(res), flush=True)
+
+
+def measure(args, workload, budget_arg, detail):
+    """Measure one workload.  detail=True: everything the headline line carries; False: the short form (step time,
+    roofline fraction, kernel times, dense attention at the same shape, algorithmic bytes)."""
     import torch
 
     from paper_2508_08256_amd import binding as B
@@ -112,11 +139,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     B.lib()  # fail loudly if the HIP library is missing
-    w = dict(WORKLOADS[args.workload])
-    if args.budget is not None:
-        w["budget"] = args.budget
-        w["label"] += f"_budget{args.budget}"
-    elif args.workload == "config4":
+    w = dict(WORKLOADS[workload])
+    if budget_arg is not None:
+        w["budget"] = budget_arg
+        w["label"] += f"_budget{budget_arg}"
+    elif workload == "config4":
         w["label"] += f"_budget{w['budget']}"
     w["group_size"] = args.group_size
     if args.group_size != 32:
@@ -132,8 +159,11 @@ def main():
     max_ctx = -(-(L + 1 + max(0, args.loop_steps)) // gran) * gran
     cfg = B.make_config(batch, Hq, Hkv, max_ctx, dtype, group_size=args.group_size)
     units, n_rep = cfg.units, cfg.n_rep
-    if NL > 1 and args.steps == 600:
-        args.steps, args.warmup, args.stage_steps = 40, 4, 16   # a step is NL layers
+    steps, warmup, ns = args.steps, args.warmup, args.stage_steps
+    if not detail:
+        steps, warmup, ns = min(steps, 240), min(warmup, 24), min(ns, 120)
+    if NL > 1 and steps >= 240:
+        steps, warmup, ns = 40, 4, 16   # a step is NL layers
 
     # ---- resident inputs: R sets of NL layer caches, quantized once (prefill), fresh q / k_new / v_new each ---
     t0 = time.time()
@@ -143,7 +173,7 @@ def main():
     for r in range(R):
         cl, ql, kl, vl = [], [], [], []
         for layer in range(NL):
-            d = synth.make_workload_device(f"{args.workload}_cache{r}_{layer}", 1000 * 2 + r * NL + layer, batch, Hq,
+            d = synth.make_workload_device(f"{workload}_cache{r}_{layer}", 1000 * 2 + r * NL + layer, batch, Hq,
                                            Hkv, lens, buds, dtype, max_ctx=max_ctx, chan=w["chan"],
                                            n_planted=w["n_planted"])
             if r == 0 and layer == 0:
@@ -178,7 +208,7 @@ def main():
 
     if args.loop_steps > 0:
         decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, buds, budget, t_setup)
-        return
+        return None
 
     # the timed steps share ONE workspace (as a model's layers would); the per-kernel timing below needs every
     # layer cache to keep its own intermediate state, hence one workspace per layer cache there
@@ -238,7 +268,11 @@ def main():
             B.decode_step_mixed(cfg, caches[r], dense_flags, qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt,
                                 ws_mixed)
         else:
-            B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0][0])
+            B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, None, None, wss[0][0])
+
+    def step_with_index_list(i):
+        r = i % R
+        B.decode_step(cfg, caches[r], qs[r], kns[r], vns[r], budgets, budget, out, idx, cnt, wss[0][0])
 
     def timed(fn, n, warm):
         for i in range(warm):
@@ -254,70 +288,68 @@ def main():
         return e0.elapsed_time(e1) / n * 1e3, (time.perf_counter() - t_wall) / n * 1e6   # us (events), us (wall)
 
     # ---- the timed region: K whole steps ----------------------------------------------------------------
-    us_step, us_wall = timed(step, args.steps, args.warmup)
+    us_step, us_wall = timed(step, steps, warmup)
+    n_kernels = B.decode_step_kernels(cfg, budget)
 
-    # ---- spread of single steps: an event between consecutive steps ------------------------------------------
-    n_dist = min(args.steps, 200)
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_dist + 1)]
-    evs[0].record()
-    for i in range(n_dist):
-        step(i)
-        evs[i + 1].record()
-    torch.cuda.synchronize()
-    single = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_dist)])
+    single, us_graph, us_step_idx = None, None, None
+    if detail:
+        us_step_idx, _ = timed(step_with_index_list, min(steps, 240), 8) if args.selector == "fier" and not args.dense_first else (None, None)
+        # ---- spread of single steps: an event between consecutive steps --------------------------------------
+        n_dist = min(steps, 200)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_dist + 1)]
+        evs[0].record()
+        for i in range(n_dist):
+            step(i)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        single = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_dist)])
 
-    # ---- the same steps replayed from one HIP graph ------------------------------------------------------------
-    us_graph = None
-    try:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            for r in range(R):
-                step(r)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for r in range(R):
-                step(r)
-        torch.cuda.synchronize()
-        n_rep_g = max(3, min(args.steps, 240) // R)
-        us_graph, _ = timed(lambda i: graph.replay(), n_rep_g, 2)
-        us_graph /= R
-        del graph
-    except Exception as e:  # a capture problem must not lose the measurement above
-        sys.stderr.write(f"bench.py: graph replay skipped: {e}\n")
+        # ---- the same steps replayed from one HIP graph --------------------------------------------------------
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for r in range(R):
+                    step(r)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for r in range(R):
+                    step(r)
+            torch.cuda.synchronize()
+            n_rep_g = max(3, min(steps, 240) // R)
+            us_graph, _ = timed(lambda i: graph.replay(), n_rep_g, 2)
+            us_graph /= R
+            del graph
+        except Exception as e:  # a capture problem must not lose the measurement above
+            sys.stderr.write(f"bench.py: graph replay skipped: {e}\n")
 
     # ---- each kernel of the fused step alone (HIP events on the launch stream, rotating caches) ----------
-    ns = args.stage_steps
-
     # argument tuples per layer cache, prepared once (slicing tensors inside the timed loop would make it CPU-bound)
     largs = [[(cfg, caches[r][l:l + 1], qs[r][l:l + 1], kns[r][l:l + 1], vns[r][l:l + 1], budgets, budget,
                out[l:l + 1], idx[l:l + 1], cnt[l:l + 1], wss[r][l]) for l in range(NL)] for r in range(R)]
 
-    def phase(p):
+    def phase(*ps):
         def run(i):
             for a in largs[i % R]:
-                B.decode_step_phase(*a, p)
+                for p in ps:
+                    B.decode_step_phase(*a, p)
         return run
 
     for r in range(R):                    # a whole step per layer cache on its own workspace
-        for p in (1, 2, 3):
-            phase(p)(r)
+        phase(1, 2, 3)(r)
     torch.cuda.synchronize()
 
-    # The score kernel adds into the unit histograms that the threshold kernel consumes and clears, so the
-    # threshold kernel cannot be repeated alone: it is timed as (score + threshold) - (score).  The third kernel
-    # only reads what the second left and can be repeated.
-    def phases12(i):
-        phase(1)(i)
-        phase(2)(i)
-
+    # The first kernel adds into the unit histograms that the second consumes and clears, so the second cannot be
+    # repeated alone: it is timed as (first + second) - (first).  In the three-kernel form (grids that are not
+    # resident at once) the third kernel only reads what the second left and is timed alone; in the two-kernel form
+    # the third is the optional index-list kernel, also timed alone.
     nw = 12 if NL == 1 else 2
     us_k1, _ = timed(phase(1), ns, nw)
     for r in range(R):
         phase(2)(r)                       # clears the accumulated histograms
-    us_k12, _ = timed(phases12, ns, nw)
+    us_k12, _ = timed(phase(1, 2), ns, nw)
     us_k2 = us_k12 - us_k1
     us_k3, _ = timed(phase(3), ns, nw)
 
@@ -329,6 +361,37 @@ def main():
         B.dense_attn(cfg, caches[r][l], qs[r][l:l + 1], 1, out1, ws_dense)
 
     us_dense, _ = timed(st_dense, max(24, ns // 10), 4)
+
+    ab = algorithmic_bytes(w, lens, buds)          # per layer
+    us_layer = us_step / NL
+    achieved = ab["total"] / (us_layer * 1e-6) / 1e9
+    # The dominant kernel by algorithmic bytes is the one that gathers the selected K / V rows (+ q in, output out):
+    # the second kernel of the two-kernel form (threshold + attention + merge in one launch, timed as first + second
+    # minus first), the third of the three-kernel form (selection + attention + merge, timed alone).
+    gather_bytes = ab["selected_kv"] + ab["q_out"]
+    if n_kernels == 2:
+        dom_name, us_dom = "step_attend_kernel (exact threshold, gather attention, merge)", us_k2
+        kernels_us = {"append_score_hist": round(us_k1 / NL, 3), "threshold_attend_merge": round(us_k2 / NL, 3),
+                      "sum": round((us_k1 + us_k2) / NL, 3), "index_list_optional": round(us_k3 / NL, 3)}
+    else:
+        dom_name, us_dom = "select_attend_kernel (selection, gather attention, merge)", us_k3
+        kernels_us = {"append_score_hist": round(us_k1 / NL, 3), "threshold": round(us_k2 / NL, 3),
+                      "select_attend_merge": round(us_k3 / NL, 3), "sum": round((us_k1 + us_k2 + us_k3) / NL, 3)}
+    dom_gbps = gather_bytes / (us_dom / NL * 1e-6) / 1e9
+    k1_gbps = ab["packed"] / (us_k1 / NL * 1e-6) / 1e9
+    dense_bytes = int(Hkv * (lens + 1).sum() * 512) + ab["q_out"]
+    config = {"workload": w["label"], "batch": batch, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128,
+              "context": L if w["L"] != "ragged" else [int(x) for x in lens],
+              "budget": budget if w["budget"] != "11%" else [int(x) for x in buds],
+              "group_size": args.group_size, "layers_per_step": NL, "rotating_caches": R * NL,
+              "kernels_per_layer_step": n_kernels, "algorithmic_bytes_per_layer": ab["total"]}
+    if not detail:
+        return {"label": w["label"], "us_per_layer": round(us_layer, 3), "achieved_GBps": round(achieved, 1),
+                "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4), "kernels_us": kernels_us,
+                "dominant_kernel": {"kernel": dom_name, "GBps": round(dom_gbps, 1),
+                                    "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "bytes_per_launch": gather_bytes},
+                "dense_attn_us": round(us_dense, 3), "speedup_vs_dense_attn": round(us_dense / us_layer, 3),
+                "steps": steps, "config": config}
 
     # what this machine's memory system gives a plain streaming copy (torch's own, 1 GiB operands, far beyond the
     # 256 MB Infinity Cache): context for the roofline figures, which are quoted against the nominal 8 TB/s
@@ -405,51 +468,41 @@ def main():
         torch.cuda.synchronize()
         del a, bq
 
-    ab = algorithmic_bytes(w, lens, buds)          # per layer
-    us_layer = us_step / NL
-    achieved = ab["total"] / (us_layer * 1e-6) / 1e9
-    # dominant kernel by algorithmic bytes: select + attend (selected K/V rows + q + out)
-    k3_bytes = ab["selected_kv"] + ab["q_out"]
-    k3_gbps = k3_bytes / (us_k3 / NL * 1e-6) / 1e9
-    k1_gbps = ab["packed"] / (us_k1 / NL * 1e-6) / 1e9
-    dense_bytes = int(Hkv * (lens + 1).sum() * 512) + ab["q_out"]
-
     # HBM traffic of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE runs,
-    # scaled by what the same counters read for a plain copy of known size); None for other workloads
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"decode_step_{args.workload}_traffic.json")
-    if os.path.exists(tpath) and args.budget is None:
+    # scaled by what the same counters read for a plain copy of known size): a constant read from that file, not a
+    # counter read in this run; None for workloads without a committed summary
+    traffic, traffic_source = None, None
+    tpath = os.path.join(ROOT, "profiles", f"decode_step_{workload}_traffic.json")
+    if os.path.exists(tpath) and budget_arg is None and args.group_size == 32 and not args.block_tokens:
         with open(tpath) as f:
-            traffic = json.load(f).get("traffic_bytes_per_launch")
+            tj = json.load(f)
+        if tj.get("kernel", "").split("(")[0].strip() == dom_name.split("(")[0].strip():
+            traffic = tj.get("traffic_bytes_per_launch")
+            traffic_source = f"profiles/decode_step_{workload}_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"
 
     res = {
         "metric": "per-layer decode-step latency (us) + achieved HBM GB/s vs peak",
         "value": round(us_layer, 3),
         "unit": "us",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(us_step / 1e3, 6),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f16" if dtype == 0 else "bf16",
         "data": "synthetic",
-        "config": {"workload": w["label"], "batch": batch, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": 128,
-                   "context": L if w["L"] != "ragged" else [int(x) for x in lens],
-                   "budget": budget if w["budget"] != "11%" else [int(x) for x in buds],
-                   "group_size": args.group_size,
-                   "layers_per_step": NL, "rotating_caches": R * NL,
-                   "algorithmic_bytes_per_layer": ab["total"]},
+        "config": config,
         "achieved_GBps": round(achieved, 1),
         "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_step_wall": round(us_wall, 3),
+        "us_per_layer_with_index_list": None if us_step_idx is None else round(us_step_idx / NL, 3),
         "single_step_us": {"min": round(float(single.min()), 3), "median": round(float(np.median(single)), 3),
-                           "p95": round(float(np.percentile(single, 95)), 3), "n": int(n_dist)},
+                           "p95": round(float(np.percentile(single, 95)), 3), "n": int(len(single))},
         "graph_replay_us_per_step": None if us_graph is None else round(us_graph, 3),
-        "kernels_us": {"append_score_hist": round(us_k1 / NL, 3), "threshold": round(us_k2 / NL, 3),
-                       "select_attend_merge": round(us_k3 / NL, 3), "sum": round((us_k1 + us_k2 + us_k3) / NL, 3)},
-        "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "select_attend_merge": round(k3_gbps, 1)},
+        "kernels_us": kernels_us,
+        "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "gather_attention": round(dom_gbps, 1)},
         "standalone_calls_us": {"fier_score": round(us_score, 3), "fier_topk": round(us_topk, 3),
                                 "fier_topk_ws": round(us_topk_ws, 3),
                                 "fier_sparse_attn": round(us_attn, 3), "fier_append_key": round(us_append, 3),
@@ -459,10 +512,10 @@ def main():
         "dense_attn_GBps": round(dense_bytes / (us_dense * 1e-6) / 1e9, 1),
         "speedup_vs_dense_attn": round(us_dense / us_layer, 3),
         "measured_ceiling": ceiling,
-        "roofline": {"bound": "hbm", "kernel": "select_attend_kernel (selection, gather attention, merge)",
-                     "achieved": round(k3_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(k3_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "bytes_per_launch": k3_bytes, "us_per_launch": round(us_k3 / NL, 3)},
+        "roofline": {"bound": "hbm", "kernel": dom_name,
+                     "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
+                     "bytes_per_launch": gather_bytes, "us_per_launch": round(us_dom / NL, 3)},
         "setup_s": round(t_setup, 1),
     }
     if stages is not None:
@@ -473,7 +526,7 @@ def main():
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(hosts, w, lens, buds)
-    print(json.dumps(res), flush=True)
+    return res
 
 
 def decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, buds, budget, t_setup):

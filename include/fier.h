@@ -109,6 +109,9 @@ size_t fier_packed_meta_bytes(const fier_config *cfg);
 /* Scratch needed by fier_sparse_attn / fier_dense_attn / fier_decode_step for selections of at
  * most max_budget tokens per unit (fier_dense_attn: pass max_budget = max_ctx). */
 size_t fier_workspace_bytes(const fier_config *cfg, int32_t max_budget);
+/* For inspection: the byte offset inside such a workspace of the scores [units][max_ctx] float that the latest
+ * fier_decode_step on it computed for its last layer (Alg. 1 step 2 as the fused step evaluates it).  0 if invalid. */
+size_t fier_workspace_scores_offset(const fier_config *cfg, int32_t max_budget);
 const char *fier_status_string(int status);
 /* Check cfg alone: FIER_OK or the error the other calls would return for it. */
 int fier_check_config(const fier_config *cfg);
@@ -166,7 +169,7 @@ int fier_topk_ws(const fier_config *cfg, const float *scores, const int32_t *seq
 
 /*
  * Alg. 1 step 4.  For every query head: p = softmax(sm_scale * q . K[S]^T), out = p V[S], with
- * S = idx[u][0 .. count[u]) (rows of this unit's cache, any order, each < max_ctx).  Inputs are
+ * S = idx[u][0 .. count[u]) (rows of this unit's cache, any order; an entry outside [0, max_ctx) is skipped).  Inputs are
  * read in the K dtype, logits, softmax and the output are binary32.  out is
  * [batch][n_q_heads][D] float, device.  count[u] == 0 gives zeros.
  */
@@ -225,13 +228,21 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
                            int32_t *count_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * One of the three kernels of fier_decode_step alone, for measurement: phase 1 = append + score + score
- * histogram, 2 = exact threshold, 3 = selection + attention over the selected rows + merge.  Same arguments
- * as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and these
- * layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
- * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with
- * one phase 2 before the next real step), phase 2 only after a phase 1, phase 3 may be repeated freely.
+ * One kernel of fier_decode_step alone, for measurement and tests.  After the first kernel (phase 1: append + score +
+ * score histogram) the step takes one of two forms, chosen from cfg and max_budget alone (fier_decode_step_kernels):
+ *   2 kernels, when all workgroups of the second one are resident on the GPU at once: phase 2 = exact threshold +
+ *     attention over the selected rows + merge in one launch; phase 3 = the ascending index list (launched by the
+ *     step only if idx_out is given; may be repeated);
+ *   3 kernels otherwise: phase 2 = exact threshold, phase 3 = selection + attention + merge, which also writes
+ *     idx_out (may be repeated).
+ * Same arguments as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and
+ * these layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
+ * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with one
+ * phase 2 before the next real step), phase 2 only after a phase 1.  Phases 2 + 16 f, f = 1..3, run the two-kernel
+ * form's second kernel with test flags (1: no workgroup picks up the threshold itself, the merging workgroup attends
+ * over all threshold-bin rows; 2: checksums of the attended rows in the control blocks).
  */
+int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget);
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
                            const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
                            float *out, int32_t *idx_out, int32_t *count_out, void *workspace,

@@ -17,9 +17,11 @@ F16, BF16 = 0, 1
 OK = 0
 EINVAL, ESHAPE, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = -1, -2, -3, -4, -5, -6
 
-SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_status_string",
+SYMBOLS = ["fier_packed_bits_bytes", "fier_packed_meta_bytes", "fier_workspace_bytes", "fier_workspace_scores_offset",
+           "fier_status_string",
            "fier_check_config", "fier_quantize_keys", "fier_append_key", "fier_score", "fier_topk", "fier_topk_ws",
-           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_static", "fier_decode_step_mixed", "fier_decode_step_phase", "fier_page_meta_bytes",
+           "fier_sparse_attn", "fier_dense_attn", "fier_decode_step", "fier_decode_step_static", "fier_decode_step_mixed", "fier_decode_step_phase",
+           "fier_decode_step_kernels", "fier_page_meta_bytes",
            "fier_page_minmax", "fier_page_append", "fier_page_score", "fier_page_mean_score", "fier_expand_pages", "fier_unpack_bits",
            "fier_unpack_meta"]
 
@@ -75,6 +77,10 @@ def lib():
         L.fier_packed_meta_bytes.argtypes = [cfgp]
         L.fier_workspace_bytes.restype = C.c_size_t
         L.fier_workspace_bytes.argtypes = [cfgp, i32]
+        L.fier_workspace_scores_offset.restype = C.c_size_t
+        L.fier_workspace_scores_offset.argtypes = [cfgp, i32]
+        L.fier_decode_step_kernels.restype = C.c_int
+        L.fier_decode_step_kernels.argtypes = [cfgp, i32]
         L.fier_status_string.restype = C.c_char_p
         L.fier_status_string.argtypes = [C.c_int]
         L.fier_check_config.restype = C.c_int
@@ -150,6 +156,21 @@ def packed_meta_bytes(cfg: Config) -> int:
 
 def workspace_bytes(cfg: Config, max_budget: int) -> int:
     return int(lib().fier_workspace_bytes(C.byref(cfg), int(max_budget)))
+
+
+def workspace_scores(cfg: Config, max_budget: int, workspace):
+    """View of the step's score array [units][max_ctx] float32 inside a workspace tensor (for inspection)."""
+    import torch
+
+    off = int(lib().fier_workspace_scores_offset(C.byref(cfg), int(max_budget)))
+    assert off > 0 and off % 4 == 0
+    n = cfg.units * cfg.max_ctx
+    return workspace[off:off + 4 * n].view(torch.float32).view(cfg.units, cfg.max_ctx)
+
+
+def decode_step_kernels(cfg: Config, max_budget: int) -> int:
+    """2 or 3: the number of kernels fier_decode_step launches per layer for this shape."""
+    return int(lib().fier_decode_step_kernels(C.byref(cfg), int(max_budget)))
 
 
 def make_workspace(cfg: Config, max_budget: int):
@@ -309,7 +330,7 @@ def decode_step_mixed(cfg: Config, caches, dense_layers, q, k_new, v_new, budget
 
 def decode_step_phase(cfg: Config, caches, q, k_new, v_new, budgets, max_budget: int, out, idx_out, count_out,
                       workspace, phase: int):
-    """One kernel of the fused step alone (1 = score, 2 = threshold, 3 = select + attend); for measurement."""
+    """One kernel of the fused step alone (see fier_decode_step_phase in fier.h); for measurement and tests."""
     arr = (Cache * len(caches))(*[c.c for c in caches])
     _check(lib().fier_decode_step_phase(C.byref(cfg), arr, len(caches), _ptr(q), _ptr(k_new), _ptr(v_new),
                                         _ptr(budgets), int(max_budget), _ptr(out), _ptr(idx_out), _ptr(count_out),

@@ -181,6 +181,20 @@ size_t fier_workspace_bytes(const fier_config* cfg, int32_t max_budget) {
   return carve(cfg, max_budget, nullptr).bytes;
 }
 
+size_t fier_workspace_scores_offset(const fier_config* cfg, int32_t max_budget) {
+  if (check_cfg(cfg) != FIER_OK || max_budget < 1) return 0;
+  if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
+  char* const base = reinterpret_cast<char*>(kAlign);  // any aligned address: only the distance matters
+  const Workspace w = carve(cfg, max_budget, base);
+  return static_cast<size_t>(reinterpret_cast<char*>(w.sb.scores) - base);
+}
+
+int fier_decode_step_kernels(const fier_config* cfg, int32_t max_budget) {
+  if (check_cfg(cfg) != FIER_OK || max_budget < 1) return 0;
+  if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
+  return fier::step_is_resident(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx) ? 2 : 3;
+}
+
 int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* stream) {
   int st = check_cfg(cfg);
   if (st != FIER_OK) return st;
@@ -294,7 +308,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
   // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel; 2 + 16 f: kernel 2 with test flags f
-  if (max_budget > cfg->max_ctx || phase < -1 || phase > 2 + 16 * 7) return FIER_EINVAL;
+  if (max_budget > cfg->max_ctx || phase < -1 || phase > 2 + 16 * 3) return FIER_EINVAL;
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
@@ -344,25 +358,32 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
                              cfg->max_ctx, cfg->group_size, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
-    if (phase == 8) {
-      e = fier::launch_threshold(w.sb, c->seq_lens, extra, budgets, max_budget, cntl, units, cfg->n_kv_heads, cfg->max_ctx, s);
-      if (e != hipSuccess) return FIER_EHIP;
-    }
-    if (phase == 9) {
-      e = fier::launch_select_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
-                                     cfg->sm_scale, idxl, outl, c->kabsmax, units, cfg->n_kv_heads, cfg->max_ctx, s);
-      if (e != hipSuccess) return FIER_EHIP;
-    }
-    if (phase == 0 || (phase & 15) == 2) {
-      const int flags = phase >> 4;
-      e = fier::launch_step_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, budgets,
-                                   max_budget, cfg->sm_scale, cntl, outl, c->kabsmax, units, cfg->n_kv_heads,
-                                   cfg->max_ctx, flags, s);
-      if (e != hipSuccess) return FIER_EHIP;
-    }
-    if ((phase == 0 || phase == 3) && idxl) {
-      e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, cfg->n_kv_heads, cfg->max_ctx, s);
-      if (e != hipSuccess) return FIER_EHIP;
+    // After scoring: one launch (exact threshold + attention + merge, then the index list if asked for) when all its
+    // workgroups are resident at once; longer grids take the threshold kernel and the selection + attention kernel,
+    // whose workgroups never wait for each other.
+    const bool one_launch = fier::step_is_resident(units, n_rep, max_budget, cfg->max_ctx) || (phase >> 4) != 0;
+    if (one_launch) {
+      if (phase == 0 || (phase & 15) == 2) {
+        e = fier::launch_step_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, budgets,
+                                     max_budget, cfg->sm_scale, cntl, outl, c->kabsmax, units, cfg->n_kv_heads,
+                                     cfg->max_ctx, phase >> 4, s);
+        if (e != hipSuccess) return FIER_EHIP;
+      }
+      if ((phase == 0 || phase == 3) && idxl) {
+        e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, cfg->n_kv_heads, cfg->max_ctx, s);
+        if (e != hipSuccess) return FIER_EHIP;
+      }
+    } else {
+      if (phase == 0 || phase == 2) {
+        e = fier::launch_threshold(w.sb, c->seq_lens, extra, budgets, max_budget, cntl, units, cfg->n_kv_heads,
+                                   cfg->max_ctx, s);
+        if (e != hipSuccess) return FIER_EHIP;
+      }
+      if (phase == 0 || phase == 3) {
+        e = fier::launch_select_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
+                                       cfg->sm_scale, idxl, outl, c->kabsmax, units, cfg->n_kv_heads, cfg->max_ctx, s);
+        if (e != hipSuccess) return FIER_EHIP;
+      }
     }
   }
   return FIER_OK;

@@ -126,7 +126,7 @@ hipError_t launch_select_attend(int dtype, KvLayout lay, int n_rep, const StepBu
 
 // Second kernel of the fused step: exact threshold, attention over the selected rows, merge.  count_out may be null.
 // flags (tests): bit 0 = no workgroup picks up the threshold itself (the merger's fallback does all threshold-bin rows),
-// bit 1 = accumulate the checksums of the attended rows in the control blocks, bit 2 = the selector gives up.
+// bit 1 = accumulate the checksums of the attended rows in the control blocks.
 hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const void* K, const void* V,
                               const void* q, const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
                               float sm_scale, int32_t* count_out, float* out, float* kabsmax, int units, int n_kv_heads,
@@ -135,6 +135,7 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
                                 int units, int n_kv_heads, int max_ctx, hipStream_t st);
 int step_ranges_per_wg(int max_budget, int max_ctx);
+bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx);
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
                        int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,

@@ -43,6 +43,7 @@ constexpr int kAGroup = 320;
 constexpr int kAZeroRow = 576;
 constexpr int kAPlane = 672;
 constexpr int kAWave = 2 * kAPlane;
+constexpr int kScoreMaxBpw = 13;  // pair blocks per wavefront at most (the launcher keeps to it)
 
 __device__ __forceinline__ float wave_allsum(float x) {
   x = row_allsum(x);
@@ -94,6 +95,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
                                                     int n_kv_heads, int max_ctx, int bpw, int gshift, int n_x, KvLayout lay) {
   __shared__ uint32_t lhist[HIST ? kSelBins : 1];
   __shared__ __attribute__((aligned(16))) unsigned char a_lds[4 * kAWave];
+  // The workgroup's scores wait here and leave as one contiguous burst at the end: stores interleaved block by block
+  // with the loads make the memory turn around between reading and writing all the time.
+  __shared__ __attribute__((aligned(16))) float lscore[kScoreMaxBpw * 4 * kPair];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -412,10 +416,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
       f = fmaf((float)dg[3], 16777216.0f, f);
       const float sc = fmaf(f, inv_scale, base);
       const int tok = P * kPair + lane;
-      if (FULL || tok < lim) {
-        scores[(size_t)unit * max_ctx + tok] = sc;
-        if (HIST) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
-      }
+      lscore[(wave + 4 * it) * kPair + lane] = sc;
+      if (HIST && (FULL || tok < lim)) atomicAdd(&lhist[sel_bin(sc, R, hscale, kSelBins)], 1u);
     };
     for (int it = 0; it + 1 < nb; ++it) {
       uint32_t w_nxt[4];
@@ -429,6 +431,24 @@ __global__ __launch_bounds__(256) void score_kernel(const uint4* kbits, const ui
     score_block(std::false_type(), nb - 1);  // the wave's last block may be a partial one
   }
 
+  // ---- the workgroup's scores: tokens [tok_wg, min(tok_wg + 256 bpw, lim)) in one go ------------------------------
+  if (!append_wg) {
+    __syncthreads();
+    const int tok_wg = range * (4 * kPair) * bpw;
+    int n_wg = lim - tok_wg;
+    n_wg = n_wg > 4 * kPair * bpw ? 4 * kPair * bpw : n_wg;
+    float* __restrict__ dst = scores + (size_t)unit * max_ctx + tok_wg;  // tok_wg is a multiple of 256: 16-byte aligned
+    for (int i = 4 * tid; i < n_wg; i += 4 * 256) {
+      const float4 v4 = *reinterpret_cast<const float4*>(lscore + i);
+      if (i + 3 < n_wg) {
+        *reinterpret_cast<float4*>(dst + i) = v4;
+      } else {
+        dst[i] = v4.x;
+        if (i + 1 < n_wg) dst[i + 1] = v4.y;
+        if (i + 2 < n_wg) dst[i + 2] = v4.z;
+      }
+    }
+  }
   FIER_PROF(2, HIST && unit == 0 && range == 3)
   FIER_PROF(8, HIST && unit == 0 && append_wg)
   if constexpr (HIST) {
@@ -472,6 +492,7 @@ static hipError_t launch_score_dt(KvLayout lay, int n_rep, const uint32_t* kbits
   const int rounds = (bpw + 11) / 12;
   bpw = (bpw + rounds - 1) / rounds;
   if (bpw >= 8 && (bpw & (bpw - 1)) == 0) ++bpw;
+  if (bpw > kScoreMaxBpw) return hipErrorInvalidValue;  // cannot happen: at most 12, + 1
   const int n_x = (n_blocks + 4 * bpw - 1) / (4 * bpw);  // scoring workgroups per unit
   dim3 grid((unsigned)units * (unsigned)(n_x + (HIST ? 1 : 0)));
 #define FIER_SCORE_CASE(R)                                                                                         \

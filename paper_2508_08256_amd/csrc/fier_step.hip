@@ -1,25 +1,26 @@
 // Second kernel of the fused decode step: exact top-B threshold (Alg. 1 step 3) and attention over the selected
-// rows (Alg. 1 step 4) in ONE launch, with no workgroup ever depending on the progress of a workgroup that may not
-// be running.
+// rows (Alg. 1 step 4) in ONE launch, for grids whose workgroups are all resident at once.
 //
 // The score kernel has left, per unit, its scores and their 512-bin histogram over [-R, R].  Here a workgroup owns
 // RPW consecutive 1024-token ranges of a unit and
 //   1. finds, from the unit's histogram, the bin `tbin` that holds the B-th largest score (the same few hundred
 //      integer additions in every workgroup of the unit: cheaper than a serial step somewhere plus the wait for it);
-//   2. classifies its own scores: tokens in bins above tbin are selected for certain ("sure" rows), tokens inside
-//      tbin are the candidates for the threshold (about 1 % of the tokens).  The sure rows go to an LDS list, the
-//      candidates to an LDS list and, as (key, index) pairs, to the unit's candidate slots in memory;
+//   2. classifies its own scores: tokens in bins above tbin are selected for certain ("sure" rows, listed in LDS),
+//      tokens inside tbin are the candidates for the threshold (about 1 % of the tokens), kept in LDS and published
+//      as (key, index) pairs in the unit's candidate slots in memory;
 //   3. counts its arrival.  The unit's LAST arriver ("selector") reads all candidates of the unit, histograms them
 //      once more inside the threshold bin (1024 sub-bins), ranks the members of the decisive sub-bin pairwise
 //      (larger key first, equal keys by lower index) and publishes the exact threshold (T, idxT) as one 64-bit word;
-//   4. meanwhile every workgroup, the selector after it has published, gathers its sure rows and attends over
-//      them -- the bulk of the work runs while the serial selection of step 3 is under way;
-//   5. then picks up the threshold word (it has long been there; if not, it polls for a bounded time), applies
-//      `key > T or (key == T and index <= idxT)` to its own few candidates, attends over the selected ones, marks
-//      itself done, stores its partial (m, l, o) per query head and counts its second arrival;
-//   6. the unit's last arriver of that second counter merges the partials.  Should a workgroup have given up at 5
-//      (its flag is missing), the merger redoes that workgroup's candidate rows itself first: the result never
-//      depends on the poll succeeding, so a workgroup only ever waits for a bounded time and every wavefront exits.
+//   4. the other workgroups poll that word -- the memory system is idle at this point, the selection takes about as
+//      long as three round trips -- and append those of their candidates with `key > T or (key == T and index <=
+//      idxT)` to their row lists;
+//   5. every workgroup attends over its rows, stores its partial (m, l, o) per query head and counts a second arrival;
+//      the unit's last arriver there merges the partials.
+// The poll of step 4 is bounded.  A workgroup that gives up attends over its sure rows only and leaves a flag
+// unset; the merging workgroup then attends over that workgroup's threshold-bin rows itself before it merges.  The
+// result therefore never depends on a poll succeeding, every wait is bounded and every wavefront exits.  The poll
+// only ever lasts long when the unit's workgroups are not running together, which is why the launcher uses this
+// kernel for resident grids and the three-kernel form (threshold kernel, then selection + attention) otherwise.
 // All selection decisions are integer comparisons of order-preserving keys: exact and deterministic.
 //
 // The ascending index list of the selection (idx_out of the step, an optional output) is written by a small
@@ -35,9 +36,9 @@ namespace {
 
 constexpr int kStepThreads = 256;
 constexpr int kCandRegs = 8;        // candidate slots a selector thread holds in registers per sweep
-constexpr int kLateRows = 256;      // rows per batch of the late (threshold-bin) gather
+constexpr int kCandLds = 256;       // candidates of a workgroup kept in LDS (the rest are read back from its slots)
 constexpr int kMaxStepWgs = (1 << 20) / kRangeTokens;  // workgroups of one unit at most (max_ctx <= 2^20, RPW >= 1)
-constexpr int kPollMax = 4096;      // polls of the threshold word before a workgroup gives up (each ~0.3 us)
+constexpr int kPollMax = 1 << 14;   // polls of the threshold word before a workgroup gives up (each >= 0.1 us)
 
 // selector scratch in LDS (dead before the partials use the same bytes)
 struct SelScratch {
@@ -49,15 +50,165 @@ struct SelScratch {
   uint32_t max_seg;
 };
 
-// The unit's threshold word: 0 = not there yet; T << 32 | idxT + 2 (never zero: idxT >= -1, never one of the marks:
-// idxT < 2^20); kThrGaveUp = the selector gave up waiting for the range workgroups; kThrClosed = the merging
-// workgroup has been here.
-constexpr unsigned long long kThrGaveUp = ~0ull;
-constexpr unsigned long long kThrClosed = ~0ull - 1;
+// The unit's threshold word: 0 = not there yet, else T << 32 | idxT + 2 (never zero: idxT >= -1).
 __device__ __forceinline__ unsigned long long pack_threshold(uint32_t T, int32_t idxT) {
   return ((unsigned long long)T << 32) | (uint32_t)(idxT + 2);
 }
-__device__ __forceinline__ bool is_threshold(unsigned long long w) { return w != 0ull && w < kThrClosed; }
+
+// Exact threshold of a unit from the candidates its nc workgroups published: slot k * nc + w of ucand holds candidate
+// k of workgroup w (k < useg[w], at most seg_cap per workgroup).  r_want >= 1 of the candidates are to be selected,
+// larger key first, equal keys by lower index; T / idxT describe the last one selected.  One more histogram inside
+// the threshold bin (kSubBins equal-width sub-bins), then the members of the decisive sub-bin are ranked pairwise.
+// Returns false if a workgroup had more candidates than slots or the decisive sub-bin more than kSubCandMax members
+// (the caller then falls back to the radix selection over the scores).  Every thread of the workgroup calls it.
+__device__ __forceinline__ bool select_among_candidates(const unsigned long long* __restrict__ ucand,
+                                                        const uint32_t* __restrict__ useg, int nc, uint32_t seg_cap,
+                                                        uint32_t r_want, int tbin, float R, float hscale,
+                                                        SelScratch* ss, uint32_t* scan_tmp, uint32_t& T,
+                                                        int32_t& idxT) {
+  const int tid = threadIdx.x;
+  constexpr int kSegRegs = (kMaxStepWgs + kStepThreads - 1) / kStepThreads;
+  // segment sizes and the first sweep of candidate slots leave together
+  uint32_t my_max = 0;
+  bool over = false;
+  if (tid == 0) {
+    ss->max_seg = 0;
+    ss->res[0] = 0;
+    ss->res[1] = 0;
+    ss->n_sub = 0;
+  }
+  uint32_t segc[kSegRegs];
+#pragma unroll
+  for (int k = 0; k < kSegRegs; ++k) {
+    const int w = k * kStepThreads + tid;
+    segc[k] = w < nc ? load_coherent(&useg[w]) : 0u;
+  }
+  unsigned long long e[kCandRegs];
+  const uint32_t slots_all = seg_cap * (uint32_t)nc;  // slots that exist for this unit's workgroups
+#pragma unroll
+  for (int k = 0; k < kCandRegs; ++k) {
+    const uint32_t sidx = (uint32_t)(k * kStepThreads + tid);
+    e[k] = sidx < slots_all ? load_coherent(&ucand[sidx]) : 0ull;
+  }
+#pragma unroll
+  for (int k = 0; k < kSegRegs; ++k) {
+    const int w = k * kStepThreads + tid;
+    if (w < nc) {
+      over = over || segc[k] > seg_cap;
+      const uint32_t sz = segc[k] > seg_cap ? seg_cap : segc[k];
+      ss->seg_size[w] = (uint16_t)sz;
+      my_max = my_max > sz ? my_max : sz;
+    }
+  }
+  for (int k = tid; k < kSubBins; k += kStepThreads) ss->hist[k] = 0;
+  __syncthreads();
+  if (my_max) atomicMax(&ss->max_seg, my_max);
+  if (__syncthreads_or(over)) return false;
+  // slots k * nc + w with k < max_seg may hold candidates: swept 8 x 256 at a time
+  const uint32_t n_scan = ss->max_seg * (uint32_t)nc;
+  const uint32_t sweep = (uint32_t)(kCandRegs * kStepThreads);
+  const uint32_t n_sweeps = (n_scan + sweep - 1) / sweep;
+  const float lo_b = hscale > 0.0f ? (float)tbin / hscale - R : 0.0f;  // lower edge of the threshold bin
+  const float scale2 = hscale * (float)kSubBins;
+  auto sub_of = [&](unsigned long long ent) {
+    return sel_bin(key_score((uint32_t)(ent >> 32)), -lo_b, scale2, kSubBins);
+  };
+  // slot sidx = k * nc + w holds a candidate if k < seg_size[w]; a thread's slots are 256 apart, so (k, w) advance
+  // by (256 / nc, 256 % nc) with a carry: no division per slot
+  const uint32_t unc = (uint32_t)nc;
+  const uint32_t step_k = (uint32_t)kStepThreads / unc, step_w = (uint32_t)kStepThreads % unc;
+  uint32_t vmask = 0;  // first sweep: which of the thread's slots hold a candidate
+  {
+    uint32_t k_s = (uint32_t)tid / unc, w_s = (uint32_t)tid % unc;
+    for (uint32_t sw = 0; sw < n_sweeps; ++sw) {
+#pragma unroll
+      for (int k = 0; k < kCandRegs; ++k) {
+        const uint32_t sidx = sw * sweep + (uint32_t)(k * kStepThreads + tid);
+        if (sw > 0) e[k] = sidx < n_scan ? load_coherent(&ucand[sidx]) : 0ull;
+        const bool valid = sidx < n_scan && k_s < (uint32_t)ss->seg_size[w_s];
+        if (valid) atomicAdd(&ss->hist[sub_of(e[k])], 1u);
+        if (sw == 0 && valid) vmask |= 1u << k;
+        k_s += step_k;
+        w_s += step_w;
+        if (w_s >= unc) {
+          w_s -= unc;
+          ++k_s;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // sub-bin t with (count in sub-bins > t) < r_want <= (count in sub-bins >= t); descending ownership
+  {
+    constexpr int PER = kSubBins / kStepThreads;
+    uint32_t cntb[PER], sum = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      cntb[k] = ss->hist[kSubBins - 1 - (PER * tid + k)];
+      sum += cntb[k];
+    }
+    uint32_t total;
+    uint32_t before = block_excl_scan_u32<4>(sum, scan_tmp, total);
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      if (before < r_want && r_want <= before + cntb[k]) {
+        ss->res[0] = (uint32_t)(kSubBins - 1 - (PER * tid + k));
+        ss->res[1] = before;
+      }
+      before += cntb[k];
+    }
+    __syncthreads();
+  }
+  const int tsub = (int)ss->res[0];
+  const uint32_t r2 = r_want - ss->res[1];  // rank wanted inside the sub-bin, 1-based
+  const uint32_t n_in_sub = ss->hist[tsub];
+  __syncthreads();
+  if (n_in_sub > (uint32_t)kSubCandMax) return false;
+  if (n_sweeps == 1) {  // the candidates are still in the registers
+#pragma unroll
+    for (int k = 0; k < kCandRegs; ++k)
+      if ((vmask >> k & 1u) && sub_of(e[k]) == tsub) ss->sub_list[atomicAdd(&ss->n_sub, 1u)] = e[k];
+  } else {
+    uint32_t k_s = (uint32_t)tid / unc, w_s = (uint32_t)tid % unc;
+    for (uint32_t sw = 0; sw < n_sweeps; ++sw) {
+#pragma unroll
+      for (int k = 0; k < kCandRegs; ++k) {
+        const uint32_t sidx = sw * sweep + (uint32_t)(k * kStepThreads + tid);
+        const bool valid = sidx < n_scan && k_s < (uint32_t)ss->seg_size[w_s];
+        if (valid) {
+          const unsigned long long ent = load_coherent(&ucand[sidx]);
+          if (sub_of(ent) == tsub) ss->sub_list[atomicAdd(&ss->n_sub, 1u)] = ent;
+        }
+        k_s += step_k;
+        w_s += step_w;
+        if (w_s >= unc) {
+          w_s -= unc;
+          ++k_s;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // rank the members of the decisive sub-bin: larger key first, equal keys by lower index
+  for (uint32_t m = tid; m < n_in_sub; m += kStepThreads) {
+    const unsigned long long me = ss->sub_list[m];
+    const uint32_t mk = (uint32_t)(me >> 32), mi = (uint32_t)me;
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n_in_sub; ++j) {
+      const unsigned long long o = ss->sub_list[j];
+      const uint32_t ok = (uint32_t)(o >> 32), oi = (uint32_t)o;
+      rank += (ok > mk) || (ok == mk && oi < mi);
+    }
+    if (rank == r2 - 1) {
+      ss->res[0] = mk;
+      ss->res[1] = mi;
+    }
+  }
+  __syncthreads();
+  T = ss->res[0];
+  idxT = (int32_t)ss->res[1];
+  return true;
+}
 
 }  // namespace
 
@@ -70,7 +221,7 @@ struct StepArgs {
   int max_budget;
   unsigned long long* cand;  // [units][cand_pitch]: slot k * nc + w = k-th candidate of workgroup w of the unit
   uint32_t* seg_cnt;         // [units][wgs_per_unit]
-  uint32_t* done;            // [units][wgs_per_unit]: 1 once the workgroup has attended over its candidate rows
+  uint32_t* done;            // [units][wgs_per_unit]: 1 once the workgroup has its threshold-bin rows in its list
   const uint4* K;
   const uint4* V;
   const uint4* q;
@@ -86,8 +237,8 @@ struct StepArgs {
   const float* newmax;
   int n_kv_heads, max_ctx, order, wgs_per_unit;
   size_t cand_pitch;
-  int flags;  // tests: bit 0 = no workgroup picks up the threshold itself (the merger attends over all threshold-bin
-              // rows); bit 1 = checksums of the attended rows; bit 2 = the selector gives up (the merger selects)
+  int flags;  // tests: bit 0 = no workgroup picks up the threshold (the merging workgroup attends over all
+              // threshold-bin rows); bit 1 = checksums of the attended rows
   KvLayout lay;
 };
 
@@ -103,9 +254,9 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
       sizeof(SelScratch) > sizeof(float) * NREP * kPartialFloats ? sizeof(SelScratch) : sizeof(float) * NREP * kPartialFloats;
   static_assert(kScratchBytes >= sizeof(float) * 4 * 130, "merge_heads needs 4 x 130 floats");
   __shared__ __attribute__((aligned(16))) unsigned char scratch[kScratchBytes];
-  __shared__ uint16_t rows[CAP];         // sure rows from the front, candidates from the back (offsets from tok0)
-  __shared__ uint16_t xrows[kLateRows];  // one batch of late rows (offsets from a base token)
-  __shared__ uint32_t ckey[kLateRows];   // keys of the workgroup's first candidates (the rest are read back from memory)
+  __shared__ uint16_t rows[CAP];        // the rows to attend over (offsets from tok0): sure rows, then selected candidates
+  __shared__ uint16_t coff[kCandLds];   // the workgroup's first candidates: offsets from tok0 ...
+  __shared__ uint32_t ckey[kCandLds];   // ... and keys
   __shared__ uint32_t scan_tmp[4];
   __shared__ int found[2];
   __shared__ uint32_t flag;
@@ -120,22 +271,17 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   const int cn = tid & 15;
   // order: 0 = grid (workgroups, units); 1 = grid (units, workgroups); 2 = one-dimensional, groups of 8 units, a
   // group's workgroups together and unit % 8 fastest (see the launcher)
-  // Per unit wgs_per_unit + 1 workgroups: number 0 is the unit's selector (no tokens of its own), numbers 1.. own the
-  // ranges.  Every order puts a unit's selector ahead of its range workgroups.
-  int unit, wg_raw;
-  const int wpu1 = a.wgs_per_unit + 1;
+  int unit, wg;
   if (a.order == 2) {
     const int id = blockIdx.x;
-    const int g = id / (8 * wpu1);
-    const int rem = id - g * 8 * wpu1;
-    wg_raw = rem >> 3;
+    const int g = id / (8 * a.wgs_per_unit);
+    const int rem = id - g * 8 * a.wgs_per_unit;
+    wg = rem >> 3;
     unit = 8 * g + (rem & 7);
   } else {
     unit = a.order ? blockIdx.x : blockIdx.y;
-    wg_raw = a.order ? blockIdx.y : blockIdx.x;
+    wg = a.order ? blockIdx.y : blockIdx.x;
   }
-  const bool is_selector = wg_raw == 0;
-  const int wg = wg_raw - 1;
   const int max_ctx = a.max_ctx;
   const int b = unit / a.n_kv_heads;
   UnitCtl* __restrict__ c = &a.ctl[unit];
@@ -147,14 +293,14 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   int B = a.budgets[b];
   int n = a.seq_lens[b] + a.extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
-  const int tok0 = is_selector ? 0 : wg * CAP;
-  if (!is_selector && tok0 >= n && wg != 0) return;
+  const int tok0 = wg * CAP;
+  if (tok0 >= n && wg != 0) return;
   const int nc = n > 0 ? (n + CAP - 1) / CAP : 1;  // workgroups of this unit that run
   FIER_PROF_WG(2)
   const int n_slots = a.wgs_per_unit + 1;          // partial slots per (unit, head): one spare for the merger
 
   const KvRows kv = a.lay.rows_of(unit);
-  if (!is_selector && kv.blocks && tid < RPW * kRangeTokens / 64) {  // in flight during the selection; barriers follow
+  if (kv.blocks && tid < RPW * kRangeTokens / 64) {  // in flight during the selection; barriers follow
     const int bi = (tok0 >> kv.shift) + tid;
     lblk[tid] = bi < a.lay.blocks_per_seq ? kv.blocks[bi] : 0;
   }
@@ -169,12 +315,11 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   for (int rr = 0; rr < RPW; ++rr) {
     const int i = tok0 + rr * kRangeTokens + 4 * tid;
     v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (!is_selector && i < n) v[rr] = *reinterpret_cast<const float4*>(s_unit + i);  // i + 3 < max_ctx; masked below
+    if (i < n) v[rr] = *reinterpret_cast<const float4*>(s_unit + i);  // i + 3 < max_ctx; entries >= n are masked below
   }
   B = B > a.max_budget ? a.max_budget : B;
   B = B > n ? n : B;
   B = B < 0 ? 0 : B;
-  if (is_selector && !(B > 0 && B < n)) return;  // everything or nothing is selected: there is no threshold to find
   if (tid == 0) {
     found[0] = B >= n ? -1 : kSelBins;  // everything / nothing selected by bin alone
     found[1] = 0;
@@ -197,197 +342,6 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   const int tbin = found[0];
   const uint32_t above = (uint32_t)found[1];
   const bool need_threshold = tbin >= 0 && tbin < kSelBins && B > 0;
-
-  // ---- the unit's selector: the exact threshold, as soon as every range workgroup has published its candidates -----
-  if (is_selector) {
-    // the rest of the unit will wait for what follows: ahead of the other workgroups' gather loops on this CU
-    __builtin_amdgcn_s_setprio(3);
-    if (tid == 0) {
-      uint32_t arrived = 0;
-      for (int spin = 0; spin < kPollMax; ++spin) {
-        arrived = load_coherent(&c->arrive[1]);
-        if (arrived >= (uint32_t)nc) break;
-        __builtin_amdgcn_s_sleep(8);
-      }
-      flag = (arrived >= (uint32_t)nc && !(a.flags & 4)) ? 1u : 0u;
-    }
-    __syncthreads();
-    FIER_PROF(13, unit == 0)
-    unsigned long long word = kThrGaveUp;  // the range workgroups did not all arrive in time: the merger selects
-    if (flag) {
-      uint32_t T = 0;
-      int32_t idxT = -1;
-    const uint32_t r_want = (uint32_t)B - above;  // candidates to take, >= 1
-    const uint32_t n_slot_rows = (uint32_t)SEGCAP;
-    // segment sizes and the first sweep of candidate slots leave together
-    uint32_t my_max = 0;
-    bool over = false;
-    if (tid == 0) {
-      ss->max_seg = 0;
-      ss->res[0] = 0;
-      ss->res[1] = 0;
-    }
-    uint32_t segc[(kMaxStepWgs + kStepThreads - 1) / kStepThreads];
-#pragma unroll
-    for (int k = 0; k < (kMaxStepWgs + kStepThreads - 1) / kStepThreads; ++k) {
-      const int w = k * kStepThreads + tid;
-      segc[k] = w < nc ? load_coherent(&useg[w]) : 0u;
-    }
-    unsigned long long e[kCandRegs];
-    const uint32_t slots_all = n_slot_rows * (uint32_t)nc;  // slots that exist for this unit's workgroups
-#pragma unroll
-    for (int k = 0; k < kCandRegs; ++k) {
-      const uint32_t sidx = (uint32_t)(k * kStepThreads + tid);
-      e[k] = sidx < slots_all ? load_coherent(&ucand[sidx]) : 0ull;
-    }
-#pragma unroll
-    for (int k = 0; k < (kMaxStepWgs + kStepThreads - 1) / kStepThreads; ++k) {
-      const int w = k * kStepThreads + tid;
-      if (w < nc) {
-        over = over || segc[k] > n_slot_rows;
-        const uint32_t sz = segc[k] > n_slot_rows ? n_slot_rows : segc[k];
-        ss->seg_size[w] = (uint16_t)sz;
-        my_max = my_max > sz ? my_max : sz;
-      }
-    }
-    for (int k = tid; k < kSubBins; k += kStepThreads) ss->hist[k] = 0;
-    __syncthreads();
-    FIER_PROF(16, unit == 0)
-    if (my_max) atomicMax(&ss->max_seg, my_max);
-    const bool overflow = __syncthreads_or(over);
-    bool done = false;
-    if (!overflow) {
-      // slots k * nc + w with k < max_seg may hold candidates: swept 8 x 256 at a time
-      const uint32_t n_scan = ss->max_seg * (uint32_t)nc;
-      const uint32_t sweep = (uint32_t)(kCandRegs * kStepThreads);
-      const uint32_t n_sweeps = (n_scan + sweep - 1) / sweep;
-      const float lo_b = hscale > 0.0f ? (float)tbin / hscale - R : 0.0f;  // lower edge of the threshold bin
-      const float scale2 = hscale * (float)kSubBins;
-      auto sub_of = [&](unsigned long long ent) {
-        return sel_bin(key_score((uint32_t)(ent >> 32)), -lo_b, scale2, kSubBins);
-      };
-      // slot sidx = k * nc + w holds candidate k of workgroup w if k < seg_size[w]; a thread's slots are 256 apart,
-      // so (k, w) advance by (256 / nc, 256 % nc) with a carry: no division per slot
-      const uint32_t unc = (uint32_t)nc;
-      const uint32_t step_k = (uint32_t)kStepThreads / unc, step_w = (uint32_t)kStepThreads % unc;
-      uint32_t vmask = 0;  // first sweep: which of the thread's slots hold a candidate
-      {
-        uint32_t k_s = (uint32_t)tid / unc, w_s = (uint32_t)tid % unc;
-        for (uint32_t sw = 0; sw < n_sweeps; ++sw) {
-#pragma unroll
-          for (int k = 0; k < kCandRegs; ++k) {
-            const uint32_t sidx = sw * sweep + (uint32_t)(k * kStepThreads + tid);
-            if (sw > 0) e[k] = sidx < n_scan ? load_coherent(&ucand[sidx]) : 0ull;
-            const bool valid = sidx < n_scan && k_s < (uint32_t)ss->seg_size[w_s];
-            if (valid) atomicAdd(&ss->hist[sub_of(e[k])], 1u);
-            if (sw == 0 && valid) vmask |= 1u << k;
-            k_s += step_k;
-            w_s += step_w;
-            if (w_s >= unc) {
-              w_s -= unc;
-              ++k_s;
-            }
-          }
-        }
-      }
-      if (tid == 0) ss->n_sub = 0;
-      __syncthreads();
-      FIER_PROF(17, unit == 0)
-      // sub-bin t with (count in sub-bins > t) < r_want <= (count in sub-bins >= t); descending ownership
-      {
-        constexpr int PER = kSubBins / kStepThreads;
-        uint32_t cntb[PER], sum = 0;
-#pragma unroll
-        for (int k = 0; k < PER; ++k) {
-          cntb[k] = ss->hist[kSubBins - 1 - (PER * tid + k)];
-          sum += cntb[k];
-        }
-        uint32_t total;
-        uint32_t before = block_excl_scan_u32<4>(sum, scan_tmp, total);
-#pragma unroll
-        for (int k = 0; k < PER; ++k) {
-          if (before < r_want && r_want <= before + cntb[k]) {
-            ss->res[0] = (uint32_t)(kSubBins - 1 - (PER * tid + k));
-            ss->res[1] = before;
-          }
-          before += cntb[k];
-        }
-        __syncthreads();
-      }
-      const int tsub = (int)ss->res[0];
-      const uint32_t r2 = r_want - ss->res[1];  // rank wanted inside the sub-bin, 1-based
-      const uint32_t n_in_sub = ss->hist[tsub];
-      __syncthreads();
-      FIER_PROF(18, unit == 0)
-      if (n_in_sub <= (uint32_t)kSubCandMax) {
-        if (n_sweeps == 1) {  // the candidates are still in the registers
-#pragma unroll
-          for (int k = 0; k < kCandRegs; ++k)
-            if ((vmask >> k & 1u) && sub_of(e[k]) == tsub) ss->sub_list[atomicAdd(&ss->n_sub, 1u)] = e[k];
-        } else {
-          uint32_t k_s = (uint32_t)tid / unc, w_s = (uint32_t)tid % unc;
-          for (uint32_t sw = 0; sw < n_sweeps; ++sw) {
-#pragma unroll
-            for (int k = 0; k < kCandRegs; ++k) {
-              const uint32_t sidx = sw * sweep + (uint32_t)(k * kStepThreads + tid);
-              const bool valid = sidx < n_scan && k_s < (uint32_t)ss->seg_size[w_s];
-              if (valid) {
-                const unsigned long long ent = load_coherent(&ucand[sidx]);
-                if (sub_of(ent) == tsub) ss->sub_list[atomicAdd(&ss->n_sub, 1u)] = ent;
-              }
-              k_s += step_k;
-              w_s += step_w;
-              if (w_s >= unc) {
-                w_s -= unc;
-                ++k_s;
-              }
-            }
-          }
-        }
-        __syncthreads();
-        // rank the members of the decisive sub-bin: larger key first, equal keys by lower index
-        for (uint32_t m = tid; m < n_in_sub; m += kStepThreads) {
-          const unsigned long long me = ss->sub_list[m];
-          const uint32_t mk = (uint32_t)(me >> 32), mi = (uint32_t)me;
-          uint32_t rank = 0;
-          for (uint32_t j = 0; j < n_in_sub; ++j) {
-            const unsigned long long o = ss->sub_list[j];
-            const uint32_t ok = (uint32_t)(o >> 32), oi = (uint32_t)o;
-            rank += (ok > mk) || (ok == mk && oi < mi);
-          }
-          if (rank == r2 - 1) {
-            ss->res[0] = mk;
-            ss->res[1] = mi;
-          }
-        }
-        __syncthreads();
-        T = ss->res[0];
-        idxT = (int32_t)ss->res[1];
-        done = true;
-      }
-    }
-    if (!done) {
-      // candidates that do not fit (scores clustered far more tightly than the a-priori range resolves): radix
-      // selection streamed over the unit's scores
-      __syncthreads();
-      stream_select<kStepThreads>([&](int k) { return s_unit[k]; }, n, tbin, R, hscale, r_want, ss->hist, scan_tmp,
-                                  ss->res, nullptr, T, idxT);
-    }
-      word = pack_threshold(T, idxT);
-    }
-    __builtin_amdgcn_s_setprio(0);
-    // Publish.  The merging workgroup closes the word with an exchange of its own when it needs the threshold; of the
-    // two, whoever finds the other's mark is the last to touch the word and the arrival counter and clears them.
-    if (tid == 0) {
-      const unsigned long long old = __hip_atomic_exchange(&c->thr, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (old != 0ull) {
-        store_coherent(&c->thr, 0ull);
-        store_coherent(&c->arrive[1], 0u);
-      }
-    }
-    FIER_PROF(15, unit == 0)
-    return;
-  }
 
   // ---- 2. classify the workgroup's tokens: sure rows and candidates ------------------------------------------------
   uint32_t dmask = 0, cmask = 0;  // bit 4 rr + j = token j of the thread in range rr
@@ -418,26 +372,94 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
         const uint32_t off = (uint32_t)(rr * kRangeTokens + 4 * tid + j);
         if (dmask >> (4 * rr + j) & 1u) rows[pd++] = (uint16_t)off;
         if (cmask >> (4 * rr + j) & 1u) {
-          rows[CAP - 1 - pc] = (uint16_t)off;
-          if (pc < (uint32_t)kLateRows) ckey[pc] = score_key(vv[j]);
+          const uint32_t key = score_key(vv[j]);
+          if (pc < (uint32_t)kCandLds) {
+            coff[pc] = (uint16_t)off;
+            ckey[pc] = key;
+          }
           if (pc < (uint32_t)SEGCAP)
-            store_coherent(&ucand[(size_t)pc * nc + wg],
-                           ((unsigned long long)score_key(vv[j]) << 32) | (uint32_t)(tok0 + (int)off));
+            store_coherent(&ucand[(size_t)pc * nc + wg], ((unsigned long long)key << 32) | (uint32_t)(tok0 + (int)off));
           ++pc;
         }
       }
     }
   }
-  const int n_sure = (int)(listed & 0xffffu);
+  int n_rows = (int)(listed & 0xffffu);
   const int n_cand = (int)(listed >> 16);
-  if (tid == 0) store_coherent(&useg[wg], (uint32_t)n_cand);
-  // ---- 3. arrival: the candidates are acknowledged, the unit's selector may read them.  Nothing is waited for.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();  // (also: the row lists are complete)
-  if (tid == 0) __hip_atomic_fetch_add(&c->arrive[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint32_t chk_sum = 0;  // (tests) sum of the token indices this thread put on the list
 
-  // ---- 4. attention over the sure rows ----------------------------------------------------------------------------
+  // ---- 3. / 4. the exact threshold: found by the unit's last arriver, picked up by the others ----------------------
+  bool picked = true;  // the workgroup's threshold-bin rows are on its list (or it has none)
+  if (need_threshold) {
+    if (tid == 0) store_coherent(&useg[wg], (uint32_t)n_cand);
+    uint32_t T = 0;
+    int32_t idxT = -1;
+    bool have = false;
+    if (last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) {
+      FIER_PROF(13, unit == 0)
+      if (!select_among_candidates(ucand, useg, nc, (uint32_t)SEGCAP, (uint32_t)B - above, tbin, R, hscale, ss, scan_tmp,
+                                   T, idxT)) {
+        // candidates that do not fit (scores clustered far more tightly than the a-priori range resolves): radix
+        // selection streamed over the unit's scores
+        __syncthreads();
+        stream_select<kStepThreads>([&](int k) { return s_unit[k]; }, n, tbin, R, hscale, (uint32_t)B - above, ss->hist,
+                                    scan_tmp, ss->res, nullptr, T, idxT);
+      }
+      if (tid == 0) {
+        store_coherent(&c->thr, pack_threshold(T, idxT));
+        c->arrive[1] = 0;
+      }
+      have = true;
+      FIER_PROF(15, unit == 0)
+    } else if (n_cand > 0 && n_cand <= SEGCAP) {
+      // the memory system is idle now and the selection short: poll
+      if (tid == 0) {
+        unsigned long long w = 0;
+        for (int spin = 0; spin < kPollMax; ++spin) {
+          w = load_coherent(&c->thr);
+          if (w) break;
+          __builtin_amdgcn_s_sleep(4);
+        }
+        thr_sh = w;
+      }
+      __syncthreads();
+      const unsigned long long w = thr_sh;
+      have = w != 0ull;
+      T = (uint32_t)(w >> 32);
+      idxT = (int32_t)(uint32_t)w - 2;
+    }
+    picked = n_cand == 0;
+    if (have && n_cand > 0 && n_cand <= SEGCAP && !(a.flags & 1)) {
+      // the selected candidates join the row list, in candidate (= token) order
+      for (int k0 = 0; k0 < n_cand; k0 += kStepThreads) {
+        const int k = k0 + tid;
+        bool sel = false;
+        uint32_t off = 0;
+        if (k < n_cand) {
+          uint32_t key;
+          if (k < kCandLds) {
+            off = coff[k];
+            key = ckey[k];
+          } else {  // the workgroup's own slot
+            const unsigned long long ent = load_coherent(&ucand[(size_t)k * nc + wg]);
+            key = (uint32_t)(ent >> 32);
+            off = (uint32_t)ent - (uint32_t)tok0;
+          }
+          sel = key > T || (key == T && tok0 + (int)off <= idxT);
+        }
+        uint32_t n_sel;
+        const uint32_t at = block_excl_scan_u32<4>(sel ? 1u : 0u, scan_tmp, n_sel);
+        if (sel) rows[n_rows + (int)at] = (uint16_t)off;
+        n_rows += (int)n_sel;
+      }
+      picked = true;
+    }
+  }
+  __syncthreads();  // the row list is complete
+  if (tid == 0 && need_threshold && picked) store_coherent(&udone[wg], 1u);
   FIER_PROF_WG(3)
+
+  // ---- 5. attention over the rows -------------------------------------------------------------------------------------
   uint4 qr[NREP];
 #pragma unroll
   for (int h = 0; h < NREP; ++h) qr[h] = a.q[((size_t)unit * NREP + h) * (kD / 8) + cn];
@@ -445,135 +467,78 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   AttnState<NREP> st;
   st.init();
   const int first_block = tok0 >> kv.shift;
-  auto row_sure = [&](int j) {
+  auto row_own = [&](int j) {
     const int t = tok0 + (int)rows[j];
     return kv.blocks ? (size_t)lblk[(t >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(t & kv.mask)
                      : kv.base + (size_t)t;
   };
   if constexpr (NREP >= 3)
-    attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_sure, 0, n_sure, a.scale_log2e, st, sh_o);
+    attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_own, 0, n_rows, a.scale_log2e, st, sh_o);
   else
-    attend_rows<DT, NREP>(a.K, a.V, qr, row_sure, 0, n_sure, a.scale_log2e, st);
+    attend_rows<DT, NREP>(a.K, a.V, qr, row_own, 0, n_rows, a.scale_log2e, st);
   FIER_PROF_WG(4)
-  uint32_t chk_cnt = (uint32_t)n_sure, chk_sum = 0;
-  if (a.flags & 2)
-    for (int j = tid; j < n_sure; j += kStepThreads) chk_sum += (uint32_t)(tok0 + (int)rows[j]);
-
-  // Attention over the candidates of tokens [base, base + span) of this unit that the threshold selects, in batches
-  // through xrows; list(k) gives the k-th candidate's offset from base, or -1.  Every thread of the workgroup calls it.
-  bool resumed = false;
-  // key_of(k, t) the key of that candidate.
-  auto attend_late = [&](uint32_t T, int32_t idxT, int base, int count, auto&& list, auto&& key_of,
-                         AttnState<NREP>& state) {
-    for (int k0 = 0; k0 < count; k0 += kLateRows) {
-      const int k = k0 + tid;
-      int off = -1;
-      if (k < count) {
-        off = list(k);
-        if (off >= 0) {
-          const int t = base + off;
-          const uint32_t key = key_of(k, t);
-          if (!(key > T || (key == T && t <= idxT))) off = -1;
-        }
-      }
-      uint32_t n_x_u;
-      const uint32_t at = block_excl_scan_u32<4>(off >= 0 ? 1u : 0u, scan_tmp, n_x_u);  // its first barrier frees xrows
-      if (off >= 0) {
-        xrows[at] = (uint16_t)off;
-        if (a.flags & 2) chk_sum += (uint32_t)(base + off);
-      }
-      __syncthreads();
-      const int n_x = (int)n_x_u;
-      auto row_late = [&](int j) { return kv.row(base + (int)xrows[j]); };
-      if constexpr (NREP >= 3)
-        attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_late, 0, n_x, a.scale_log2e, state, sh_o, resumed);
-      else
-        attend_rows<DT, NREP>(a.K, a.V, qr, row_late, 0, n_x, a.scale_log2e, state);
-      resumed = true;
-      if (tid == 0) chk_cnt += (uint32_t)n_x;
-    }
-  };
-
-  // ---- 5. the workgroup's own candidates, once the threshold is known ---------------------------------------------
-  resumed = true;  // the state continues from the sure rows
-  if (need_threshold && n_cand > 0) {
-    __syncthreads();
-    if (tid == 0) {
-      unsigned long long w = 0;
-      if (!(a.flags & 1))
-        for (int spin = 0; spin < kPollMax; ++spin) {
-          w = load_coherent(&c->thr);
-          if (w) break;
-          __builtin_amdgcn_s_sleep(16);
-        }
-      thr_sh = w;
-    }
-    __syncthreads();
-    const unsigned long long w = thr_sh;
-    if (is_threshold(w)) {
-      attend_late((uint32_t)(w >> 32), (int32_t)(uint32_t)w - 2, tok0, n_cand,
-                  [&](int k) { return (int)rows[CAP - 1 - k]; },
-                  [&](int k, int t) { return k < kLateRows ? ckey[k] : score_key(s_unit[t]); }, st);
-      if (tid == 0) store_coherent(&udone[wg], 1u);
-    }
-  } else if (tid == 0) {
-    store_coherent(&udone[wg], 1u);  // nothing to pick up
-  }
-
   if (a.flags & 2) {
+    for (int j = tid; j < n_rows; j += kStepThreads) chk_sum += (uint32_t)(tok0 + (int)rows[j]);
     chk_sum = wave_sum_u32(chk_sum);
     if (lane == 0 && chk_sum) atomicAdd(&c->chk_sum, chk_sum);
-    if (tid == 0 && chk_cnt) atomicAdd(&c->chk_cnt, chk_cnt);
-    chk_sum = 0;
-    chk_cnt = 0;
+    if (tid == 0 && n_rows) atomicAdd(&c->chk_cnt, (uint32_t)n_rows);
   }
-  FIER_PROF_WG(5)
   store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, a.po, a.pm, a.pl);
   FIER_PROF_WG(6)
 
   if (!last_arriver(&c->arrive[2], (uint32_t)nc, &flag)) return;
-  // ---- 6. the unit's last workgroup: anything left over, then the merge ---------------------------------------------
+  // ---- the unit's last workgroup: anything left over, then the merge ----------------------------------------------
   int n_used = nc;
   uint32_t T = 0;
   int32_t idxT = -1;
   if (need_threshold) {
-    // Close the threshold word.  Normally it holds the selector's result; if the selector gave up, or is still at
-    // work, the threshold is found here by the radix selection streamed over the unit's scores.  Whoever of the two
-    // finds the other's mark clears the word and the arrival counter (the selector polls that counter).
-    if (tid == 0) thr_sh = __hip_atomic_exchange(&c->thr, kThrClosed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    const unsigned long long wthr = thr_sh;
-    if (wthr != 0ull && tid == 0) {
-      c->thr = 0ull;
-      c->arrive[1] = 0;
-    }
-    if (is_threshold(wthr)) {
-      T = (uint32_t)(wthr >> 32);
-      idxT = (int32_t)(uint32_t)wthr - 2;
-    } else {
-      __syncthreads();
-      stream_select<kStepThreads>([&](int k) { return s_unit[k]; }, n, tbin, R, hscale, (uint32_t)B - above, ss->hist,
-                                  scan_tmp, ss->res, nullptr, T, idxT);
-      __syncthreads();
-    }
+    const unsigned long long wthr = load_coherent(&c->thr);  // published before its writer's second arrival
+    T = (uint32_t)(wthr >> 32);
+    idxT = (int32_t)(uint32_t)wthr - 2;
     bool missing = false;
-    for (int w = tid; w < nc; w += kStepThreads) missing = missing || load_coherent(&udone[w]) == 0u;
+    for (int w = tid; w < nc; w += kStepThreads) {
+      const bool m = load_coherent(&udone[w]) == 0u;
+      ss->seg_size[w] = m ? 1 : 0;
+      missing = missing || m;
+    }
     if (__syncthreads_or(missing)) {
-      // some workgroup did not pick up the threshold: its candidate rows are attended over here, into the spare slot
+      // Some workgroup did not put its threshold-bin rows on its list: they are attended over here, 256 candidates
+      // at a time through the row list (this workgroup's own rows are done), into the spare partial slot.
       st.init();
-      resumed = false;
+      bool resumed = false;
+      uint32_t cnt_x = 0, sum_x = 0;
       for (int w = 0; w < nc; ++w) {
-        if (load_coherent(&udone[w]) != 0u) continue;  // the same value in every thread
+        if (!ss->seg_size[w]) continue;  // the same in every thread
         const int base = w * CAP;
         const int span = n - base < CAP ? n - base : CAP;
-        attend_late(T, idxT, base, span,
-                    [&](int k) { return sel_bin(s_unit[base + k], R, hscale, kSelBins) == tbin ? k : -1; },
-                    [&](int, int t) { return score_key(s_unit[t]); }, st);
+        for (int k0 = 0; k0 < span; k0 += kStepThreads) {
+          const int t = base + k0 + tid;
+          bool sel = false;
+          if (k0 + tid < span) {
+            const float x = s_unit[t];
+            const uint32_t key = score_key(x);
+            sel = sel_bin(x, R, hscale, kSelBins) == tbin && (key > T || (key == T && t <= idxT));
+          }
+          uint32_t n_x;
+          const uint32_t at = block_excl_scan_u32<4>(sel ? 1u : 0u, scan_tmp, n_x);  // its first barrier frees the list
+          if (sel) {
+            rows[at] = (uint16_t)(k0 + tid);
+            sum_x += (uint32_t)t;
+          }
+          __syncthreads();
+          auto row_any = [&](int j) { return kv.row(base + (int)rows[j]); };
+          if constexpr (NREP >= 3)
+            attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_any, 0, (int)n_x, a.scale_log2e, st, sh_o, resumed);
+          else
+            attend_rows<DT, NREP>(a.K, a.V, qr, row_any, 0, (int)n_x, a.scale_log2e, st);
+          resumed = true;
+          cnt_x += n_x;
+        }
       }
       if (a.flags & 2) {
-        chk_sum = wave_sum_u32(chk_sum);
-        if (lane == 0 && chk_sum) atomicAdd(&c->chk_sum, chk_sum);
-        if (tid == 0 && chk_cnt) atomicAdd(&c->chk_cnt, chk_cnt);
+        sum_x = wave_sum_u32(sum_x);
+        if (lane == 0 && sum_x) atomicAdd(&c->chk_sum, sum_x);
+        if (tid == 0 && cnt_x) atomicAdd(&c->chk_cnt, cnt_x);
       }
       store_partials<NREP, true>(st, sh_o, unit, n_slots, nc, a.po, a.pm, a.pl);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the spare slot is read back below by other wavefronts
@@ -585,11 +550,12 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   FIER_PROF_WG(7)
   // counters and flags back to zero for the next call, the unit's histogram too (all its readers have arrived); the
   // selection for the index-list kernel
-  for (int w = tid; w < nc; w += kStepThreads) udone[w] = 0u;
+  if (need_threshold)
+    for (int w = tid; w < nc; w += kStepThreads) udone[w] = 0u;
   for (int k = tid; k < kSelBins; k += kStepThreads) gh[k] = 0;
   if (tid == 0) {
     c->arrive[2] = 0;
-    if (!need_threshold) c->arrive[1] = 0;  // no selector ran
+    c->thr = 0ull;
     c->tbin = tbin;
     c->above = above;
     c->budget = B;
@@ -649,6 +615,9 @@ __global__ __launch_bounds__(1024) void step_emit_idx_kernel(const float* __rest
   }
 }
 
+// Workgroups of the step's second kernel that a 256-CU chip holds at once (the kernel's second launch bound).
+static long step_resident_wgs(int n_rep) { return 256L * (n_rep <= 2 ? 5 : (n_rep <= 4 ? 4 : (n_rep <= 6 ? 3 : 2))); }
+
 int step_ranges_per_wg(int max_budget, int max_ctx) {
   // about a hundred selected rows per workgroup: rows per 1024-token range = 1024 * budget / context
   const double per_range = 1024.0 * (double)max_budget / (double)max_ctx;
@@ -674,10 +643,9 @@ static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffe
   // Order 1 only while every workgroup is resident at once (the second launch bound of the kernel: 5 / 4 / 3 / 2
   // workgroups per CU, 256 CUs): its workgroups poll for their unit's threshold, and a unit spread over two rounds
   // of workgroups would have the first round waiting for the second.
-  const long resident = 256L * (n_rep <= 2 ? 5 : (n_rep <= 4 ? 4 : (n_rep <= 6 ? 3 : 2)));
-  const int gw = n_wgs + 1;  // a unit's selector and its range workgroups
-  const int order = (long)units * gw <= resident ? 1 : (units % 8 == 0 ? 2 : 0);
-  dim3 grid = order == 2 ? dim3((unsigned)units * (unsigned)gw) : (order ? dim3(units, gw) : dim3(gw, units));
+  const long resident = step_resident_wgs(n_rep);
+  const int order = (long)units * n_wgs <= resident ? 1 : (units % 8 == 0 ? 2 : 0);
+  dim3 grid = order == 2 ? dim3((unsigned)units * (unsigned)n_wgs) : (order ? dim3(units, n_wgs) : dim3(n_wgs, units));
   StepArgs a;
   a.scores = sb.scores;
   a.ctl = sb.ctl;
@@ -747,6 +715,13 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
   if (rpw == 4) FIER_STEP_RPW(DT_BF16, 4);
   FIER_STEP_RPW(DT_BF16, 8);
 #undef FIER_STEP_RPW
+}
+
+// Whether the one-launch form (step_attend_kernel) suits this shape: all its workgroups resident at once.
+bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx) {
+  const int rpw = step_ranges_per_wg(max_budget, max_ctx);
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  return (long)units * ((n_ranges + rpw - 1) / rpw) <= step_resident_wgs(n_rep);
 }
 
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,

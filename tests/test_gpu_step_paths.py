@@ -6,8 +6,6 @@ and a direct check of WHICH rows it attended over.
   among thousands inside its 2e-3 tolerance, the checksums can.
 * With test flag 1 no workgroup picks up the published threshold: all threshold-bin rows are then attended over by the
   merging workgroup's fallback.  Same selection, same checksums, output equal to the ordinary path up to summation order.
-* With test flag 4 the unit's selector gives up at once, as it would after waiting in vain for the range workgroups: the
-  merging workgroup then finds the threshold itself (radix selection over the scores) and attends over the rows.
 * R = 0 (a zero query, or an all-zero key cache): every score is zero, the budget goes to the lowest indices.
 * The hand-off between workgroups (candidates, threshold word, partials) repeated over a few hundred launches with many
   small workgroups per unit: every launch must reproduce the first one bit for bit.
@@ -23,7 +21,7 @@ from paper_2508_08256_amd import synth  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 F16, BF16 = 0, 1
-FORCE_LATE, CHECKSUMS, SELECTOR_GIVES_UP = 1, 2, 4
+FORCE_LATE, CHECKSUMS = 1, 2
 
 
 @pytest.fixture(scope="module")
@@ -100,15 +98,10 @@ def test_attended_rows_are_the_reported_selection(gu, oracle, name, make):
     _check_sums(idx2, cnt2, sums2)
     assert np.abs(out2 - want).max() <= 2e-3
     assert np.abs(out2 - out).max() <= 1e-5 * max(1.0, float(np.abs(out).max()))
-    # the selector gives up: the merging workgroup selects and attends
-    out3, idx3, cnt3, sums3 = _step(gu, wl, CHECKSUMS | SELECTOR_GIVES_UP)
-    assert np.array_equal(idx3, idx) and np.array_equal(cnt3, cnt)
-    _check_sums(idx3, cnt3, sums3)
-    assert np.abs(out3 - want).max() <= 2e-3
 
 
 @pytest.mark.parametrize("kind", ["zero_query", "zero_keys", "zero_keys_then_append"])
-@pytest.mark.parametrize("flags", [CHECKSUMS, CHECKSUMS | FORCE_LATE, CHECKSUMS | SELECTOR_GIVES_UP])
+@pytest.mark.parametrize("flags", [CHECKSUMS, CHECKSUMS | FORCE_LATE])
 def test_zero_score_range(gu, oracle, kind, flags):
     """R = sum_c |q_c| absmax_c = 0: the histogram has no width, every score is exactly zero and the ties go to the
     lowest token indices (a unit with a live query sits next to the degenerate one)."""
