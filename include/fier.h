@@ -238,9 +238,10 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
  * Same arguments as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and
  * these layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
  * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with one
- * phase 2 before the next real step), phase 2 only after a phase 1.  Phases 2 + 16 f, f = 1..3, run the two-kernel
- * form's second kernel with test flags (1: no workgroup picks up the threshold itself, the merging workgroup attends
- * over all threshold-bin rows; 2: checksums of the attended rows in the control blocks).
+ * phase 2 before the next real step), phase 2 only after a phase 1.  Phases 2 + 16 f and 3 + 16 f, f = 1..3, are for
+ * tests: the two-kernel form whatever the shape, its second kernel with flags f (1: no workgroup picks up the
+ * threshold itself, the merging workgroup attends over all threshold-bin rows; 2: checksums of the attended rows in
+ * the control blocks).
  */
 int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget);
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,

@@ -308,7 +308,8 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
   // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel; 2 + 16 f: kernel 2 with test flags f
-  if (max_budget > cfg->max_ctx || phase < -1 || phase > 2 + 16 * 3) return FIER_EINVAL;
+  if (max_budget > cfg->max_ctx || phase < -1 || phase > 3 + 16 * 3 || (phase > 3 && (phase & 15) != 2 && (phase & 15) != 3))
+    return FIER_EINVAL;
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
@@ -369,7 +370,7 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
                                      cfg->max_ctx, phase >> 4, s);
         if (e != hipSuccess) return FIER_EHIP;
       }
-      if ((phase == 0 || phase == 3) && idxl) {
+      if ((phase == 0 || (phase & 15) == 3) && idxl) {
         e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, cfg->n_kv_heads, cfg->max_ctx, s);
         if (e != hipSuccess) return FIER_EHIP;
       }

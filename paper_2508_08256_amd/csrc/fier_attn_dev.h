@@ -8,7 +8,7 @@
 
 namespace fier {
 
-constexpr int kAttnUnroll = 4;                  // rows per 16-lane row per iteration
+constexpr int kAttnUnroll = 2;                  // rows per 16-lane row per iteration
 constexpr int kRowsPerIter = 4 * 4 * kAttnUnroll;  // 4 waves x 4 lane rows x unroll
 
 // Running softmax state of one 16-lane row of a wavefront, per query head: lane cn holds channels 8cn..8cn+7.

@@ -134,7 +134,7 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 // The ascending index list of the selection that kernel made (an optional output of the step).
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
                                 int units, int n_kv_heads, int max_ctx, hipStream_t st);
-int step_ranges_per_wg(int max_budget, int max_ctx);
+int step_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx);
 bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx);
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,

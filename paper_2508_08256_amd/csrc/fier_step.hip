@@ -11,16 +11,17 @@
 //   3. counts its arrival.  The unit's LAST arriver ("selector") reads all candidates of the unit, histograms them
 //      once more inside the threshold bin (1024 sub-bins), ranks the members of the decisive sub-bin pairwise
 //      (larger key first, equal keys by lower index) and publishes the exact threshold (T, idxT) as one 64-bit word;
-//   4. the other workgroups poll that word -- the memory system is idle at this point, the selection takes about as
-//      long as three round trips -- and append those of their candidates with `key > T or (key == T and index <=
-//      idxT)` to their row lists;
-//   5. every workgroup attends over its rows, stores its partial (m, l, o) per query head and counts a second arrival;
-//      the unit's last arriver there merges the partials.
-// The poll of step 4 is bounded.  A workgroup that gives up attends over its sure rows only and leaves a flag
-// unset; the merging workgroup then attends over that workgroup's threshold-bin rows itself before it merges.  The
-// result therefore never depends on a poll succeeding, every wait is bounded and every wavefront exits.  The poll
-// only ever lasts long when the unit's workgroups are not running together, which is why the launcher uses this
-// kernel for resident grids and the three-kernel form (threshold kernel, then selection + attention) otherwise.
+//   4. meanwhile every other workgroup attends over its sure rows (the selector after it has published): the bulk of
+//      the gather runs while the serial selection is under way;
+//   5. then picks up the threshold word (it is usually there by then; if not, the workgroup polls for a bounded
+//      time), appends those of its candidates with `key > T or (key == T and index <= idxT)` to its row list and
+//      attends over them too; stores its partial (m, l, o) per query head and counts a second arrival;
+//   6. the unit's last arriver there merges the partials.
+// A workgroup whose poll runs out leaves a flag unset; the merging workgroup then attends over that workgroup's
+// threshold-bin rows itself before it merges.  The result therefore never depends on a poll succeeding, every wait
+// is bounded and every wavefront exits.  A poll only ever lasts long when the unit's workgroups are not running
+// together, which is why the launcher uses this kernel for resident grids and the three-kernel form (threshold
+// kernel, then selection + attention) otherwise.
 // All selection decisions are integer comparisons of order-preserving keys: exact and deterministic.
 //
 // The ascending index list of the selection (idx_out of the step, an optional output) is written by a small
@@ -388,15 +389,34 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   const int n_cand = (int)(listed >> 16);
   uint32_t chk_sum = 0;  // (tests) sum of the token indices this thread put on the list
 
-  // ---- 3. / 4. the exact threshold: found by the unit's last arriver, picked up by the others ----------------------
+  // ---- 3. the exact threshold, found by the unit's last arriver ------------------------------------------------------
+  uint4 qr[NREP];
+#pragma unroll
+  for (int h = 0; h < NREP; ++h) qr[h] = a.q[((size_t)unit * NREP + h) * (kD / 8) + cn];
+  const uint4* q_unit = a.q + (size_t)unit * NREP * (kD / 8);
+  AttnState<NREP> st;
+  st.init();
+  const int first_block = tok0 >> kv.shift;
+  auto row_own = [&](int j) {
+    const int t = tok0 + (int)rows[j];
+    return kv.blocks ? (size_t)lblk[(t >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(t & kv.mask)
+                     : kv.base + (size_t)t;
+  };
+  auto attend_own = [&](int from, int to, bool resume) {
+    if constexpr (NREP >= 3)
+      attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_own, from, to, a.scale_log2e, st, sh_o, resume);
+    else
+      attend_rows<DT, NREP>(a.K, a.V, qr, row_own, from, to, a.scale_log2e, st);
+  };
   bool picked = true;  // the workgroup's threshold-bin rows are on its list (or it has none)
+  uint32_t T = 0;
+  int32_t idxT = -1;
+  bool have = false;
   if (need_threshold) {
     if (tid == 0) store_coherent(&useg[wg], (uint32_t)n_cand);
-    uint32_t T = 0;
-    int32_t idxT = -1;
-    bool have = false;
     if (last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) {
       FIER_PROF(13, unit == 0)
+      __builtin_amdgcn_s_setprio(3);
       if (!select_among_candidates(ucand, useg, nc, (uint32_t)SEGCAP, (uint32_t)B - above, tbin, R, hscale, ss, scan_tmp,
                                    T, idxT)) {
         // candidates that do not fit (scores clustered far more tightly than the a-priori range resolves): radix
@@ -409,10 +429,23 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
         store_coherent(&c->thr, pack_threshold(T, idxT));
         c->arrive[1] = 0;
       }
+      __builtin_amdgcn_s_setprio(0);
       have = true;
+      __syncthreads();  // the scratch is reused below
       FIER_PROF(15, unit == 0)
-    } else if (n_cand > 0 && n_cand <= SEGCAP) {
-      // the memory system is idle now and the selection short: poll
+    }
+  } else {
+    __syncthreads();  // the row list is complete
+  }
+  FIER_PROF_WG(3)
+  // ---- 4. attention over the sure rows, while the unit's threshold is being found ----------------------------------
+  attend_own(0, n_rows, false);
+  const int n_sure = n_rows;
+  FIER_PROF_WG(4)
+  // ---- 5. the threshold is picked up; the selected candidates join the row list -----------------------------------
+  if (need_threshold) {
+    if (!have && n_cand > 0 && n_cand <= SEGCAP) {
+      __syncthreads();
       if (tid == 0) {
         unsigned long long w = 0;
         for (int spin = 0; spin < kPollMax; ++spin) {
@@ -430,7 +463,8 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
     }
     picked = n_cand == 0;
     if (have && n_cand > 0 && n_cand <= SEGCAP && !(a.flags & 1)) {
-      // the selected candidates join the row list, in candidate (= token) order
+      __syncthreads();  // every wavefront is done with the rows listed so far
+      // in candidate (= token) order
       for (int k0 = 0; k0 < n_cand; k0 += kStepThreads) {
         const int k = k0 + tid;
         bool sel = false;
@@ -454,29 +488,11 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
       }
       picked = true;
     }
+    __syncthreads();  // the row list is complete
+    if (tid == 0 && picked) store_coherent(&udone[wg], 1u);
   }
-  __syncthreads();  // the row list is complete
-  if (tid == 0 && need_threshold && picked) store_coherent(&udone[wg], 1u);
-  FIER_PROF_WG(3)
-
-  // ---- 5. attention over the rows -------------------------------------------------------------------------------------
-  uint4 qr[NREP];
-#pragma unroll
-  for (int h = 0; h < NREP; ++h) qr[h] = a.q[((size_t)unit * NREP + h) * (kD / 8) + cn];
-  const uint4* q_unit = a.q + (size_t)unit * NREP * (kD / 8);
-  AttnState<NREP> st;
-  st.init();
-  const int first_block = tok0 >> kv.shift;
-  auto row_own = [&](int j) {
-    const int t = tok0 + (int)rows[j];
-    return kv.blocks ? (size_t)lblk[(t >> kv.shift) - first_block] * kv.block_stride + kv.base + (size_t)(t & kv.mask)
-                     : kv.base + (size_t)t;
-  };
-  if constexpr (NREP >= 3)
-    attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_own, 0, n_rows, a.scale_log2e, st, sh_o);
-  else
-    attend_rows<DT, NREP>(a.K, a.V, qr, row_own, 0, n_rows, a.scale_log2e, st);
-  FIER_PROF_WG(4)
+  attend_own(n_sure, n_rows, true);
+  FIER_PROF_WG(5)
   if (a.flags & 2) {
     for (int j = tid; j < n_rows; j += kStepThreads) chk_sum += (uint32_t)(tok0 + (int)rows[j]);
     chk_sum = wave_sum_u32(chk_sum);
@@ -489,8 +505,6 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   if (!last_arriver(&c->arrive[2], (uint32_t)nc, &flag)) return;
   // ---- the unit's last workgroup: anything left over, then the merge ----------------------------------------------
   int n_used = nc;
-  uint32_t T = 0;
-  int32_t idxT = -1;
   if (need_threshold) {
     const unsigned long long wthr = load_coherent(&c->thr);  // published before its writer's second arrival
     T = (uint32_t)(wthr >> 32);
@@ -618,11 +632,14 @@ __global__ __launch_bounds__(1024) void step_emit_idx_kernel(const float* __rest
 // Workgroups of the step's second kernel that a 256-CU chip holds at once (the kernel's second launch bound).
 static long step_resident_wgs(int n_rep) { return 256L * (n_rep <= 2 ? 5 : (n_rep <= 4 ? 4 : (n_rep <= 6 ? 3 : 2))); }
 
-int step_ranges_per_wg(int max_budget, int max_ctx) {
-  // about a hundred selected rows per workgroup: rows per 1024-token range = 1024 * budget / context
+// Ranges per workgroup of the one-launch form: about a hundred selected rows per workgroup (rows per 1024-token range
+// = 1024 * budget / context), and more than that where fewer, larger workgroups make the grid resident at once.
+int step_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx) {
   const double per_range = 1024.0 * (double)max_budget / (double)max_ctx;
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   int rpw = 1;
   while (rpw < 8 && per_range * rpw < 96.0) rpw *= 2;
+  while (rpw < 8 && (long)units * ((n_ranges + rpw - 1) / rpw) > step_resident_wgs(n_rep)) rpw *= 2;
   return rpw;
 }
 
@@ -703,7 +720,7 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 #define FIER_STEP_RPW(DT, RPW)                                                                                        \
   return launch_step_attend_dt<DT, RPW>(lay, n_rep, sb, K, V, q, seq_lens, extra, budgets, max_budget, sm_scale,      \
                                         count_out, out, kabsmax, units, n_kv_heads, max_ctx, flags, st)
-  const int rpw = step_ranges_per_wg(max_budget, max_ctx);
+  const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   if (dtype == DT_F16) {
     if (rpw == 1) FIER_STEP_RPW(DT_F16, 1);
     if (rpw == 2) FIER_STEP_RPW(DT_F16, 2);
@@ -718,8 +735,12 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 }
 
 // Whether the one-launch form (step_attend_kernel) suits this shape: all its workgroups resident at once.
+int g_force_form = 0;  // TEMPORARY experiment hook
+extern "C" void fier_debug_force_form(int f) { g_force_form = f; }
 bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx) {
-  const int rpw = step_ranges_per_wg(max_budget, max_ctx);
+  if (g_force_form == 3) return false;
+  if (n_rep > 2) return false;  // measured: with 3+ query heads per kv head the three-kernel form is the faster one
+  const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   return (long)units * ((n_ranges + rpw - 1) / rpw) <= step_resident_wgs(n_rep);
 }

@@ -56,7 +56,7 @@ def _step(gu, wl, flags, append=True):
     ws = dw.workspace(mb)
     args = (dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt, ws)
     _clear_checksums(ws, wl.units)
-    for p in (1, 2 + 16 * flags, 3):
+    for p in (1, 2 + 16 * flags, 3 + 16 * flags):     # + 16 f: the two-kernel form whatever the shape
         B.decode_step_phase(*args, p)
     torch.cuda.synchronize()
     return out.cpu().numpy()[0], idx.cpu().numpy()[0], cnt.cpu().numpy()[0], _ctl_checksums(ws, wl.units)
