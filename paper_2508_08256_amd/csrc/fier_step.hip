@@ -414,7 +414,31 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   bool have = false;
   if (need_threshold) {
     if (tid == 0) store_coherent(&useg[wg], (uint32_t)n_cand);
-    if (last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) {
+    // The selector attends over its own rows only after it has published the threshold, so it should be a workgroup
+    // with few rows: the unit's last workgroup (a partial range as a rule) holds its arrival back until the nc - 1
+    // others have arrived and then selects without counting itself.  It waits for a bounded time; if that runs out it
+    // arrives like the others and whoever then arrives last selects.
+    bool selects = false;
+    if (wg == nc - 1 && nc > 1) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this workgroup's candidates have been acknowledged
+      if (tid == 0) {
+        uint32_t arrived = 0;
+        for (int spin = 0; spin < kPollMax; ++spin) {
+          arrived = load_coherent(&c->arrive[1]);
+          if (arrived >= (uint32_t)(nc - 1)) break;
+          __builtin_amdgcn_s_sleep(2);
+        }
+        flag = arrived >= (uint32_t)(nc - 1) ? 1u : 0u;
+      }
+      __syncthreads();
+      selects = flag != 0u;
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      asm volatile("" ::: "memory");
+      if (!selects) selects = last_arriver(&c->arrive[1], (uint32_t)nc, &flag);
+    } else {
+      selects = last_arriver(&c->arrive[1], (uint32_t)nc, &flag);
+    }
+    if (selects) {
       FIER_PROF(13, unit == 0)
       __builtin_amdgcn_s_setprio(3);
       if (!select_among_candidates(ucand, useg, nc, (uint32_t)SEGCAP, (uint32_t)B - above, tbin, R, hscale, ss, scan_tmp,
@@ -604,10 +628,13 @@ __global__ __launch_bounds__(1024) void step_emit_idx_kernel(const float* __rest
   const float* __restrict__ s = scores + (size_t)unit * max_ctx;
   int32_t* __restrict__ out = idx + (size_t)unit * max_budget;
   uint32_t run = 0;
+  // the next stretch's scores are on their way while this one is scanned and written
+  float4 v_next = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (4 * tid < n) v_next = *reinterpret_cast<const float4*>(s + 4 * tid);
   for (int i0 = 0; i0 < n; i0 += 4096) {
     const int i = i0 + 4 * tid;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n) v = *reinterpret_cast<const float4*>(s + i);
+    const float4 v = v_next;
+    if (i + 4096 < n) v_next = *reinterpret_cast<const float4*>(s + i + 4096);
     const float vv[4] = {v.x, v.y, v.z, v.w};
     uint32_t selm = 0;
 #pragma unroll
@@ -735,11 +762,10 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 }
 
 // Whether the one-launch form (step_attend_kernel) suits this shape: all its workgroups resident at once.
-int g_force_form = 0;  // TEMPORARY experiment hook
-extern "C" void fier_debug_force_form(int f) { g_force_form = f; }
 bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx) {
-  if (g_force_form == 3) return false;
-  if (n_rep > 2) return false;  // measured: with 3+ query heads per kv head the three-kernel form is the faster one
+  // measured: with 3+ query heads per kv head the three-kernel form is the faster one (8 units of 131072 tokens,
+  // 4 heads per kv head: 24 us against 31 us after the score kernel)
+  if (n_rep > 2) return false;
   const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   return (long)units * ((n_ranges + rpw - 1) / rpw) <= step_resident_wgs(n_rep);
