@@ -549,9 +549,11 @@ def decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, bud
     cnt = torch.zeros((NLt, cfg.units), dtype=torch.int32, device="cuda")
     lens0 = seq_lens.clone()
 
-    def tokens(n):
+    def tokens(n, with_list=False):
+        # the attention output is the step's result; the ascending index list is an optional output
         for _ in range(n):
-            B.decode_step(cfg, layers, q, kn, vn, budgets, budget, out, idx, cnt, ws)
+            B.decode_step(cfg, layers, q, kn, vn, budgets, budget, out, idx if with_list else None,
+                          cnt if with_list else None, ws)
             seq_lens.add_(1)
 
     def timed_tokens(fn):
@@ -566,6 +568,7 @@ def decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, bud
 
     tokens(4)                                   # warm-up
     us_eager = timed_tokens(lambda: tokens(N))
+    us_eager_list = timed_tokens(lambda: tokens(N, True))
     us_graph = None
     try:
         seq_lens.copy_(lens0)
@@ -599,6 +602,7 @@ def decode_loop(args, w, cfg, caches, qs, kns, vns, seq_lens, budgets, lens, bud
         "achieved_GBps": round(ab["total"] / (us_layer * 1e-6) / 1e9, 1),
         "hbm_frac": round(ab["total"] / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
         "us_per_token_eager": round(us_eager, 3),
+        "us_per_layer_with_index_list": round(us_eager_list / NLt, 3),
         "us_per_token_graph": None if us_graph is None else round(us_graph, 3),
         "us_per_layer_graph": None if us_graph is None else round(us_graph / NLt, 3),
         "setup_s": round(t_setup, 1),

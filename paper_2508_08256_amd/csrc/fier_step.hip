@@ -8,9 +8,11 @@
 //   2. classifies its own scores: tokens in bins above tbin are selected for certain ("sure" rows, listed in LDS),
 //      tokens inside tbin are the candidates for the threshold (about 1 % of the tokens), kept in LDS and published
 //      as (key, index) pairs in the unit's candidate slots in memory;
-//   3. counts its arrival.  The unit's LAST arriver ("selector") reads all candidates of the unit, histograms them
-//      once more inside the threshold bin (1024 sub-bins), ranks the members of the decisive sub-bin pairwise
-//      (larger key first, equal keys by lower index) and publishes the exact threshold (T, idxT) as one 64-bit word;
+//   3. counts its arrival.  One workgroup of the unit (the "selector": the unit's last workgroup, which as a rule
+//      owns a partial range and few rows, once the others have arrived; whoever arrives last if that does not
+//      happen within a bounded time) reads all candidates of the unit, histograms them once more inside the
+//      threshold bin (1024 sub-bins), ranks the members of the decisive sub-bin pairwise (larger key first, equal
+//      keys by lower index) and publishes the exact threshold (T, idxT) as one 64-bit word;
 //   4. meanwhile every other workgroup attends over its sure rows (the selector after it has published): the bulk of
 //      the gather runs while the serial selection is under way;
 //   5. then picks up the threshold word (it is usually there by then; if not, the workgroup polls for a bounded
