@@ -71,7 +71,8 @@ struct UnitCtl {        // one per unit at the head of the workspace
   float scale;          // kSelBins / (2 R)
   uint32_t T;           // threshold key inside tbin
   int32_t idxT;         // among keys == T inside tbin, indices <= idxT are selected
-  uint32_t pad;
+  uint32_t starved;     // one-launch step: a workgroup went on without the unit's scores (the output is then NaN);
+                        // zero between calls
   unsigned long long thr;  // the step's threshold as one word, T << 32 | idxT + 2, published by the unit's selector
                            // to its other workgroups; zero between calls
   uint32_t chk_cnt;     // checksums of the rows the step attended over (count, sum of token indices); only
@@ -134,6 +135,14 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 // The ascending index list of the selection that kernel made (an optional output of the step).
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
                                 int units, int n_kv_heads, int max_ctx, hipStream_t st);
+// The whole step in one launch (scoring workgroups, then selecting / attending ones that wait for their unit's scores).
+hipError_t launch_step_fused(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const uint32_t* kbits,
+                             const uint32_t* kmeta, float* kabsmax, void* K, void* V, const void* q,
+                             const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
+                             const void* k_new, const void* v_new, float sm_scale, int32_t* count_out, float* out,
+                             int units, int n_kv_heads, int max_ctx, int group_size, int flags, hipStream_t st);
+bool step_fused_fits(int units, int n_rep, int max_ctx);                     // the shape can run as one launch
+bool step_fused_pays(int units, int n_rep, int max_budget, int max_ctx);  // ... and that is the faster form
 int step_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx);
 bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx);
 

@@ -158,15 +158,21 @@ __device__ __forceinline__ void append_load_rows(const uint32_t* __restrict__ K,
 }
 
 // rows, t0, ntok: from append_load_rows (which may run well before: the loads are the long part of the chain)
-template <int DT>
+// COHERENT: the K/V rows are written through to memory (another workgroup of the same launch may gather them).
+template <int DT, bool COHERENT = false>
 __device__ __forceinline__ void append_finish(uint32_t* __restrict__ K, uint32_t* __restrict__ V, const KvRows kv,
                                               uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta, int unit,
                                               int L, int max_ctx, uint32_t kn, uint32_t vn, int lane,
                                               const uint32_t (&rows)[kG], int t0, int ntok, GroupCode& gc,
                                               uint4& mine) {
   const int n_groups = max_ctx / kG;
-  K[kv.row(L) * (kD / 2) + lane] = kn;
-  V[kv.row(L) * (kD / 2) + lane] = vn;
+  if constexpr (COHERENT) {
+    store_coherent(&K[kv.row(L) * (kD / 2) + lane], kn);
+    store_coherent(&V[kv.row(L) * (kD / 2) + lane], vn);
+  } else {
+    K[kv.row(L) * (kD / 2) + lane] = kn;
+    V[kv.row(L) * (kD / 2) + lane] = vn;
+  }
   const int Gi = L / kG;
   mine = make_uint4(0, 0, 0, 0);
   quantize_group<DT>(rows, ntok, lane, 0, mine, gc);
@@ -195,7 +201,7 @@ __device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* _
 // time.  Every pair block of the group that holds a token gets its code words rewritten; on_block(pb, mine, gs)
 // is called once per such block with the calling lane's code word of token t0 + 64 pb + lane (zero if absent) and the
 // group's scale.
-template <int DT, class OnBlock>
+template <int DT, bool COHERENT = false, class OnBlock>
 __device__ __forceinline__ GroupScale append_row_long(uint32_t* __restrict__ K, uint32_t* __restrict__ V,
                                                       const KvRows kv, uint32_t* __restrict__ kbits,
                                                       uint32_t* __restrict__ kmeta,
@@ -203,8 +209,13 @@ __device__ __forceinline__ GroupScale append_row_long(uint32_t* __restrict__ K, 
                                                       int lane, int& t0, int& ntok, OnBlock on_block) {
   const int g = kG * ns;
   const int n_groups = max_ctx / g;
-  K[kv.row(L) * (kD / 2) + lane] = kn;
-  V[kv.row(L) * (kD / 2) + lane] = vn;
+  if constexpr (COHERENT) {
+    store_coherent(&K[kv.row(L) * (kD / 2) + lane], kn);
+    store_coherent(&V[kv.row(L) * (kD / 2) + lane], vn);
+  } else {
+    K[kv.row(L) * (kD / 2) + lane] = kn;
+    V[kv.row(L) * (kD / 2) + lane] = vn;
+  }
   const int Gi = L / g;
   t0 = Gi * g;
   ntok = L - t0 + 1;
