@@ -118,7 +118,6 @@ Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
   w.sb.seg_pitch = (int)seg_pitch;
   w.sb.ctl = reinterpret_cast<fier::UnitCtl*>(take(units * sizeof(fier::UnitCtl)));
   w.sb.hist = reinterpret_cast<uint32_t*>(take(units * fier::kSelBins * sizeof(uint32_t)));
-  w.sb.done = reinterpret_cast<uint32_t*>(take(units * seg_pitch * sizeof(uint32_t)));
   w.zero_bytes = off;
   w.sb.range_cnt = reinterpret_cast<uint32_t*>(take(units * ranges * sizeof(uint32_t)));
   w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * cand_pitch * sizeof(unsigned long long)));

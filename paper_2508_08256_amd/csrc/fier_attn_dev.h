@@ -271,10 +271,12 @@ __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); 
 // into slot `slot` of the unit's partial arrays.  The four lane rows of a wavefront are folded with cross-lane
 // moves first, so that only one state per wavefront and head goes through LDS and all heads share one barrier.
 // sh: NREP * kPartialFloats floats.  Contains barriers: every thread of the workgroup calls it.
+// mark: the slot's l goes out as -(l + 1) (l >= 0, so the sign is free): a workgroup of the step records that way that
+// its partial lacks its threshold-bin rows (merge_heads takes such a slot with its true l).
 template <int NREP, bool COHERENT>
 __device__ __forceinline__ void store_partials(const AttnState<NREP>& st, float* sh, int unit, int n_slots, int slot,
                                                float* __restrict__ po, float* __restrict__ pm,
-                                               float* __restrict__ pl) {
+                                               float* __restrict__ pl, bool mark = false) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int rs = lane >> 4, cn = lane & 15;
@@ -323,13 +325,13 @@ __device__ __forceinline__ void store_partials(const AttnState<NREP>& st, float*
       store_coherent(&po[ps * kD + ch], acc);
       if (ch == 0) {
         store_coherent(&pm[ps], M);
-        store_coherent(&pl[ps], lsum);
+        store_coherent(&pl[ps], mark ? -(lsum + 1.f) : lsum);
       }
     } else {
       po[ps * kD + ch] = acc;
       if (ch == 0) {
         pm[ps] = M;
-        pl[ps] = lsum;
+        pl[ps] = mark ? -(lsum + 1.f) : lsum;
       }
     }
   }
@@ -356,6 +358,7 @@ __device__ __forceinline__ float wave_allmax_f(float x) {
 // ... of one head with a running maximum, 32 or 40 slots per batch: their (m, l) sit one per lane and reach the other
 // lanes as scalars, the independent 8-byte loads of o are in flight together, so that the round trips
 // to memory overlap; with fewer than four heads several groups share a head and meet in LDS.
+// A slot stored with a mark (l < 0, see store_partials) counts with its true l.
 // sh: 4 * 130 floats.  Has barriers.
 template <int NREP>
 __device__ __forceinline__ void merge_heads(const float* __restrict__ po, const float* __restrict__ pm,
@@ -377,13 +380,14 @@ __device__ __forceinline__ void merge_heads(const float* __restrict__ po, const 
       const int sj = s0 + GPH * lane;
       const bool okj = lane < BATCH && sj < n_used;
       const float mj = okj ? load_coherent(&pm[base + sj]) : -INFINITY;
-      const float lj = okj ? load_coherent(&pl[base + sj]) : 0.f;
+      float lj = okj ? load_coherent(&pl[base + sj]) : 0.f;
       unsigned long long os[BATCH];
 #pragma unroll
       for (int k = 0; k < BATCH; ++k) {
         const int s = s0 + GPH * k;
         os[k] = load_coherent(reinterpret_cast<const unsigned long long*>(&po[(base + (s < n_used ? s : s0)) * kD + k2]));
       }
+      lj = lj < 0.f ? -lj - 1.f : lj;
       const float mx = fmaxf(M, wave_allmax_f(mj));
       const float mref = mx == -INFINITY ? 0.f : mx;
       const float alpha = __builtin_amdgcn_exp2f(M - mref);

@@ -179,20 +179,25 @@ __device__ __forceinline__ unsigned long long load_coherent(const unsigned long 
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// "Last arriver": returns true in every thread of exactly one workgroup per counter: the one whose increment
-// brings it to `expected`.  Everything the other workgroups published with store_coherent / atomics before
-// arriving can then be read with load_coherent.  Nobody waits for anybody.  flag: one word of LDS.
-__device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expected, uint32_t* flag) {
+// Arrival at a unit's counter: adds `inc` and returns, in every thread, the value the counter held before.
+// Everything the workgroups that arrived earlier published with store_coherent / atomics before arriving can then be
+// read with load_coherent.  Nobody waits for anybody.  flag: one word of LDS.
+__device__ __forceinline__ uint32_t arrive_add(uint32_t* counter, uint32_t inc, uint32_t* flag) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's stores and atomics have been acknowledged
   __syncthreads();                                  // ... and so have those of the other waves
-  if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(counter, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
-  const bool last = *flag == expected - 1;
+  const uint32_t before = *flag;
   // reader side: nothing the last arriver loads afterwards may be moved above the counter's return by the compiler
   // (the hardware issues a wave's memory operations in program order, and load_coherent never hits a stale line)
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   asm volatile("" ::: "memory");
-  return last;
+  return before;
+}
+// "Last arriver": true in every thread of exactly one workgroup per counter, the one whose increment brings it to
+// `expected`.
+__device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expected, uint32_t* flag) {
+  return arrive_add(counter, 1u, flag) == expected - 1;
 }
 
 }  // namespace fier

@@ -83,7 +83,6 @@ static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte line");
 struct StepBuffers {    // carved from the caller's workspace
   UnitCtl* ctl;         // [units]
   uint32_t* hist;       // [units][kSelBins]: filled by the score kernel, read and cleared by the step's second kernel
-  uint32_t* done;       // [units][seg_pitch]: workgroup has attended over its threshold-bin rows; zero between calls
   uint32_t* range_cnt;  // [units][n_ranges] (fier_topk_ws): selected tokens per 1024-token range, then their scan
   unsigned long long* cand;  // [units][cand_pitch] candidates (key << 32 | token index)
   uint32_t* seg_cnt;    // [units][seg_pitch] candidates published by each workgroup
@@ -93,7 +92,7 @@ struct StepBuffers {    // carved from the caller's workspace
   float* pm;
   float* pl;
   size_t cand_pitch;    // candidate slots per unit
-  int seg_pitch;        // workgroup entries per unit in seg_cnt and done
+  int seg_pitch;        // workgroup entries per unit in seg_cnt
 };
 
 hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,

@@ -19,11 +19,11 @@
 //      time), appends those of its candidates with `key > T or (key == T and index <= idxT)` to its row list and
 //      attends over them too; stores its partial (m, l, o) per query head and counts a second arrival;
 //   6. the unit's last arriver there merges the partials.
-// A workgroup whose poll runs out leaves a flag unset; the merging workgroup then attends over that workgroup's
-// threshold-bin rows itself before it merges.  The result therefore never depends on a poll succeeding, every wait
-// is bounded and every wavefront exits.  A poll only ever lasts long when the unit's workgroups are not running
-// together, which is why the launcher uses this kernel for resident grids and the three-kernel form (threshold
-// kernel, then selection + attention) otherwise.
+// A workgroup whose poll runs out says so in its partial (the sign of its l); the merging workgroup then attends over
+// that workgroup's threshold-bin rows itself and merges again.  The result therefore never depends on a poll
+// succeeding, every wait is bounded and every wavefront exits.  A poll only ever lasts long when the unit's
+// workgroups are not running together, which is why the launcher uses this kernel for resident grids and the
+// three-kernel form (threshold kernel, then selection + attention) otherwise.
 // All selection decisions are integer comparisons of order-preserving keys: exact and deterministic.
 //
 // The ascending index list of the selection (idx_out of the step, an optional output) is written by a small
@@ -226,7 +226,6 @@ struct StepArgs {
   int max_budget;
   unsigned long long* cand;  // [units][cand_pitch]: slot k * nc + w = k-th candidate of workgroup w of the unit
   uint32_t* seg_cnt;         // [units][wgs_per_unit]
-  uint32_t* done;            // [units][wgs_per_unit]: 1 once the workgroup has its threshold-bin rows in its list
   const uint4* K;
   const uint4* V;
   const uint4* q;
@@ -350,7 +349,6 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
   const float* __restrict__ s_unit = a.scores + (size_t)unit * max_ctx;
   unsigned long long* __restrict__ ucand = a.cand + (size_t)unit * a.cand_pitch;
   uint32_t* __restrict__ useg = a.seg_cnt + (size_t)unit * a.wgs_per_unit;
-  uint32_t* __restrict__ udone = a.done + (size_t)unit * a.wgs_per_unit;
 
   // ---- 1. the workgroup's scores; meanwhile the threshold bin from the histogram ---------------------------------
   float4 v[RPW];
@@ -564,7 +562,6 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
       picked = true;
     }
     __syncthreads();  // the row list is complete
-    if (tid == 0 && picked) store_coherent(&udone[wg], 1u);
   }
   attend_own(n_sure, n_rows, true);
   FIER_PROF_WG(5)
@@ -574,25 +571,28 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     if (lane == 0 && chk_sum) atomicAdd(&c->chk_sum, chk_sum);
     if (tid == 0 && n_rows) atomicAdd(&c->chk_cnt, (uint32_t)n_rows);
   }
-  store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, a.po, a.pm, a.pl);
+  // a partial that lacks the workgroup's threshold-bin rows is marked as such (the sign of its l), and the workgroup
+  // counts itself in the upper half of the arrival counter: the merging workgroup learns from the counter's value,
+  // without loading anything, whether there are such rows
+  store_partials<NREP, true>(st, sh_o, unit, n_slots, wg, a.po, a.pm, a.pl, !picked);
   FIER_PROF_WG(6)
 
-  if (!last_arriver(&c->arrive[2], (uint32_t)nc, &flag)) return;
+  const uint32_t before = arrive_add(&c->arrive[2], picked ? 1u : 0x10001u, &flag);
+  if ((before & 0xffffu) != (uint32_t)nc - 1u) return;
   // ---- the unit's last workgroup: anything left over, then the merge ----------------------------------------------
   int n_used = nc;
   if (need_threshold) {
-    const unsigned long long wthr = load_coherent(&c->thr);  // published before its writer's second arrival
-    T = (uint32_t)(wthr >> 32);
-    idxT = (int32_t)(uint32_t)wthr - 2;
-    bool missing = false;
-    for (int w = tid; w < nc; w += kStepThreads) {
-      const bool m = load_coherent(&udone[w]) == 0u;
-      ss->seg_size[w] = m ? 1 : 0;
-      missing = missing || m;
+    if (!have) {  // published before its writer's second arrival; in flight together with the partials
+      const unsigned long long wthr = load_coherent(&c->thr);
+      T = (uint32_t)(wthr >> 32);
+      idxT = (int32_t)(uint32_t)wthr - 2;
     }
-    if (__syncthreads_or(missing)) {
+    if ((before >> 16) != 0u || !picked) {  // the same in every thread
       // Some workgroup did not put its threshold-bin rows on its list: they are attended over here, 256 candidates
       // at a time through the row list (this workgroup's own rows are done), into the spare partial slot.
+      for (int w = tid; w < nc; w += kStepThreads)
+        ss->seg_size[w] = load_coherent(&a.pl[(size_t)unit * NREP * n_slots + w]) < 0.f ? 1 : 0;  // head 0's slots
+      __syncthreads();
       st.init();
       bool resumed = false;
       uint32_t cnt_x = 0, sum_x = 0;
@@ -647,10 +647,8 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     }
   }
   FIER_PROF_WG(7)
-  // counters and flags back to zero for the next call, the unit's histogram too (all its readers have arrived); the
+  // counters back to zero for the next call, the unit's histogram too (all its readers have arrived); the
   // selection for the index-list kernel
-  if (need_threshold)
-    for (int w = tid; w < nc; w += kStepThreads) udone[w] = 0u;
   for (int k = tid; k < kSelBins; k += kStepThreads) gh[k] = 0;
   if (tid == 0) {
     c->arrive[2] = 0;
@@ -798,7 +796,6 @@ static bool fill_step_args(StepArgs& a, int rpw, int order, KvLayout lay, const 
   a.max_budget = max_budget;
   a.cand = sb.cand;
   a.seg_cnt = sb.seg_cnt;
-  a.done = sb.done;
   a.K = (const uint4*)K;
   a.V = (const uint4*)V;
   a.q = (const uint4*)q;
