@@ -19,8 +19,9 @@
 //      time), appends those of its candidates with `key > T or (key == T and index <= idxT)` to its row list and
 //      attends over them too; stores its partial (m, l, o) per query head and counts a second arrival;
 //   6. the unit's last arriver there merges the partials.
-// A workgroup whose poll runs out says so in its partial (the sign of its l); the merging workgroup then attends over
-// that workgroup's threshold-bin rows itself and merges again.  The result therefore never depends on a poll
+// A workgroup whose poll runs out says so in its partial (the sign of its l) and in the upper half of the second
+// arrival counter; the merging workgroup then attends over that workgroup's threshold-bin rows itself before it
+// merges.  The result therefore never depends on a poll
 // succeeding, every wait is bounded and every wavefront exits.  A poll only ever lasts long when the unit's
 // workgroups are not running together, which is why the launcher uses this kernel for resident grids and the
 // three-kernel form (threshold kernel, then selection + attention) otherwise.
@@ -28,6 +29,9 @@
 //
 // The ascending index list of the selection (idx_out of the step, an optional output) is written by a small
 // separate kernel from the scores and the threshold this kernel leaves in the unit's control block.
+//
+// For small grids the same workgroups also run in ONE launch together with the scoring workgroups
+// (step_fused_kernel): they then begin by waiting for their unit's scores, which come from the same launch.
 #include "fier_attn_dev.h"
 #include "fier_dev.h"
 #include "fier_kernels.h"
