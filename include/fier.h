@@ -235,7 +235,8 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
  *     at once.  The scoring workgroups and the selecting / attending workgroups share one launch; the latter wait
  *     (for a bounded time) until their unit's scores are complete.  Should that bound ever run out -- a GPU so
  *     oversubscribed by other work that a unit's scoring workgroups do not finish within a few tenths of a second -- the unit's
- *     output is NaN and its count -1, and the workspace has to be re-zeroed.
+ *     output is NaN and its count -1, the workspace has to be re-zeroed and the layer's packed cache rebuilt
+ *     (fier_quantize_keys).
  *   2 kernels: one or two query heads per kv head, all workgroups of the second kernel resident at once.  Phase 1 =
  *     append + score + score histogram; phase 2 = exact threshold + attention over the selected rows + merge in one
  *     launch; phase 3 = the ascending index list (launched by the step only if idx_out is given; may be repeated).
@@ -248,9 +249,13 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
  * for timing (follow it with one phase 2 before the next real step), phase 2 only after a phase 1.
  * Phases 2 + 16 f and 3 + 16 f, f = 1..3, are for tests: the two-kernel form whatever the shape, its second kernel
  * with flags f (1: no workgroup picks up the threshold itself, the merging workgroup attends over all threshold-bin
- * rows; 2: checksums of the attended rows in the control blocks).  Phase 4 + 16 f, f = 0..3: the one-kernel form
+ * rows; 2: checksums of the attended rows in the control blocks).  Phase 4 + 16 f, f = 0..7: the one-kernel form
  * whatever the shape (FIER_EINVAL with more than two query heads per kv head or more than one dispatch round of
- * scoring workgroups), same flags; follow it with 3 + 16 f for the index list.
+ * scoring workgroups), same flags; follow it with 3 + 16 (f & 3) for the index list.  Flag 4 (this form only) makes
+ * the bounded wait for the scores run out on purpose -- the scoring workgroups do not report, the others give up
+ * after a few polls -- to show what the caller then sees: NaN outputs and counts of -1; the workspace has to be
+ * zero-filled again afterwards and the layer's packed cache rebuilt with fier_quantize_keys (the appended rows are
+ * in place, their bound may be missing from kabsmax).
  */
 int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget);
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,

@@ -309,8 +309,9 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
   // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel of the two- or three-kernel form; 2 + 16 f,
   // 3 + 16 f: kernels 2, 3 of the two-kernel form with test flags f; 4 + 16 f: the one-launch form with test flags f
-  if (max_budget > cfg->max_ctx || phase < -1 || phase > 4 + 16 * 3 ||
-      (phase > 3 && (phase & 15) != 2 && (phase & 15) != 3 && (phase & 15) != 4))
+  if (max_budget > cfg->max_ctx || phase < -1 || phase > 4 + 16 * 7 ||
+      (phase > 3 && (phase & 15) != 2 && (phase & 15) != 3 && (phase & 15) != 4) ||
+      ((phase >> 4) > 3 && (phase & 15) != 4))
     return FIER_EINVAL;
   if (phase > 0 && (phase & 15) == 4 && !fier::step_fused_fits(units_of(cfg), n_rep_of(cfg), cfg->max_ctx)) return FIER_EINVAL;
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))

@@ -39,6 +39,7 @@ bool fill_score_args(ScoreArgs& sa, KvLayout lay, const uint32_t* kbits, const u
   sa.bpw = score_blocks_per_wave(units, max_ctx, hist, rounds_out);
   const int n_blocks = (max_ctx + kPair - 1) / kPair;
   sa.n_x = (n_blocks + 4 * sa.bpw - 1) / (4 * sa.bpw);  // scoring workgroups per unit
+  sa.no_arrival = 0;
   sa.lay = lay;
   return sa.bpw <= kScoreMaxBpw;  // always: at most 12, + 1
 }

@@ -91,6 +91,7 @@ struct ScoreArgs {
   const uint32_t* v_new;
   float* newmax;
   int n_kv_heads, max_ctx, bpw, gshift, n_x;
+  int no_arrival;  // one-launch step, tests only: the scoring workgroups do not count their arrival
   KvLayout lay;
 };
 
@@ -553,7 +554,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs& sa, const int block_
       // the unit's selecting workgroups wait for the count of its scoring workgroups
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      if (tid == 0) __hip_atomic_fetch_add(&ctl[unit].arrive[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0 && !sa.no_arrival)
+        __hip_atomic_fetch_add(&ctl[unit].arrive[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

@@ -248,7 +248,8 @@ struct StepArgs {
   int score_bpw;  // ... and pair blocks per wavefront of its scoring workgroups
   size_t cand_pitch;
   int flags;  // tests: bit 0 = no workgroup picks up the threshold (the merging workgroup attends over all
-              // threshold-bin rows); bit 1 = checksums of the attended rows
+              // threshold-bin rows); bit 1 = checksums of the attended rows; bit 2 (one-launch step) = the scoring
+              // workgroups do not count their arrival and the others give up after a few polls
   KvLayout lay;
 };
 
@@ -325,7 +326,8 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     const uint32_t expect = (uint32_t)((app ? 1 : 0) + (len_scored > 0 ? (len_scored + per_wg - 1) / per_wg : 1));
     if (tid == 0) {
       uint32_t got = 0;
-      for (int spin = 0; spin < kPollScoresMax; ++spin) {
+      const int spin_max = (a.flags & 4) ? 8 : kPollScoresMax;
+      for (int spin = 0; spin < spin_max; ++spin) {
         got = load_coherent(&c->arrive[0]);
         if (got >= expect) break;
         __builtin_amdgcn_s_sleep(8);
@@ -909,6 +911,7 @@ static hipError_t launch_step_fused_dt(KvLayout lay, int n_rep, const StepBuffer
                       count_out, out, kabsmax, units, n_kv_heads, max_ctx, flags))
     return hipErrorInvalidValue;
   a.score_bpw = sa.bpw;
+  sa.no_arrival = (flags & 4) ? 1 : 0;
   const int n_score_wgs = units * (sa.n_x + 1);
   dim3 grid((unsigned)n_score_wgs + (unsigned)units * (unsigned)a.wgs_per_unit);
   if (n_rep == 1)

@@ -189,3 +189,36 @@ def test_hand_off_between_workgroups_is_stable_over_many_launches(gu, oracle, fo
         else:
             assert torch.equal(got[1], first[1]) and torch.equal(got[2], first[2]), f"selection differs at launch {it}"
             assert torch.equal(got[0], first[0]), f"output differs at launch {it}"
+
+
+def test_one_launch_form_reports_scores_that_never_arrived(gu, oracle):
+    """The one-launch form's only wait without a fallback: a unit's selecting workgroups wait for its scoring
+    workgroups.  With test flag 4 the scoring workgroups do not report and the others give up after a few polls (every
+    workgroup still exits normally): the caller must see NaN outputs and counts of -1, not a plausible wrong result.
+    After re-zeroing the workspace and rebuilding the packed cache an ordinary step is right again."""
+    STARVE = 4
+    wl = synth.make_workload("starve", 91, 2, 8, 4, [3000, 1777], [300, 200], F16, n_planted=4)
+    dw = gu.DeviceWorkload(wl)
+    B.quantize_keys(dw.cfg, dw.cache)
+    mb = int(wl.budgets.max())
+    out = torch.zeros((1, wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
+    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
+    ws = dw.workspace(mb)
+    q, kn, vn = dw.q[None].contiguous(), dw.k_new[None].contiguous(), dw.v_new[None].contiguous()
+    args = (dw.cfg, [dw.cache], q, kn, vn, dw.budgets, mb, out, idx, cnt, ws)
+    B.decode_step_phase(*args, 4 + 16 * STARVE)
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all()
+    assert (cnt == -1).all()
+    # recovery as the header prescribes
+    ws.zero_()
+    B.quantize_keys(dw.cfg, dw.cache)
+    B.decode_step(*args)
+    torch.cuda.synchronize()
+    r = oracle_step(oracle, wl, append=True)
+    idx_g, cnt_g = idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
+    check_index_sets(idx_g, cnt_g, r["idx"], r["count"], r["scores"], r["L"])
+    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                            np.ascontiguousarray(np.where(idx_g < 0, 0, idx_g)), cnt_g, 4)
+    assert np.abs(out.cpu().numpy()[0] - want).max() <= 2e-3
