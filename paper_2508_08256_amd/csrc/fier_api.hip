@@ -122,6 +122,7 @@ Workspace carve(const fier_config* c, int32_t max_budget, void* base) {
   w.sb.range_cnt = reinterpret_cast<uint32_t*>(take(units * ranges * sizeof(uint32_t)));
   w.sb.cand = reinterpret_cast<unsigned long long*>(take(units * cand_pitch * sizeof(unsigned long long)));
   w.sb.seg_cnt = reinterpret_cast<uint32_t*>(take(units * seg_pitch * sizeof(uint32_t)));
+  w.sb.sel_cnt = reinterpret_cast<uint32_t*>(take(units * seg_pitch * sizeof(uint32_t)));
   w.sb.scores = reinterpret_cast<float*>(take(units * (size_t)c->max_ctx * sizeof(float)));
   w.sb.newmax = reinterpret_cast<float*>(take(units * kD * sizeof(float)));
   w.sb.po = reinterpret_cast<float*>(take(heads * (ranges + 1) * kD * sizeof(float)));
@@ -367,7 +368,8 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
                                   cfg->n_kv_heads, cfg->max_ctx, cfg->group_size, phase >> 4, s);
       if (e != hipSuccess) return FIER_EHIP;
       if (phase == 0 && idxl) {
-        e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, cfg->n_kv_heads, cfg->max_ctx, s);
+        e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, n_rep, cfg->n_kv_heads,
+                                         cfg->max_ctx, s);
         if (e != hipSuccess) return FIER_EHIP;
       }
       continue;
@@ -390,7 +392,8 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
         if (e != hipSuccess) return FIER_EHIP;
       }
       if ((phase == 0 || (phase & 15) == 3) && idxl) {
-        e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, cfg->n_kv_heads, cfg->max_ctx, s);
+        e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, n_rep, cfg->n_kv_heads,
+                                         cfg->max_ctx, s);
         if (e != hipSuccess) return FIER_EHIP;
       }
     } else {

@@ -86,13 +86,15 @@ struct StepBuffers {    // carved from the caller's workspace
   uint32_t* range_cnt;  // [units][n_ranges] (fier_topk_ws): selected tokens per 1024-token range, then their scan
   unsigned long long* cand;  // [units][cand_pitch] candidates (key << 32 | token index)
   uint32_t* seg_cnt;    // [units][seg_pitch] candidates published by each workgroup
+  uint32_t* sel_cnt;    // [units][seg_pitch] rows each workgroup of the step's second kernel selected (for the
+                        // index-list kernel)
   float* scores;        // [units][max_ctx]
   float* newmax;        // [units][128]: |dequantized key| bound of the group re-quantized by this step's append
   float* po;            // attention partials, n_ranges + 1 slots per (unit, query head)
   float* pm;
   float* pl;
   size_t cand_pitch;    // candidate slots per unit
-  int seg_pitch;        // workgroup entries per unit in seg_cnt
+  int seg_pitch;        // workgroup entries per unit in seg_cnt and sel_cnt
 };
 
 hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbits, uint32_t* kmeta, float* kabsmax,
@@ -133,7 +135,7 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
                               int max_ctx, int flags, hipStream_t st);
 // The ascending index list of the selection that kernel made (an optional output of the step).
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
-                                int units, int n_kv_heads, int max_ctx, hipStream_t st);
+                                int units, int n_rep, int n_kv_heads, int max_ctx, hipStream_t st);
 // The whole step in one launch (scoring workgroups, then selecting / attending ones that wait for their unit's scores).
 hipError_t launch_step_fused(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const uint32_t* kbits,
                              const uint32_t* kmeta, float* kabsmax, void* K, void* V, const void* q,

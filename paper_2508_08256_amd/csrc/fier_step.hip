@@ -229,6 +229,7 @@ struct StepArgs {
   const int32_t* budgets;
   int max_budget;
   unsigned long long* cand;  // [units][cand_pitch]: slot k * nc + w = k-th candidate of workgroup w of the unit
+  uint32_t* sel_cnt;         // [units][wgs_per_unit]: rows each workgroup ended up with (for the index-list kernel)
   uint32_t* seg_cnt;         // [units][wgs_per_unit]
   const uint4* K;
   const uint4* V;
@@ -355,6 +356,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
   const float* __restrict__ s_unit = a.scores + (size_t)unit * max_ctx;
   unsigned long long* __restrict__ ucand = a.cand + (size_t)unit * a.cand_pitch;
   uint32_t* __restrict__ useg = a.seg_cnt + (size_t)unit * a.wgs_per_unit;
+  uint32_t* __restrict__ usel = a.sel_cnt + (size_t)unit * a.wgs_per_unit;
 
   // ---- 1. the workgroup's scores; meanwhile the threshold bin from the histogram ---------------------------------
   float4 v[RPW];
@@ -569,6 +571,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     }
     __syncthreads();  // the row list is complete
   }
+  if (tid == 0) store_coherent(&usel[wg], (uint32_t)n_rows);  // the merging workgroup may add to it
   attend_own(n_sure, n_rows, true);
   FIER_PROF_WG(5)
   if (a.flags & 2) {
@@ -606,6 +609,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
         if (!ss->seg_size[w]) continue;  // the same in every thread
         const int base = w * CAP;
         const int span = n - base < CAP ? n - base : CAP;
+        const uint32_t cnt_before = cnt_x;
         for (int k0 = 0; k0 < span; k0 += kStepThreads) {
           const int t = base + k0 + tid;
           bool sel = false;
@@ -629,6 +633,8 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
           resumed = true;
           cnt_x += n_x;
         }
+        // that workgroup's row count, for the index-list kernel (it arrived long ago: its own store is there)
+        if (tid == 0) store_coherent(&usel[w], load_coherent(&usel[w]) + (cnt_x - cnt_before));
       }
       if (a.flags & 2) {
         sum_x = wave_sum_u32(sum_x);
@@ -728,33 +734,48 @@ __global__ __launch_bounds__(kStepThreads, 5) void step_fused_kernel(const Score
   step_attend_body<DT, NREP, RPW, true>(a, unit, wg, *reinterpret_cast<StepLds<NREP, RPW>*>(raw));
 }
 
-// The ascending index list of the step's selection: idx[unit][0 .. budget) from the scores and the threshold the
-// step left in the control block.  grid (units), block 1024: the workgroup walks its unit 4096 tokens at a time and
-// keeps a running offset, so the list comes out in token order.  An optional output of the step, off its fast path.
-__global__ __launch_bounds__(1024) void step_emit_idx_kernel(const float* __restrict__ scores,
-                                                             const int32_t* __restrict__ seq_lens, int extra,
-                                                             const UnitCtl* __restrict__ ctl, int max_budget,
-                                                             int32_t* __restrict__ idx, int n_kv_heads, int max_ctx) {
-  __shared__ uint32_t scan_tmp[16];
-  const int unit = blockIdx.x, tid = threadIdx.x;
+// The ascending index list of the step's selection: idx[unit][0 .. budget) from the scores, the threshold the step
+// left in the control block and the row count every workgroup of the step's second kernel recorded.  grid (units,
+// workgroups per unit), block 256: workgroup (unit, wg) covers the same rpw 1024-token ranges as workgroup wg of the
+// step, starts its part of the list at the sum of the counts of the workgroups before it and fills it in token
+// order.  An optional output of the step, off its fast path.
+__global__ __launch_bounds__(kStepThreads) void step_emit_idx_kernel(const float* __restrict__ scores,
+                                                                     const int32_t* __restrict__ seq_lens, int extra,
+                                                                     const UnitCtl* __restrict__ ctl,
+                                                                     const uint32_t* __restrict__ sel_cnt, int rpw,
+                                                                     int wgs_per_unit, int max_budget,
+                                                                     int32_t* __restrict__ idx, int n_kv_heads,
+                                                                     int max_ctx) {
+  __shared__ uint32_t scan_tmp[4];
+  const int unit = blockIdx.x, wg = blockIdx.y, tid = threadIdx.x;
   int n = seq_lens[unit / n_kv_heads] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
+  const int tok0 = wg * rpw * kRangeTokens;
+  if (tok0 >= n) return;
+  const float* __restrict__ s = scores + (size_t)unit * max_ctx;
+  // this workgroup's scores, the counts of the workgroups before it and the unit's threshold leave together
+  float4 v[8];
+#pragma unroll
+  for (int rr = 0; rr < 8; ++rr) {
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
+    v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (rr < rpw && i < n) v[rr] = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx
+  }
+  uint32_t mine = 0;
+  for (int w = tid; w < wg; w += kStepThreads) mine += sel_cnt[(size_t)unit * wgs_per_unit + w];
   const UnitCtl* __restrict__ c = &ctl[unit];
   const int tbin = c->tbin;
   const float R = c->R, scale = c->scale;
   const uint32_t T = c->T;
   const int32_t idxT = c->idxT;
-  const float* __restrict__ s = scores + (size_t)unit * max_ctx;
+  uint32_t run;
+  block_excl_scan_u32<4>(mine, scan_tmp, run);  // run = the list position of this workgroup's first row
   int32_t* __restrict__ out = idx + (size_t)unit * max_budget;
-  uint32_t run = 0;
-  // the next stretch's scores are on their way while this one is scanned and written
-  float4 v_next = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (4 * tid < n) v_next = *reinterpret_cast<const float4*>(s + 4 * tid);
-  for (int i0 = 0; i0 < n; i0 += 4096) {
-    const int i = i0 + 4 * tid;
-    const float4 v = v_next;
-    if (i + 4096 < n) v_next = *reinterpret_cast<const float4*>(s + i + 4096);
-    const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int rr = 0; rr < 8; ++rr) {
+    if (rr >= rpw || tok0 + rr * kRangeTokens >= n) break;  // the same for the whole workgroup
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
+    const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
     uint32_t selm = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -764,7 +785,7 @@ __global__ __launch_bounds__(1024) void step_emit_idx_kernel(const float* __rest
       selm |= sel ? 1u << j : 0u;
     }
     uint32_t total;
-    uint32_t pos = run + block_excl_scan_u32<16>((uint32_t)__builtin_popcount(selm), scan_tmp, total);
+    uint32_t pos = run + block_excl_scan_u32<4>((uint32_t)__builtin_popcount(selm), scan_tmp, total);
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       if (selm >> j & 1u) {
@@ -802,6 +823,7 @@ static bool fill_step_args(StepArgs& a, int rpw, int order, KvLayout lay, const 
   a.max_budget = max_budget;
   a.cand = sb.cand;
   a.seg_cnt = sb.seg_cnt;
+  a.sel_cnt = sb.sel_cnt;
   a.K = (const uint4*)K;
   a.V = (const uint4*)V;
   a.q = (const uint4*)q;
@@ -980,8 +1002,13 @@ bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx) {
 }
 
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
-                                int units, int n_kv_heads, int max_ctx, hipStream_t st) {
-  step_emit_idx_kernel<<<units, 1024, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, max_budget, idx, n_kv_heads, max_ctx);
+                                int units, int n_rep, int n_kv_heads, int max_ctx, hipStream_t st) {
+  // the same split into workgroups as the step's second kernel
+  const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  const int n_wgs = (n_ranges + rpw - 1) / rpw;
+  step_emit_idx_kernel<<<dim3(units, n_wgs), kStepThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.sel_cnt, rpw,
+                                                                     n_wgs, max_budget, idx, n_kv_heads, max_ctx);
   return hipGetLastError();
 }
 
