@@ -46,23 +46,25 @@ constexpr int kAttnRowsDenseMin = 512;   // rows per workgroup when attending ov
 constexpr int kAttnRowsDenseMax = 3200;  // picks a multiple of 128 in this range (see dense_rows_per_wg)
 
 // ---- fused decode step -------------------------------------------------------------------------------
-// Two kernels per layer: (1) append + score + score histogram, (2) exact threshold + attention over the selected rows
-// + merge.  Each unit's tokens are spread over many workgroups; the few serial steps (exact threshold among the
-// candidates of the threshold bin, merge of the attention partials) are done by whichever workgroup of the unit
-// arrives last at a device-scope counter ("last arriver").  fier_topk_ws reuses the histogram machinery with a
-// threshold kernel of its own.
+// Per layer: (1) append + score + score histogram, (2) exact threshold + attention over the selected rows + merge --
+// as one launch for small grids, as two where the workgroups of (2) are all resident at once, with (2) split into a
+// threshold kernel and a selection + attention kernel otherwise.  Each unit's tokens are spread over many
+// workgroups; the few serial steps (exact threshold among the candidates of the threshold bin, merge of the
+// attention partials) are done by one workgroup of the unit, as a rule the one that arrives last at a device-scope
+// counter ("last arriver").  fier_topk_ws reuses the threshold kernel.
 constexpr int kSelBins = 512;          // equal-width score histogram bins over [-R, R] (few enough that the
                                        // per-workgroup histograms merge with ~100 device atomics each)
 constexpr int kRangeTokens = 1024;     // tokens per range: the unit of work of the step's second kernel
-constexpr int kClassifyTokens = 4096;  // tokens per workgroup in fier_topk_ws's threshold kernel
+constexpr int kClassifyTokens = 4096;  // tokens per stretch of a threshold-kernel workgroup
 constexpr int kSegCand = 1024;         // candidate slots per workgroup of that kernel
 constexpr int kSelCandMax = 4096;      // candidates per unit its exact selection handles in LDS
 constexpr int kSubBins = 1024;         // second-level bins inside the threshold bin
 constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 
 struct UnitCtl {        // one per unit at the head of the workspace
-  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention, [1] classification (step) / threshold kernel
-                        // (fier_topk_ws), [2] attention partials of the step; zero between calls
+  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention; scoring workgroups of the one-launch step,
+                        // [1] classification (step) / threshold kernel, [2] attention partials of the step (upper
+                        // half: workgroups whose partial lacks their threshold-bin rows); zero between calls
   uint32_t topk_max;    // fier_topk_ws: bit pattern of the largest |score| of the unit; zero between calls
   int32_t tbin;         // bins above are selected, bins below are not (-1: everything, kSelBins: nothing)
   uint32_t above;       // tokens in bins above tbin
