@@ -40,8 +40,9 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
                                                                 unsigned long long* __restrict__ cand,
                                                                 uint32_t* __restrict__ seg_cnt,
                                                                 int32_t* __restrict__ count_out, int n_ranges,
-                                                                int n_chunks, int n_kv_heads, int max_ctx) {
-  __shared__ uint32_t wsum[NV][kThrWaves];
+                                                                int n_chunks, int tail_tokens, int n_kv_heads,
+                                                                int max_ctx) {
+  __shared__ uint32_t wsum[NV + 1][kThrWaves];  // the last row: a folded tail range
   __shared__ uint32_t flag;
   __shared__ int found[2];
   __shared__ uint32_t scan_tmp[kThrWaves];
@@ -124,7 +125,28 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
     const uint32_t g = wave_sum_u32(n_gt);
     if (lane == 0) wsum[k][wave] = g;
   }
+  // A last range that would be a workgroup of its own (a capacity of 2^k rows plus the appended one is the common
+  // case) -- and with it one more dispatch round for a few tokens per unit -- is classified by the unit's last
+  // workgroup instead, one token per thread: tail_tokens (<= 1024) tokens from the end of its chunk.
+  const bool takes_tail = tail_tokens > 0 && chunk == n_chunks - 1;
+  bool tail_cand = false;
+  float tail_x = 0.f;
+  if (takes_tail) {
+    const int i = (chunk + 1) * kChunkTokens + tid;
+    const bool ok = tid < tail_tokens && i < n;
+    if (ok) tail_x = s[i];
+    const int bin = sel_bin(tail_x, R, scale, kSelBins);
+    tail_cand = ok && bin == tbin;
+    const uint32_t g = wave_sum_u32(ok && bin > tbin ? 1u : 0u);
+    if (lane == 0) wsum[NV][wave] = g;
+  }
   // candidates go to this workgroup's own segment; the slot comes from an LDS counter
+  if (tail_cand) {
+    const uint32_t pos = atomicAdd(&n_local, 1u);
+    if (pos < (uint32_t)kSegCand)
+      store_coherent(&ucand[(size_t)chunk * kSegCand + pos],
+                     ((unsigned long long)score_key(tail_x) << 32) | (uint32_t)((chunk + 1) * kChunkTokens + tid));
+  }
   if (cmask) {
     uint32_t pos = atomicAdd(&n_local, (uint32_t)__builtin_popcount(cmask));
 #pragma unroll
@@ -149,7 +171,14 @@ __global__ __launch_bounds__(kThrThreads) void threshold_kernel(const float* __r
       store_coherent(&urange[r], wsum[k][4 * q4] + wsum[k][4 * q4 + 1] + wsum[k][4 * q4 + 2] + wsum[k][4 * q4 + 3]);
   }
   if (tid == 4 * NV) store_coherent(&useg[chunk], n_local);
-  const int nc = n > 0 ? (n + kChunkTokens - 1) / kChunkTokens : 1;  // workgroups of this unit
+  if (takes_tail && tid == 4 * NV + 1) {
+    uint32_t g = 0;
+#pragma unroll
+    for (int w = 0; w < kThrWaves; ++w) g += wsum[NV][w];
+    store_coherent(&urange[n_ranges - 1], g);
+  }
+  int nc = n > 0 ? (n + kChunkTokens - 1) / kChunkTokens : 1;  // workgroups of this unit
+  nc = nc > n_chunks ? n_chunks : nc;                            // (a folded tail has none of its own)
   FIER_PROF(12, unit == 0 && chunk == 1)
   FIER_PROF_WG(3)
   if (!last_arriver(&c->arrive[1], (uint32_t)nc, &flag)) return;
@@ -245,16 +274,22 @@ hipError_t launch_threshold(const StepBuffers& sb, const int32_t* seq_lens, int 
   // tokens per workgroup: 4096 NV.  One stretch per thread while the grid fits the machine at once (two workgroups
   // of 1024 threads per CU, 256 CUs), two beyond that (measured best at 1000 to 2000 workgroups), four for more
   // than 2048 workgroups of two; the candidate segments are sized for NV = 1 (the most)
-  auto wgs = [&](int v) { return (size_t)units * ((max_ctx + kClassifyTokens * v - 1) / (kClassifyTokens * v)); };
+  // a last chunk that is a single range goes to the workgroup before it (see the kernel)
+  auto folds = [&](int v) { return n_ranges > 1 && (n_ranges - 1) % (4 * v) == 0; };
+  auto chunks = [&](int v) {
+    return folds(v) ? (n_ranges - 1) / (4 * v) : (max_ctx + kClassifyTokens * v - 1) / (kClassifyTokens * v);
+  };
+  auto wgs = [&](int v) { return (size_t)units * chunks(v); };
   int nv = 1;
   if (wgs(1) > 512) nv = 2;
   if (wgs(2) > 2048) nv = 4;
-  const int n_chunks = (max_ctx + kClassifyTokens * nv - 1) / (kClassifyTokens * nv);
+  const int n_chunks = chunks(nv);
+  const int tail_tokens = folds(nv) ? max_ctx - (n_ranges - 1) * kRangeTokens : 0;
   dim3 grid(units, n_chunks);
 #define FIER_THR_CASE(NV)                                                                                            \
   threshold_kernel<NV><<<grid, kThrThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.hist, budgets,         \
                                                      max_budget, sb.range_cnt, sb.cand, sb.seg_cnt, count_out,      \
-                                                     n_ranges, n_chunks, n_kv_heads, max_ctx)
+                                                     n_ranges, n_chunks, tail_tokens, n_kv_heads, max_ctx)
   if (nv == 1)
     FIER_THR_CASE(1);
   else if (nv == 2)
