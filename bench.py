@@ -352,7 +352,6 @@ def measure(args, workload, budget_arg, detail):
     us_k12, _ = timed(phase(1, 2), ns, nw)
     us_k2 = us_k12 - us_k1
     us_k3, _ = timed(phase(3), ns, nw)
-    us_one = timed(phase(4), ns, nw)[0] if n_kernels == 1 else None      # the one-launch form alone
 
     # layer (r, l) of the flattened cache list, for the per-layer calls
     flat = [(r, l) for r in range(R) for l in range(NL)]
@@ -370,14 +369,7 @@ def measure(args, workload, budget_arg, detail):
     # the second kernel of the two-kernel form (threshold + attention + merge in one launch, timed as first + second
     # minus first), the third of the three-kernel form (selection + attention + merge, timed alone).
     gather_bytes = ab["selected_kv"] + ab["q_out"]
-    if n_kernels == 1:
-        # one launch does everything: its algorithmic bytes are the step's
-        dom_name, us_dom, gather_bytes = "step_fused_kernel (the whole step in one launch)", us_one, ab["total"]
-        kernels_us = {"one_launch_step": round(us_one / NL, 3), "index_list_optional": round(us_k3 / NL, 3),
-                      "as_two_kernels": {"append_score_hist": round(us_k1 / NL, 3),
-                                         "threshold_attend_merge": round(us_k2 / NL, 3),
-                                         "sum": round((us_k1 + us_k2) / NL, 3)}}
-    elif n_kernels == 2:
+    if n_kernels == 2:
         dom_name, us_dom = "step_attend_kernel (exact threshold, gather attention, merge)", us_k2
         kernels_us = {"append_score_hist": round(us_k1 / NL, 3), "threshold_attend_merge": round(us_k2 / NL, 3),
                       "sum": round((us_k1 + us_k2) / NL, 3), "index_list_optional": round(us_k3 / NL, 3)}
@@ -510,8 +502,7 @@ def measure(args, workload, budget_arg, detail):
                            "p95": round(float(np.percentile(single, 95)), 3), "n": int(len(single))},
         "graph_replay_us_per_step": None if us_graph is None else round(us_graph, 3),
         "kernels_us": kernels_us,
-        "kernel_GBps": {"append_score_hist": round(k1_gbps, 1),
-                        ("whole_step" if n_kernels == 1 else "gather_attention"): round(dom_gbps, 1)},
+        "kernel_GBps": {"append_score_hist": round(k1_gbps, 1), "gather_attention": round(dom_gbps, 1)},
         "standalone_calls_us": {"fier_score": round(us_score, 3), "fier_topk": round(us_topk, 3),
                                 "fier_topk_ws": round(us_topk_ws, 3),
                                 "fier_sparse_attn": round(us_attn, 3), "fier_append_key": round(us_append, 3),

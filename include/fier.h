@@ -228,34 +228,22 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
                            int32_t *count_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * One kernel of fier_decode_step alone, for measurement and tests.  The step takes one of three forms, chosen from
- * cfg and max_budget alone; fier_decode_step_kernels returns the number of kernels of the form a shape gets (not
- * counting the optional index-list kernel), 0 for an invalid configuration:
- *   1 kernel: small grids with one or two query heads per kv head, all of whose workgroups are resident on the GPU
- *     at once.  The scoring workgroups and the selecting / attending workgroups share one launch; the latter wait
- *     (for a bounded time) until their unit's scores are complete.  Should that bound ever run out -- a GPU so
- *     oversubscribed by other work that a unit's scoring workgroups do not finish within a few tenths of a second -- the unit's
- *     output is NaN and its count -1, the workspace has to be re-zeroed and the layer's packed cache rebuilt
- *     (fier_quantize_keys).
- *   2 kernels: one or two query heads per kv head, all workgroups of the second kernel resident at once.  Phase 1 =
- *     append + score + score histogram; phase 2 = exact threshold + attention over the selected rows + merge in one
- *     launch; phase 3 = the ascending index list (launched by the step only if idx_out is given; may be repeated).
- *   3 kernels otherwise: phase 1 as above, phase 2 = exact threshold, phase 3 = selection + attention + merge, which
- *     also writes idx_out (may be repeated).
- * Same arguments as fier_decode_step.  Phases 1, 2, 3 issue the kernels of the two- or three-kernel form (a shape
- * that would get one kernel is run in the two-kernel form): phase p works on what phases 1..p-1 of the latest step
- * on this workspace and these layers left behind, so the sequence 1, 2, 3 gives the result of fier_decode_step.
- * Phase 1 adds its scores to the workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated
- * for timing (follow it with one phase 2 before the next real step), phase 2 only after a phase 1.
- * Phases 2 + 16 f and 3 + 16 f, f = 1..3, are for tests: the two-kernel form whatever the shape, its second kernel
- * with flags f (1: no workgroup picks up the threshold itself, the merging workgroup attends over all threshold-bin
- * rows; 2: checksums of the attended rows in the control blocks).  Phase 4 + 16 f, f = 0..7: the one-kernel form
- * whatever the shape (FIER_EINVAL with more than two query heads per kv head or more than one dispatch round of
- * scoring workgroups), same flags; follow it with 3 + 16 (f & 3) for the index list.  Flag 4 (this form only) makes
- * the bounded wait for the scores run out on purpose -- the scoring workgroups do not report, the others give up
- * after a few polls -- to show what the caller then sees: NaN outputs and counts of -1; the workspace has to be
- * zero-filled again afterwards and the layer's packed cache rebuilt with fier_quantize_keys (the appended rows are
- * in place, their bound may be missing from kabsmax).
+ * One kernel of fier_decode_step alone, for measurement and tests.  After the first kernel (phase 1: append + score +
+ * score histogram) the step takes one of two forms, chosen from cfg and max_budget alone; fier_decode_step_kernels
+ * returns the number of kernels of the form a shape gets (not counting the optional index-list kernel), 0 for an
+ * invalid configuration:
+ *   2 kernels, with one or two query heads per kv head and all workgroups of the second kernel resident on the GPU at
+ *     once: phase 2 = exact threshold + attention over the selected rows + merge in one launch; phase 3 = the
+ *     ascending index list (launched by the step only if idx_out is given; may be repeated);
+ *   3 kernels otherwise: phase 2 = exact threshold, phase 3 = selection + attention + merge, which also writes
+ *     idx_out (may be repeated).
+ * Same arguments as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and
+ * these layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
+ * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with one
+ * phase 2 before the next real step), phase 2 only after a phase 1.  Phases 2 + 16 f and 3 + 16 f, f = 1..3, are for
+ * tests: the two-kernel form whatever the shape, its second kernel with flags f (1: no workgroup picks up the
+ * threshold itself, the merging workgroup attends over all threshold-bin rows; 2: checksums of the attended rows in
+ * the control blocks).
  */
 int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget);
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,

@@ -169,8 +169,8 @@ def workspace_scores(cfg: Config, max_budget: int, workspace):
 
 
 def decode_step_kernels(cfg: Config, max_budget: int) -> int:
-    """1, 2 or 3: the number of kernels fier_decode_step launches per layer for this shape (the optional index-list
-    kernel of the one- and two-kernel forms not counted)."""
+    """2 or 3: the number of kernels fier_decode_step launches per layer for this shape (the optional index-list
+    kernel of the two-kernel form not counted)."""
     return int(lib().fier_decode_step_kernels(C.byref(cfg), int(max_budget)))
 
 

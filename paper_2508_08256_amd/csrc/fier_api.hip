@@ -192,7 +192,6 @@ size_t fier_workspace_scores_offset(const fier_config* cfg, int32_t max_budget) 
 int fier_decode_step_kernels(const fier_config* cfg, int32_t max_budget) {
   if (check_cfg(cfg) != FIER_OK || max_budget < 1) return 0;
   if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
-  if (fier::step_fused_pays(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx)) return 1;
   return fier::step_is_resident(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx) ? 2 : 3;
 }
 
@@ -308,13 +307,10 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if (!layers || n_layers < 1 || !q || !budgets || !out || max_budget < 1) return FIER_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
-  // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel of the two- or three-kernel form; 2 + 16 f,
-  // 3 + 16 f: kernels 2, 3 of the two-kernel form with test flags f; 4 + 16 f: the one-launch form with test flags f
-  if (max_budget > cfg->max_ctx || phase < -1 || phase > 4 + 16 * 7 ||
-      (phase > 3 && (phase & 15) != 2 && (phase & 15) != 3 && (phase & 15) != 4) ||
-      ((phase >> 4) > 3 && (phase & 15) != 4))
+  // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel; 2 + 16 f, 3 + 16 f: kernels 2, 3 of the
+  // two-kernel form with test flags f
+  if (max_budget > cfg->max_ctx || phase < -1 || phase > 3 + 16 * 3 || (phase > 3 && (phase & 15) != 2 && (phase & 15) != 3))
     return FIER_EINVAL;
-  if (phase > 0 && (phase & 15) == 4 && !fier::step_fused_fits(units_of(cfg), n_rep_of(cfg), cfg->max_ctx)) return FIER_EINVAL;
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
@@ -356,22 +352,6 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
                             rows_per_wg, n_splits, cfg->sm_scale, wd.po, wd.pm, wd.pl, wd.sb.ctl, outl, units,
                             cfg->n_kv_heads, cfg->max_ctx, s);
       if (e != hipSuccess) return FIER_EHIP;
-      continue;
-    }
-    // One launch for the whole step where that is the faster form (small grids: every workgroup, scoring and
-    // attending, resident at once).
-    const bool fused = (phase == 0 && fier::step_fused_pays(units, n_rep, max_budget, cfg->max_ctx)) ||
-                       (phase > 0 && (phase & 15) == 4);
-    if (fused) {
-      e = fier::launch_step_fused(cfg->kv_dtype, lay, n_rep, w.sb, c->kbits, c->kmeta, c->kabsmax, c->k, c->v, ql,
-                                  c->seq_lens, extra, budgets, max_budget, kn, vn, cfg->sm_scale, cntl, outl, units,
-                                  cfg->n_kv_heads, cfg->max_ctx, cfg->group_size, phase >> 4, s);
-      if (e != hipSuccess) return FIER_EHIP;
-      if (phase == 0 && idxl) {
-        e = fier::launch_step_emit_idx(w.sb, c->seq_lens, extra, max_budget, idxl, units, n_rep, cfg->n_kv_heads,
-                                         cfg->max_ctx, s);
-        if (e != hipSuccess) return FIER_EHIP;
-      }
       continue;
     }
     if (phase == 0 || phase == 1) {

@@ -9,8 +9,10 @@
 // libfier_prof.so.  The library proper is compiled without the flag and contains none of this.
 #ifdef FIER_PROF_ENABLE
 extern __device__ unsigned long long fier_prof_slots[64];
-#define FIER_PROF(slot, cond) \
-  if ((cond) && threadIdx.x == 0) fier_prof_slots[slot] = wall_clock64();
+#define FIER_PROF(slot, cond)                                              \
+  __builtin_amdgcn_sched_barrier(0);                                       \
+  if ((cond) && threadIdx.x == 0) fier_prof_slots[slot] = wall_clock64();  \
+  __builtin_amdgcn_sched_barrier(0);
 // one time stamp per workgroup and point (the host reduces them)
 extern __device__ unsigned long long fier_prof_wg[8][4096];
 #define FIER_PROF_WG(point)                                                                  \

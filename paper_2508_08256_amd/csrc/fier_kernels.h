@@ -47,8 +47,8 @@ constexpr int kAttnRowsDenseMax = 3200;  // picks a multiple of 128 in this rang
 
 // ---- fused decode step -------------------------------------------------------------------------------
 // Per layer: (1) append + score + score histogram, (2) exact threshold + attention over the selected rows + merge --
-// as one launch for small grids, as two where the workgroups of (2) are all resident at once, with (2) split into a
-// threshold kernel and a selection + attention kernel otherwise.  Each unit's tokens are spread over many
+// (2) is one kernel where its workgroups are all resident at once, and split into a threshold kernel and a selection
+// + attention kernel otherwise.  Each unit's tokens are spread over many
 // workgroups; the few serial steps (exact threshold among the candidates of the threshold bin, merge of the
 // attention partials) are done by one workgroup of the unit, as a rule the one that arrives last at a device-scope
 // counter ("last arriver").  fier_topk_ws reuses the threshold kernel.
@@ -62,7 +62,7 @@ constexpr int kSubBins = 1024;         // second-level bins inside the threshold
 constexpr int kSubCandMax = 512;       // members of the threshold sub-bin ranked pairwise
 
 struct UnitCtl {        // one per unit at the head of the workspace
-  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention; scoring workgroups of the one-launch step,
+  uint32_t arrive[3];   // arrival counters: [0] stand-alone attention,
                         // [1] classification (step) / threshold kernel, [2] attention partials of the step (upper
                         // half: workgroups whose partial lacks their threshold-bin rows); zero between calls
   uint32_t topk_max;    // fier_topk_ws: bit pattern of the largest |score| of the unit; zero between calls
@@ -73,8 +73,7 @@ struct UnitCtl {        // one per unit at the head of the workspace
   float scale;          // kSelBins / (2 R)
   uint32_t T;           // threshold key inside tbin
   int32_t idxT;         // among keys == T inside tbin, indices <= idxT are selected
-  uint32_t starved;     // one-launch step: a workgroup went on without the unit's scores (the output is then NaN);
-                        // zero between calls
+  uint32_t pad;
   unsigned long long thr;  // the step's threshold as one word, T << 32 | idxT + 2, published by the unit's selector
                            // to its other workgroups; zero between calls
   uint32_t chk_cnt;     // checksums of the rows the step attended over (count, sum of token indices); only
@@ -138,14 +137,6 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 // The ascending index list of the selection that kernel made (an optional output of the step).
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
                                 int units, int n_rep, int n_kv_heads, int max_ctx, hipStream_t st);
-// The whole step in one launch (scoring workgroups, then selecting / attending ones that wait for their unit's scores).
-hipError_t launch_step_fused(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const uint32_t* kbits,
-                             const uint32_t* kmeta, float* kabsmax, void* K, void* V, const void* q,
-                             const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
-                             const void* k_new, const void* v_new, float sm_scale, int32_t* count_out, float* out,
-                             int units, int n_kv_heads, int max_ctx, int group_size, int flags, hipStream_t st);
-bool step_fused_fits(int units, int n_rep, int max_ctx);                     // the shape can run as one launch
-bool step_fused_pays(int units, int n_rep, int max_budget, int max_ctx);  // ... and that is the faster form
 int step_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx);
 bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx);
 

@@ -66,16 +66,20 @@ __device__ __forceinline__ void code_rows(const uint32_t (&rows)[kG], int ntok, 
   uint32_t r = rows[0];
 #pragma unroll
   for (int t = 0; t < kG; ++t) {
-    const float a = lo16f<DT>(r) - g.zf0;
-    const float b = hi16f<DT>(r) - g.zf1;
-    const bool present = FULL || t < ntok;
-    const bool c0 = present && (a + a >= g.sf0), c1 = present && (b + b >= g.sf1);
-    const uint64_t even = __ballot(c0);
-    const uint64_t odd = __ballot(c1);
-    b0 |= c0 ? (1u << t) : 0u;
-    b1 |= c1 ? (1u << t) : 0u;
-    if (lane == lane_base + t)
-      mine = make_uint4((uint32_t)even, (uint32_t)(even >> 32), (uint32_t)odd, (uint32_t)(odd >> 32));
+    // ntok is the same in every lane: a row that is not there costs one scalar branch, not a row's worth of work
+    // (the appending wavefront of a decode step is a single wavefront on the step's critical path, and a group that
+    // has just been opened holds one token)
+    if (FULL || t < ntok) {
+      const float a = lo16f<DT>(r) - g.zf0;
+      const float b = hi16f<DT>(r) - g.zf1;
+      const bool c0 = a + a >= g.sf0, c1 = b + b >= g.sf1;
+      const uint64_t even = __ballot(c0);
+      const uint64_t odd = __ballot(c1);
+      b0 |= c0 ? (1u << t) : 0u;
+      b1 |= c1 ? (1u << t) : 0u;
+      if (lane == lane_base + t)
+        mine = make_uint4((uint32_t)even, (uint32_t)(even >> 32), (uint32_t)odd, (uint32_t)(odd >> 32));
+    }
     if (t + 1 < kG) {
       // An empty statement that "produces" the next row and `mine`: the next row's compares cannot start before
       // this row's ballots have been used up.  Left to itself the compiler makes the ballots of all 32 rows first,
@@ -109,7 +113,8 @@ __device__ __forceinline__ void quantize_group(const uint32_t (&rows)[kG], int n
   MinMax m;
   minmax_first<DT>(m, rows[0]);
 #pragma unroll
-  for (int t = 1; t < kG; ++t) minmax_update<DT>(m, rows[t], t < ntok);
+  for (int t = 1; t < kG; ++t)
+    if (t < ntok) minmax_update<DT>(m, rows[t], true);  // the same in every lane: a scalar branch per absent row
   const GroupScale g = group_scale<DT>(m);
   uint32_t b0, b1;
   code_rows<DT>(rows, ntok, g, lane, lane_base, mine, b0, b1);
@@ -158,21 +163,15 @@ __device__ __forceinline__ void append_load_rows(const uint32_t* __restrict__ K,
 }
 
 // rows, t0, ntok: from append_load_rows (which may run well before: the loads are the long part of the chain)
-// COHERENT: the K/V rows are written through to memory (another workgroup of the same launch may gather them).
-template <int DT, bool COHERENT = false>
+template <int DT>
 __device__ __forceinline__ void append_finish(uint32_t* __restrict__ K, uint32_t* __restrict__ V, const KvRows kv,
                                               uint32_t* __restrict__ kbits, uint32_t* __restrict__ kmeta, int unit,
                                               int L, int max_ctx, uint32_t kn, uint32_t vn, int lane,
                                               const uint32_t (&rows)[kG], int t0, int ntok, GroupCode& gc,
                                               uint4& mine) {
   const int n_groups = max_ctx / kG;
-  if constexpr (COHERENT) {
-    store_coherent(&K[kv.row(L) * (kD / 2) + lane], kn);
-    store_coherent(&V[kv.row(L) * (kD / 2) + lane], vn);
-  } else {
-    K[kv.row(L) * (kD / 2) + lane] = kn;
-    V[kv.row(L) * (kD / 2) + lane] = vn;
-  }
+  K[kv.row(L) * (kD / 2) + lane] = kn;
+  V[kv.row(L) * (kD / 2) + lane] = vn;
   const int Gi = L / kG;
   mine = make_uint4(0, 0, 0, 0);
   quantize_group<DT>(rows, ntok, lane, 0, mine, gc);
@@ -201,7 +200,7 @@ __device__ __forceinline__ void append_row(uint32_t* __restrict__ K, uint32_t* _
 // time.  Every pair block of the group that holds a token gets its code words rewritten; on_block(pb, mine, gs)
 // is called once per such block with the calling lane's code word of token t0 + 64 pb + lane (zero if absent) and the
 // group's scale.
-template <int DT, bool COHERENT = false, class OnBlock>
+template <int DT, class OnBlock>
 __device__ __forceinline__ GroupScale append_row_long(uint32_t* __restrict__ K, uint32_t* __restrict__ V,
                                                       const KvRows kv, uint32_t* __restrict__ kbits,
                                                       uint32_t* __restrict__ kmeta,
@@ -209,13 +208,8 @@ __device__ __forceinline__ GroupScale append_row_long(uint32_t* __restrict__ K, 
                                                       int lane, int& t0, int& ntok, OnBlock on_block) {
   const int g = kG * ns;
   const int n_groups = max_ctx / g;
-  if constexpr (COHERENT) {
-    store_coherent(&K[kv.row(L) * (kD / 2) + lane], kn);
-    store_coherent(&V[kv.row(L) * (kD / 2) + lane], vn);
-  } else {
-    K[kv.row(L) * (kD / 2) + lane] = kn;
-    V[kv.row(L) * (kD / 2) + lane] = vn;
-  }
+  K[kv.row(L) * (kD / 2) + lane] = kn;
+  V[kv.row(L) * (kD / 2) + lane] = vn;
   const int Gi = L / g;
   t0 = Gi * g;
   ntok = L - t0 + 1;

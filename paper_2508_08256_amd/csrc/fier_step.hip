@@ -29,13 +29,9 @@
 //
 // The ascending index list of the selection (idx_out of the step, an optional output) is written by a small
 // separate kernel from the scores and the threshold this kernel leaves in the unit's control block.
-//
-// For small grids the same workgroups also run in ONE launch together with the scoring workgroups
-// (step_fused_kernel): they then begin by waiting for their unit's scores, which come from the same launch.
 #include "fier_attn_dev.h"
 #include "fier_dev.h"
 #include "fier_kernels.h"
-#include "fier_score_dev.h"
 #include "fier_select_dev.h"
 
 namespace fier {
@@ -47,7 +43,6 @@ constexpr int kCandRegs = 8;        // candidate slots a selector thread holds i
 constexpr int kCandLds = 256;       // candidates of a workgroup kept in LDS (the rest are read back from its slots)
 constexpr int kMaxStepWgs = (1 << 20) / kRangeTokens;  // workgroups of one unit at most (max_ctx <= 2^20, RPW >= 1)
 constexpr int kPollMax = 1 << 14;   // polls of the threshold word before a workgroup gives up (each >= 0.1 us)
-constexpr int kPollScoresMax = 1 << 18;  // one-launch step: polls for the unit's scores (each >= 0.2 us)
 
 // selector scratch in LDS (dead before the partials use the same bytes)
 struct SelScratch {
@@ -245,12 +240,9 @@ struct StepArgs {
   float* kabsmax;
   const float* newmax;
   int n_kv_heads, max_ctx, order, wgs_per_unit;
-  int n_units;    // one-launch step: units of the call ...
-  int score_bpw;  // ... and pair blocks per wavefront of its scoring workgroups
   size_t cand_pitch;
   int flags;  // tests: bit 0 = no workgroup picks up the threshold (the merging workgroup attends over all
-              // threshold-bin rows); bit 1 = checksums of the attended rows; bit 2 (one-launch step) = the scoring
-              // workgroups do not count their arrival and the others give up after a few polls
+              // threshold-bin rows); bit 1 = checksums of the attended rows
   KvLayout lay;
 };
 
@@ -271,10 +263,8 @@ struct StepLds {
   int32_t lblk[RPW * kRangeTokens / 64];  // paged rows: block numbers of this workgroup's tokens
 };
 
-// Workgroup `wg` of unit `unit`.  FUSED: the scores, the histogram, R and the appended rows come from workgroups of
-// this same launch (the scoring role of step_fused_kernel): the workgroup first waits until the unit's scoring
-// workgroups have all arrived, and reads what they wrote with loads that cannot hit a stale line.
-template <int DT, int NREP, int RPW, bool FUSED>
+// Workgroup `wg` of unit `unit`.
+template <int DT, int NREP, int RPW>
 __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int unit, const int wg,
                                                  StepLds<NREP, RPW>& lds) {
   constexpr int CAP = kRangeTokens * RPW;  // tokens the workgroup owns
@@ -299,52 +289,14 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
   uint32_t* __restrict__ gh = a.ghist + (size_t)unit * kSelBins;
   // what does not depend on the sequence length leaves with it: the unit's histogram (thread t owns bins 511 - 2t
   // and 510 - 2t: descending score order), the range of the binning, the budget
-  uint2 hpair = make_uint2(0u, 0u);
-  float R = 0.f, hscale = 0.f;
-  if constexpr (!FUSED) {
-    hpair = *reinterpret_cast<const uint2*>(gh + (kSelBins - 2 - 2 * tid));
-    R = c->R;
-    hscale = c->scale;
-  }
+  const uint2 hpair = *reinterpret_cast<const uint2*>(gh + (kSelBins - 2 - 2 * tid));
+  const float R = c->R, hscale = c->scale;
   int B = a.budgets[b];
-  const int len_before = a.seq_lens[b];
-  int n = len_before + a.extra;
+  int n = a.seq_lens[b] + a.extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
   const int tok0 = wg * CAP;
   if (tok0 >= n && wg != 0) return;
   const int nc = n > 0 ? (n + CAP - 1) / CAP : 1;  // workgroups of this unit that run
-  bool starved = false;  // FUSED: the unit's scores did not arrive within the bound
-  if constexpr (FUSED) {
-    // The unit's scoring workgroups come before every workgroup of this role in the dispatch order, so they have been
-    // dispatched (or are about to be, on another XCD) and finish without waiting for anybody: the wait ends.  It is
-    // bounded all the same; a workgroup that runs out of time flags the unit, whose output is then NaN.
-    // the scoring role's own arithmetic: one appending workgroup if the unit receives a row, and the scoring
-    // workgroups whose first token lies below the length (the first one always runs)
-    const int len_old = len_before < 0 ? 0 : (len_before > max_ctx ? max_ctx : len_before);
-    const bool app = a.extra != 0 && len_old < max_ctx;
-    const int len_scored = len_old + (app ? 1 : 0);
-    const int per_wg = 4 * kPair * a.score_bpw;
-    const uint32_t expect = (uint32_t)((app ? 1 : 0) + (len_scored > 0 ? (len_scored + per_wg - 1) / per_wg : 1));
-    if (tid == 0) {
-      uint32_t got = 0;
-      const int spin_max = (a.flags & 4) ? 8 : kPollScoresMax;
-      for (int spin = 0; spin < spin_max; ++spin) {
-        got = load_coherent(&c->arrive[0]);
-        if (got >= expect) break;
-        __builtin_amdgcn_s_sleep(8);
-      }
-      flag = got >= expect ? 1u : 0u;
-    }
-    __syncthreads();
-    starved = flag == 0u;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    asm volatile("" ::: "memory");
-    const unsigned long long hp = load_coherent(reinterpret_cast<const unsigned long long*>(gh + (kSelBins - 2 - 2 * tid)));
-    hpair = make_uint2((uint32_t)hp, (uint32_t)(hp >> 32));
-    R = load_coherent(&c->R);
-    hscale = load_coherent(&c->scale);
-    if (starved && tid == 0) store_coherent(&c->starved, 1u);
-  }
   FIER_PROF_WG(2)
   const int n_slots = a.wgs_per_unit + 1;          // partial slots per (unit, head): one spare for the merger
 
@@ -364,16 +316,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
   for (int rr = 0; rr < RPW; ++rr) {
     const int i = tok0 + rr * kRangeTokens + 4 * tid;
     v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n) {  // i + 3 < max_ctx; entries >= n are masked below
-      if constexpr (FUSED) {
-        const unsigned long long lo = load_coherent(reinterpret_cast<const unsigned long long*>(s_unit + i));
-        const unsigned long long hi = load_coherent(reinterpret_cast<const unsigned long long*>(s_unit + i + 2));
-        v[rr] = make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)),
-                            __uint_as_float((uint32_t)hi), __uint_as_float((uint32_t)(hi >> 32)));
-      } else {
-        v[rr] = *reinterpret_cast<const float4*>(s_unit + i);
-      }
-    }
+    if (i < n) v[rr] = *reinterpret_cast<const float4*>(s_unit + i);  // i + 3 < max_ctx; entries >= n are masked below
   }
   B = B > a.max_budget ? a.max_budget : B;
   B = B > n ? n : B;
@@ -503,7 +446,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
         // candidates that do not fit (scores clustered far more tightly than the a-priori range resolves): radix
         // selection streamed over the unit's scores
         __syncthreads();
-        stream_select<kStepThreads>([&](int k) { return FUSED ? load_coherent(&s_unit[k]) : s_unit[k]; }, n, tbin, R, hscale, (uint32_t)B - above, ss->hist,
+        stream_select<kStepThreads>([&](int k) { return s_unit[k]; }, n, tbin, R, hscale, (uint32_t)B - above, ss->hist,
                                     scan_tmp, ss->res, nullptr, T, idxT);
       }
       if (tid == 0) {
@@ -614,7 +557,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
           const int t = base + k0 + tid;
           bool sel = false;
           if (k0 + tid < span) {
-            const float x = FUSED ? load_coherent(&s_unit[t]) : s_unit[t];
+            const float x = s_unit[t];
             const uint32_t key = score_key(x);
             sel = sel_bin(x, R, hscale, kSelBins) == tbin && (key > T || (key == T && t <= idxT));
           }
@@ -648,53 +591,36 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     }
   }
   merge_heads<NREP>(a.po, a.pm, a.pl, unit, n_slots, n_used, sh_o, a.out + (size_t)unit * NREP * kD);
-  bool unit_starved = false;
-  if constexpr (FUSED) {
-    // some workgroup of the unit went on without the unit's scores: no result
-    unit_starved = load_coherent(&c->starved) != 0u;
-    if (unit_starved) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the merge's stores to the same words are done
-      __syncthreads();
-      for (int k = tid; k < NREP * kD; k += kStepThreads) a.out[(size_t)unit * NREP * kD + k] = __uint_as_float(0x7fc00000u);
-    }
-  }
   FIER_PROF_WG(7)
   // counters back to zero for the next call, the unit's histogram too (all its readers have arrived); the
   // selection for the index-list kernel
   for (int k = tid; k < kSelBins; k += kStepThreads) gh[k] = 0;
   if (tid == 0) {
     c->arrive[2] = 0;
-    if constexpr (FUSED) {
-      c->arrive[0] = 0;
-      c->starved = 0;
-    }
     c->thr = 0ull;
     c->tbin = tbin;
     c->above = above;
     c->budget = B;
     c->T = T;
     c->idxT = idxT;
-    if (a.count_out) a.count_out[unit] = unit_starved ? -1 : B;
+    if (a.count_out) a.count_out[unit] = B;
   }
   // the step appended a row: fold the bound of its re-quantized group into the unit's per-channel bound
   if (a.extra && a.seq_lens[b] < max_ctx && tid < kD) {
     float* slot = a.kabsmax + (size_t)unit * kD + tid;
-    const float nm = FUSED ? load_coherent(&a.newmax[(size_t)unit * kD + tid]) : a.newmax[(size_t)unit * kD + tid];
+    const float nm = a.newmax[(size_t)unit * kD + tid];
     if (nm > *slot) *slot = nm;
   }
 }
 
 // order: 0 = grid (workgroups, units); 1 = grid (units, workgroups); 2 = one-dimensional, groups of 8 units, a
-// group's workgroups together and unit % 8 fastest; 3 = one-dimensional, units fastest (see the launchers)
+// group's workgroups together and unit % 8 fastest (see the launcher)
 __device__ __forceinline__ void step_unit_wg(const StepArgs& a, int id_x, int id_y, int& unit, int& wg) {
   if (a.order == 2) {
     const int g = id_x / (8 * a.wgs_per_unit);
     const int rem = id_x - g * 8 * a.wgs_per_unit;
     wg = rem >> 3;
     unit = 8 * g + (rem & 7);
-  } else if (a.order == 3) {
-    wg = id_x / a.n_units;
-    unit = id_x - wg * a.n_units;
   } else {
     unit = a.order ? id_x : id_y;
     wg = a.order ? id_y : id_x;
@@ -710,28 +636,7 @@ __global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NRE
   __shared__ StepLds<NREP, RPW> lds;
   int unit, wg;
   step_unit_wg(a, (int)blockIdx.x, (int)blockIdx.y, unit, wg);
-  step_attend_body<DT, NREP, RPW, false>(a, unit, wg, lds);
-}
-
-// The whole step in ONE launch.  The first n_score_wgs workgroups are the scoring kernel's (the appending ones
-// first); the others are the workgroups of step_attend_kernel, each of which starts by waiting for its unit's
-// scoring workgroups.  Workgroups are dispatched in index order, so whenever a waiting workgroup occupies a slot the
-// scoring workgroups it waits for already run or have run: they wait for nobody and end.  What the launch saves
-// against two kernels: the drain of the first and the start of the second (2.3 us), and the units finish scoring one
-// after the other, so selection and gather of the first units run while the last are still being scored.
-template <int DT, int NREP, int RPW>
-__global__ __launch_bounds__(kStepThreads, 5) void step_fused_kernel(const ScoreArgs sa, const StepArgs a,
-                                                                     const int n_score_wgs) {
-  constexpr size_t kBytes = sizeof(StepLds<NREP, RPW>) > (size_t)kScoreLdsBytes ? sizeof(StepLds<NREP, RPW>) : (size_t)kScoreLdsBytes;
-  __shared__ __attribute__((aligned(16))) unsigned char raw[kBytes];
-  if ((int)blockIdx.x < n_score_wgs) {
-    score_body<DT, NREP, true, true>(sa, (int)blockIdx.x, n_score_wgs, reinterpret_cast<uint32_t*>(raw),
-                                     raw + kScoreLdsHist, reinterpret_cast<float*>(raw + kScoreLdsHist + kScoreLdsA));
-    return;
-  }
-  int unit, wg;
-  step_unit_wg(a, (int)blockIdx.x - n_score_wgs, 0, unit, wg);
-  step_attend_body<DT, NREP, RPW, true>(a, unit, wg, *reinterpret_cast<StepLds<NREP, RPW>*>(raw));
+  step_attend_body<DT, NREP, RPW>(a, unit, wg, lds);
 }
 
 // The ascending index list of the step's selection: idx[unit][0 .. budget) from the scores, the threshold the step
@@ -841,8 +746,6 @@ static bool fill_step_args(StepArgs& a, int rpw, int order, KvLayout lay, const 
   a.max_ctx = max_ctx;
   a.order = order;
   a.wgs_per_unit = n_wgs;
-  a.n_units = units;
-  a.score_bpw = 0;
   a.cand_pitch = sb.cand_pitch;
   a.flags = flags;
   a.lay = lay;
@@ -912,83 +815,6 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
   if (rpw == 4) FIER_STEP_RPW(DT_BF16, 4);
   FIER_STEP_RPW(DT_BF16, 8);
 #undef FIER_STEP_RPW
-}
-
-// The one-launch step: scoring workgroups (the appending ones first, then a unit's ranges next to each other, as in
-// the scoring kernel), then the selecting / attending workgroups, units fastest -- in groups of 8 units when the unit
-// count is a multiple of 8, so that a unit keeps to one XCD.
-template <int DT, int RPW>
-static hipError_t launch_step_fused_dt(KvLayout lay, int n_rep, const StepBuffers& sb, const uint32_t* kbits,
-                                       const uint32_t* kmeta, float* kabsmax, void* K, void* V, const void* q,
-                                       const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
-                                       const void* k_new, const void* v_new, float sm_scale, int32_t* count_out,
-                                       float* out, int units, int n_kv_heads, int max_ctx, int group_size, int flags,
-                                       hipStream_t st) {
-  ScoreArgs sa;
-  if (!fill_score_args(sa, lay, kbits, kmeta, kabsmax, q, seq_lens, extra, sb.scores, &sb, K, V, k_new, v_new, units,
-                       n_kv_heads, max_ctx, group_size, true))
-    return hipErrorInvalidValue;
-  StepArgs a;
-  if (!fill_step_args(a, RPW, units % 8 == 0 ? 2 : 3, lay, sb, K, V, q, seq_lens, extra, budgets, max_budget, sm_scale,
-                      count_out, out, kabsmax, units, n_kv_heads, max_ctx, flags))
-    return hipErrorInvalidValue;
-  a.score_bpw = sa.bpw;
-  sa.no_arrival = (flags & 4) ? 1 : 0;
-  const int n_score_wgs = units * (sa.n_x + 1);
-  dim3 grid((unsigned)n_score_wgs + (unsigned)units * (unsigned)a.wgs_per_unit);
-  if (n_rep == 1)
-    step_fused_kernel<DT, 1, RPW><<<grid, kStepThreads, 0, st>>>(sa, a, n_score_wgs);
-  else if (n_rep == 2)
-    step_fused_kernel<DT, 2, RPW><<<grid, kStepThreads, 0, st>>>(sa, a, n_score_wgs);
-  else
-    return hipErrorInvalidValue;
-  return hipGetLastError();
-}
-
-hipError_t launch_step_fused(int dtype, KvLayout lay, int n_rep, const StepBuffers& sb, const uint32_t* kbits,
-                             const uint32_t* kmeta, float* kabsmax, void* K, void* V, const void* q,
-                             const int32_t* seq_lens, int extra, const int32_t* budgets, int max_budget,
-                             const void* k_new, const void* v_new, float sm_scale, int32_t* count_out, float* out,
-                             int units, int n_kv_heads, int max_ctx, int group_size, int flags, hipStream_t st) {
-#define FIER_FUSED_RPW(DT, RPW)                                                                                      \
-  return launch_step_fused_dt<DT, RPW>(lay, n_rep, sb, kbits, kmeta, kabsmax, K, V, q, seq_lens, extra, budgets,     \
-                                       max_budget, k_new, v_new, sm_scale, count_out, out, units, n_kv_heads,        \
-                                       max_ctx, group_size, flags, st)
-  const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
-  if (dtype == DT_F16) {
-    if (rpw == 1) FIER_FUSED_RPW(DT_F16, 1);
-    if (rpw == 2) FIER_FUSED_RPW(DT_F16, 2);
-    if (rpw == 4) FIER_FUSED_RPW(DT_F16, 4);
-    FIER_FUSED_RPW(DT_F16, 8);
-  }
-  if (rpw == 1) FIER_FUSED_RPW(DT_BF16, 1);
-  if (rpw == 2) FIER_FUSED_RPW(DT_BF16, 2);
-  if (rpw == 4) FIER_FUSED_RPW(DT_BF16, 4);
-  FIER_FUSED_RPW(DT_BF16, 8);
-#undef FIER_FUSED_RPW
-}
-
-// Whether the one-launch step can take this shape: one or two query heads per kv head (the kernel is built for
-// those), the scoring grid one dispatch round.
-bool step_fused_fits(int units, int n_rep, int max_ctx) {
-  if (n_rep > 2) return false;
-  int rounds = 1;
-  score_blocks_per_wave(units, max_ctx, true, &rounds);
-  return rounds == 1;
-}
-
-// Whether it is also the faster form: measured so where ALL its workgroups, scoring and attending, are resident at
-// once (32 units of up to 16k tokens: about 1 us less than two launches).  On larger grids the attending workgroups
-// take slots from the scoring ones and their gathers slow the last scoring workgroups down, which costs more than
-// the launch that is saved (32 units of 32k tokens: 39.6 against 36.4 us).
-bool step_fused_pays(int units, int n_rep, int max_budget, int max_ctx) {
-  if (!step_fused_fits(units, n_rep, max_ctx) || !step_is_resident(units, n_rep, max_budget, max_ctx)) return false;
-  const int bpw = score_blocks_per_wave(units, max_ctx, true);
-  const int n_blocks = (max_ctx + kPair - 1) / kPair;
-  const long score_wgs = (long)units * ((n_blocks + 4 * bpw - 1) / (4 * bpw) + 1);
-  const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
-  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  return score_wgs + (long)units * ((n_ranges + rpw - 1) / rpw) <= step_resident_wgs(n_rep);
 }
 
 // Whether the one-launch form (step_attend_kernel) suits this shape: all its workgroups resident at once.

@@ -192,11 +192,10 @@ def test_binding_passes_the_workspace_size(monkeypatch):
 
 
 def test_form_of_the_step_follows_from_the_shape():
-    """fier_decode_step_kernels: one launch for small grids, two for MHA-like shapes whose second kernel is resident
-    at once, three for 3+ query heads per kv head or grids of several rounds; 0 for an invalid configuration."""
+    """fier_decode_step_kernels: two kernels for MHA-like shapes whose second kernel is resident at once, three for 3+
+    query heads per kv head or grids of several rounds; 0 for an invalid configuration."""
     k = B.decode_step_kernels
-    assert k(B.make_config(1, 8, 8, 4160), 512) == 1                 # 8 units x 4k tokens
-    assert k(B.make_config(1, 32, 32, 16448), 1800) == 1             # 32 units x 16k: everything resident together
+    assert k(B.make_config(1, 8, 8, 4160), 512) == 2                 # 8 units x 4k tokens
     assert k(B.make_config(1, 32, 32, 32832), 3604) == 2             # 32 units x 32k
     assert k(B.make_config(1, 32, 32, 65600), 256) == 2
     assert k(B.make_config(1, 32, 32, 65600), 16384) == 2

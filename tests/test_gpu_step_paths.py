@@ -43,9 +43,8 @@ def _clear_checksums(ws, units):
     ctl[:, 14:16] = 0
 
 
-def _step(gu, wl, flags, append=True, form=2):
-    """One fused step issued kernel by kernel with test flags: form 2 = scoring kernel, then threshold + attention in
-    one kernel; form 1 = the whole step in one launch.  The index list comes from its own kernel in both."""
+def _step(gu, wl, flags, append=True):
+    """One fused step issued kernel by kernel with test flags on the second one."""
     dw = gu.DeviceWorkload(wl)
     B.quantize_keys(dw.cfg, dw.cache)
     mb = int(wl.budgets.max())
@@ -57,8 +56,7 @@ def _step(gu, wl, flags, append=True, form=2):
     ws = dw.workspace(mb)
     args = (dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt, ws)
     _clear_checksums(ws, wl.units)
-    phases = (1, 2 + 16 * flags, 3 + 16 * flags) if form == 2 else (4 + 16 * flags, 3 + 16 * flags)
-    for p in phases:                                  # + 16 f: these forms whatever the shape
+    for p in (1, 2 + 16 * flags, 3 + 16 * flags):     # + 16 f: the two-kernel form whatever the shape
         B.decode_step_phase(*args, p)
     torch.cuda.synchronize()
     return out.cpu().numpy()[0], idx.cpu().numpy()[0], cnt.cpu().numpy()[0], _ctl_checksums(ws, wl.units)
@@ -83,32 +81,28 @@ WORKLOADS = [
 ]
 
 
-@pytest.mark.parametrize("form", [2, 1], ids=["two_kernels", "one_launch"])
 @pytest.mark.parametrize("name,make", WORKLOADS, ids=[w[0] for w in WORKLOADS])
-def test_attended_rows_are_the_reported_selection(gu, oracle, name, make, form):
+def test_attended_rows_are_the_reported_selection(gu, oracle, name, make):
     wl = make()
-    if form == 1 and wl.n_rep > 2:
-        pytest.skip("the one-launch form is built for one or two query heads per kv head")
-    print(f"[step paths] {name} form {form}", flush=True)
+    print(f"[step paths] {name}", flush=True)
     r = oracle_step(oracle, wl, append=True)
-    out, idx, cnt, sums = _step(gu, wl, CHECKSUMS, form=form)
+    out, idx, cnt, sums = _step(gu, wl, CHECKSUMS)
     check_index_sets(idx, cnt, r["idx"], r["count"], r["scores"], r["L"])
     _check_sums(idx, cnt, sums)
     want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
                             np.ascontiguousarray(np.where(idx < 0, 0, idx)), cnt, 4)
     assert np.abs(out - want).max() <= 2e-3
     # the fallback: nobody picks up the threshold, the merging workgroup attends over every threshold-bin row
-    out2, idx2, cnt2, sums2 = _step(gu, wl, CHECKSUMS | FORCE_LATE, form=form)
+    out2, idx2, cnt2, sums2 = _step(gu, wl, CHECKSUMS | FORCE_LATE)
     assert np.array_equal(idx2, idx) and np.array_equal(cnt2, cnt)
     _check_sums(idx2, cnt2, sums2)
     assert np.abs(out2 - want).max() <= 2e-3
     assert np.abs(out2 - out).max() <= 1e-5 * max(1.0, float(np.abs(out).max()))
 
 
-@pytest.mark.parametrize("form", [2, 1], ids=["two_kernels", "one_launch"])
 @pytest.mark.parametrize("kind", ["zero_query", "zero_keys", "zero_keys_then_append"])
 @pytest.mark.parametrize("flags", [CHECKSUMS, CHECKSUMS | FORCE_LATE])
-def test_zero_score_range(gu, oracle, kind, flags, form):
+def test_zero_score_range(gu, oracle, kind, flags):
     """R = sum_c |q_c| absmax_c = 0: the histogram has no width, every score is exactly zero and the ties go to the
     lowest token indices (a unit with a live query sits next to the degenerate one)."""
     wl = synth.make_workload("r0", 77, 2, 4, 2, [1500, 300], [100, 37], F16, n_planted=2)
@@ -120,7 +114,7 @@ def test_zero_score_range(gu, oracle, kind, flags, form):
             wl.k_new[1] = 0
     append = True
     r = oracle_step(oracle, wl, append=append)
-    out, idx, cnt, sums = _step(gu, wl, flags, append=append, form=form)
+    out, idx, cnt, sums = _step(gu, wl, flags, append=append)
     check_index_sets(idx, cnt, r["idx"], r["count"], r["scores"], r["L"])
     _check_sums(idx, cnt, sums)
     u = 0 if kind == "zero_query" else 1
@@ -147,13 +141,11 @@ def test_zero_score_range(gu, oracle, kind, flags, form):
         check_index_sets(i2.cpu().numpy(), c2.cpu().numpy(), r["idx"], r["count"], r["scores"], r["L"])
 
 
-@pytest.mark.parametrize("form", [2, 1], ids=["two_kernels", "one_launch"])
-def test_hand_off_between_workgroups_is_stable_over_many_launches(gu, oracle, form):
+def test_hand_off_between_workgroups_is_stable_over_many_launches(gu, oracle):
     """Many units, many small workgroups per unit (a budget near the context makes every 1024-token range a workgroup
     of its own), a few hundred launches on one workspace: the candidates, the threshold word, the flags and the
-    partials all cross workgroups through memory (in the one-launch form the scores, the histogram and the appended
-    rows as well), so a stale read would show as a launch that differs from the first.  The first launch is checked
-    against the oracle."""
+    partials all cross workgroups through memory, so a stale read would show as a launch that differs from the
+    first.  The first launch is checked against the oracle."""
     lens = [6100 + 517 * (i % 5) for i in range(16)]
     buds = [int(0.45 * l) for l in lens]
     wl = synth.make_workload("handoff", 55, 16, 4, 4, lens, buds, F16, n_planted=8)
@@ -170,13 +162,11 @@ def test_hand_off_between_workgroups_is_stable_over_many_launches(gu, oracle, fo
     first = None
     # a priming launch: the first append raises the unit's per-channel bound, and with it the histogram's range and the
     # split of a workgroup's rows into sure ones and candidates (hence the order they are summed in) for later launches
-    for p in ((1, 2, 3) if form == 2 else (4, 3)):
-        B.decode_step_phase(dw.cfg, [dw.cache], q, kn, vn, dw.budgets, mb, out, idx, cnt, ws, p)
+    B.decode_step(dw.cfg, [dw.cache], q, kn, vn, dw.budgets, mb, out, idx, cnt, ws)
     for it in range(300):
         out.fill_(float("nan"))
         # every launch appends the same row at the same place (seq_lens is the caller's and stays as it is)
-        for p in ((1, 2, 3) if form == 2 else (4, 3)):
-            B.decode_step_phase(dw.cfg, [dw.cache], q, kn, vn, dw.budgets, mb, out, idx, cnt, ws, p)
+        B.decode_step(dw.cfg, [dw.cache], q, kn, vn, dw.budgets, mb, out, idx, cnt, ws)
         torch.cuda.synchronize()
         got = (out.clone(), idx.clone(), cnt.clone())
         if first is None:
@@ -190,35 +180,3 @@ def test_hand_off_between_workgroups_is_stable_over_many_launches(gu, oracle, fo
             assert torch.equal(got[1], first[1]) and torch.equal(got[2], first[2]), f"selection differs at launch {it}"
             assert torch.equal(got[0], first[0]), f"output differs at launch {it}"
 
-
-def test_one_launch_form_reports_scores_that_never_arrived(gu, oracle):
-    """The one-launch form's only wait without a fallback: a unit's selecting workgroups wait for its scoring
-    workgroups.  With test flag 4 the scoring workgroups do not report and the others give up after a few polls (every
-    workgroup still exits normally): the caller must see NaN outputs and counts of -1, not a plausible wrong result.
-    After re-zeroing the workspace and rebuilding the packed cache an ordinary step is right again."""
-    STARVE = 4
-    wl = synth.make_workload("starve", 91, 2, 8, 4, [3000, 1777], [300, 200], F16, n_planted=4)
-    dw = gu.DeviceWorkload(wl)
-    B.quantize_keys(dw.cfg, dw.cache)
-    mb = int(wl.budgets.max())
-    out = torch.zeros((1, wl.units, wl.n_rep, 128), dtype=torch.float32, device="cuda")
-    idx = torch.full((1, wl.units, mb), -1, dtype=torch.int32, device="cuda")
-    cnt = torch.zeros((1, wl.units), dtype=torch.int32, device="cuda")
-    ws = dw.workspace(mb)
-    q, kn, vn = dw.q[None].contiguous(), dw.k_new[None].contiguous(), dw.v_new[None].contiguous()
-    args = (dw.cfg, [dw.cache], q, kn, vn, dw.budgets, mb, out, idx, cnt, ws)
-    B.decode_step_phase(*args, 4 + 16 * STARVE)
-    torch.cuda.synchronize()
-    assert torch.isnan(out).all()
-    assert (cnt == -1).all()
-    # recovery as the header prescribes
-    ws.zero_()
-    B.quantize_keys(dw.cfg, dw.cache)
-    B.decode_step(*args)
-    torch.cuda.synchronize()
-    r = oracle_step(oracle, wl, append=True)
-    idx_g, cnt_g = idx.cpu().numpy()[0], cnt.cpu().numpy()[0]
-    check_index_sets(idx_g, cnt_g, r["idx"], r["count"], r["scores"], r["L"])
-    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
-                            np.ascontiguousarray(np.where(idx_g < 0, 0, idx_g)), cnt_g, 4)
-    assert np.abs(out.cpu().numpy()[0] - want).max() <= 2e-3
