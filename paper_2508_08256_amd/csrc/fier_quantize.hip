@@ -301,6 +301,11 @@ hipError_t launch_quantize(int dtype, KvLayout lay, const void* K, uint32_t* kbi
   const int rounds = (bpw + 11) / 12;
   bpw = (bpw + rounds - 1) / rounds;
   if (bpw >= 4 && (bpw & (bpw - 1)) == 0) ++bpw;
+  // Nine blocks per wavefront wherever that still leaves a workgroup per CU: measured best at every large shape
+  // (config-2 shape, us: 88 at 5, 86 at 7, 78 at 9, 81 at 10, 85 at 11, 82 at 17; the 128k shape gets 9 from the
+  // rule above anyway).  The differences between neighbouring values are strides between the concurrently streaming
+  // workgroups (bpw x 64 KiB) meeting the memory channels differently.
+  if (bpw < 9 && (long)n_pairs * units >= 4L * 9 * 256) bpw = 9;
   dim3 grid((n_pairs + 4 * bpw - 1) / (4 * bpw), units);
   if (dtype == DT_F16)
     launch_quantize_dt<DT_F16>(lay, (const uint32_t*)K, kbits, kmeta, kabsmax, seq_lens, units, n_kv_heads, max_ctx, ns,
