@@ -497,6 +497,8 @@ def measure(args, workload, budget_arg, detail):
         "achieved_GBps": round(achieved, 1),
         "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
         "us_per_step_wall": round(us_wall, 3),
+        "timed_step_outputs": "attention output and kept-up-to-date caches (idx_out / count_out NULL: the ascending "
+                              "index list is an optional output; the same loop with it: us_per_layer_with_index_list)",
         "us_per_layer_with_index_list": None if us_step_idx is None else round(us_step_idx / NL, 3),
         "single_step_us": {"min": round(float(single.min()), 3), "median": round(float(np.median(single)), 3),
                            "p95": round(float(np.percentile(single, 95)), 3), "n": int(len(single))},
