@@ -704,16 +704,21 @@ __global__ __launch_bounds__(kStepThreads) void step_emit_idx_kernel(const float
 // Workgroups of the step's second kernel that a 256-CU chip holds at once (the kernel's second launch bound).
 static long step_resident_wgs(int n_rep) { return 256L * (n_rep <= 2 ? 5 : (n_rep <= 4 ? 4 : (n_rep <= 6 ? 3 : 2))); }
 
-// Ranges per workgroup of the one-launch form: at least 120 selected rows per workgroup (rows per 1024-token range
-// = 1024 * budget / context; measured on 32 units of 32k tokens with 112 rows per range: 34.6 us per step with one
-// range per workgroup, 33.6 with two, 38.1 with four), and more than that where fewer, larger workgroups make the
-// grid resident at once.
+// Ranges per workgroup of the one-launch form (rows per 1024-token range = 1024 * budget / context):
+//   * at least 96 selected rows per workgroup;
+//   * more where fewer, larger workgroups make the grid resident at once;
+//   * and twice as many where that still leaves two workgroups per CU and at most 288 rows per workgroup.  Measured
+//     (us per step): 32 units x 32k, 112 rows per range: 35.0 with one range per workgroup, 34.0 with two, 38.1 with
+//     four; 32 units x 16k (two ranges = one workgroup per CU): 25.8 / 27.4; 32 units x 64k, B = 7209: 50.9 with two
+//     ranges (225 rows), 51.5 with four; 64 units x 32k: 50.6 with two, 51.9 with four.
 int step_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx) {
   const double per_range = 1024.0 * (double)max_budget / (double)max_ctx;
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  auto wgs = [&](int r) { return (long)units * ((n_ranges + r - 1) / r); };
   int rpw = 1;
-  while (rpw < 8 && per_range * rpw < 120.0) rpw *= 2;
-  while (rpw < 8 && (long)units * ((n_ranges + rpw - 1) / rpw) > step_resident_wgs(n_rep)) rpw *= 2;
+  while (rpw < 8 && per_range * rpw < 96.0) rpw *= 2;
+  while (rpw < 8 && wgs(rpw) > step_resident_wgs(n_rep)) rpw *= 2;
+  if (rpw < 8 && per_range * (2 * rpw) <= 288.0 && wgs(2 * rpw) >= 512) rpw *= 2;
   return rpw;
 }
 
