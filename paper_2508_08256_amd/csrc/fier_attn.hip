@@ -316,13 +316,24 @@ static hipError_t launch_select_attend_dt(KvLayout lay, int n_rep, const StepBuf
   return hipGetLastError();
 }
 
-int select_attend_ranges_per_wg(int max_budget, int max_ctx) {
-  // at least 120 selected rows per workgroup (rows per 1024-token range = 1024 * budget / context).  Measured:
-  // 128 rows at the 4 x 32 / 8-head 128k shape 26.8 us against 34.4 us at 64 rows and 29.4 us at 256; 226 rows on the
-  // ragged 16-sequence batch 61.8 us against 63.7 us at 113
+// Ranges per workgroup (rows per 1024-token range = 1024 * budget / context): at least 96 selected rows per workgroup,
+// and twice that -- up to 288 rows -- where the grid is far beyond what the chip holds at once (more than two rounds)
+// or a unit has more than 64 workgroups (its merge then reads that many partials).  Measured (us per step; 32 query
+// / 8 kv heads): batch 16 x 16k at 11 % 67.2 -> 61.1, batch 8 x 64k 110.8 -> 105.4, the ragged 16-sequence batch
+// 63.7 -> 61.8 (this kernel), batch 1 x 128k at 11 % 48.3 -> 46.0 with twice the ranges; but batch 1 x 32k 28.0 ->
+// 30.6, batch 2 x 32k (24 query heads) 32.2 -> 34.0, batch 4 x 32k 41.7 -> 42.5, and the 4 x 128k shape at B = 4096
+// 26.8 -> 29.4 (this kernel) -- grids of about one round -- lose by it, as does halving (64 rows: 34.4).
+int select_attend_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx) {
   const double per_range = 1024.0 * (double)max_budget / (double)max_ctx;
+  const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
+  const long capacity = 256L * (n_rep >= 3 ? 4 : 7);  // workgroups of this kernel resident at once
   int rpw = 1;
-  while (rpw < 8 && per_range * rpw < 120.0) rpw *= 2;
+  while (rpw < 8 && per_range * rpw < 96.0) rpw *= 2;
+  while (rpw < 8 && per_range * (2 * rpw) <= 288.0) {
+    const long per_unit = (n_ranges + rpw - 1) / rpw;
+    if (per_unit * units <= 2 * capacity && per_unit <= 64) break;
+    rpw *= 2;
+  }
   return rpw;
 }
 
@@ -333,7 +344,7 @@ hipError_t launch_select_attend(int dtype, KvLayout lay, int n_rep, const StepBu
 #define FIER_SA_RPW(DT, RPW)                                                                                        \
   return launch_select_attend_dt<DT, RPW>(lay, n_rep, sb, K, V, q, seq_lens, extra, max_budget, sm_scale, idx_out, out, \
                                           kabsmax, units, n_kv_heads, max_ctx, st)
-  const int rpw = select_attend_ranges_per_wg(max_budget, max_ctx);
+  const int rpw = select_attend_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   if (dtype == DT_F16) {
     if (rpw == 1) FIER_SA_RPW(DT_F16, 1);
     if (rpw == 2) FIER_SA_RPW(DT_F16, 2);
