@@ -232,18 +232,18 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
  * score histogram) the step takes one of two forms, chosen from cfg and max_budget alone; fier_decode_step_kernels
  * returns the number of kernels of the form a shape gets (not counting the optional index-list kernel), 0 for an
  * invalid configuration:
- *   2 kernels, with one or two query heads per kv head and all workgroups of the second kernel resident on the GPU at
- *     once: phase 2 = exact threshold + attention over the selected rows + merge in one launch; phase 3 = the
- *     ascending index list (launched by the step only if idx_out is given; may be repeated);
- *   3 kernels otherwise: phase 2 = exact threshold, phase 3 = selection + attention + merge, which also writes
- *     idx_out (may be repeated).
+ *   2 kernels, with one or two query heads per kv head, or with a second kernel of at most twice the workgroups
+ *     the GPU holds at once: phase 2 = exact threshold + attention over the selected rows + merge in one launch;
+ *     phase 3 = the ascending index list (launched by the step only if idx_out is given; may be repeated);
+ *   3 kernels otherwise (three or more query heads per kv head on longer grids): phase 2 = exact threshold,
+ *     phase 3 = selection + attention + merge, which also writes idx_out (may be repeated).
  * Same arguments as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and
  * these layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
  * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with one
  * phase 2 before the next real step), phase 2 only after a phase 1.  Phases 2 + 16 f and 3 + 16 f, f = 1..3, are for
  * tests: the two-kernel form whatever the shape, its second kernel with flags f (1: no workgroup picks up the
  * threshold itself, the merging workgroup attends over all threshold-bin rows; 2: checksums of the attended rows in
- * the control blocks).
+ * the control blocks); phases 2 + 64 and 3 + 64: the three-kernel form whatever the shape.
  */
 int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget);
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,

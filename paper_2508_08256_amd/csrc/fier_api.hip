@@ -192,7 +192,7 @@ size_t fier_workspace_scores_offset(const fier_config* cfg, int32_t max_budget) 
 int fier_decode_step_kernels(const fier_config* cfg, int32_t max_budget) {
   if (check_cfg(cfg) != FIER_OK || max_budget < 1) return 0;
   if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
-  return fier::step_is_resident(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx) ? 2 : 3;
+  return fier::step_two_kernel_form(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx) ? 2 : 3;
 }
 
 int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* stream) {
@@ -308,9 +308,10 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
   if ((k_new == nullptr) != (v_new == nullptr)) return FIER_EINVAL;
   if ((idx_out == nullptr) != (count_out == nullptr)) return FIER_EINVAL;
   // phase -1: validate only; 0: the whole step; 1, 2, 3: one kernel; 2 + 16 f, 3 + 16 f: kernels 2, 3 of the
-  // two-kernel form with test flags f
-  if (max_budget > cfg->max_ctx || phase < -1 || phase > 3 + 16 * 3 || (phase > 3 && (phase & 15) != 2 && (phase & 15) != 3))
-    return FIER_EINVAL;
+  // two-kernel form with test flags f; 2 + 64, 3 + 64: kernels 2, 3 of the three-kernel form
+  const bool phase_ok = (phase >= -1 && phase <= 3) ||
+                        (phase > 3 && ((phase & 15) == 2 || (phase & 15) == 3) && (phase >> 4) <= 4);
+  if (max_budget > cfg->max_ctx || !phase_ok) return FIER_EINVAL;
   if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new) || misaligned(idx_out))
     return FIER_EALIGN;
   for (int l = 0; l < n_layers; ++l) {
@@ -360,11 +361,12 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
                              cfg->max_ctx, cfg->group_size, s);
       if (e != hipSuccess) return FIER_EHIP;
     }
-    // After scoring: one launch (exact threshold + attention + merge, then the index list if asked for) when all its
-    // workgroups are resident at once; longer grids take the threshold kernel and the selection + attention kernel,
-    // whose workgroups never wait for each other.
-    const bool one_launch = fier::step_is_resident(units, n_rep, max_budget, cfg->max_ctx) || (phase >> 4) != 0;
-    if (one_launch) {
+    // After scoring: one launch (exact threshold + attention + merge, then the index list if asked for) wherever
+    // that measured faster; grouped-query grids too long to be resident at once take the threshold kernel and the
+    // selection + attention kernel, whose workgroups never wait for each other.
+    const bool two_kernels =
+        phase > 3 ? (phase >> 4) <= 3 : fier::step_two_kernel_form(units, n_rep, max_budget, cfg->max_ctx);
+    if (two_kernels) {
       if (phase == 0 || (phase & 15) == 2) {
         e = fier::launch_step_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, budgets,
                                      max_budget, cfg->sm_scale, cntl, outl, c->kabsmax, units, cfg->n_kv_heads,
@@ -377,12 +379,12 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
         if (e != hipSuccess) return FIER_EHIP;
       }
     } else {
-      if (phase == 0 || phase == 2) {
+      if (phase == 0 || (phase & 15) == 2) {
         e = fier::launch_threshold(w.sb, c->seq_lens, extra, budgets, max_budget, cntl, units, cfg->n_kv_heads,
                                    cfg->max_ctx, s);
         if (e != hipSuccess) return FIER_EHIP;
       }
-      if (phase == 0 || phase == 3) {
+      if (phase == 0 || (phase & 15) == 3) {
         e = fier::launch_select_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, max_budget,
                                        cfg->sm_scale, idxl, outl, c->kabsmax, units, cfg->n_kv_heads, cfg->max_ctx, s);
         if (e != hipSuccess) return FIER_EHIP;

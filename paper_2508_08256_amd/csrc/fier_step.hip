@@ -629,9 +629,11 @@ __device__ __forceinline__ void step_unit_wg(const StepArgs& a, int id_x, int id
 
 // grid: wgs_per_unit workgroups per unit (dispatch order given by `order`), block 256.
 // (the second launch bound asks the compiler for the registers-per-thread that let 5 / 4 / 3 / 2 workgroups share a
-// CU: the gather wants many rows in flight per CU more than it wants registers)
+// CU: the gather wants many rows in flight per CU more than it wants registers -- but not at the price of spills:
+// with 4 query heads per kv head a bound of 4 left 60 bytes of scratch per lane and cost 3 to 5 us per step)
+constexpr int step_wgs_per_cu(int n_rep) { return n_rep <= 2 ? 5 : (n_rep <= 3 ? 4 : (n_rep <= 5 ? 3 : 2)); }
 template <int DT, int NREP, int RPW>
-__global__ __launch_bounds__(kStepThreads, NREP <= 2 ? 5 : (NREP <= 4 ? 4 : (NREP <= 6 ? 3 : 2))) void step_attend_kernel(
+__global__ __launch_bounds__(kStepThreads, step_wgs_per_cu(NREP)) void step_attend_kernel(
     const StepArgs a) {
   __shared__ StepLds<NREP, RPW> lds;
   int unit, wg;
@@ -702,7 +704,7 @@ __global__ __launch_bounds__(kStepThreads) void step_emit_idx_kernel(const float
 }
 
 // Workgroups of the step's second kernel that a 256-CU chip holds at once (the kernel's second launch bound).
-static long step_resident_wgs(int n_rep) { return 256L * (n_rep <= 2 ? 5 : (n_rep <= 4 ? 4 : (n_rep <= 6 ? 3 : 2))); }
+static long step_resident_wgs(int n_rep) { return 256L * step_wgs_per_cu(n_rep); }
 
 // Ranges per workgroup of the one-launch form (rows per 1024-token range = 1024 * budget / context):
 //   * at least 96 selected rows per workgroup;
@@ -824,14 +826,20 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 #undef FIER_STEP_RPW
 }
 
-// Whether the one-launch form (step_attend_kernel) suits this shape: all its workgroups resident at once.
-bool step_is_resident(int units, int n_rep, int max_budget, int max_ctx) {
-  // measured: with 3+ query heads per kv head the three-kernel form is the faster one (8 units of 131072 tokens,
-  // 4 heads per kv head: 24 us against 31 us after the score kernel)
-  if (n_rep > 2) return false;
+// Whether the step's second part is one launch (step_attend_kernel) for this shape.
+bool step_two_kernel_form(int units, int n_rep, int max_budget, int max_ctx) {
+  // Measured against the threshold kernel + selection-and-attention kernel (us per step, fp16, budget = 11 % of the
+  // context unless noted): with 4 query heads per kv head, 8 units x 32k 25.8 / 28.5, 64 x 32k 57.0 / 62.0, 128 x 32k
+  // 95.7 / 108.8, 32 x 128k (budget 4096) 65.7 / 71.5, and on grids that are not resident at once 64 x 128k 121.2 /
+  // 118.0, 256 x 32k 194.2 / 191.9; with one query head per kv head on such grids 256 x 128k 391 / 425, 2048 x 4k
+  // 194 / 215, 1024 x 32k 664 / 698, 512 x 32k 341 / 348, 1024 x 8k 214 / 206.
+  //   On the ragged batch of 128 such units x 8k..64k (budget 11 % of each length), whose grid at full length is 1.5
+  //   times the resident one: 107 / 117.  Hence: always with 1 or 2 query heads per kv head; with more, up to twice
+  //   the resident grid.
+  if (n_rep <= 2) return true;
   const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
-  return (long)units * ((n_ranges + rpw - 1) / rpw) <= step_resident_wgs(n_rep);
+  return (long)units * ((n_ranges + rpw - 1) / rpw) <= 2 * step_resident_wgs(n_rep);
 }
 
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,

@@ -91,8 +91,12 @@ def _run_case(gu, oracle, seed, rng, big):
         cnt = torch.full((1, wl.units), -1, dtype=torch.int32, device="cuda")
         kn = gu.to_dev(kn_w, dtype)[None].contiguous() if c["append"] else None
         vn = gu.to_dev(vn_w, dtype)[None].contiguous() if c["append"] else None
-        B.decode_step(dw.cfg, [dw.cache], gu.to_dev(q_w, dtype)[None].contiguous(), kn, vn, dw.budgets, mb, out, idx,
-                      cnt, ws)
+        args = (dw.cfg, [dw.cache], gu.to_dev(q_w, dtype)[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt, ws)
+        if seed % 3 == 2:    # the three-kernel form (the one long grouped-query grids take), whatever the shape
+            for p in (1, 2 + 64, 3 + 64):
+                B.decode_step_phase(*args, p)
+        else:
+            B.decode_step(*args)
         torch.cuda.synchronize()
         # the oracle, step by step, with the same group size
         if c["append"]:

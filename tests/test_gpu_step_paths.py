@@ -7,6 +7,7 @@ and a direct check of WHICH rows it attended over.
 * With test flag 1 no workgroup picks up the published threshold: all threshold-bin rows are then attended over by the
   merging workgroup's fallback.  Same selection, same checksums, output equal to the ordinary path up to summation order.
 * R = 0 (a zero query, or an all-zero key cache): every score is zero, the budget goes to the lowest indices.
+* The three-kernel form (threshold kernel, then selection + attention) on shapes whose step takes the two-kernel one.
 * The hand-off between workgroups (candidates, threshold word, partials) repeated over a few hundred launches with many
   small workgroups per unit: every launch must reproduce the first one bit for bit.
 """
@@ -22,6 +23,7 @@ from paper_2508_08256_amd import synth  # noqa: E402
 pytestmark = pytest.mark.gpu
 F16, BF16 = 0, 1
 FORCE_LATE, CHECKSUMS = 1, 2
+THREE_KERNELS = 4     # phases 2 + 64, 3 + 64
 
 
 @pytest.fixture(scope="module")
@@ -56,7 +58,8 @@ def _step(gu, wl, flags, append=True):
     ws = dw.workspace(mb)
     args = (dw.cfg, [dw.cache], dw.q[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt, ws)
     _clear_checksums(ws, wl.units)
-    for p in (1, 2 + 16 * flags, 3 + 16 * flags):     # + 16 f: the two-kernel form whatever the shape
+    # + 16 f, f = 1..3: the two-kernel form whatever the shape; + 64: the three-kernel form whatever the shape
+    for p in (1, 2 + 16 * flags, 3 + 16 * flags):
         B.decode_step_phase(*args, p)
     torch.cuda.synchronize()
     return out.cpu().numpy()[0], idx.cpu().numpy()[0], cnt.cpu().numpy()[0], _ctl_checksums(ws, wl.units)
@@ -98,6 +101,19 @@ def test_attended_rows_are_the_reported_selection(gu, oracle, name, make):
     _check_sums(idx2, cnt2, sums2)
     assert np.abs(out2 - want).max() <= 2e-3
     assert np.abs(out2 - out).max() <= 1e-5 * max(1.0, float(np.abs(out).max()))
+
+
+@pytest.mark.parametrize("name,make", WORKLOADS, ids=[w[0] for w in WORKLOADS])
+def test_three_kernel_form_on_any_shape(gu, oracle, name, make):
+    """The form long grouped-query grids take, forced on small shapes: same selection, same output bar."""
+    wl = make()
+    print(f"[step paths, three kernels] {name}", flush=True)
+    r = oracle_step(oracle, wl, append=True)
+    out, idx, cnt, _ = _step(gu, wl, THREE_KERNELS)
+    check_index_sets(idx, cnt, r["idx"], r["count"], r["scores"], r["L"])
+    want = oracle.attention(r["K"], r["V"], wl.q, r["L"], r["sm_scale"], wl.dtype,
+                            np.ascontiguousarray(np.where(idx < 0, 0, idx)), cnt, 4)
+    assert np.abs(out - want).max() <= 2e-3
 
 
 @pytest.mark.parametrize("kind", ["zero_query", "zero_keys", "zero_keys_then_append"])
