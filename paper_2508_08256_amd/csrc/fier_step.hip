@@ -365,22 +365,52 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     const uint32_t packed = (uint32_t)__builtin_popcount(dmask) | ((uint32_t)__builtin_popcount(cmask) << 16);
     const uint32_t at = block_excl_scan_u32<4>(packed, scan_tmp, listed);
     uint32_t pd = at & 0xffffu, pc = at >> 16;
+    if constexpr (RPW >= 2) {
+      // the few tokens of a thread that are listed, by their bits (ascending bit = ascending token): a thread holds
+      // 4 RPW tokens of which a few per cent are selected, so walking the set bits beats 4 RPW predicated blocks
+      // (measured: 1.9 us of 67 at 8 ranges per workgroup, 0.3 of 34.5 at two; with one range the blocks are faster)
+      for (uint32_t m = dmask; m; m &= m - 1u) {
+        const uint32_t bit = (uint32_t)__builtin_ctz(m);
+        rows[pd++] = (uint16_t)((bit >> 2) * (uint32_t)kRangeTokens + 4u * (uint32_t)tid + (bit & 3u));
+      }
+      for (uint32_t m = cmask; m; m &= m - 1u) {
+        const uint32_t bit = (uint32_t)__builtin_ctz(m);
+        float x = 0.f;  // the token's score, picked from the registers without indexing them
 #pragma unroll
-    for (int rr = 0; rr < RPW; ++rr) {
-      const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
+        for (int rr = 0; rr < RPW; ++rr) {
+          x = bit == 4u * rr ? v[rr].x : x;
+          x = bit == 4u * rr + 1u ? v[rr].y : x;
+          x = bit == 4u * rr + 2u ? v[rr].z : x;
+          x = bit == 4u * rr + 3u ? v[rr].w : x;
+        }
+        const uint32_t off = (bit >> 2) * (uint32_t)kRangeTokens + 4u * (uint32_t)tid + (bit & 3u);
+        const uint32_t key = score_key(x);
+        if (pc < (uint32_t)kCandLds) {
+          coff[pc] = (uint16_t)off;
+          ckey[pc] = key;
+        }
+        if (pc < (uint32_t)SEGCAP)
+          store_coherent(&ucand[(size_t)pc * nc + wg], ((unsigned long long)key << 32) | (uint32_t)(tok0 + (int)off));
+        ++pc;
+      }
+    } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t off = (uint32_t)(rr * kRangeTokens + 4 * tid + j);
-        if (dmask >> (4 * rr + j) & 1u) rows[pd++] = (uint16_t)off;
-        if (cmask >> (4 * rr + j) & 1u) {
-          const uint32_t key = score_key(vv[j]);
-          if (pc < (uint32_t)kCandLds) {
-            coff[pc] = (uint16_t)off;
-            ckey[pc] = key;
+      for (int rr = 0; rr < RPW; ++rr) {
+        const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t off = (uint32_t)(rr * kRangeTokens + 4 * tid + j);
+          if (dmask >> (4 * rr + j) & 1u) rows[pd++] = (uint16_t)off;
+          if (cmask >> (4 * rr + j) & 1u) {
+            const uint32_t key = score_key(vv[j]);
+            if (pc < (uint32_t)kCandLds) {
+              coff[pc] = (uint16_t)off;
+              ckey[pc] = key;
+            }
+            if (pc < (uint32_t)SEGCAP)
+              store_coherent(&ucand[(size_t)pc * nc + wg], ((unsigned long long)key << 32) | (uint32_t)(tok0 + (int)off));
+            ++pc;
           }
-          if (pc < (uint32_t)SEGCAP)
-            store_coherent(&ucand[(size_t)pc * nc + wg], ((unsigned long long)key << 32) | (uint32_t)(tok0 + (int)off));
-          ++pc;
         }
       }
     }
