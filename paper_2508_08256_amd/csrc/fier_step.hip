@@ -314,9 +314,11 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
   float4 v[RPW];
 #pragma unroll
   for (int rr = 0; rr < RPW; ++rr) {
+    // i + 3 < max_ctx; entries >= n are masked below.  A thread past the end loads the unit's first scores instead of
+    // branching round the load: with branches the compiler cannot count the loads in flight and waits for all of them
+    // before the histogram scan below, which needs none of them
     const int i = tok0 + rr * kRangeTokens + 4 * tid;
-    v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n) v[rr] = *reinterpret_cast<const float4*>(s_unit + i);  // i + 3 < max_ctx; entries >= n are masked below
+    v[rr] = *reinterpret_cast<const float4*>(s_unit + (i < n ? i : 0));
   }
   B = B > a.max_budget ? a.max_budget : B;
   B = B > n ? n : B;
