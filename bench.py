@@ -327,12 +327,16 @@ def measure(args, workload, budget_arg, detail):
 
     # ---- each kernel of the fused step alone (HIP events on the launch stream, rotating caches) ----------
     # argument tuples per layer cache, prepared once (slicing tensors inside the timed loop would make it CPU-bound)
+    # (the kernels of the form the timed step takes: without the index list; the list kernel of the two-kernel form
+    # is timed with the list given, where a call with the list takes that form too)
     largs = [[(cfg, caches[r][l:l + 1], qs[r][l:l + 1], kns[r][l:l + 1], vns[r][l:l + 1], budgets, budget,
-               out[l:l + 1], idx[l:l + 1], cnt[l:l + 1], wss[r][l]) for l in range(NL)] for r in range(R)]
+               out[l:l + 1], None, None, wss[r][l]) for l in range(NL)] for r in range(R)]
+    largs_list = [[a[:8] + (idx[l:l + 1], cnt[l:l + 1]) + a[10:] for l, a in enumerate(la)] for la in largs]
+    list_kernel = n_kernels == 2 and B.decode_step_kernels(cfg, budget, True) == 2
 
-    def phase(*ps):
+    def phase(*ps, with_list=False):
         def run(i):
-            for a in largs[i % R]:
+            for a in (largs_list if with_list else largs)[i % R]:
                 for p in ps:
                     B.decode_step_phase(*a, p)
         return run
@@ -342,16 +346,20 @@ def measure(args, workload, budget_arg, detail):
     torch.cuda.synchronize()
 
     # The first kernel adds into the unit histograms that the second consumes and clears, so the second cannot be
-    # repeated alone: it is timed as (first + second) - (first).  In the three-kernel form (grids that are not
-    # resident at once) the third kernel only reads what the second left and is timed alone; in the two-kernel form
-    # the third is the optional index-list kernel, also timed alone.
+    # repeated alone: it is timed as (first + second) - (first).  In the three-kernel form the third kernel only
+    # reads what the second left and is timed alone; in the two-kernel form the third is the optional index-list
+    # kernel, also timed alone (null where a call that asks for the list takes the three-kernel form instead).
     nw = 12 if NL == 1 else 2
     us_k1, _ = timed(phase(1), ns, nw)
     for r in range(R):
         phase(2)(r)                       # clears the accumulated histograms
     us_k12, _ = timed(phase(1, 2), ns, nw)
     us_k2 = us_k12 - us_k1
-    us_k3, _ = timed(phase(3), ns, nw)
+    us_k3 = None
+    if n_kernels == 3:
+        us_k3, _ = timed(phase(3), ns, nw)
+    elif list_kernel:
+        us_k3, _ = timed(phase(3, with_list=True), ns, nw)
 
     # layer (r, l) of the flattened cache list, for the per-layer calls
     flat = [(r, l) for r in range(R) for l in range(NL)]
@@ -372,7 +380,8 @@ def measure(args, workload, budget_arg, detail):
     if n_kernels == 2:
         dom_name, us_dom = "step_attend_kernel (exact threshold, gather attention, merge)", us_k2
         kernels_us = {"append_score_hist": round(us_k1 / NL, 3), "threshold_attend_merge": round(us_k2 / NL, 3),
-                      "sum": round((us_k1 + us_k2) / NL, 3), "index_list_optional": round(us_k3 / NL, 3)}
+                      "sum": round((us_k1 + us_k2) / NL, 3),
+                      "index_list_optional": round(us_k3 / NL, 3) if us_k3 is not None else None}
     else:
         dom_name, us_dom = "select_attend_kernel (selection, gather attention, merge)", us_k3
         kernels_us = {"append_score_hist": round(us_k1 / NL, 3), "threshold": round(us_k2 / NL, 3),
@@ -384,7 +393,9 @@ def measure(args, workload, budget_arg, detail):
               "context": L if w["L"] != "ragged" else [int(x) for x in lens],
               "budget": budget if w["budget"] != "11%" else [int(x) for x in buds],
               "group_size": args.group_size, "layers_per_step": NL, "rotating_caches": R * NL,
-              "kernels_per_layer_step": n_kernels, "algorithmic_bytes_per_layer": ab["total"]}
+              "kernels_per_layer_step": n_kernels,
+              "kernels_per_layer_step_with_index_list": B.decode_step_kernels(cfg, budget, True),
+              "algorithmic_bytes_per_layer": ab["total"]}
     if not detail:
         return {"label": w["label"], "us_per_layer": round(us_layer, 3), "achieved_GBps": round(achieved, 1),
                 "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4), "kernels_us": kernels_us,

@@ -229,14 +229,15 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
 
 /*
  * One kernel of fier_decode_step alone, for measurement and tests.  After the first kernel (phase 1: append + score +
- * score histogram) the step takes one of two forms, chosen from cfg and max_budget alone; fier_decode_step_kernels
- * returns the number of kernels of the form a shape gets (not counting the optional index-list kernel), 0 for an
- * invalid configuration:
- *   2 kernels, with one or two query heads per kv head, or with a second kernel of at most twice the workgroups
- *     the GPU holds at once: phase 2 = exact threshold + attention over the selected rows + merge in one launch;
- *     phase 3 = the ascending index list (launched by the step only if idx_out is given; may be repeated);
- *   3 kernels otherwise (three or more query heads per kv head on longer grids): phase 2 = exact threshold,
- *     phase 3 = selection + attention + merge, which also writes idx_out (may be repeated).
+ * score histogram) the step takes one of two forms, chosen from cfg, max_budget and whether idx_out is given;
+ * fier_decode_step_kernels returns the number of kernels of the form a call gets (not counting the optional
+ * index-list kernel; with_index_list != 0: a call with idx_out), 0 for an invalid configuration:
+ *   2 kernels, with one or two query heads per kv head; with more of them if idx_out is null and the second kernel
+ *     has at most twice the workgroups the GPU holds at once: phase 2 = exact threshold + attention over the selected
+ *     rows + merge in one launch; phase 3 = the ascending index list (launched by the step only if idx_out is given;
+ *     may be repeated);
+ *   3 kernels otherwise: phase 2 = exact threshold, phase 3 = selection + attention + merge, which also writes
+ *     idx_out (may be repeated).
  * Same arguments as fier_decode_step.  Phase p works on what phases 1..p-1 of the latest step on this workspace and
  * these layers left behind, so the sequence 1, 2, 3 equals fier_decode_step.  Phase 1 adds its scores to the
  * workspace's histograms and phase 2 consumes and clears them: phase 1 may be repeated for timing (follow it with one
@@ -245,7 +246,7 @@ int fier_decode_step_mixed(const fier_config *cfg, const fier_cache *layers, int
  * threshold itself, the merging workgroup attends over all threshold-bin rows; 2: checksums of the attended rows in
  * the control blocks); phases 2 + 64 and 3 + 64: the three-kernel form whatever the shape.
  */
-int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget);
+int fier_decode_step_kernels(const fier_config *cfg, int32_t max_budget, int32_t with_index_list);
 int fier_decode_step_phase(const fier_config *cfg, const fier_cache *layers, int32_t n_layers, const void *q,
                            const void *k_new, const void *v_new, const int32_t *budgets, int32_t max_budget,
                            float *out, int32_t *idx_out, int32_t *count_out, void *workspace,

@@ -80,7 +80,7 @@ def lib():
         L.fier_workspace_scores_offset.restype = C.c_size_t
         L.fier_workspace_scores_offset.argtypes = [cfgp, i32]
         L.fier_decode_step_kernels.restype = C.c_int
-        L.fier_decode_step_kernels.argtypes = [cfgp, i32]
+        L.fier_decode_step_kernels.argtypes = [cfgp, i32, i32]
         L.fier_status_string.restype = C.c_char_p
         L.fier_status_string.argtypes = [C.c_int]
         L.fier_check_config.restype = C.c_int
@@ -168,10 +168,10 @@ def workspace_scores(cfg: Config, max_budget: int, workspace):
     return workspace[off:off + 4 * n].view(torch.float32).view(cfg.units, cfg.max_ctx)
 
 
-def decode_step_kernels(cfg: Config, max_budget: int) -> int:
-    """2 or 3: the number of kernels fier_decode_step launches per layer for this shape (the optional index-list
-    kernel of the two-kernel form not counted)."""
-    return int(lib().fier_decode_step_kernels(C.byref(cfg), int(max_budget)))
+def decode_step_kernels(cfg: Config, max_budget: int, with_index_list: bool = False) -> int:
+    """2 or 3: the number of kernels fier_decode_step launches per layer for this shape, without or with idx_out
+    (the optional index-list kernel of the two-kernel form not counted)."""
+    return int(lib().fier_decode_step_kernels(C.byref(cfg), int(max_budget), 1 if with_index_list else 0))
 
 
 def make_workspace(cfg: Config, max_budget: int):

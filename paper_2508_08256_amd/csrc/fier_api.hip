@@ -189,10 +189,10 @@ size_t fier_workspace_scores_offset(const fier_config* cfg, int32_t max_budget) 
   return static_cast<size_t>(reinterpret_cast<char*>(w.sb.scores) - base);
 }
 
-int fier_decode_step_kernels(const fier_config* cfg, int32_t max_budget) {
+int fier_decode_step_kernels(const fier_config* cfg, int32_t max_budget, int32_t with_index_list) {
   if (check_cfg(cfg) != FIER_OK || max_budget < 1) return 0;
   if (max_budget > cfg->max_ctx) max_budget = cfg->max_ctx;
-  return fier::step_two_kernel_form(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx) ? 2 : 3;
+  return fier::step_two_kernel_form(units_of(cfg), n_rep_of(cfg), max_budget, cfg->max_ctx, with_index_list != 0) ? 2 : 3;
 }
 
 int fier_quantize_keys(const fier_config* cfg, const fier_cache* cache, void* stream) {
@@ -362,10 +362,12 @@ static int decode_step_impl(const fier_config* cfg, const fier_cache* layers, in
       if (e != hipSuccess) return FIER_EHIP;
     }
     // After scoring: one launch (exact threshold + attention + merge, then the index list if asked for) wherever
-    // that measured faster; grouped-query grids too long to be resident at once take the threshold kernel and the
-    // selection + attention kernel, whose workgroups never wait for each other.
+    // that measured faster; grouped-query shapes take the threshold kernel and the selection + attention kernel,
+    // whose workgroups never wait for each other, on grids far beyond the resident one and whenever the index list
+    // is asked for (that form writes it while it selects).
     const bool two_kernels =
-        phase > 3 ? (phase >> 4) <= 3 : fier::step_two_kernel_form(units, n_rep, max_budget, cfg->max_ctx);
+        phase > 3 ? (phase >> 4) <= 3
+                  : fier::step_two_kernel_form(units, n_rep, max_budget, cfg->max_ctx, idx_out != nullptr);
     if (two_kernels) {
       if (phase == 0 || (phase & 15) == 2) {
         e = fier::launch_step_attend(cfg->kv_dtype, lay, n_rep, w.sb, c->k, c->v, ql, c->seq_lens, extra, budgets,

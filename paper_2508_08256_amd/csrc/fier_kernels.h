@@ -47,8 +47,8 @@ constexpr int kAttnRowsDenseMax = 3200;  // picks a multiple of 128 in this rang
 
 // ---- fused decode step -------------------------------------------------------------------------------
 // Per layer: (1) append + score + score histogram, (2) exact threshold + attention over the selected rows + merge --
-// (2) is one kernel for up to 2 query heads per kv head and wherever its workgroups are all resident at once, and
-// split into a threshold kernel and a selection + attention kernel otherwise.  Each unit's tokens are spread over many
+// (2) is one kernel for up to 2 query heads per kv head and, unless the index list is asked for, on grids of up to
+// twice the workgroups resident at once; it is split into a threshold kernel and a selection + attention kernel otherwise.  Each unit's tokens are spread over many
 // workgroups; the few serial steps (exact threshold among the candidates of the threshold bin, merge of the
 // attention partials) are done by one workgroup of the unit, as a rule the one that arrives last at a device-scope
 // counter ("last arriver").  fier_topk_ws reuses the threshold kernel.
@@ -138,7 +138,7 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, int extra, int max_budget, int32_t* idx,
                                 int units, int n_rep, int n_kv_heads, int max_ctx, hipStream_t st);
 int step_ranges_per_wg(int units, int n_rep, int max_budget, int max_ctx);
-bool step_two_kernel_form(int units, int n_rep, int max_budget, int max_ctx);
+bool step_two_kernel_form(int units, int n_rep, int max_budget, int max_ctx, bool with_index_list);
 
 hipError_t launch_topk(const float* scores, const int32_t* seq_lens, int extra, const int32_t* budgets,
                        int max_budget, int32_t* idx, int32_t* count, int units, int n_kv_heads, int max_ctx,

@@ -859,7 +859,7 @@ hipError_t launch_step_attend(int dtype, KvLayout lay, int n_rep, const StepBuff
 }
 
 // Whether the step's second part is one launch (step_attend_kernel) for this shape.
-bool step_two_kernel_form(int units, int n_rep, int max_budget, int max_ctx) {
+bool step_two_kernel_form(int units, int n_rep, int max_budget, int max_ctx, bool with_index_list) {
   // Measured against the threshold kernel + selection-and-attention kernel (us per step, fp16, budget = 11 % of the
   // context unless noted): with 4 query heads per kv head, 8 units x 32k 25.8 / 28.5, 64 x 32k 57.0 / 62.0, 128 x 32k
   // 95.7 / 108.8, 32 x 128k (budget 4096) 65.7 / 71.5, and on grids that are not resident at once 64 x 128k 121.2 /
@@ -868,7 +868,12 @@ bool step_two_kernel_form(int units, int n_rep, int max_budget, int max_ctx) {
   //   On the ragged batch of 128 such units x 8k..64k (budget 11 % of each length), whose grid at full length is 1.5
   //   times the resident one: 107 / 117.  Hence: always with 1 or 2 query heads per kv head; with more, up to twice
   //   the resident grid.
+  //   With the ascending index list as an output the one-launch form needs one more kernel, which reads the scores
+  //   again (config 2 +4.3 us, 32 units x 128k +10), while the selection + attention kernel writes the list as it
+  //   selects: 32 x 128k at 4 heads per kv head 73.4 / 68.5, the ragged batch 115.3 / 108.7, 8 x 32k 29.3 / 28.5, but
+  //   config 2 37.5 / 41.2.  Hence: with the list and 3 or more heads per kv head, three kernels.
   if (n_rep <= 2) return true;
+  if (with_index_list) return false;
   const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   return (long)units * ((n_ranges + rpw - 1) / rpw) <= 2 * step_resident_wgs(n_rep);

@@ -192,18 +192,22 @@ def test_binding_passes_the_workspace_size(monkeypatch):
 
 
 def test_form_of_the_step_follows_from_the_shape():
-    """fier_decode_step_kernels: two kernels with one or two query heads per kv head, and with more of them where the
-    second kernel's grid is resident at once; three otherwise; 0 for an invalid configuration."""
+    """fier_decode_step_kernels: two kernels with one or two query heads per kv head; with more of them where the
+    second kernel's grid is at most twice the resident one and the index list is not asked for; three otherwise;
+    0 for an invalid configuration."""
     k = B.decode_step_kernels
-    assert k(B.make_config(1, 8, 8, 4160), 512) == 2                 # 8 units x 4k tokens
-    assert k(B.make_config(1, 32, 32, 32832), 3604) == 2             # 32 units x 32k
-    assert k(B.make_config(1, 32, 32, 65600), 256) == 2
-    assert k(B.make_config(1, 32, 32, 65600), 16384) == 2
-    assert k(B.make_config(2, 32, 16, 32832, B.BF16), 3604) == 2     # two query heads per kv head
+    for with_list in (False, True):
+        assert k(B.make_config(1, 8, 8, 4160), 512, with_list) == 2                 # 8 units x 4k tokens
+        assert k(B.make_config(1, 32, 32, 32832), 3604, with_list) == 2             # 32 units x 32k
+        assert k(B.make_config(1, 32, 32, 65600), 256, with_list) == 2
+        assert k(B.make_config(1, 32, 32, 65600), 16384, with_list) == 2
+        assert k(B.make_config(2, 32, 16, 32832, B.BF16), 3604, with_list) == 2     # two query heads per kv head
+        assert k(B.make_config(4, 32, 32, 131136), 4096, with_list) == 2            # 128 MHA units x 128k
+        assert k(B.make_config(32, 32, 8, 131136, B.BF16), 4096, with_list) == 3    # GQA far beyond the resident grid
     assert k(B.make_config(8, 32, 8, 32832, B.BF16), 3604) == 2      # four query heads per kv head, resident grid
     assert k(B.make_config(4, 32, 8, 131136, B.BF16), 4096) == 2
     assert k(B.make_config(8, 32, 8, 131136, B.BF16), 4096) == 2     # up to twice the resident grid
-    assert k(B.make_config(32, 32, 8, 131136, B.BF16), 4096) == 3    # beyond that
-    assert k(B.make_config(4, 32, 32, 131136), 4096) == 2            # 128 MHA units x 128k: several rounds
+    assert k(B.make_config(8, 32, 8, 32832, B.BF16), 3604, True) == 3    # the same with the index list as an output
+    assert k(B.make_config(4, 32, 8, 131136, B.BF16), 4096, True) == 3
     assert k(B.make_config(2, 30, 8, 4096), 64) == 0
     assert k(B.make_config(1, 8, 8, 4160), 0) == 0

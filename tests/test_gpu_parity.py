@@ -468,9 +468,17 @@ def _full_size_layers(gu, oracle, shape, seeds, samples, block_tokens=0):
     out = torch.zeros((NL, batch, Hq, 128), dtype=torch.float32, device="cuda")
     idx = torch.full((NL, cfg.units, budget), -1, dtype=torch.int32, device="cuda")
     cnt = torch.zeros((NL, cfg.units), dtype=torch.int32, device="cuda")
-    B.decode_step(cfg, caches, torch.stack(qs).contiguous(), torch.stack(kns).contiguous(), torch.stack(vns).contiguous(),
-                  budgets_dev, budget, out, idx, cnt, B.make_workspace(cfg, budget))
+    # first without the index list, the call bench.py times (grouped-query shapes take the one-launch form of the
+    # second kernel then), then with it; the second call appends the same rows at the same places once more
+    out_nl = torch.zeros_like(out)
+    ws = B.make_workspace(cfg, budget)
+    step_args = (cfg, caches, torch.stack(qs).contiguous(), torch.stack(kns).contiguous(), torch.stack(vns).contiguous(),
+                 budgets_dev, budget)
+    B.decode_step(*step_args, out_nl, None, None, ws)
+    B.decode_step(*step_args, out, idx, cnt, ws)
     torch.cuda.synchronize()
+    print(f"[full-size] kernels per layer step: {B.decode_step_kernels(cfg, budget)} without the index list, "
+          f"{B.decode_step_kernels(cfg, budget, True)} with it", flush=True)
     unit_len = np.repeat(lens, Hkv)
     unit_bud = np.minimum(np.repeat(buds, Hkv), unit_len + 1)
     outs, idxs = [], []
@@ -497,6 +505,9 @@ def _full_size_layers(gu, oracle, shape, seeds, samples, block_tokens=0):
                                     np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 16)
             err = np.abs(out_g[su] - want.reshape(len(su), n_rep, 128)).max(axis=(1, 2))
             assert err.max() <= 2e-3, (l, su, err)
+            out_n = out_nl[l].cpu().numpy().reshape(cfg.units, n_rep, 128)
+            err_n = np.abs(out_n[su] - want.reshape(len(su), n_rep, 128)).max(axis=(1, 2))
+            assert err_n.max() <= 2e-3, ("without the index list", l, su, err_n)
             # packed state of the units after the append, bit for bit
             sub = B.make_config(1, n_rep, 1, max_ctx, dtype)
             recall = []
@@ -532,6 +543,8 @@ def _full_size_layers(gu, oracle, shape, seeds, samples, block_tokens=0):
             sel = idx_g[u, :unit_bud[u]]
             assert np.all(np.diff(sel) > 0) and sel[0] >= 0 and sel[-1] <= unit_len[u], u
         assert np.all(np.isfinite(out_g))
+        out_n = out_nl[l].cpu().numpy().reshape(cfg.units, n_rep, 128)
+        assert np.all(np.isfinite(out_n)) and np.abs(out_n - out_g).max() <= 2e-3   # the same selection, every unit
         outs.append(out_g)
         idxs.append(idx_g)
     return outs, idxs

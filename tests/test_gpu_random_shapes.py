@@ -92,6 +92,10 @@ def _run_case(gu, oracle, seed, rng, big):
         kn = gu.to_dev(kn_w, dtype)[None].contiguous() if c["append"] else None
         vn = gu.to_dev(vn_w, dtype)[None].contiguous() if c["append"] else None
         args = (dw.cfg, [dw.cache], gu.to_dev(q_w, dtype)[None].contiguous(), kn, vn, dw.budgets, mb, out, idx, cnt, ws)
+        # the same step without the index list first (grouped-query shapes then take the one-launch form of the
+        # second kernel; appending the same row at the same place twice leaves the cache as one append does)
+        out0 = torch.full_like(out, float("nan"))
+        B.decode_step(*args[:7], out0, None, None, ws)
         if seed % 3 == 2:    # the three-kernel form (the one long grouped-query grids take), whatever the shape
             for p in (1, 2 + 64, 3 + 64):
                 B.decode_step_phase(*args, p)
@@ -110,6 +114,8 @@ def _run_case(gu, oracle, seed, rng, big):
         want = oracle.attention(K, V, q_w, L, 1.0 / np.sqrt(128.0), dtype,
                                 np.ascontiguousarray(np.where(ig < 0, 0, ig)), cg, 4)
         assert np.isfinite(og).all() and np.abs(og - want).max() <= 2e-3, t
+        og0 = out0.cpu().numpy()[0]
+        assert np.isfinite(og0).all() and np.abs(og0 - want).max() <= 2e-3, ("without the index list", t)
         got = dw.cache.unpack()
         for u in range(wl.units):
             n = int(L[u])
