@@ -678,27 +678,28 @@ __global__ __launch_bounds__(kStepThreads, step_wgs_per_cu(NREP)) void step_atte
 // workgroups per unit), block 256: workgroup (unit, wg) covers the same rpw 1024-token ranges as workgroup wg of the
 // step, starts its part of the list at the sum of the counts of the workgroups before it and fills it in token
 // order.  An optional output of the step, off its fast path.
+template <int RPW>
 __global__ __launch_bounds__(kStepThreads) void step_emit_idx_kernel(const float* __restrict__ scores,
                                                                      const int32_t* __restrict__ seq_lens, int extra,
                                                                      const UnitCtl* __restrict__ ctl,
-                                                                     const uint32_t* __restrict__ sel_cnt, int rpw,
+                                                                     const uint32_t* __restrict__ sel_cnt,
                                                                      int wgs_per_unit, int max_budget,
                                                                      int32_t* __restrict__ idx, int n_kv_heads,
                                                                      int max_ctx) {
-  __shared__ uint32_t scan_tmp[4];
+  __shared__ uint32_t wtot[RPW + 1][4];  // per wavefront: selected tokens of each range, rows of the workgroups before
   const int unit = blockIdx.x, wg = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   int n = seq_lens[unit / n_kv_heads] + extra;
   n = n < 0 ? 0 : (n > max_ctx ? max_ctx : n);
-  const int tok0 = wg * rpw * kRangeTokens;
+  const int tok0 = wg * RPW * kRangeTokens;
   if (tok0 >= n) return;
   const float* __restrict__ s = scores + (size_t)unit * max_ctx;
   // this workgroup's scores, the counts of the workgroups before it and the unit's threshold leave together
-  float4 v[8];
+  float4 v[RPW];
 #pragma unroll
-  for (int rr = 0; rr < 8; ++rr) {
+  for (int rr = 0; rr < RPW; ++rr) {
     const int i = tok0 + rr * kRangeTokens + 4 * tid;
-    v[rr] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (rr < rpw && i < n) v[rr] = *reinterpret_cast<const float4*>(s + i);  // i + 3 < max_ctx
+    v[rr] = *reinterpret_cast<const float4*>(s + (i < n ? i : 0));  // i + 3 < max_ctx; masked below
   }
   uint32_t mine = 0;
   for (int w = tid; w < wg; w += kStepThreads) mine += sel_cnt[(size_t)unit * wgs_per_unit + w];
@@ -707,31 +708,45 @@ __global__ __launch_bounds__(kStepThreads) void step_emit_idx_kernel(const float
   const float R = c->R, scale = c->scale;
   const uint32_t T = c->T;
   const int32_t idxT = c->idxT;
-  uint32_t run;
-  block_excl_scan_u32<4>(mine, scan_tmp, run);  // run = the list position of this workgroup's first row
-  int32_t* __restrict__ out = idx + (size_t)unit * max_budget;
+  // all ranges' positions with one barrier: per range a scan inside the wavefront, the wavefronts' totals through LDS
+  uint32_t selm[RPW], incl[RPW];
 #pragma unroll
-  for (int rr = 0; rr < 8; ++rr) {
-    if (rr >= rpw || tok0 + rr * kRangeTokens >= n) break;  // the same for the whole workgroup
+  for (int rr = 0; rr < RPW; ++rr) {
     const int i = tok0 + rr * kRangeTokens + 4 * tid;
     const float vv[4] = {v[rr].x, v[rr].y, v[rr].z, v[rr].w};
-    uint32_t selm = 0;
+    selm[rr] = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int bin = sel_bin(vv[j], R, scale, kSelBins);
       const uint32_t key = score_key(vv[j]);
-      const bool sel = i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
-      selm |= sel ? 1u << j : 0u;
+      const bool sel =
+          i + j < n && (bin > tbin || (bin == tbin && (key > T || (key == T && i + j <= idxT))));
+      selm[rr] |= sel ? 1u << j : 0u;
     }
-    uint32_t total;
-    uint32_t pos = run + block_excl_scan_u32<4>((uint32_t)__builtin_popcount(selm), scan_tmp, total);
+    incl[rr] = wave_incl_scan_u32((uint32_t)__builtin_popcount(selm[rr]), lane);
+  }
+  const uint32_t mine_w = wave_sum_u32(mine);
+  if (lane == 63) {
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) wtot[rr][wave] = incl[rr];
+    wtot[RPW][wave] = mine_w;
+  }
+  __syncthreads();
+  uint32_t run = wtot[RPW][0] + wtot[RPW][1] + wtot[RPW][2] + wtot[RPW][3];  // the list position of this workgroup's first row
+  int32_t* __restrict__ out = idx + (size_t)unit * max_budget;
+#pragma unroll
+  for (int rr = 0; rr < RPW; ++rr) {
+    const uint32_t t0 = wtot[rr][0], t1 = wtot[rr][1], t2 = wtot[rr][2], t3 = wtot[rr][3];
+    const uint32_t wave_off = (wave > 0 ? t0 : 0u) + (wave > 1 ? t1 : 0u) + (wave > 2 ? t2 : 0u);
+    uint32_t pos = run + wave_off + incl[rr] - (uint32_t)__builtin_popcount(selm[rr]);
+    const int i = tok0 + rr * kRangeTokens + 4 * tid;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      if (selm >> j & 1u) {
+      if (selm[rr] >> j & 1u) {
         if (pos < (uint32_t)max_budget) out[pos] = i + j;
         ++pos;
       }
-    run += total;
+    run += t0 + t1 + t2 + t3;
   }
 }
 
@@ -885,8 +900,15 @@ hipError_t launch_step_emit_idx(const StepBuffers& sb, const int32_t* seq_lens, 
   const int rpw = step_ranges_per_wg(units, n_rep, max_budget, max_ctx);
   const int n_ranges = (max_ctx + kRangeTokens - 1) / kRangeTokens;
   const int n_wgs = (n_ranges + rpw - 1) / rpw;
-  step_emit_idx_kernel<<<dim3(units, n_wgs), kStepThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.sel_cnt, rpw,
-                                                                     n_wgs, max_budget, idx, n_kv_heads, max_ctx);
+  const dim3 grid(units, n_wgs);
+#define FIER_EMIT(RPW)                                                                                              \
+  step_emit_idx_kernel<RPW><<<grid, kStepThreads, 0, st>>>(sb.scores, seq_lens, extra, sb.ctl, sb.sel_cnt, n_wgs, \
+                                                           max_budget, idx, n_kv_heads, max_ctx)
+  if (rpw == 1) FIER_EMIT(1);
+  else if (rpw == 2) FIER_EMIT(2);
+  else if (rpw == 4) FIER_EMIT(4);
+  else FIER_EMIT(8);
+#undef FIER_EMIT
   return hipGetLastError();
 }
 
