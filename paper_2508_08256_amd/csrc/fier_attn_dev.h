@@ -30,12 +30,21 @@ struct AttnState {
 // then skipped: it gets no weight.
 constexpr size_t kNoRow = ~(size_t)0;
 
+// A K / V row is read once per step: where a step gathers many of them they are loaded with the streaming hint
+// (STREAM of attend_rows).
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+  const u4_t v = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+
 // Attend over entries [start, end) of a row list; row_of(j) gives the row of entry j in the K / V arrays (the
 // callers map a token to its row: contiguous, or through the block table), or kNoRow if CHECKED and the entry
 // is to be skipped (safe_row is then read in its place and masked).  The workgroup's
 // 16 lane rows (4 waves x 4) take entries round-robin in batches of kAttnUnroll.  Calls may follow each other
 // on the same state: the running softmax simply continues.
-template <int DT, int NREP, bool CHECKED = false, class RowOf>
+template <int DT, int NREP, bool CHECKED = false, bool STREAM = false, class RowOf>
 __device__ __forceinline__ void attend_rows(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                             const uint4 (&qr)[NREP], RowOf row_of, int start, int end,
                                             float scale_log2e, AttnState<NREP>& st, size_t safe_row = 0) {
@@ -54,8 +63,8 @@ __device__ __forceinline__ void attend_rows(const uint4* __restrict__ K, const u
         r = r == kNoRow ? safe_row : r;
       }
       const size_t ro = r * (kD / 8) + cn;
-      kk[u] = K[ro];
-      vv[u] = V[ro];
+      kk[u] = STREAM ? load_stream(K + ro) : K[ro];
+      vv[u] = STREAM ? load_stream(V + ro) : V[ro];
     }
 #pragma unroll
     for (int r = 0; r < NREP; ++r) {

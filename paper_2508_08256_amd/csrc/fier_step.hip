@@ -264,7 +264,7 @@ struct StepLds {
 };
 
 // Workgroup `wg` of unit `unit`.
-template <int DT, int NREP, int RPW>
+template <int DT, int NREP, int RPW, bool STREAM>
 __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int unit, const int wg,
                                                  StepLds<NREP, RPW>& lds) {
   constexpr int CAP = kRangeTokens * RPW;  // tokens the workgroup owns
@@ -438,7 +438,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
     if constexpr (NREP >= 3)
       attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_own, from, to, a.scale_log2e, st, sh_o, resume);
     else
-      attend_rows<DT, NREP>(a.K, a.V, qr, row_own, from, to, a.scale_log2e, st);
+      attend_rows<DT, NREP, false, STREAM>(a.K, a.V, qr, row_own, from, to, a.scale_log2e, st);
   };
   bool picked = true;  // the workgroup's threshold-bin rows are on its list (or it has none)
   uint32_t T = 0;
@@ -604,7 +604,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
           if constexpr (NREP >= 3)
             attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_any, 0, (int)n_x, a.scale_log2e, st, sh_o, resumed);
           else
-            attend_rows<DT, NREP>(a.K, a.V, qr, row_any, 0, (int)n_x, a.scale_log2e, st);
+            attend_rows<DT, NREP, false, STREAM>(a.K, a.V, qr, row_any, 0, (int)n_x, a.scale_log2e, st);
           resumed = true;
           cnt_x += n_x;
         }
@@ -664,13 +664,14 @@ __device__ __forceinline__ void step_unit_wg(const StepArgs& a, int id_x, int id
 // CU: the gather wants many rows in flight per CU more than it wants registers -- but not at the price of spills:
 // with 4 query heads per kv head a bound of 4 left 60 bytes of scratch per lane and cost 3 to 5 us per step)
 constexpr int step_wgs_per_cu(int n_rep) { return n_rep <= 2 ? 5 : (n_rep <= 3 ? 4 : (n_rep <= 5 ? 3 : 2)); }
-template <int DT, int NREP, int RPW>
+// STREAM (one or two query heads per kv head): the gathered rows are loaded with the streaming hint.
+template <int DT, int NREP, int RPW, bool STREAM>
 __global__ __launch_bounds__(kStepThreads, step_wgs_per_cu(NREP)) void step_attend_kernel(
     const StepArgs a) {
   __shared__ StepLds<NREP, RPW> lds;
   int unit, wg;
   step_unit_wg(a, (int)blockIdx.x, (int)blockIdx.y, unit, wg);
-  step_attend_body<DT, NREP, RPW>(a, unit, wg, lds);
+  step_attend_body<DT, NREP, RPW, STREAM>(a, unit, wg, lds);
 }
 
 // The ascending index list of the step's selection: idx[unit][0 .. budget) from the scores, the threshold the step
@@ -832,13 +833,25 @@ static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffe
   if (!fill_step_args(a, RPW, order, lay, sb, K, V, q, seq_lens, extra, budgets, max_budget, sm_scale, count_out, out,
                       kabsmax, units, n_kv_heads, max_ctx, flags))
     return hipErrorInvalidValue;
+  // The streaming hint on the gathered K / V rows (they are read once and leave the caches to the scores, candidates
+  // and partials): measured, us per step without / with it, 32 units x 32k 34.4 / 32.6, 32 x 64k at B = 16384 77.9 /
+  // 73.1, at B = 7209 51.1 / 49.3, 128 units x 32k 87.2 / 82.8, 32 x 16k 25.8 / 25.6, 32 x 64k at B = 256 or 1024 no
+  // difference; 8 units x 4k 19.3 / 20.2 (rows that fit the caches are better off in them).  Hence from 8 MB of
+  // gathered rows per launch.  The matrix-core gather (3 or more heads per kv head) lost by it: 32 units x 128k
+  // 64.0 / 64.5, the ragged 128-unit batch 104.9 / 109.0.
+  const bool stream = n_rep <= 2 && (long)units * max_budget * (2 * kD * 2) >= (8L << 20);
 #define FIER_STEP_CASE(R)                                                   \
   case R:                                                                   \
-    step_attend_kernel<DT, R, RPW><<<grid, kStepThreads, 0, st>>>(a);       \
+    step_attend_kernel<DT, R, RPW, false><<<grid, kStepThreads, 0, st>>>(a); \
+    break;
+#define FIER_STEP_CASE_S(R)                                                       \
+  case R:                                                                         \
+    if (stream) step_attend_kernel<DT, R, RPW, true><<<grid, kStepThreads, 0, st>>>(a);  \
+    else step_attend_kernel<DT, R, RPW, false><<<grid, kStepThreads, 0, st>>>(a); \
     break;
   switch (n_rep) {
-    FIER_STEP_CASE(1)
-    FIER_STEP_CASE(2)
+    FIER_STEP_CASE_S(1)
+    FIER_STEP_CASE_S(2)
     FIER_STEP_CASE(3)
     FIER_STEP_CASE(4)
     FIER_STEP_CASE(5)
@@ -849,6 +862,7 @@ static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffe
       return hipErrorInvalidValue;
   }
 #undef FIER_STEP_CASE
+#undef FIER_STEP_CASE_S
   return hipGetLastError();
 }
 
