@@ -30,13 +30,6 @@ struct AttnState {
 // then skipped: it gets no weight.
 constexpr size_t kNoRow = ~(size_t)0;
 
-// A K / V row is read once per step: where a step gathers many of them they are loaded with the streaming hint
-// (STREAM of attend_rows).
-__device__ __forceinline__ uint4 load_stream(const uint4* p) {
-  typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
-  const u4_t v = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(p));
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
 
 
 // Attend over entries [start, end) of a row list; row_of(j) gives the row of entry j in the K / V arrays (the

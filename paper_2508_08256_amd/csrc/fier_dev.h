@@ -202,4 +202,11 @@ __device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expecte
   return arrive_add(counter, 1u, flag) == expected - 1;
 }
 
+// A load with the streaming hint, for data that is read once (K / V rows of a large gather, the packed key codes).
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+  const u4_t v = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 }  // namespace fier
