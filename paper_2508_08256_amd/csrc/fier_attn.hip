@@ -16,7 +16,8 @@ namespace fier {
 // Stand-alone attention (fier_sparse_attn: rows from an index list; fier_dense_attn: all rows).  grid (n_splits,
 // units), block 256: a workgroup attends over rows_per_wg entries and stores one partial per query head; the unit's
 // last workgroup merges the partials of the splits in use (arrival counter in the unit's control block).
-template <int DT, int NREP>
+// STREAM: whole-cache attention loads its rows with the streaming hint.
+template <int DT, int NREP, bool STREAM>
 __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                          const uint4* __restrict__ q, const int32_t* __restrict__ idx,
                                                          const int32_t* __restrict__ count,
@@ -80,12 +81,12 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
     if (sel)
       attend_rows_mfma<DT, NREP, true>(K, V, q_unit, row_sel, start, end, scale_log2e, st, sh_o, false, safe_row);
     else
-      attend_rows_mfma<DT, NREP>(K, V, q_unit, row_all, start, end, scale_log2e, st, sh_o);
+      attend_rows_mfma<DT, NREP, false, STREAM>(K, V, q_unit, row_all, start, end, scale_log2e, st, sh_o);
   } else {
     if (sel)
       attend_rows<DT, NREP, true>(K, V, qr, row_sel, start, end, scale_log2e, st, safe_row);
     else
-      attend_rows<DT, NREP>(K, V, qr, row_all, start, end, scale_log2e, st);
+      attend_rows<DT, NREP, false, STREAM>(K, V, qr, row_all, start, end, scale_log2e, st);
   }
   store_partials<NREP, true>(st, sh_o, unit, n_splits, split, po, pm, pl);
   // the unit's last workgroup merges the partials of the splits in use
@@ -252,11 +253,17 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
   dim3 grid = unit_major ? dim3(units, n_splits) : dim3(n_splits, units);
   const float sl2 = sm_scale * 1.4426950408889634f;
   if (!idx && rows_per_wg > kAttnRowsDenseMax) return hipErrorInvalidValue;  // the kernel's block-number window
+  // Whole-cache attention reads every row once: from 64 MB of rows on they are loaded with the streaming hint
+  // (measured: 32 units x 32k 98-101 -> 90-91 us, 32 x 64k 186 -> 165-172, 32 x 128k at 4 heads per kv head 398-406 ->
+  // 384; 8 units x 4k, which the caches hold, 15.5 -> 19.2 with it).
+  const bool stream = idx == nullptr && (long)units * max_ctx * (2 * kD * 2) >= (64L << 20);
+#define FIER_ATTN_ARGS                                                                                             \
+  (const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits, \
+      sl2, po, pm, pl, ctl, out, n_kv_heads, max_ctx, unit_major, lay
 #define FIER_ATTN_CASE(R)                                                                                          \
   case R:                                                                                                          \
-    attn_split_kernel<DT, R><<<grid, 256, 0, st>>>((const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count,  \
-                                                   seq_lens, extra, max_budget, rows_per_wg, n_splits, sl2, po, pm, \
-                                                   pl, ctl, out, n_kv_heads, max_ctx, unit_major, lay);            \
+    if (stream) attn_split_kernel<DT, R, true><<<grid, 256, 0, st>>>(FIER_ATTN_ARGS);                              \
+    else attn_split_kernel<DT, R, false><<<grid, 256, 0, st>>>(FIER_ATTN_ARGS);                                    \
     break;
   switch (n_rep) {
     FIER_ATTN_CASE(1)
@@ -271,6 +278,7 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
       return hipErrorInvalidValue;
   }
 #undef FIER_ATTN_CASE
+#undef FIER_ATTN_ARGS
   return hipGetLastError();
 }
 

@@ -203,6 +203,7 @@ __device__ __forceinline__ bool last_arriver(uint32_t* counter, uint32_t expecte
 }
 
 // A load with the streaming hint, for data that is read once (K / V rows of a large gather, the packed key codes).
+__device__ __forceinline__ uint32_t load_stream(const uint32_t* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ uint4 load_stream(const uint4* p) {
   typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
   const u4_t v = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(p));

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const uint32_t* __restric
   auto load_half = [&](uint32_t (&rows)[kG], int P, int h) {
     const uint32_t* src = K + kv.row(P * kPair + h * kG) * (kD / 2) + lane;
 #pragma unroll
-    for (int t = 0; t < kG; ++t) rows[t] = src[t * (kD / 2)];
+    for (int t = 0; t < kG; ++t) rows[t] = load_stream(src + t * (kD / 2));
   };
   auto minmax_keys = [&](const uint32_t (&rows)[kG], short2_t& mn, short2_t& mx) {
     mn = mx = order_keys(rows[0]);

@@ -504,11 +504,10 @@ static hipError_t launch_score_dt(KvLayout lay, int n_rep, const uint32_t* kbits
   if (bpw > kScoreMaxBpw) return hipErrorInvalidValue;  // cannot happen: at most 12, + 1
   const int n_x = (n_blocks + 4 * bpw - 1) / (4 * bpw);  // scoring workgroups per unit
   dim3 grid((unsigned)units * (unsigned)(n_x + (HIST ? 1 : 0)));
-  // Streaming hint on the loads of the codes and their metadata.  Measured, us per fused step without / with it:
-  // 32 units x 128k at 4 query heads per kv head 63.7 / 58.9, 32 x 128k 58.4 / 56.5, 128 x 32k 83.8 / 81.4, the ragged
-  // 128-unit batch 104.3 / 102.3, 32 x 64k 50.0 / 49.1 (B = 7209), 33.5 / 32.5 (B = 256); but 32 x 32k 32.5 / 32.8,
-  // 32 x 16k 25.7 / 25.9, 32 x 8k 49.1 / 49.5 (B = 8192), 8 x 4k 19.5 / 19.8.  Hence from 64 MB of codes and
-  // metadata per launch.
+  // Streaming hint on the loads of the codes and their metadata (read once per step).  Measured with the step
+  // rotating over 12 layer caches, this kernel alone, us without / with it: 32 units x 128k 34.4 / 30.6, 32 x 64k
+  // 19.2 / 16.5, the ragged 128-unit batch 34.5 / 31.5 (whole steps: 62.2 / 61.5, 32.6 / 31.9, 102.3 / 100.7);
+  // shapes of 32 units x 32k and below lost 0.2-0.4 us per step with it.  Hence from 64 MB per launch.
   const bool stream = (long)units * max_ctx * 32 >= (64L << 20);
 #define FIER_SCORE_ARGS                                                                                            \
   (const uint4*)kbits, (const uint4*)kmeta, kabsmax, (const uint16_t*)q, seq_lens, extra, scores,                  \

@@ -834,11 +834,12 @@ static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffe
                       kabsmax, units, n_kv_heads, max_ctx, flags))
     return hipErrorInvalidValue;
   // The streaming hint on the gathered K / V rows (they are read once and leave the caches to the scores, candidates
-  // and partials): measured, us per step without / with it, 32 units x 32k 34.4 / 32.6, 32 x 64k at B = 16384 77.9 /
-  // 73.1, at B = 7209 51.1 / 49.3, 128 units x 32k 87.2 / 82.8, 32 x 16k 25.8 / 25.6, 32 x 64k at B = 256 or 1024 no
-  // difference; 8 units x 4k 19.3 / 20.2 (rows that fit the caches are better off in them).  Hence from 8 MB of
-  // gathered rows per launch.  The matrix-core gather (3 or more heads per kv head) lost by it: 32 units x 128k
-  // 64.0 / 64.5, the ragged 128-unit batch 104.9 / 109.0.
+  // and partials).  Measured with the step rotating over 12 layer caches, us per step without / with the hint here
+  // and on the score kernel's loads: 32 units x 32k 33.5 / 32.95 (this kernel alone 22.7 / 21.3), 32 x 64k at
+  // B = 16384 76.8 / 72.3 (59.0 / 53.2), at B = 256 32.6 / 31.9; 8 units x 4k, whose rows the caches hold, lost 0.9 us
+  // with it.  Hence from 8 MB of gathered rows per launch.  (Rotating over 3 to 6 caches overstates the gain: 2 us
+  // at 32 x 32k.)  The matrix-core gather (3 or more heads per kv head) lost by it: 32 units x 128k +0.5 us, the
+  // ragged 128-unit batch +4.
   const bool stream = n_rep <= 2 && (long)units * max_budget * (2 * kD * 2) >= (8L << 20);
 #define FIER_STEP_CASE(R)                                                   \
   case R:                                                                   \
