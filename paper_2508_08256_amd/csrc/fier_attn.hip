@@ -218,7 +218,8 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
                      : kv.base + (size_t)t;
   };
   if constexpr (NREP >= 3)
-    attend_rows_mfma<DT, NREP>(K, V, q + (size_t)unit * NREP * (kD / 8), row_of, 0, (int)n_sel_total, scale_log2e, st,
+    attend_rows_mfma<DT, NREP, false, false, true>(K, V, q + (size_t)unit * NREP * (kD / 8), row_of, 0, (int)n_sel_total,
+                                                   scale_log2e, st,
                                sh_o);
   else
     attend_rows<DT, NREP>(K, V, qr, row_of, 0, (int)n_sel_total, scale_log2e, st);

@@ -122,7 +122,7 @@ constexpr int kAttnMfmaLds = 4 * 144;  // LDS floats attend_rows_mfma needs: per
 // attend_rows) and the P.V product stays on the vector ALUs.  One running (m, l) per head and wavefront.
 // q_unit: the unit's NREP query rows; sh: kAttnMfmaLds floats of LDS.  resume: st holds the result of an earlier
 // call by the same workgroup and the running softmax continues from it.  CHECKED / safe_row as in attend_rows.
-template <int DT, int NREP, bool CHECKED = false, bool STREAM = false, class RowOf>
+template <int DT, int NREP, bool CHECKED = false, bool STREAM = false, bool STREAM_V = STREAM, class RowOf>
 __device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                  const uint4* __restrict__ q_unit, RowOf row_of, int start, int end,
                                                  float scale_log2e, AttnState<NREP>& st, float* sh, bool resume = false,
@@ -181,7 +181,7 @@ __device__ __forceinline__ void attend_rows_mfma(const uint4* __restrict__ K, co
       const int jv = j0 + 4 * u + kq;
       size_t rv = row_of(jv < end ? jv : start);
       if (CHECKED) rv = rv == kNoRow ? safe_row : rv;  // its probability is zero: the K side masks it
-      vv[u] = STREAM ? load_stream(V + rv * (kD / 8) + n) : V[rv * (kD / 8) + n];
+      vv[u] = STREAM_V ? load_stream(V + rv * (kD / 8) + n) : V[rv * (kD / 8) + n];
     }
     floatx4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll

@@ -436,7 +436,7 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
   };
   auto attend_own = [&](int from, int to, bool resume) {
     if constexpr (NREP >= 3)
-      attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_own, from, to, a.scale_log2e, st, sh_o, resume);
+      attend_rows_mfma<DT, NREP, false, false, STREAM>(a.K, a.V, q_unit, row_own, from, to, a.scale_log2e, st, sh_o, resume);
     else
       attend_rows<DT, NREP, false, STREAM>(a.K, a.V, qr, row_own, from, to, a.scale_log2e, st);
   };
@@ -602,7 +602,8 @@ __device__ __forceinline__ void step_attend_body(const StepArgs& a, const int un
           __syncthreads();
           auto row_any = [&](int j) { return kv.row(base + (int)rows[j]); };
           if constexpr (NREP >= 3)
-            attend_rows_mfma<DT, NREP>(a.K, a.V, q_unit, row_any, 0, (int)n_x, a.scale_log2e, st, sh_o, resumed);
+            attend_rows_mfma<DT, NREP, false, false, STREAM>(a.K, a.V, q_unit, row_any, 0, (int)n_x, a.scale_log2e, st, sh_o,
+                                                             resumed);
           else
             attend_rows<DT, NREP, false, STREAM>(a.K, a.V, qr, row_any, 0, (int)n_x, a.scale_log2e, st);
           resumed = true;
@@ -664,7 +665,8 @@ __device__ __forceinline__ void step_unit_wg(const StepArgs& a, int id_x, int id
 // CU: the gather wants many rows in flight per CU more than it wants registers -- but not at the price of spills:
 // with 4 query heads per kv head a bound of 4 left 60 bytes of scratch per lane and cost 3 to 5 us per step)
 constexpr int step_wgs_per_cu(int n_rep) { return n_rep <= 2 ? 5 : (n_rep <= 3 ? 4 : (n_rep <= 5 ? 3 : 2)); }
-// STREAM (one or two query heads per kv head): the gathered rows are loaded with the streaming hint.
+// STREAM: the gathered rows are loaded with the streaming hint (with three or more query heads per kv head, where
+// the K rows go to the matrix cores in four pieces per row, the V rows only).
 template <int DT, int NREP, int RPW, bool STREAM>
 __global__ __launch_bounds__(kStepThreads, step_wgs_per_cu(NREP)) void step_attend_kernel(
     const StepArgs a) {
@@ -838,13 +840,10 @@ static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffe
   // and on the score kernel's loads: 32 units x 32k 33.5 / 32.95 (this kernel alone 22.7 / 21.3), 32 x 64k at
   // B = 16384 76.8 / 72.3 (59.0 / 53.2), at B = 256 32.6 / 31.9; 8 units x 4k, whose rows the caches hold, lost 0.9 us
   // with it.  Hence from 8 MB of gathered rows per launch.  (Rotating over 3 to 6 caches overstates the gain: 2 us
-  // at 32 x 32k.)  The matrix-core gather (3 or more heads per kv head) lost by it: 32 units x 128k +0.5 us, the
-  // ragged 128-unit batch +4.
-  const bool stream = n_rep <= 2 && (long)units * max_budget * (2 * kD * 2) >= (8L << 20);
-#define FIER_STEP_CASE(R)                                                   \
-  case R:                                                                   \
-    step_attend_kernel<DT, R, RPW, false><<<grid, kStepThreads, 0, st>>>(a); \
-    break;
+  // at 32 x 32k.)  The matrix-core gather (3 or more heads per kv head) lost by it on the K rows, which it loads in
+  // four pieces per row (32 units x 128k +0.6 us, the ragged 128-unit batch +4), and gains on the V rows alone:
+  // 32 x 128k 61.5 / 59.7, the ragged batch 101.3 / 100.8.
+  const bool stream = (long)units * max_budget * (2 * kD * 2) >= (8L << 20);
 #define FIER_STEP_CASE_S(R)                                                       \
   case R:                                                                         \
     if (stream) step_attend_kernel<DT, R, RPW, true><<<grid, kStepThreads, 0, st>>>(a);  \
@@ -853,16 +852,15 @@ static hipError_t launch_step_attend_dt(KvLayout lay, int n_rep, const StepBuffe
   switch (n_rep) {
     FIER_STEP_CASE_S(1)
     FIER_STEP_CASE_S(2)
-    FIER_STEP_CASE(3)
-    FIER_STEP_CASE(4)
-    FIER_STEP_CASE(5)
-    FIER_STEP_CASE(6)
-    FIER_STEP_CASE(7)
-    FIER_STEP_CASE(8)
+    FIER_STEP_CASE_S(3)
+    FIER_STEP_CASE_S(4)
+    FIER_STEP_CASE_S(5)
+    FIER_STEP_CASE_S(6)
+    FIER_STEP_CASE_S(7)
+    FIER_STEP_CASE_S(8)
     default:
       return hipErrorInvalidValue;
   }
-#undef FIER_STEP_CASE
 #undef FIER_STEP_CASE_S
   return hipGetLastError();
 }
