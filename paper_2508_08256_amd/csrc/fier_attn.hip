@@ -16,7 +16,8 @@ namespace fier {
 // Stand-alone attention (fier_sparse_attn: rows from an index list; fier_dense_attn: all rows).  grid (n_splits,
 // units), block 256: a workgroup attends over rows_per_wg entries and stores one partial per query head; the unit's
 // last workgroup merges the partials of the splits in use (arrival counter in the unit's control block).
-// STREAM: whole-cache attention loads its rows with the streaming hint.
+// STREAM: the rows are loaded with the streaming hint (a gather with three or more query heads per kv head: its V
+// rows only).
 template <int DT, int NREP, bool STREAM>
 __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                          const uint4* __restrict__ q, const int32_t* __restrict__ idx,
@@ -79,12 +80,13 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const uint4* __restrict
   if constexpr (NREP >= 3) {
     const uint4* q_unit = q + (size_t)unit * NREP * (kD / 8);
     if (sel)
-      attend_rows_mfma<DT, NREP, true>(K, V, q_unit, row_sel, start, end, scale_log2e, st, sh_o, false, safe_row);
+      attend_rows_mfma<DT, NREP, true, false, STREAM>(K, V, q_unit, row_sel, start, end, scale_log2e, st, sh_o, false,
+                                                      safe_row);
     else
       attend_rows_mfma<DT, NREP, false, STREAM>(K, V, q_unit, row_all, start, end, scale_log2e, st, sh_o);
   } else {
     if (sel)
-      attend_rows<DT, NREP, true>(K, V, qr, row_sel, start, end, scale_log2e, st, safe_row);
+      attend_rows<DT, NREP, true, STREAM>(K, V, qr, row_sel, start, end, scale_log2e, st, safe_row);
     else
       attend_rows<DT, NREP, false, STREAM>(K, V, qr, row_all, start, end, scale_log2e, st);
   }
@@ -257,7 +259,8 @@ static hipError_t launch_attn_dt(KvLayout lay, int n_rep, const void* K, const v
   // Whole-cache attention reads every row once: from 64 MB of rows on they are loaded with the streaming hint
   // (measured: 32 units x 32k 98-101 -> 90-91 us, 32 x 64k 186 -> 165-172, 32 x 128k at 4 heads per kv head 398-406 ->
   // 384; 8 units x 4k, which the caches hold, 15.5 -> 19.2 with it).
-  const bool stream = idx == nullptr && (long)units * max_ctx * (2 * kD * 2) >= (64L << 20);
+  const bool stream = idx == nullptr ? (long)units * max_ctx * (2 * kD * 2) >= (64L << 20)
+                                     : (long)units * max_budget * (2 * kD * 2) >= (8L << 20);  // as in the fused step
 #define FIER_ATTN_ARGS                                                                                             \
   (const uint4*)K, (const uint4*)V, (const uint4*)q, idx, count, seq_lens, extra, max_budget, rows_per_wg, n_splits, \
       sl2, po, pm, pl, ctl, out, n_kv_heads, max_ctx, unit_major, lay
